@@ -1,0 +1,161 @@
+/*
+ * dark.h - C ABI of the DARK attention library for AMD MI355X (gfx950).
+ *
+ * The library computes the positive-random-feature estimator of the data-aligned
+ * softmax kernel exp(q^T Sigma k / sqrt(d)), Sigma = M^T M (paper: Section 4.1,
+ * Eq. (3)), and the linear-time attention built on it (paper: Section 2,
+ * "Efficient attention via random feature kernels").
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every data pointer is DEVICE memory owned by the caller, 16-byte aligned,
+ *    contiguous, row-major with the last listed index fastest.  The library never
+ *    allocates, frees or synchronises: it enqueues kernels on `hip_stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ *    Scratch memory comes from the caller (`ws`, at least
+ *    dark_workspace_bytes() bytes, 256-byte aligned).  Calls that share a
+ *    workspace must be ordered on one stream.
+ *  - Q, K: [B, H, L, d];  V: [B, H, L, dv];  M: [H, r, d] (shared over the batch);
+ *    W: [H, m, r], or [m, r] when w_shared != 0.  M and W are always float32.
+ *    Q, K, V, dOut, phi and out have the element type `io_dtype`
+ *    (out: `out_dtype`); gradients are always float32.
+ *  - Each query and key is multiplied by sqrt(scale) before the feature map, so
+ *    the estimated kernel is exp(scale * q^T Sigma k); scale == 0 selects
+ *    1/sqrt(d) (paper: Section 2, footnote on absorbing the 1/sqrt(d) scaling).
+ *  - No epsilon is added anywhere.  Stabilising shifts inside the exponentials
+ *    cancel exactly in every attention output.
+ *  - Return value: DARK_OK, or an error code.  All argument checks happen before
+ *    the first HIP call, so they can be exercised without a GPU.  On error the
+ *    outputs are undefined.  Results are run-to-run bitwise deterministic (no
+ *    floating-point atomics).
+ *  - B == 0 or L == 0 is a valid empty problem: nothing is enqueued, DARK_OK.
+ */
+#ifndef DARK_H_
+#define DARK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DARK_OK = 0,
+  DARK_EINVAL = 1,       /* null pointer, non-positive dimension, bad enum value */
+  DARK_EUNSUPPORTED = 2, /* shape / dtype not supported by the requested path */
+  DARK_EWORKSPACE = 3,   /* ws == NULL or ws_bytes too small */
+  DARK_EALIGN = 4,       /* a pointer is not 16-byte aligned (ws: 256) */
+  DARK_EHIP = 5          /* a HIP runtime call failed (launch error) */
+} dark_status;
+
+typedef enum { DARK_F32 = 0, DARK_BF16 = 1 } dark_dtype;
+
+typedef enum {
+  DARK_OP_FEATURIZE = 0,
+  DARK_OP_ATTN_FWD = 1,
+  DARK_OP_ATTN_CAUSAL_FWD = 2,
+  DARK_OP_ATTN_BWD = 3
+} dark_op;
+
+typedef enum {
+  DARK_PATH_AUTO = 0,   /* fused MFMA kernels when the shape allows, else the fp32 kernels */
+  DARK_PATH_F32 = 1,    /* fp32 arithmetic throughout (any shape, any io_dtype) */
+  DARK_PATH_FUSED = 2   /* fused MFMA kernels or DARK_EUNSUPPORTED */
+} dark_path;
+
+typedef struct {
+  int32_t B, H, L;   /* batch, heads, sequence length */
+  int32_t d;         /* query/key dimension */
+  int32_t r;         /* rows of M (r <= d in the paper; any r >= 1 accepted) */
+  int32_t m;         /* number of random features */
+  int32_t dv;        /* value dimension */
+  int32_t chunk;     /* causal chunk length, 0 = 128; a schedule, not semantics */
+  int32_t io_dtype;  /* dark_dtype of Q, K, V, dOut, phi */
+  int32_t out_dtype; /* dark_dtype of out */
+  float scale;       /* 0 = 1/sqrt(d) */
+  int32_t w_shared;  /* W is [m, r] for all heads */
+  int32_t path;      /* dark_path */
+} dark_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int dark_version(void);
+
+/* Human-readable name of a status code (static storage). */
+const char* dark_status_string(dark_status s);
+
+/*
+ * Bytes of scratch the given operation needs for these parameters on the path the
+ * library would choose (0 on invalid parameters).  `op` is a dark_op; for
+ * DARK_OP_ATTN_BWD the causal flag is taken from `causal`.
+ */
+size_t dark_workspace_bytes(const dark_params* p, int op, int causal);
+
+/*
+ * Feature map phi_Sigma (paper: Section 4.1, definition before Eq. (3)), with
+ * omega~_j = M^T w_j (Appendix B, derivation of Eq. (3)).  For every row x of X
+ * [B, H, L, d]:   x' = sqrt(scale) x,  logit_j = w_j^T (M x') - 1/2 ||M x'||^2,
+ *                 phi_j = exp(logit_j - c) / sqrt(m).
+ * is_query != 0: c is the maximum logit of the row, stab is [B, H, L];
+ * is_query == 0: c is the maximum logit over the whole (b, h) slice, stab is [B, H].
+ * phi: [B, H, L, m] in io_dtype.  stab (float32) receives c; phi * exp(c) is the
+ * unstabilised feature vector.  stab may be NULL.
+ */
+dark_status dark_featurize(const dark_params* p, const void* X, const float* M, const float* W,
+                           int is_query, void* phi, float* stab,
+                           void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Bidirectional random-feature attention (paper: Section 2, "Efficient attention
+ * via random feature kernels", with the normalisation of the footnote there):
+ *   S = phi(K)^T V,  z = phi(K)^T 1,  out_i = phi(q_i)^T S / phi(q_i)^T z
+ * per (b, h), with phi as in dark_featurize.  out: [B, H, L, dv] in out_dtype.
+ */
+dark_status dark_attn_fwd(const dark_params* p, const void* Q, const void* K, const void* V,
+                          const float* M, const float* W, void* out,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Causal form: out_i uses only keys l <= i (prefix sums of S and z).  The
+ * sequence is processed in chunks of p->chunk positions; the result does not
+ * depend on the chunk length.  L need not be a multiple of the chunk length.
+ * Same arguments as dark_attn_fwd.
+ */
+dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void* K, const void* V,
+                                 const float* M, const float* W, void* out,
+                                 void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Gradients of sum(out * dOut) for dark_attn_fwd (causal == 0) or
+ * dark_attn_causal_fwd (causal != 0).  The paper makes M learnable (Section 4,
+ * Sigma = M^T M is learned); the gradients are the chain rule through the
+ * definitions above, with W held fixed.
+ *   dQ, dK: [B, H, L, d], dV: [B, H, L, dv], float32, overwritten.
+ *   dM: [H, r, d], float32, overwritten with the sum over the batch of both the
+ *   query-side and the key-side contributions.  Any of dQ, dK, dV, dM may be NULL
+ *   (that gradient is skipped).
+ * The forward quantities are recomputed; no saved activations are needed.
+ */
+dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const void* K,
+                          const void* V, const float* M, const float* W, const void* dOut,
+                          float* dQ, float* dK, float* dV, float* dM,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel
+ * launch of the library is bracketed by HIP events on the launch stream.
+ * dark_timing_read() synchronises with the recorded events, adds their elapsed
+ * times into per-kernel totals and returns, for kernel slot `k`
+ * (0 <= k < dark_timing_slots()), its name (static storage), the number of
+ * launches and the summed milliseconds since the last dark_timing_reset().
+ * Host pointers.  Not thread-safe; meant for single-threaded measurement only.
+ */
+void dark_timing_enable(int on);
+void dark_timing_reset(void);
+int dark_timing_slots(void);
+dark_status dark_timing_read(int k, const char** name, int64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARK_H_ */

@@ -1,0 +1,238 @@
+"""Python binding over the C-ABI DARK attention library (libdark.so).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels behind ``include/dark.h``.  PyTorch supplies device memory (tensors)
+and the current HIP stream.  There is no CPU fallback: if the shared library is
+missing the import of this binding's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdark.so")
+
+DARK_OK, DARK_EINVAL, DARK_EUNSUPPORTED, DARK_EWORKSPACE, DARK_EALIGN, DARK_EHIP = range(6)
+DARK_F32, DARK_BF16 = 0, 1
+OP_FEATURIZE, OP_ATTN_FWD, OP_ATTN_CAUSAL_FWD, OP_ATTN_BWD = range(4)
+PATH_AUTO, PATH_F32, PATH_FUSED = range(3)
+
+
+class DarkParams(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("m", ctypes.c_int32), ("dv", ctypes.c_int32),
+        ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("w_shared", ctypes.c_int32), ("path", ctypes.c_int32),
+    ]
+
+
+class DarkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libdark.so (built in-tree by ``build.py``); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2603_04127_amd.build or __graft_entry__.build())")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    pp = ctypes.POINTER(DarkParams)
+    L.dark_version.restype = i32
+    L.dark_status_string.restype = ctypes.c_char_p
+    L.dark_status_string.argtypes = [i32]
+    L.dark_workspace_bytes.restype = sz
+    L.dark_workspace_bytes.argtypes = [pp, i32, i32]
+    L.dark_featurize.restype = i32
+    L.dark_featurize.argtypes = [pp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    for f in (L.dark_attn_fwd, L.dark_attn_causal_fwd):
+        f.restype = i32
+        f.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_attn_bwd.restype = i32
+    L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_timing_enable.argtypes = [i32]
+    L.dark_timing_enable.restype = None
+    L.dark_timing_reset.restype = None
+    L.dark_timing_slots.restype = i32
+    L.dark_timing_read.restype = i32
+    L.dark_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int64),
+                                   ctypes.POINTER(ctypes.c_double)]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().dark_status_string(int(status)).decode()
+
+
+def make_params(B, H, L, d, r, m, dv, *, io_dtype=DARK_F32, out_dtype=None, chunk=0, scale=0.0, w_shared=False,
+                path=PATH_AUTO) -> DarkParams:
+    return DarkParams(B, H, L, d, r, m, dv, chunk, io_dtype, io_dtype if out_dtype is None else out_dtype,
+                      float(scale), int(bool(w_shared)), path)
+
+
+def workspace_bytes(p: DarkParams, op: int, causal: bool = False) -> int:
+    return int(lib().dark_workspace_bytes(ctypes.byref(p), op, int(causal)))
+
+
+# ----------------------------------------------------------------------------
+# torch-facing helpers
+# ----------------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return DARK_F32
+    if t.dtype == torch.bfloat16:
+        return DARK_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes: int, device):
+    """A cached device byte buffer of at least nbytes (torch owns the memory)."""
+    torch = _torch()
+    key = (device.type, device.index)
+    buf = _ws_cache.get(key)
+    if buf is None or buf.numel() < nbytes:
+        _ws_cache.pop(key, None)
+        buf = None
+        buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+def _params_from(Q, V, M, W, *, out_dtype=None, chunk=0, scale=0.0, path=PATH_AUTO) -> DarkParams:
+    B, H, L, d = Q.shape
+    dv = V.shape[-1] if V is not None else 1
+    r = M.shape[-2]
+    w_shared = W.dim() == 2
+    m = W.shape[-2]
+    torch = _torch()
+    if M.dtype != torch.float32 or W.dtype != torch.float32:
+        raise TypeError("M and W must be float32")
+    if tuple(M.shape) != (H, r, d) or W.shape[-1] != r or (not w_shared and W.shape[0] != H):
+        raise ValueError("M must be [H, r, d] and W [H, m, r] or [m, r]")
+    io = _dtype_code(Q)
+    od = io if out_dtype is None else (DARK_BF16 if out_dtype == torch.bfloat16 else DARK_F32)
+    return make_params(B, H, L, d, r, m, dv, io_dtype=io, out_dtype=od, chunk=chunk, scale=scale, w_shared=w_shared,
+                       path=path)
+
+
+def _check(status: int, where: str):
+    if status != DARK_OK:
+        raise DarkError(status, where)
+
+
+def dark_featurize(X, M, W, is_query: bool, *, scale=0.0, path=PATH_AUTO):
+    """phi_Sigma of every row of X [B,H,L,d] -> (phi [B,H,L,m], stab)."""
+    torch = _torch()
+    p = _params_from(X, None, M, W, scale=scale, path=path)
+    B, H, L, _ = X.shape
+    phi = torch.empty((B, H, L, p.m), dtype=X.dtype, device=X.device)
+    stab = torch.empty((B, H, L) if is_query else (B, H), dtype=torch.float32, device=X.device)
+    nb = workspace_bytes(p, OP_FEATURIZE)
+    ws = _workspace(nb, X.device)
+    _check(lib().dark_featurize(ctypes.byref(p), _ptr(X), _ptr(M), _ptr(W), int(is_query), _ptr(phi), _ptr(stab),
+                                ws.data_ptr(), ws.numel(), _stream()), "dark_featurize")
+    return phi, stab
+
+
+def _attn(fn_name, op, Q, K, V, M, W, out, chunk, scale, path, out_dtype):
+    torch = _torch()
+    p = _params_from(Q, V, M, W, out_dtype=out_dtype, chunk=chunk, scale=scale, path=path)
+    if K.shape != Q.shape or V.shape[:3] != Q.shape[:3] or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V shapes/dtypes disagree")
+    if out is None:
+        od = Q.dtype if out_dtype is None else out_dtype
+        out = torch.empty(V.shape, dtype=od, device=Q.device)
+    nb = workspace_bytes(p, op)
+    ws = _workspace(nb, Q.device)
+    fn = getattr(lib(), fn_name)
+    _check(fn(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(out), ws.data_ptr(), ws.numel(),
+              _stream()), fn_name)
+    return out
+
+
+def dark_attn_fwd(Q, K, V, M, W, *, out=None, scale=0.0, path=PATH_AUTO, out_dtype=None):
+    """Bidirectional random-feature attention, out [B,H,L,dv]."""
+    return _attn("dark_attn_fwd", OP_ATTN_FWD, Q, K, V, M, W, out, 0, scale, path, out_dtype)
+
+
+def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None):
+    """Causal random-feature attention (keys l <= i), out [B,H,L,dv]."""
+    return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype)
+
+
+def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path=PATH_AUTO, need=("dQ", "dK", "dV", "dM")):
+    """Gradients of sum(out*dOut): returns dict with float32 dQ, dK, dV, dM."""
+    torch = _torch()
+    p = _params_from(Q, V, M, W, chunk=chunk, scale=scale, path=path)
+    f32 = dict(dtype=torch.float32, device=Q.device)
+    g = {
+        "dQ": torch.empty(Q.shape, **f32) if "dQ" in need else None,
+        "dK": torch.empty(K.shape, **f32) if "dK" in need else None,
+        "dV": torch.empty(V.shape, **f32) if "dV" in need else None,
+        "dM": torch.empty(M.shape, **f32) if "dM" in need else None,
+    }
+    nb = workspace_bytes(p, OP_ATTN_BWD, causal)
+    ws = _workspace(nb, Q.device)
+    _check(lib().dark_attn_bwd(ctypes.byref(p), int(causal), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(dOut),
+                               _ptr(g["dQ"]), _ptr(g["dK"]), _ptr(g["dV"]), _ptr(g["dM"]), ws.data_ptr(), ws.numel(),
+                               _stream()), "dark_attn_bwd")
+    return g
+
+
+# ----------------------------------------------------------------------------
+# per-kernel timing (benchmarks)
+# ----------------------------------------------------------------------------
+def timing_enable(on: bool):
+    lib().dark_timing_enable(int(on))
+
+
+def timing_reset():
+    lib().dark_timing_reset()
+
+
+def timing_read() -> dict:
+    """{kernel name: (launches, total_ms)} for kernels launched since the last reset."""
+    L = lib()
+    out = {}
+    for k in range(L.dark_timing_slots()):
+        name = ctypes.c_char_p()
+        n = ctypes.c_int64()
+        ms = ctypes.c_double()
+        _check(L.dark_timing_read(k, ctypes.byref(name), ctypes.byref(n), ctypes.byref(ms)), "dark_timing_read")
+        if n.value:
+            out[name.value.decode()] = (n.value, ms.value)
+    return out

@@ -1,0 +1,109 @@
+// Internal declarations shared by the translation units of the DARK attention library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dark.h"
+
+namespace dark {
+
+// ---------------------------------------------------------------------------
+// Kernel slots for the optional per-kernel timing (dark_timing_*).
+// ---------------------------------------------------------------------------
+enum KernelId : int {
+  KID_GEMM = 0,        // fp32 batched GEMM of the fp32 path
+  KID_LOAD,            // dtype conversion / [V|1] staging
+  KID_ROWSTAT,         // logits: subtract norm term, row maxima
+  KID_HEADMAX,         // per-head maximum of row maxima
+  KID_EXP,             // exponentiation
+  KID_SUM_SLICES,      // fixed-order sum of per-slice partial states
+  KID_FINISH,          // numerator / denominator
+  KID_SCAN,            // exclusive scan of chunk states
+  KID_BWD_ELEM,        // element-wise kernels of the backward pass
+  KID_PREP,            // fused path: A = sqrt(scale)*log2(e) * W M, operand packing
+  KID_KV_REDUCE,       // fused path: phi(K)^T [V|1] per L-slice
+  KID_KV_MERGE,        // fused path: fixed-order merge of slice states
+  KID_READOUT,         // fused path: phi(Q) S / phi(Q) z
+  KID_CAUSAL_STATE,    // fused causal path: per-chunk state
+  KID_CAUSAL_SCAN,     // fused causal path: exclusive scan over chunk states
+  KID_CAUSAL_OUT,      // fused causal path: inter + intra chunk readout
+  KID_COUNT
+};
+
+const char* kernel_name(int k);
+bool timing_on();
+void timing_before(int kid, hipStream_t st);
+void timing_after(int kid, hipStream_t st);
+
+// Launch helper: optional event bracketing, launch-error check.
+#define DARK_LAUNCH(kid, st, kernel, grid, block, shmem, ...)                    \
+  do {                                                                           \
+    if (::dark::timing_on()) ::dark::timing_before((kid), (st));                 \
+    hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (st), __VA_ARGS__);     \
+    if (::dark::timing_on()) ::dark::timing_after((kid), (st));                  \
+    if (hipGetLastError() != hipSuccess) return DARK_EHIP;                       \
+  } while (0)
+
+#define DARK_TRY(expr)                       \
+  do {                                       \
+    dark_status _s = (expr);                 \
+    if (_s != DARK_OK) return _s;            \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// Bump allocator over the caller's workspace.  With base == nullptr it only
+// measures (used by dark_workspace_bytes).
+// ---------------------------------------------------------------------------
+struct Arena {
+  char* base;
+  size_t cap;
+  size_t off;
+  bool overflow;
+  Arena(void* b, size_t c) : base(static_cast<char*>(b)), cap(c), off(0), overflow(false) {}
+  template <typename T>
+  T* take(size_t n) {
+    size_t bytes = (n * sizeof(T) + 255) & ~size_t(255);
+    size_t at = off;
+    off += bytes;
+    if (base == nullptr) return nullptr;
+    if (off > cap) {
+      overflow = true;
+      return nullptr;
+    }
+    return reinterpret_cast<T*>(base + at);
+  }
+};
+
+struct Problem {
+  dark_params p;
+  float scale;     // resolved (never 0)
+  int chunk;       // resolved
+  hipStream_t st;
+  long long BH() const { return (long long)p.B * p.H; }
+  long long rows() const { return (long long)p.B * p.H * p.L; }
+};
+
+// Parameter validation shared by all entry points (no HIP call).
+dark_status check_params(const dark_params* p, Problem* out);
+inline bool aligned(const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) == 0; }
+
+// fp32 path (generic.hip).  With arena.base == nullptr these only measure.
+dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,
+                          int is_query, void* phi, float* stab);
+dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K,
+                         const void* V, const float* M, const float* W, void* out);
+dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K,
+                         const void* V, const float* M, const float* W, const void* dOut, float* dQ,
+                         float* dK, float* dV, float* dM);
+
+// fused MFMA path (fused.hip).
+bool fused_supported(const Problem& pb, int op, bool causal);
+dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const void* K, const void* V,
+                           const float* M, const float* W, void* out);
+dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, const void* K,
+                                  const void* V, const float* M, const float* W, void* out);
+
+}  // namespace dark

@@ -1,0 +1,776 @@
+// fp32 path of the DARK attention library: every step is a small, general fp32
+// kernel (a strided batched GEMM plus element-wise / reduction kernels), composed
+// on the host.  It accepts any shape and either io dtype, and is the path used
+// for fp32 problems, for shapes the fused MFMA kernels do not cover, and for the
+// backward pass.  Intermediates (features, chunk states) live in the caller's
+// workspace.
+//
+// Steps follow the paper: Section 4.1 (feature map with x~ = M x, h = exp(-|x~|^2/2)),
+// Appendix B (omega~ = M^T w, hence logits = x' (W M)^T), Section 2 (K'^T V first,
+// then Q' times it, then normalise).
+#include <cmath>
+
+#include "common.h"
+
+namespace dark {
+namespace {
+
+constexpr int kWave = 64;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+__device__ inline float load_as_f32(const float* p, long long i) { return p[i]; }
+__device__ inline float load_as_f32(const __hip_bfloat16* p, long long i) {
+  unsigned short b = reinterpret_cast<const unsigned short*>(p)[i];
+  return __uint_as_float(((unsigned)b) << 16);
+}
+__device__ inline void store_from_f32(float* p, long long i, float v) { p[i] = v; }
+__device__ inline void store_from_f32(__hip_bfloat16* p, long long i, float v) {
+  // round to nearest even
+  unsigned u = __float_as_uint(v);
+  unsigned r;
+  if ((u & 0x7fffffffu) > 0x7f800000u) {
+    r = (u >> 16) | 0x40u;  // quiet NaN
+  } else {
+    r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  }
+  reinterpret_cast<unsigned short*>(p)[i] = (unsigned short)r;
+}
+
+// ---------------------------------------------------------------------------
+// Strided, three-level batched fp32 GEMM:  C = alpha * A B + beta * C.
+// A is M x K, B is K x N, C is M x N, each with arbitrary element strides, so
+// transposes are free.  The innermost batch index (b2) may shorten M, N and K
+// ("ragged" chunks): effective size = clamp(lim - b2 * step, 0, size) if lim > 0.
+// mask == 1 writes zeros where column > row (lower-triangular result).
+// ---------------------------------------------------------------------------
+struct Gemm {
+  const float* A;
+  const float* B;
+  float* C;
+  int M, N, K;
+  long long sAm, sAk, sBk, sBn, sCm, sCn;
+  int nb0, nb1, nb2;
+  long long sA0, sA1, sA2, sB0, sB1, sB2, sC0, sC1, sC2;
+  float alpha, beta;
+  int mask;
+  int mlim, mstep, nlim, nstep, klim, kstep;
+};
+
+constexpr int GT = 64;  // C tile edge
+constexpr int GK = 16;  // K step
+
+__global__ __launch_bounds__(256) void k_gemm(Gemm g) {
+  __shared__ float As[GK][GT + 4];
+  __shared__ float Bs[GK][GT + 4];
+  const int tilesN = (g.N + GT - 1) / GT;
+  const int tilesM = (g.M + GT - 1) / GT;
+  long long bid = blockIdx.x;
+  const int tn = (int)(bid % tilesN);
+  bid /= tilesN;
+  const int tm = (int)(bid % tilesM);
+  bid /= tilesM;
+  const int b2 = (int)(bid % g.nb2);
+  bid /= g.nb2;
+  const int b1 = (int)(bid % g.nb1);
+  const int b0 = (int)(bid / g.nb1);
+
+  int Me = g.M, Ne = g.N, Ke = g.K;
+  if (g.mlim > 0) Me = max(0, min(g.M, g.mlim - b2 * g.mstep));
+  if (g.nlim > 0) Ne = max(0, min(g.N, g.nlim - b2 * g.nstep));
+  if (g.klim > 0) Ke = max(0, min(g.K, g.klim - b2 * g.kstep));
+  const int m0 = tm * GT, n0 = tn * GT;
+  if (m0 >= Me || n0 >= Ne) return;
+
+  const float* A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
+  const float* B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
+  float* C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
+
+  const int tid = threadIdx.x;
+  const int tx = tid % 16, ty = tid / 16;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  const bool a_k_fast = g.sAk <= g.sAm;  // make consecutive threads walk the smaller stride
+  const bool b_k_fast = g.sBk <= g.sBn;
+
+  for (int k0 = 0; k0 < Ke; k0 += GK) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int idx = tid + t * 256;
+      int ki, mi;
+      if (a_k_fast) {
+        ki = idx % GK;
+        mi = idx / GK;
+      } else {
+        mi = idx % GT;
+        ki = idx / GT;
+      }
+      int gm = m0 + mi, gk = k0 + ki;
+      As[ki][mi] = (gm < Me && gk < Ke) ? A[gm * g.sAm + gk * g.sAk] : 0.f;
+      int ni;
+      if (b_k_fast) {
+        ki = idx % GK;
+        ni = idx / GK;
+      } else {
+        ni = idx % GT;
+        ki = idx / GT;
+      }
+      int gn = n0 + ni;
+      gk = k0 + ki;
+      Bs[ki][ni] = (gn < Ne && gk < Ke) ? B[gk * g.sBk + gn * g.sBn] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < GK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int gm = m0 + ty * 4 + i;
+    if (gm >= Me) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int gn = n0 + tx * 4 + j;
+      if (gn >= Ne) continue;
+      float* c = C + gm * g.sCm + gn * g.sCn;
+      float v = g.alpha * acc[i][j];
+      if (g.beta != 0.f) v += g.beta * (*c);
+      if (g.mask == 1 && gn > gm) v = 0.f;
+      *c = v;
+    }
+  }
+}
+
+// dst[row][0..cols) = (float)src[row][0..cols);  dst[row][cols] = 1 if ones.
+template <typename T>
+__global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, long long rows, int cols, int ld,
+                            int ones) {
+  long long total = rows * ld;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    long long row = i / ld;
+    int c = (int)(i % ld);
+    float v;
+    if (c < cols)
+      v = load_as_f32(src, row * cols + c);
+    else
+      v = ones ? 1.f : 0.f;
+    dst[i] = v;
+  }
+}
+
+// One wave per row: n = 1/2 |x~|^2, logits = U - n (in place), rowmax.
+__global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const float* __restrict__ Xt,
+                                                 float* __restrict__ rowmax, long long rows, int m, int r) {
+  long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
+  if (row >= rows) return;
+  int lane = threadIdx.x % kWave;
+  const float* xt = Xt + row * r;
+  float s = 0.f;
+  for (int t = lane; t < r; t += kWave) s = fmaf(xt[t], xt[t], s);
+  s = 0.5f * wave_sum(s);
+  float* u = U + row * m;
+  float mx = -INFINITY;
+  for (int j = lane; j < m; j += kWave) {
+    float v = u[j] - s;
+    u[j] = v;
+    mx = fmaxf(mx, v);
+  }
+  mx = wave_max(mx);
+  if (lane == 0) rowmax[row] = mx;
+}
+
+// One block per (b,h): maximum of L row maxima.
+__global__ __launch_bounds__(256) void k_headmax(const float* __restrict__ rowmax, float* __restrict__ headmax, int L) {
+  __shared__ float sm[4];
+  const float* p = rowmax + (long long)blockIdx.x * L;
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < L; i += 256) mx = fmaxf(mx, p[i]);
+  mx = wave_max(mx);
+  if (threadIdx.x % kWave == 0) sm[threadIdx.x / kWave] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) headmax[blockIdx.x] = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+}
+
+// Phi = exp(logit - c) * mult.  c = rowc[row] (per_head == 0) or headc[row / L].
+template <typename T>
+__global__ void k_exp(const float* __restrict__ logit, T* __restrict__ out, const float* __restrict__ cvec,
+                      long long rows, int m, int L, int per_head, float mult) {
+  long long total = rows * m;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    long long row = i / m;
+    float c = per_head ? cvec[row / L] : cvec[row];
+    store_from_f32(out, i, expf(logit[i] - c) * mult);
+  }
+}
+
+// out[o*so_out + e] = sum_{p<P} in[o*so + p*sp + e], p ascending (fixed order).
+__global__ void k_sum_slices(const float* __restrict__ in, float* __restrict__ out, long long n_outer, int P,
+                             long long E, long long so, long long sp) {
+  long long total = n_outer * E;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    long long o = i / E, e = i % E;
+    const float* q = in + o * so + e;
+    float s = 0.f;
+    for (int p = 0; p < P; ++p) s += q[p * sp];
+    out[i] = s;
+  }
+}
+
+// out[row][c] = ND[row][c] / ND[row][dv]
+template <typename T>
+__global__ void k_finish(const float* __restrict__ ND, T* __restrict__ out, long long rows, int dv) {
+  long long total = rows * dv;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    long long row = i / dv;
+    int c = (int)(i % dv);
+    const float* nd = ND + row * (dv + 1);
+    store_from_f32(out, i, nd[c] / nd[dv]);
+  }
+}
+
+// Exclusive scan over the chunk axis of st[bh][chunk][E] (forward, or reverse for the
+// backward pass), in place.
+__global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long long E, int reverse) {
+  long long total = BH * E;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    long long bh = i / E, e = i % E;
+    float* p = st + bh * nchunk * E + e;
+    float run = 0.f;
+    if (!reverse) {
+      for (int c = 0; c < nchunk; ++c) {
+        float t = p[c * E];
+        p[c * E] = run;
+        run += t;
+      }
+    } else {
+      for (int c = nchunk - 1; c >= 0; --c) {
+        float t = p[c * E];
+        p[c * E] = run;
+        run += t;
+      }
+    }
+  }
+}
+
+// Backward, per row (one wave): from ND = [N | D] and G = dOut,
+//   dN = G / D,  dD = -(G . out) / D  with out = N / D;  written as dND = [dN | dD].
+__global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const float* __restrict__ G,
+                                             float* __restrict__ dND, long long rows, int dv) {
+  long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
+  if (row >= rows) return;
+  int lane = threadIdx.x % kWave;
+  const float* nd = ND + row * (dv + 1);
+  const float* gp = G + row * dv;
+  float* o = dND + row * (dv + 1);
+  float invD = 1.f / nd[dv];
+  float dot = 0.f;
+  for (int c = lane; c < dv; c += kWave) {
+    float gv = gp[c];
+    o[c] = gv * invD;
+    dot = fmaf(gv, nd[c] * invD, dot);
+  }
+  dot = wave_sum(dot);
+  if (lane == 0) o[dv] = -dot * invD;
+}
+
+// Backward, per row (one wave): dlogit = dPhi * Phi (in place in dPhi),
+// dn = -sum_j dlogit_j,  dXt = dn * Xt (in place in Xt).
+__global__ __launch_bounds__(256) void k_dlogit(float* __restrict__ dPhi, const float* __restrict__ Phi,
+                                                float* __restrict__ Xt, long long rows, int m, int r) {
+  long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
+  if (row >= rows) return;
+  int lane = threadIdx.x % kWave;
+  float* dp = dPhi + row * m;
+  const float* ph = Phi + row * m;
+  float s = 0.f;
+  for (int j = lane; j < m; j += kWave) {
+    float v = dp[j] * ph[j];
+    dp[j] = v;
+    s += v;
+  }
+  float dn = -wave_sum(s);
+  float* xt = Xt + row * r;
+  for (int t = lane; t < r; t += kWave) xt[t] *= dn;
+}
+
+// ------------------------------ host helpers -------------------------------
+inline int grid_for(long long total, int block = 256) {
+  long long g = (total + block - 1) / block;
+  if (g > 65535LL * 16) g = 65535LL * 16;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+Gemm gemm_base(const float* A, const float* B, float* C, int M, int N, int K) {
+  Gemm g{};
+  g.A = A;
+  g.B = B;
+  g.C = C;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.nb0 = g.nb1 = g.nb2 = 1;
+  g.alpha = 1.f;
+  g.beta = 0.f;
+  return g;
+}
+
+dark_status run_gemm(const Gemm& g, hipStream_t st) {
+  long long tiles = (long long)((g.M + GT - 1) / GT) * ((g.N + GT - 1) / GT);
+  long long blocks = tiles * g.nb0 * g.nb1 * g.nb2;
+  if (blocks <= 0) return DARK_OK;
+  if (blocks > 0x7fffffffLL) return DARK_EUNSUPPORTED;
+  DARK_LAUNCH(KID_GEMM, st, k_gemm, dim3((unsigned)blocks), dim3(256), 0, g);
+  return DARK_OK;
+}
+
+// Convert (or alias) an io tensor to fp32 rows with leading dimension ld.
+dark_status to_f32(const Problem& pb, const void* src, float* dst, long long rows, int cols, int ld, int ones) {
+  if (pb.p.io_dtype == DARK_BF16)
+    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<__hip_bfloat16>, dim3(grid_for(rows * ld)), dim3(256), 0,
+                (const __hip_bfloat16*)src, dst, rows, cols, ld, ones);
+  else
+    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<float>, dim3(grid_for(rows * ld)), dim3(256), 0, (const float*)src, dst,
+                rows, cols, ld, ones);
+  return DARK_OK;
+}
+
+struct FeatBufs {
+  float* Xf;      // [rows, d] fp32 copy of the input (or the input itself)
+  float* Xt;      // [rows, r]  x~ = sqrt(scale) M x
+  float* Phi;     // [rows, m]  logits, then features
+  float* rowmax;  // [rows]
+  float* headmax; // [BH]
+};
+
+// A_s[h] = sqrt(scale) * W[h] M[h]   (Appendix B: omega~_j = M^T w_j), [H, m, d].
+dark_status make_As(const Problem& pb, const float* M, const float* W, float* As) {
+  const dark_params& p = pb.p;
+  Gemm g = gemm_base(W, M, As, p.m, p.d, p.r);
+  g.sAm = p.r; g.sAk = 1; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
+  g.nb1 = p.H;
+  g.sA1 = p.w_shared ? 0 : (long long)p.m * p.r;
+  g.sB1 = (long long)p.r * p.d;
+  g.sC1 = (long long)p.m * p.d;
+  g.alpha = std::sqrt(pb.scale);
+  return run_gemm(g, pb.st);
+}
+
+// Logits and features of all rows of one input tensor (Section 4.1).
+//   Xt  = sqrt(scale) X M^T;  U = X A_s^T;  logit = U - 1/2|Xt|^2;  Phi = exp(logit - c).
+// Queries: c = row maximum.  Keys: c = maximum over the (b,h) slice.
+dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, const float* As, bool is_query) {
+  const dark_params& p = pb.p;
+  const long long rows = pb.rows();
+  const float alpha = std::sqrt(pb.scale);
+  {
+    Gemm g = gemm_base(fb.Xf, M, fb.Xt, p.L, p.r, p.d);
+    g.sAm = p.d; g.sAk = 1; g.sBk = 1; g.sBn = p.d; g.sCm = p.r; g.sCn = 1;
+    g.nb0 = p.B; g.nb1 = p.H;
+    g.sA0 = (long long)p.H * p.L * p.d; g.sA1 = (long long)p.L * p.d;
+    g.sB0 = 0; g.sB1 = (long long)p.r * p.d;
+    g.sC0 = (long long)p.H * p.L * p.r; g.sC1 = (long long)p.L * p.r;
+    g.alpha = alpha;
+    DARK_TRY(run_gemm(g, pb.st));
+  }
+  {
+    Gemm g = gemm_base(fb.Xf, As, fb.Phi, p.L, p.m, p.d);
+    g.sAm = p.d; g.sAk = 1; g.sBk = 1; g.sBn = p.d; g.sCm = p.m; g.sCn = 1;
+    g.nb0 = p.B; g.nb1 = p.H;
+    g.sA0 = (long long)p.H * p.L * p.d; g.sA1 = (long long)p.L * p.d;
+    g.sB0 = 0; g.sB1 = (long long)p.m * p.d;
+    g.sC0 = (long long)p.H * p.L * p.m; g.sC1 = (long long)p.L * p.m;
+    DARK_TRY(run_gemm(g, pb.st));
+  }
+  DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
+              fb.rowmax, rows, p.m, p.r);
+  if (!is_query)
+    DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
+  return DARK_OK;
+}
+
+dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, bool is_query) {
+  const long long rows = pb.rows();
+  DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * pb.p.m)), dim3(256), 0, fb.Phi, fb.Phi,
+              is_query ? fb.rowmax : fb.headmax, rows, pb.p.m, pb.p.L, is_query ? 0 : 1, 1.0f);
+  return DARK_OK;
+}
+
+int slice_len(const Problem&) { return 4096; }
+
+}  // namespace
+
+// ===========================================================================
+// dark_featurize
+// ===========================================================================
+dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,
+                          int is_query, void* phi, float* stab) {
+  const dark_params& p = pb.p;
+  const long long rows = pb.rows();
+  FeatBufs fb{};
+  float* As = ar.take<float>((size_t)p.H * p.m * p.d);
+  fb.Xf = p.io_dtype == DARK_BF16 ? ar.take<float>((size_t)rows * p.d) : nullptr;
+  fb.Xt = ar.take<float>((size_t)rows * p.r);
+  fb.Phi = ar.take<float>((size_t)rows * p.m);
+  fb.rowmax = ar.take<float>((size_t)rows);
+  fb.headmax = ar.take<float>((size_t)pb.BH());
+  if (ar.base == nullptr) return DARK_OK;
+  if (ar.overflow) return DARK_EWORKSPACE;
+
+  if (p.io_dtype == DARK_BF16)
+    DARK_TRY(to_f32(pb, X, fb.Xf, rows, p.d, p.d, 0));
+  else
+    fb.Xf = const_cast<float*>(static_cast<const float*>(X));
+  DARK_TRY(make_As(pb, M, W, As));
+  DARK_TRY(features(pb, fb, M, As, is_query != 0));
+  const float mult = 1.0f / std::sqrt((float)p.m);
+  const float* cvec = is_query ? fb.rowmax : fb.headmax;
+  if (p.io_dtype == DARK_BF16)
+    DARK_LAUNCH(KID_EXP, pb.st, k_exp<__hip_bfloat16>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi,
+                (__hip_bfloat16*)phi, cvec, rows, p.m, p.L, is_query ? 0 : 1, mult);
+  else
+    DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi, (float*)phi, cvec,
+                rows, p.m, p.L, is_query ? 0 : 1, mult);
+  if (stab != nullptr) {
+    long long n = is_query ? rows : pb.BH();
+    // plain copy through the sum kernel (P = 1)
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(n)), dim3(256), 0, cvec, stab, 1LL, 1, n, n, n);
+  }
+  return DARK_OK;
+}
+
+// ===========================================================================
+// forward attention (bidirectional and causal) and backward, fp32
+// ===========================================================================
+namespace {
+
+struct AttnBufs {
+  float* As;
+  FeatBufs q, k;
+  float* Vx;      // [rows, dv+1] = [V | 1]
+  float* part;    // bidirectional: [BH, P, m, dv+1] per-slice states
+  float* SZ;      // bidirectional: [BH, m, dv+1];  causal: [BH, nchunk, m, dv+1] exclusive prefix states
+  float* ND;      // [rows, dv+1] numerators and denominator
+  float* Pm;      // causal: [BH, nchunk, C, C] masked score tiles
+  int P, nchunk;
+};
+
+void plan_attn(const Problem& pb, Arena& ar, bool causal, bool keep_xt, AttnBufs& b) {
+  const dark_params& p = pb.p;
+  const long long rows = pb.rows();
+  const int dv1 = p.dv + 1;
+  const bool conv = p.io_dtype == DARK_BF16;
+  b.As = ar.take<float>((size_t)p.H * p.m * p.d);
+  b.q.Xf = conv ? ar.take<float>((size_t)rows * p.d) : nullptr;
+  b.k.Xf = conv ? ar.take<float>((size_t)rows * p.d) : nullptr;
+  b.q.Xt = ar.take<float>((size_t)rows * p.r);
+  b.k.Xt = keep_xt ? ar.take<float>((size_t)rows * p.r) : b.q.Xt;
+  b.q.Phi = ar.take<float>((size_t)rows * p.m);
+  b.k.Phi = ar.take<float>((size_t)rows * p.m);
+  b.q.rowmax = ar.take<float>((size_t)rows);
+  b.k.rowmax = ar.take<float>((size_t)rows);
+  b.q.headmax = b.k.headmax = ar.take<float>((size_t)pb.BH());
+  b.Vx = ar.take<float>((size_t)rows * dv1);
+  b.ND = ar.take<float>((size_t)rows * dv1);
+  b.P = (p.L + slice_len(pb) - 1) / slice_len(pb);
+  b.nchunk = (p.L + pb.chunk - 1) / pb.chunk;
+  if (causal) {
+    b.part = nullptr;
+    b.SZ = ar.take<float>((size_t)pb.BH() * b.nchunk * p.m * dv1);
+    b.Pm = ar.take<float>((size_t)pb.BH() * b.nchunk * pb.chunk * pb.chunk);
+  } else {
+    b.part = ar.take<float>((size_t)pb.BH() * b.P * p.m * dv1);
+    b.SZ = ar.take<float>((size_t)pb.BH() * p.m * dv1);
+    b.Pm = nullptr;
+  }
+}
+
+// Batch strides of a [B,H,L,cols] tensor split along L into pieces of `piece` rows.
+inline void bhl(long long& s0, long long& s1, long long& s2, const dark_params& p, long long cols, int piece) {
+  s0 = (long long)p.H * p.L * cols;
+  s1 = (long long)p.L * cols;
+  s2 = (long long)piece * cols;
+}
+
+// States: per piece (slice or chunk) of the sequence, Phi_piece^T X_piece  ->  dst[bh][piece][mm][nn].
+dark_status piece_states(const Problem& pb, const float* Phi, int mm, const float* X, int nn, int ldx, float* dst,
+                         int piece, int npiece, float beta) {
+  const dark_params& p = pb.p;
+  Gemm g = gemm_base(Phi, X, dst, mm, nn, piece);
+  g.sAm = 1; g.sAk = mm; g.sBk = ldx; g.sBn = 1; g.sCm = nn; g.sCn = 1;
+  g.nb0 = p.B; g.nb1 = p.H; g.nb2 = npiece;
+  bhl(g.sA0, g.sA1, g.sA2, p, mm, piece);
+  bhl(g.sB0, g.sB1, g.sB2, p, ldx, piece);
+  g.sC2 = (long long)mm * nn;
+  g.sC1 = g.sC2 * npiece;
+  g.sC0 = g.sC1 * p.H;
+  g.klim = p.L; g.kstep = piece;
+  g.beta = beta;
+  return run_gemm(g, pb.st);
+}
+
+// Rows times a per-(b,h[,chunk]) matrix:  dst[rows_piece][nn] (+)= X_piece[rows][kk] * St(^T).
+// st_t == false: St is [kk][nn] (row-major, leading dimension ld_st);  true: St is [nn][kk].
+// batch_shared: St is indexed by the head only ([H, ...], e.g. A_s) instead of by (b, h).
+dark_status rows_times_state(const Problem& pb, const float* X, int kk, int ldx, const float* St, int ld_st, bool st_t,
+                             bool per_chunk, long long st_elems, float* dst, int nn, int ldd, int piece, int npiece,
+                             float alpha, float beta, bool batch_shared = false) {
+  const dark_params& p = pb.p;
+  Gemm g = gemm_base(X, St, dst, piece, nn, kk);
+  g.sAm = ldx; g.sAk = 1;
+  if (st_t) { g.sBk = 1; g.sBn = ld_st; } else { g.sBk = ld_st; g.sBn = 1; }
+  g.sCm = ldd; g.sCn = 1;
+  g.nb0 = p.B; g.nb1 = p.H; g.nb2 = npiece;
+  bhl(g.sA0, g.sA1, g.sA2, p, ldx, piece);
+  bhl(g.sC0, g.sC1, g.sC2, p, ldd, piece);
+  g.sB2 = per_chunk ? st_elems : 0;
+  g.sB1 = per_chunk ? st_elems * npiece : st_elems;
+  g.sB0 = batch_shared ? 0 : g.sB1 * p.H;
+  g.mlim = p.L; g.mstep = piece;
+  g.alpha = alpha; g.beta = beta;
+  return run_gemm(g, pb.st);
+}
+
+// Score-like tiles per chunk:  T[bh][c][i][l] = sum_k X[cC+i][k] Y[cC+l][k], lower-triangular.
+dark_status chunk_tiles(const Problem& pb, const float* X, int ldx, const float* Y, int ldy, int kk, float* T) {
+  const dark_params& p = pb.p;
+  const int C = pb.chunk;
+  const int nchunk = (p.L + C - 1) / C;
+  Gemm g = gemm_base(X, Y, T, C, C, kk);
+  g.sAm = ldx; g.sAk = 1; g.sBk = 1; g.sBn = ldy; g.sCm = C; g.sCn = 1;
+  g.nb0 = p.B; g.nb1 = p.H; g.nb2 = nchunk;
+  bhl(g.sA0, g.sA1, g.sA2, p, ldx, C);
+  bhl(g.sB0, g.sB1, g.sB2, p, ldy, C);
+  g.sC2 = (long long)C * C; g.sC1 = g.sC2 * nchunk; g.sC0 = g.sC1 * p.H;
+  g.mlim = p.L; g.mstep = C; g.nlim = p.L; g.nstep = C;
+  g.mask = 1;
+  return run_gemm(g, pb.st);
+}
+
+// dst_chunk[rows][nn] += T_chunk(^T) [rows][C] * X_chunk[C][nn].
+dark_status tile_times_rows(const Problem& pb, const float* T, bool transpose, const float* X, int ldx, float* dst,
+                            int nn, int ldd) {
+  const dark_params& p = pb.p;
+  const int C = pb.chunk;
+  const int nchunk = (p.L + C - 1) / C;
+  Gemm g = gemm_base(T, X, dst, C, nn, C);
+  if (transpose) { g.sAm = 1; g.sAk = C; } else { g.sAm = C; g.sAk = 1; }
+  g.sBk = ldx; g.sBn = 1; g.sCm = ldd; g.sCn = 1;
+  g.nb0 = p.B; g.nb1 = p.H; g.nb2 = nchunk;
+  g.sA2 = (long long)C * C; g.sA1 = g.sA2 * nchunk; g.sA0 = g.sA1 * p.H;
+  bhl(g.sB0, g.sB1, g.sB2, p, ldx, C);
+  bhl(g.sC0, g.sC1, g.sC2, p, ldd, C);
+  g.mlim = p.L; g.mstep = C; g.klim = p.L; g.kstep = C;
+  g.beta = 1.f;
+  return run_gemm(g, pb.st);
+}
+
+// Everything the forward pass computes up to ND = [numerator | denominator].
+dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void* Q, const void* K, const void* V,
+                         const float* M, const float* W) {
+  const dark_params& p = pb.p;
+  const long long rows = pb.rows();
+  const int dv1 = p.dv + 1;
+  if (p.io_dtype == DARK_BF16) {
+    DARK_TRY(to_f32(pb, Q, b.q.Xf, rows, p.d, p.d, 0));
+    DARK_TRY(to_f32(pb, K, b.k.Xf, rows, p.d, p.d, 0));
+  } else {
+    b.q.Xf = const_cast<float*>(static_cast<const float*>(Q));
+    b.k.Xf = const_cast<float*>(static_cast<const float*>(K));
+  }
+  DARK_TRY(to_f32(pb, V, b.Vx, rows, p.dv, dv1, 1));
+  DARK_TRY(make_As(pb, M, W, b.As));
+  DARK_TRY(features(pb, b.q, M, b.As, true));
+  DARK_TRY(exp_inplace(pb, b.q, true));
+  DARK_TRY(features(pb, b.k, M, b.As, false));
+  DARK_TRY(exp_inplace(pb, b.k, false));
+  const long long st_elems = (long long)p.m * dv1;
+  if (!causal) {
+    // [S|z] = Phi_K^T [V|1]: per-slice partial states, then a fixed-order sum (Section 2: K'^T V first).
+    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, dv1, b.part, slice_len(pb), b.P, 0.f));
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.part, b.SZ,
+                pb.BH(), b.P, st_elems, st_elems * b.P, st_elems);
+    // [N|D] = Phi_Q [S|z]   (then left-multiplying by Q')
+    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, dv1, false, false, st_elems, b.ND, dv1, dv1, p.L, 1, 1.f,
+                              0.f));
+  } else {
+    const int C = pb.chunk;
+    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, dv1, b.SZ, C, b.nchunk, 0.f));
+    DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.SZ, pb.BH(), b.nchunk,
+                st_elems, 0);
+    // inter-chunk: Phi_Q,c [S|z]_{<c};  intra-chunk: tril(Phi_Q,c Phi_K,c^T) [V_c|1]
+    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, dv1, false, true, st_elems, b.ND, dv1, dv1, C, b.nchunk,
+                              1.f, 0.f));
+    DARK_TRY(chunk_tiles(pb, b.q.Phi, p.m, b.k.Phi, p.m, p.m, b.Pm));
+    DARK_TRY(tile_times_rows(pb, b.Pm, false, b.Vx, dv1, b.ND, dv1, dv1));
+  }
+  return DARK_OK;
+}
+
+}  // namespace
+
+dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K, const void* V,
+                         const float* M, const float* W, void* out) {
+  AttnBufs b{};
+  plan_attn(pb, ar, causal, false, b);
+  if (ar.base == nullptr) return DARK_OK;
+  if (ar.overflow) return DARK_EWORKSPACE;
+  DARK_TRY(forward_core(pb, b, causal, Q, K, V, M, W));
+  const long long rows = pb.rows();
+  if (pb.p.out_dtype == DARK_BF16)
+    DARK_LAUNCH(KID_FINISH, pb.st, k_finish<__hip_bfloat16>, dim3(grid_for(rows * pb.p.dv)), dim3(256), 0, b.ND,
+                (__hip_bfloat16*)out, rows, pb.p.dv);
+  else
+    DARK_LAUNCH(KID_FINISH, pb.st, k_finish<float>, dim3(grid_for(rows * pb.p.dv)), dim3(256), 0, b.ND, (float*)out,
+                rows, pb.p.dv);
+  return DARK_OK;
+}
+
+// Backward.  With G = dOut, N_i / D_i the numerator / denominator of out_i and the
+// (prefix) states S_i, z_i:
+//   dN_i = G_i / D_i,   dD_i = -(G_i . out_i) / D_i
+//   R_l  = sum_{i >= l} Phi_Q,i [dN_i | dD_i]^T            (all i if bidirectional)
+//   dV_l = R_l[:, :dv]^T Phi_K,l
+//   dPhi_Q,i = [S_i | z_i] [dN_i | dD_i]^T,   dPhi_K,l = R_l [v_l | 1]^T
+//   dlogit = dPhi * Phi,  dn = -sum_j dlogit_j,  dXt = dn Xt
+//   dX = dlogit A_s + sqrt(scale) dXt M
+//   dM_h = sum_b sqrt(scale) ( W^T (dlogit_Q^T Q + dlogit_K^T K) + dXt_Q^T Q + dXt_K^T K )
+// Stabilising shifts cancel between dPhi and Phi, so the stabilised features are used
+// throughout.  Causal: states are exclusive prefix (S) / suffix (R) sums over chunks plus
+// masked within-chunk tiles  P = tril(Phi_Q Phi_K^T),  E = tril([dN|dD] [V|1]^T).
+dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K, const void* V,
+                         const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
+                         float* dM) {
+  const dark_params& p = pb.p;
+  const long long rows = pb.rows();
+  const int dv1 = p.dv + 1;
+  const int C = pb.chunk;
+  AttnBufs b{};
+  plan_attn(pb, ar, causal, true, b);
+  const long long st_elems = (long long)p.m * dv1;
+  float* Gf = p.io_dtype == DARK_BF16 ? ar.take<float>((size_t)rows * p.dv) : nullptr;
+  float* dND = ar.take<float>((size_t)rows * dv1);
+  float* dPq = ar.take<float>((size_t)rows * p.m);
+  float* dPk = ar.take<float>((size_t)rows * p.m);
+  float* R = ar.take<float>((size_t)pb.BH() * (causal ? b.nchunk : 1) * st_elems);
+  float* Rpart = causal ? nullptr : ar.take<float>((size_t)pb.BH() * b.P * st_elems);
+  float* Em = causal ? ar.take<float>((size_t)pb.BH() * b.nchunk * C * C) : nullptr;
+  float* Tpart = ar.take<float>((size_t)pb.BH() * b.P * p.m * p.d);
+  float* T = ar.take<float>((size_t)pb.BH() * p.m * p.d);
+  float* T2part = ar.take<float>((size_t)pb.BH() * b.P * p.r * p.d);
+  float* T2 = ar.take<float>((size_t)pb.BH() * p.r * p.d);
+  if (ar.base == nullptr) return DARK_OK;
+  if (ar.overflow) return DARK_EWORKSPACE;
+
+  DARK_TRY(forward_core(pb, b, causal, Q, K, V, M, W));
+  if (p.io_dtype == DARK_BF16)
+    DARK_TRY(to_f32(pb, dOut, Gf, rows, p.dv, p.dv, 0));
+  else
+    Gf = const_cast<float*>(static_cast<const float*>(dOut));
+  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND, Gf, dND, rows, p.dv);
+  float* dVo = dV;
+
+  if (!causal) {
+    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, dv1, Rpart, slice_len(pb), b.P, 0.f));
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, Rpart, R,
+                pb.BH(), b.P, st_elems, st_elems * b.P, st_elems);
+    DARK_TRY(rows_times_state(pb, dND, dv1, dv1, b.SZ, dv1, true, false, st_elems, dPq, p.m, p.m, p.L, 1, 1.f, 0.f));
+    DARK_TRY(rows_times_state(pb, b.Vx, dv1, dv1, R, dv1, true, false, st_elems, dPk, p.m, p.m, p.L, 1, 1.f, 0.f));
+    if (dV) DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, dv1, false, false, st_elems, dVo, p.dv, p.dv, p.L, 1,
+                                      1.f, 0.f));
+  } else {
+    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, dv1, R, C, b.nchunk, 0.f));
+    DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, R, pb.BH(), b.nchunk,
+                st_elems, 1);
+    DARK_TRY(chunk_tiles(pb, dND, dv1, b.Vx, dv1, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
+    // b.Pm = tril(Phi_Q Phi_K^T) is left over from forward_core.
+    DARK_TRY(rows_times_state(pb, dND, dv1, dv1, b.SZ, dv1, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,
+                              0.f));
+    DARK_TRY(tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m));
+    DARK_TRY(rows_times_state(pb, b.Vx, dv1, dv1, R, dv1, true, true, st_elems, dPk, p.m, p.m, C, b.nchunk, 1.f, 0.f));
+    DARK_TRY(tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m));
+    if (dV) {
+      DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, dv1, false, true, st_elems, dVo, p.dv, p.dv, C, b.nchunk,
+                                1.f, 0.f));
+      DARK_TRY(tile_times_rows(pb, b.Pm, true, dND, dv1, dVo, p.dv, p.dv));
+    }
+  }
+  // dlogit (in dPq / dPk), dXt (in Xt buffers)
+  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dlogit, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, dPq, b.q.Phi, b.q.Xt, rows,
+              p.m, p.r);
+  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dlogit, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, dPk, b.k.Phi, b.k.Xt, rows,
+              p.m, p.r);
+  const float alpha = std::sqrt(pb.scale);
+  const long long as_elems = (long long)p.m * p.d, m_elems = (long long)p.r * p.d;
+  for (int side = 0; side < 2; ++side) {
+    float* dX = side == 0 ? dQ : dK;
+    if (!dX) continue;
+    float* dl = side == 0 ? dPq : dPk;
+    float* dxt = side == 0 ? b.q.Xt : b.k.Xt;
+    DARK_TRY(rows_times_state(pb, dl, p.m, p.m, b.As, p.d, false, false, as_elems, dX, p.d, p.d, p.L, 1, 1.f, 0.f,
+                              true));
+    // M is [H, r, d] shared over the batch: per-head stride only.
+    Gemm g = gemm_base(dxt, M, dX, p.L, p.d, p.r);
+    g.sAm = p.r; g.sAk = 1; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
+    g.nb0 = p.B; g.nb1 = p.H;
+    g.sA0 = (long long)p.H * p.L * p.r; g.sA1 = (long long)p.L * p.r;
+    g.sB0 = 0; g.sB1 = m_elems;
+    g.sC0 = (long long)p.H * p.L * p.d; g.sC1 = (long long)p.L * p.d;
+    g.alpha = alpha; g.beta = 1.f;
+    DARK_TRY(run_gemm(g, pb.st));
+  }
+  if (dM) {
+    const int SL = slice_len(pb);
+    DARK_TRY(piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, SL, b.P, 0.f));
+    DARK_TRY(piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, SL, b.P, 1.f));
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * as_elems)), dim3(256), 0, Tpart, T,
+                pb.BH(), b.P, as_elems, as_elems * b.P, as_elems);
+    DARK_TRY(piece_states(pb, b.q.Xt, p.r, b.q.Xf, p.d, p.d, T2part, SL, b.P, 0.f));
+    DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, SL, b.P, 1.f));
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * m_elems)), dim3(256), 0, T2part, T2,
+                pb.BH(), b.P, m_elems, m_elems * b.P, m_elems);
+    // T2_bh = alpha * W_h^T T_bh + alpha * T2_bh
+    Gemm g = gemm_base(W, T, T2, p.r, p.d, p.m);
+    g.sAm = 1; g.sAk = p.r; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
+    g.nb0 = p.B; g.nb1 = p.H;
+    g.sA0 = 0; g.sA1 = p.w_shared ? 0 : (long long)p.m * p.r;
+    g.sB0 = as_elems * p.H; g.sB1 = as_elems;
+    g.sC0 = m_elems * p.H; g.sC1 = m_elems;
+    g.alpha = alpha; g.beta = alpha;
+    DARK_TRY(run_gemm(g, pb.st));
+    // dM_h = sum_b T2_bh, b ascending
+    DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for((long long)p.H * m_elems)), dim3(256), 0, T2, dM,
+                (long long)p.H, p.B, m_elems, m_elems, m_elems * p.H);
+  }
+  return DARK_OK;
+}
+
+}  // namespace dark

@@ -1,0 +1,106 @@
+"""Helpers shared by the GPU parity tests: error metrics and oracle drivers."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import dark_oracle as O
+
+# Tolerances of the benchmark contract: fp32 inputs 1e-4, bf16 inputs (fp32 accumulation) 2e-2.
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def errors(got, want):
+    """(normalised max error, floored element-wise relative error).
+
+    normalised: max|g-o| / max|o|.
+    element-wise: max |g-o| / (|o| + 0.02 max|o|): relative error of every element, with a
+    floor so that elements that are tiny only because large terms cancelled are judged against
+    the scale of the tensor rather than against their own size."""
+    g = np.asarray(got, dtype=np.float64)
+    o = np.asarray(want, dtype=np.float64)
+    assert g.shape == o.shape, (g.shape, o.shape)
+    if o.size == 0:
+        return 0.0, 0.0
+    assert np.all(np.isfinite(g)), "non-finite values in GPU result"
+    scale = np.abs(o).max()
+    diff = np.abs(g - o)
+    return float(diff.max() / scale), float((diff / (np.abs(o) + 0.02 * scale)).max())
+
+
+def assert_close(got, want, tol, what=""):
+    e1, e2 = errors(got, want)
+    assert e1 <= tol and e2 <= tol, f"{what}: normalised max err {e1:.3e}, element-wise {e2:.3e} > {tol:g}"
+    return e1, e2
+
+
+def head(inp, b, h):
+    W = inp["W"]
+    Wh = W if W.ndim == 2 else W[h]
+    return inp["Q"][b, h], inp["K"][b, h], inp["V"][b, h], inp["M"][h], Wh
+
+
+def oracle_attn(inp, causal, scale=None):
+    """Full oracle output [B,H,L,dv] (small problems)."""
+    B, H, L, _ = inp["Q"].shape
+    out = np.zeros(inp["V"].shape)
+    for b in range(B):
+        for h in range(H):
+            Q, K, V, M, W = head(inp, b, h)
+            out[b, h] = O.attn_causal(Q, K, V, M, W, scale) if causal else O.attn_bidir(Q, K, V, M, W, scale)
+    return out
+
+
+def oracle_bwd(inp, causal, scale=None):
+    B, H, L, d = inp["Q"].shape
+    dQ = np.zeros(inp["Q"].shape)
+    dK = np.zeros(inp["K"].shape)
+    dV = np.zeros(inp["V"].shape)
+    dM = np.zeros(inp["M"].shape)
+    for b in range(B):
+        for h in range(H):
+            Q, K, V, M, W = head(inp, b, h)
+            a, bb, c, e = O.attn_bwd_brute(Q, K, V, M, W, inp["dOut"][b, h], causal, scale)
+            dQ[b, h], dK[b, h], dV[b, h] = a, bb, c
+            dM[h] += e
+    return dQ, dK, dV, dM
+
+
+def random_problem(seed, B, H, L, d, r, m, dv, bf16=False, w_shared=False, amp=1.0, backward=False):
+    """Small free-form problem (not one of the benchmark configurations)."""
+    from paper_2603_04127_amd import synth
+    g = np.random.default_rng(seed)
+    sp = np.logspace(0.5, -1.0, d) * amp
+    T = np.sqrt(sp)[:, None] * np.linalg.qr(g.standard_normal((d, d)))[0].T
+    inp = {
+        "Q": (g.standard_normal((B, H, L, d)) @ T).astype(np.float32),
+        "K": (g.standard_normal((B, H, L, d)) @ T).astype(np.float32),
+        "V": g.standard_normal((B, H, L, dv)).astype(np.float32),
+        "M": (g.standard_normal((H, r, d)) / np.sqrt(d)).astype(np.float32),
+        "W": g.standard_normal((m, r) if w_shared else (H, m, r)).astype(np.float32),
+    }
+    names = ["Q", "K", "V"]
+    if backward:
+        inp["dOut"] = g.standard_normal((B, H, L, dv)).astype(np.float32)
+        names.append("dOut")
+    if bf16:
+        for n in names:
+            bits = synth.to_bf16_bits(inp[n])
+            inp[n + "_bits"] = bits
+            inp[n] = synth.bf16_bits_to_f32(bits)
+    return inp
+
+
+def to_device(inp, bf16):
+    """torch device tensors of a problem: bf16 tensors are built from the stored bit patterns."""
+    import torch
+    dev = {}
+    for n in ("Q", "K", "V", "dOut"):
+        if n not in inp:
+            continue
+        if bf16:
+            dev[n] = torch.from_numpy(inp[n + "_bits"].view(np.int16)).view(torch.bfloat16).cuda()
+        else:
+            dev[n] = torch.from_numpy(inp[n]).cuda()
+    dev["M"] = torch.from_numpy(inp["M"]).cuda()
+    dev["W"] = torch.from_numpy(inp["W"]).cuda()
+    return dev

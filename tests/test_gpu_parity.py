@@ -1,0 +1,175 @@
+"""GPU parity: the HIP library (through the C-ABI binding) against the fp64 oracle,
+element by element on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import paper_2603_04127_amd as dk
+from paper_2603_04127_amd import synth
+from oracle import dark_oracle as O
+from tests import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _np(t):
+    return t.detach().float().cpu().numpy()
+
+
+PATHS = [dk.PATH_F32, dk.PATH_AUTO]
+
+
+# ---------------------------------------------------------------------------
+# dark_featurize
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("is_query", [True, False])
+def test_featurize(bf16, is_query):
+    inp = U.random_problem(1, B=2, H=3, L=150, d=24, r=16, m=80, dv=8, bf16=bf16, amp=3.0)
+    dev = U.to_device(inp, bf16)
+    phi, stab = dk.dark_featurize(dev["Q"], dev["M"], dev["W"], is_query)
+    torch.cuda.synchronize()
+    phi, stab = _np(phi), _np(stab)
+    tol = U.TOL["bf16" if bf16 else "f32"]
+    for b in range(2):
+        for h in range(3):
+            want, c = O.featurize(inp["Q"][b, h], inp["M"][h], inp["W"][h], is_query)
+            got_c = stab[b, h]
+            assert np.abs(got_c - c).max() <= 1e-4 * max(1.0, np.abs(c).max())
+            U.assert_close(phi[b, h], want, tol, f"phi[{b},{h}]")
+            if not bf16:
+                # stabiliser-independent comparison in the log domain
+                lg = np.log(np.maximum(phi[b, h].astype(np.float64), 1e-300)) + (got_c[:, None] if is_query else got_c)
+                ref = O.logits(inp["Q"][b, h], inp["M"][h], inp["W"][h]) - 0.5 * np.log(80)
+                big = want > 1e-30            # fp32 features below ~1e-38 flush to zero
+                assert np.abs(lg - ref)[big].max() < 2e-4
+
+
+# ---------------------------------------------------------------------------
+# forward, small shapes spanning several tiles with ragged tails
+# ---------------------------------------------------------------------------
+SMALL = [
+    # B, H, L,   d,  r,  m,  dv
+    (2, 3, 300, 24, 16, 80, 40),
+    (1, 2, 257, 64, 64, 64, 64),
+    (1, 1, 130, 7, 5, 33, 3),
+]
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("shape", SMALL)
+@pytest.mark.parametrize("causal", [False, True])
+def test_forward_small(shape, bf16, causal, path):
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(2, B, H, L, d, r, m, dv, bf16=bf16, amp=2.0)
+    dev = U.to_device(inp, bf16)
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    out = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=path)
+    torch.cuda.synchronize()
+    want = U.oracle_attn(inp, causal)
+    U.assert_close(_np(out), want, U.TOL["bf16" if bf16 else "f32"], f"out {shape} causal={causal}")
+
+
+@pytest.mark.parametrize("chunk", [16, 100, 128, 512])
+def test_causal_chunk_is_only_a_schedule(chunk):
+    inp = U.random_problem(3, 1, 2, 300, 16, 16, 48, 20)
+    dev = U.to_device(inp, False)
+    out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], chunk=chunk)
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, True), 1e-4, f"chunk={chunk}")
+
+
+def test_config1_full():
+    cfg = synth.CONFIGS[1]
+    inp = synth.make_inputs(cfg)
+    dev = U.to_device(inp, False)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    outc = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, False), 1e-4, "config 1")
+    U.assert_close(_np(outc), U.oracle_attn(inp, True), 1e-4, "config 1 causal")
+    # causal and bidirectional agree at the last position
+    U.assert_close(_np(outc)[..., -1, :], _np(out)[..., -1, :], 1e-4, "last row")
+
+
+def test_shared_w_and_scale():
+    inp = U.random_problem(4, 2, 2, 96, 16, 8, 40, 12, w_shared=True)
+    dev = U.to_device(inp, False)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], scale=0.2)
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, False, scale=0.2), 1e-4, "w_shared, scale")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_degenerate_sizes(causal):
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    # L = 1, m = 1, d = 1: out == V
+    inp = U.random_problem(5, 1, 1, 1, 1, 1, 1, 4)
+    dev = U.to_device(inp, False)
+    out = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(_np(out), inp["V"], rtol=1e-6)
+    # empty sequence
+    e = {k: v[:, :, :0].contiguous() for k, v in dev.items() if k in ("Q", "K", "V")}
+    out = fn(e["Q"], e["K"], e["V"], dev["M"], dev["W"])
+    assert out.shape == (1, 1, 0, 4)
+    # chunk longer than the sequence
+    inp = U.random_problem(6, 1, 1, 40, 8, 8, 16, 4)
+    dev = U.to_device(inp, False)
+    if causal:
+        out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], chunk=1024)
+        torch.cuda.synchronize()
+        U.assert_close(_np(out), U.oracle_attn(inp, True), 1e-4, "chunk > L")
+
+
+def test_large_logits_are_stabilised():
+    # logits of several hundred: exp() would overflow fp32 without the stabilising shifts
+    inp = U.random_problem(7, 1, 1, 200, 16, 16, 32, 8, amp=400.0)
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
+    assert lg.max() > 100
+    dev = U.to_device(inp, False)
+    for causal in (False, True):
+        fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+        out = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+        torch.cuda.synchronize()
+        U.assert_close(_np(out), U.oracle_attn(inp, causal), 2e-3, "large logits")
+
+
+def test_bitwise_deterministic():
+    inp = U.random_problem(8, 2, 2, 700, 32, 32, 128, 32, bf16=True)
+    dev = U.to_device(inp, True)
+    for fn in (dk.dark_attn_fwd, dk.dark_attn_causal_fwd):
+        a = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"]).clone()
+        b = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+        torch.cuda.synchronize()
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------
+# backward
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shape", [(2, 2, 200, 24, 16, 48, 20), (1, 1, 130, 16, 16, 64, 16)])
+def test_backward_small(shape, causal, bf16):
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(9, B, H, L, d, r, m, dv, bf16=bf16, backward=True)
+    dev = U.to_device(inp, bf16)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], causal, chunk=64)
+    torch.cuda.synchronize()
+    want = dict(zip(("dQ", "dK", "dV", "dM"), U.oracle_bwd(inp, causal)))
+    # gradients are fp32 on both dtypes (inputs only are rounded), so the fp32 path meets the fp32 bar
+    tol = 2e-4
+    for k in ("dQ", "dK", "dV", "dM"):
+        U.assert_close(_np(g[k]), want[k], tol, f"{k} causal={causal}")
+
+
+def test_backward_optional_outputs():
+    inp = U.random_problem(10, 1, 2, 64, 8, 8, 16, 8, backward=True)
+    dev = U.to_device(inp, False)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, need=("dM",))
+    torch.cuda.synchronize()
+    assert g["dQ"] is None and g["dV"] is None
+    U.assert_close(_np(g["dM"]), U.oracle_bwd(inp, True)[3], 2e-4, "dM only")
