@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the DARK attention hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+a forward call of the configuration's entry point (dark_attn_fwd for the
+bidirectional configurations, dark_attn_causal_fwd for the causal ones; the
+finetuning configuration adds dark_attn_bwd).  Inputs are resident in HBM before
+the timed region; several distinct input copies are rotated so that the 256 MB
+memory-side cache cannot serve a step's reads from the previous step.
+
+Prints one JSON line (see the repository's design notes for the field meanings).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu": (157.3, "TFLOP/s")}
+
+
+def algorithmic_work(cfg):
+    """Per-step algorithmic flops and HBM bytes of the forward pass, and per kernel.
+
+    Per token-head: projections of q and k through A = W M (2dm each), the norm terms
+    (2dr each; the query-side one cancels in the ratio but is part of the definition),
+    phi(K)^T [V|1] (2m(dv+1)) and phi(Q)[S|z] (2m(dv+1)).  Bytes: read Q, K, V, write out.
+    Causal adds the within-chunk triangle: m(C+1) for the scores and (dv+1)(C+1) for their
+    product with [V|1]."""
+    th = cfg.B * cfg.H * cfg.L
+    s_in = 2 if cfg.dtype == "bf16" else 4
+    d, r, m, dv = cfg.d, cfg.r, cfg.m, cfg.dv
+    f_tok = 4 * d * m + 4 * d * r + 4 * m * (dv + 1)
+    if cfg.causal:
+        f_tok += m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1)
+    b_tok = (2 * d + dv) * s_in + dv * s_in
+    per_kernel = {
+        # kernel name -> (bound, algorithmic units per launch) ; bytes for hbm, flops otherwise
+        "fused_kv_reduce": ("hbm", th * (d + dv) * s_in),
+        "fused_readout": ("hbm", th * (d + dv) * s_in),
+        "fused_causal_state": ("hbm", th * (d + dv) * s_in),
+        "fused_causal_out": ("mfma", th * (2 * d * m + 2 * m * (dv + 1) + m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1))),
+        "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
+    }
+    return th * f_tok, th * b_tok, per_kernel
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2, the headline)")
+    ap.add_argument("--path", choices=["auto", "f32", "fused"], default="auto")
+    ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every GPU box has one GPU); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2603_04127_amd as dk
+    from paper_2603_04127_amd import synth
+    from tests import parity_util as U
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dk.lib()  # fail loudly if the HIP library is missing
+    cfg = synth.CONFIGS[args.config]
+    path = {"auto": dk.PATH_AUTO, "f32": dk.PATH_F32, "fused": dk.PATH_FUSED}[args.path]
+    bf16 = cfg.dtype == "bf16"
+    t0 = time.time()
+    inp = synth.make_inputs(cfg)
+    dev0 = U.to_device(inp, bf16)
+    copies = []
+    for k in range(max(1, args.copies)):
+        c = dict(dev0)
+        if k:
+            for n in ("Q", "K", "V", "dOut"):
+                if n in c:
+                    # same distribution, different memory: rotate batch and sequence
+                    c[n] = torch.roll(dev0[n], shifts=(k % max(cfg.B, 1), 17 * k), dims=(0, 2)).contiguous()
+        c["out"] = torch.empty_like(c["V"])
+        copies.append(c)
+    gen_s = time.time() - t0
+
+    def step(c):
+        if cfg.causal:
+            dk.dark_attn_causal_fwd(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"], chunk=cfg.chunk, path=path)
+        else:
+            dk.dark_attn_fwd(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"], path=path)
+        if cfg.backward:
+            dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], cfg.causal, chunk=cfg.chunk)
+
+    for i in range(args.warmup):
+        step(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        step(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    ms = dt / args.steps * 1e3
+    tokens = cfg.B * cfg.L
+    flops, nbytes, per_kernel = algorithmic_work(cfg)
+
+    # Per-kernel device time: a second loop with HIP events around every launch, recorded by the
+    # library on the launch stream.
+    dk.timing_reset()
+    dk.timing_enable(True)
+    for i in range(args.steps):
+        step(copies[i % len(copies)])
+    torch.cuda.synchronize()
+    kt = dk.timing_read()
+    dk.timing_enable(False)
+    kernels = {k: {"launches": n, "avg_us": 1e3 * t / n, "us_per_step": 1e3 * t / args.steps} for k, (n, t) in kt.items()}
+    dom = max(kt.items(), key=lambda kv: kv[1][1])[0]
+    bound, units = per_kernel.get(dom, ("hbm", nbytes))
+    us_step = kernels[dom]["us_per_step"]
+    peak, unit = PEAK[bound]
+    achieved = units / (us_step * 1e-6) / (1e9 if bound == "hbm" else 1e12)
+    roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": None, "avg_kernel_us": kernels[dom]["avg_us"],
+                "launches_per_step": kernels[dom]["launches"] / args.steps}
+
+    line = {
+        "metric": "DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)",
+        "value": tokens / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "L": cfg.L, "d": cfg.d, "m": cfg.m, "dv": cfg.dv,
+                   "causal": cfg.causal, "backward": cfg.backward, "path": args.path, "input_copies": len(copies)},
+        "tflops": flops / (ms * 1e-3) / 1e12,
+        "algorithmic_gbps": nbytes / (ms * 1e-3) / 1e9,
+        "step_frac_of_binding_roofline": max(flops / 2.5e15, nbytes / 8e12) / (ms * 1e-3),
+        "roofline": roofline,
+        "kernels": kernels,
+        "input_generation_s": gen_s,
+    }
+
+    if not args.no_cpu_baseline:
+        # The oracle as it stands, on a bounded sample of the same workload: whole heads of batch 0
+        # until about --cpu-seconds of CPU time have been spent.
+        from oracle import dark_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        heads = 0
+        t2 = time.perf_counter()
+        while heads < cfg.B * cfg.H and (time.perf_counter() - t2) < args.cpu_seconds:
+            b, h = divmod(heads, cfg.H)
+            Q, K, V, M, W = U.head(inp, b, h)
+            Ls = min(cfg.L, 8192)     # causal oracle is a per-token loop: bound the sample length
+            if cfg.causal:
+                O.attn_causal(Q[:Ls], K[:Ls], V[:Ls], M, W)
+            else:
+                Ls = cfg.L
+                O.attn_bidir(Q, K, V, M, W)
+            heads += 1
+        el = time.perf_counter() - t2
+        line["cpu_baseline"] = {
+            "value": (heads * Ls / cfg.H) / el, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{heads} (b,h) slices of {Ls} positions of {cfg.name} (fp64 numpy oracle, forward only), "
+                      f"{el:.1f} s; scaled by 1/H to tokens",
+        }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -182,12 +182,16 @@ __global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, 
   }
 }
 
-// One wave per row: n = 1/2 |x~|^2, logits = U - n (in place), rowmax.
+// One wave per row: n = 1/2 |x~|^2, logits = U - n (+ bias_j) in place, rowmax.
+// bias (optional) is a per-(b,h) vector of m per-feature shifts (the key-side stabilisers,
+// which the query side adds back so that every product phi_Q,j * phi_K,j is unchanged).
 __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const float* __restrict__ Xt,
-                                                 float* __restrict__ rowmax, long long rows, int m, int r) {
+                                                 float* __restrict__ rowmax, const float* __restrict__ bias,
+                                                 long long rows, int m, int r, int L) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
+  const float* bs = bias ? bias + (row / L) * m : nullptr;
   const float* xt = Xt + row * r;
   float s = 0.f;
   for (int t = lane; t < r; t += kWave) s = fmaf(xt[t], xt[t], s);
@@ -196,6 +200,7 @@ __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const fl
   float mx = -INFINITY;
   for (int j = lane; j < m; j += kWave) {
     float v = u[j] - s;
+    if (bs) v += bs[j];
     u[j] = v;
     mx = fmaxf(mx, v);
   }
@@ -215,15 +220,36 @@ __global__ __launch_bounds__(256) void k_headmax(const float* __restrict__ rowma
   if (threadIdx.x == 0) headmax[blockIdx.x] = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
 }
 
-// Phi = exp(logit - c) * mult.  c = rowc[row] (per_head == 0) or headc[row / L].
+// Per-feature maximum over the L rows of each (b,h): colmax[bh][j] = max_l logit[bh][l][j].
+// One block per (bh, 64-column group); threads = 64 columns x 4 row phases.
+__global__ __launch_bounds__(256) void k_colmax(const float* __restrict__ logit, float* __restrict__ colmax, int L,
+                                                int m) {
+  __shared__ float sm[4][64];
+  const int groups = (m + 63) / 64;
+  const long long bh = blockIdx.x / groups;
+  const int j = (blockIdx.x % groups) * 64 + threadIdx.x % 64;
+  const int ph = threadIdx.x / 64;
+  float mx = -INFINITY;
+  if (j < m) {
+    const float* p = logit + bh * L * (long long)m + j;
+    for (int l = ph; l < L; l += 4) mx = fmaxf(mx, p[(long long)l * m]);
+  }
+  sm[ph][threadIdx.x % 64] = mx;
+  __syncthreads();
+  if (ph == 0 && j < m)
+    colmax[bh * m + j] = fmaxf(fmaxf(sm[0][threadIdx.x], sm[1][threadIdx.x]), fmaxf(sm[2][threadIdx.x], sm[3][threadIdx.x]));
+}
+
+// Phi = exp(logit - c) * mult.  mode 0: c = cvec[row];  1: c = cvec[row / L] (per head);
+// 2: c = cvec[(row / L) * m + j] (per head and feature).
 template <typename T>
 __global__ void k_exp(const float* __restrict__ logit, T* __restrict__ out, const float* __restrict__ cvec,
-                      long long rows, int m, int L, int per_head, float mult) {
+                      long long rows, int m, int L, int mode, float mult) {
   long long total = rows * m;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
     long long row = i / m;
-    float c = per_head ? cvec[row / L] : cvec[row];
+    float c = mode == 0 ? cvec[row] : (mode == 1 ? cvec[row / L] : cvec[(row / L) * m + (i % m)]);
     store_from_f32(out, i, expf(logit[i] - c) * mult);
   }
 }
@@ -368,8 +394,11 @@ struct FeatBufs {
   float* Xt;      // [rows, r]  x~ = sqrt(scale) M x
   float* Phi;     // [rows, m]  logits, then features
   float* rowmax;  // [rows]
-  float* headmax; // [BH]
+  float* headmax; // [BH]      per-head maximum (dark_featurize, keys)
+  float* colmax;  // [BH, m]   per-feature maxima of the key logits (attention paths)
 };
+
+enum StabMode { STAB_QUERY_ROW = 0, STAB_KEY_HEAD = 1, STAB_KEY_FEATURE = 2 };
 
 // A_s[h] = sqrt(scale) * W[h] M[h]   (Appendix B: omega~_j = M^T w_j), [H, m, d].
 dark_status make_As(const Problem& pb, const float* M, const float* W, float* As) {
@@ -386,8 +415,11 @@ dark_status make_As(const Problem& pb, const float* M, const float* W, float* As
 
 // Logits and features of all rows of one input tensor (Section 4.1).
 //   Xt  = sqrt(scale) X M^T;  U = X A_s^T;  logit = U - 1/2|Xt|^2;  Phi = exp(logit - c).
-// Queries: c = row maximum.  Keys: c = maximum over the (b,h) slice.
-dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, const float* As, bool is_query) {
+// Queries: c = row maximum (after adding `qbias`, if given).  Keys: c = maximum over the
+// (b,h) slice (STAB_KEY_HEAD, the dark_featurize contract) or per feature over the slice
+// (STAB_KEY_FEATURE, used inside attention where the query side adds the shifts back).
+dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, const float* As, StabMode mode,
+                     const float* qbias = nullptr) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
   const float alpha = std::sqrt(pb.scale);
@@ -411,16 +443,20 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
     DARK_TRY(run_gemm(g, pb.st));
   }
   DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
-              fb.rowmax, rows, p.m, p.r);
-  if (!is_query)
+              fb.rowmax, mode == STAB_QUERY_ROW ? qbias : nullptr, rows, p.m, p.r, p.L);
+  if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
+  if (mode == STAB_KEY_FEATURE)
+    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(256), 0, fb.Phi,
+                fb.colmax, p.L, p.m);
   return DARK_OK;
 }
 
-dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, bool is_query) {
+dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
   const long long rows = pb.rows();
-  DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * pb.p.m)), dim3(256), 0, fb.Phi, fb.Phi,
-              is_query ? fb.rowmax : fb.headmax, rows, pb.p.m, pb.p.L, is_query ? 0 : 1, 1.0f);
+  const float* c = mode == STAB_QUERY_ROW ? fb.rowmax : (mode == STAB_KEY_HEAD ? fb.headmax : fb.colmax);
+  DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * pb.p.m)), dim3(256), 0, fb.Phi, fb.Phi, c, rows,
+              pb.p.m, pb.p.L, (int)mode, 1.0f);
   return DARK_OK;
 }
 
@@ -450,7 +486,7 @@ dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const flo
   else
     fb.Xf = const_cast<float*>(static_cast<const float*>(X));
   DARK_TRY(make_As(pb, M, W, As));
-  DARK_TRY(features(pb, fb, M, As, is_query != 0));
+  DARK_TRY(features(pb, fb, M, As, is_query ? STAB_QUERY_ROW : STAB_KEY_HEAD));
   const float mult = 1.0f / std::sqrt((float)p.m);
   const float* cvec = is_query ? fb.rowmax : fb.headmax;
   if (p.io_dtype == DARK_BF16)
@@ -497,7 +533,8 @@ void plan_attn(const Problem& pb, Arena& ar, bool causal, bool keep_xt, AttnBufs
   b.k.Phi = ar.take<float>((size_t)rows * p.m);
   b.q.rowmax = ar.take<float>((size_t)rows);
   b.k.rowmax = ar.take<float>((size_t)rows);
-  b.q.headmax = b.k.headmax = ar.take<float>((size_t)pb.BH());
+  b.q.headmax = b.k.headmax = nullptr;
+  b.q.colmax = b.k.colmax = ar.take<float>((size_t)pb.BH() * p.m);
   b.Vx = ar.take<float>((size_t)rows * dv1);
   b.ND = ar.take<float>((size_t)rows * dv1);
   b.P = (p.L + slice_len(pb) - 1) / slice_len(pb);
@@ -608,10 +645,13 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
   }
   DARK_TRY(to_f32(pb, V, b.Vx, rows, p.dv, dv1, 1));
   DARK_TRY(make_As(pb, M, W, b.As));
-  DARK_TRY(features(pb, b.q, M, b.As, true));
-  DARK_TRY(exp_inplace(pb, b.q, true));
-  DARK_TRY(features(pb, b.k, M, b.As, false));
-  DARK_TRY(exp_inplace(pb, b.k, false));
+  // Keys first: phi_K,lj = exp(logit_lj - c_j), c_j the per-feature maximum over the head.  The
+  // queries add c_j back (phi_Q,ij = exp(logit_ij + c_j - rowmax_i)), so every product
+  // phi_Q,ij phi_K,lj is the unshifted one times a per-row factor that cancels in N / D.
+  DARK_TRY(features(pb, b.k, M, b.As, STAB_KEY_FEATURE));
+  DARK_TRY(exp_inplace(pb, b.k, STAB_KEY_FEATURE));
+  DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax));
+  DARK_TRY(exp_inplace(pb, b.q, STAB_QUERY_ROW));
   const long long st_elems = (long long)p.m * dv1;
   if (!causal) {
     // [S|z] = Phi_K^T [V|1]: per-slice partial states, then a fixed-order sum (Section 2: K'^T V first).
