@@ -1,15 +1,764 @@
-// Fused MFMA path (placeholder until the kernels land): reports every problem as unsupported,
-// so DARK_PATH_AUTO uses the fp32 kernels and DARK_PATH_FUSED fails loudly.
+// Fused MFMA path of the DARK attention library (gfx950): bf16 inputs, fp32 accumulation.
+//
+// Per (b,h), with alpha = sqrt(scale), A = W M (Appendix B: omega~_j = M^T w_j) and
+// everything kept in the log2 domain:
+//   A' = alpha log2(e) A           (fp16 MFMA operand; x is bf16, exactly representable in fp16)
+//   M' = alpha sqrt(log2(e)/2) M   so that n'(x) = |M' x|^2 = log2(e) * 1/2 |M x'|^2
+//   key features    phi_K,lj = exp2(x_l . A'_j - n'(x_l) - c)      (Section 4.1 feature map)
+//   query features  phi_Q,ij = exp2(x_i . A'_j + c - mu_i)
+// c is a shift shared by a block of 64 features (chosen from the data, it cancels against the
+// same shift on the query side) and mu_i a per-row shift (cancels in the ratio), so no
+// exponential can overflow.  The query-side norm term is a per-row factor and is dropped.
+//
+// Kernels (Section 2, "Efficient attention via random feature kernels": K'^T V first, then Q'):
+//   k_prep       A', M' for every head
+//   k_kv_reduce  per (b,h, L-slice, 256-feature block): [S|z] += phi_K^T [V|1], features never
+//                leave registers; MFMA 1 (projection) feeds MFMA 2 (phi^T V) through the
+//                accumulator layout, which is already the operand layout after a bf16 pack
+//   k_kv_merge   fixed-order merge of the slice states (deterministic), bf16 S^T for the readout
+//   k_readout    per (b,h, token range): out = phi_Q S / phi_Q z
+#include <cmath>
+#include <cstdlib>
+
 #include "common.h"
 
 namespace dark {
-bool fused_supported(const Problem&, int, bool) { return false; }
-dark_status fused_attn_fwd(const Problem&, Arena&, const void*, const void*, const void*, const float*,
-                           const float*, void*) {
-  return DARK_EUNSUPPORTED;
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kTau = 16.0f;  // a running shift is only raised when exceeded by 2^kTau
+constexpr int kTile = 64;      // tokens per tile in the K pass
+
+__device__ inline unsigned pack_bf16(float a, float b) {
+  bf16x2 p;
+  p[0] = (__bf16)a;
+  p[1] = (__bf16)b;
+  return *reinterpret_cast<unsigned*>(&p);
 }
+__device__ inline unsigned pack_f16_from_bf16pair(unsigned w) {
+  // w holds two bf16; both are exactly representable in fp16 unless out of its range
+  float lo = __uint_as_float(w << 16);
+  float hi = __uint_as_float(w & 0xffff0000u);
+  fp16x2 h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  return *reinterpret_cast<unsigned*>(&h);
+}
+__device__ inline u32x4 bf16x8_to_f16x8(u32x4 r) {
+  u32x4 o;
+  o[0] = pack_f16_from_bf16pair(r[0]);
+  o[1] = pack_f16_from_bf16pair(r[1]);
+  o[2] = pack_f16_from_bf16pair(r[2]);
+  o[3] = pack_f16_from_bf16pair(r[3]);
+  return o;
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// acc + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs, fp32 arithmetic (v_dot2_f32_bf16)
+__device__ inline float dot2_bf16(unsigned a, unsigned b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&a), *reinterpret_cast<bf16x2*>(&b), acc, false);
+}
+constexpr unsigned kOnesBf16x2 = 0x3f803f80u;
+__device__ inline float wave_max64(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---------------------------------------------------------------------------
+// k_prep: A'[h][j][:] = alpha log2e sum_t W[h][j][t] M[h][t][:]  (fp16),  M' = alpha sqrt(log2e/2) M.
+// One block per (h, 4 feature rows); the last blocks of each head convert M.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const float* __restrict__ W,
+                                              _Float16* __restrict__ Ah, _Float16* __restrict__ Mh, int m, int r,
+                                              int d, int w_shared, float alpha) {
+  const int h = blockIdx.y;
+  const int nA = (m + 3) / 4;
+  const float* Mp = M + (size_t)h * r * d;
+  if ((int)blockIdx.x < nA) {
+    const int j = blockIdx.x * 4 + threadIdx.x / 64;
+    if (j >= m) return;
+    const float* w = W + (w_shared ? 0 : (size_t)h * m * r) + (size_t)j * r;
+    for (int c = threadIdx.x % 64; c < d; c += 64) {
+      float s = 0.f;
+      for (int t = 0; t < r; ++t) s = fmaf(w[t], Mp[(size_t)t * d + c], s);
+      Ah[((size_t)h * m + j) * d + c] = (_Float16)(s * alpha * kLog2e);
+    }
+  } else {
+    const float f = alpha * sqrtf(0.5f * kLog2e);
+    for (int i = (blockIdx.x - nA) * 256 + threadIdx.x; i < r * d; i += 256 * (gridDim.x - nA))
+      Mh[(size_t)h * r * d + i] = (_Float16)(Mp[i] * f);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// k_kv_reduce
+// Workgroup = 4 waves = 256 features (wave w owns features [64w, 64w+64) of the block) over one
+// L-slice of one (b,h).  Per 64-token tile:
+//   stage   K tile -> LDS as fp16 [64][D+8];  V tile -> LDS transposed bf16 [DV][64+4]
+//   norms   wave w: x~ = X[16w..16w+16) M'^T by MFMA 16x16x32, n' = row sums of squares -> LDS
+//   proj    U[tok][feat] = X A'^T  (MFMA 32x32x16 f16; A' fragments stay in registers)
+//   exp     phi = exp2(U - n' - c) in the accumulator registers, packed to bf16
+//   reduce  S[feat][dv] += phi^T V (MFMA 32x32x16 bf16), z[feat] += column sums of phi
+// Triple-buffered staging, one barrier per tile.
+// ---------------------------------------------------------------------------
+template <int D, int DV, int R>
+struct KvSmem {
+  static constexpr int XS = D + 8;       // fp16 elements per X row (pad keeps 16-byte rows off one bank group)
+  static constexpr int VS = kTile + 4;   // bf16 elements per V^T row
+  static constexpr size_t x_bytes = (size_t)3 * kTile * XS * 2;
+  static constexpr size_t v_bytes = (size_t)3 * DV * VS * 2;
+  static constexpr size_t m_bytes = (size_t)R * XS * 2;
+  static constexpr size_t n_bytes = (size_t)2 * kTile * 4;
+  static constexpr size_t total = x_bytes + v_bytes + m_bytes + n_bytes;
+};
+
+template <int D, int DV, int R, int MINW>
+__global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* __restrict__ Kg,
+                                                         const unsigned short* __restrict__ Vg,
+                                                         const _Float16* __restrict__ Ah,
+                                                         const _Float16* __restrict__ Mh, float* __restrict__ Spart,
+                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
+                                                         int L, int m, int P, int slice_len, int n_work) {
+  using SM = KvSmem<D, DV, R>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  _Float16* Xs = reinterpret_cast<_Float16*>(smem);
+  unsigned short* Vt = reinterpret_cast<unsigned short*>(smem + SM::x_bytes);
+  _Float16* Ms = reinterpret_cast<_Float16*>(smem + SM::x_bytes + SM::v_bytes);
+  float* ns = reinterpret_cast<float*>(smem + SM::x_bytes + SM::v_bytes + SM::m_bytes);
+
+  // blockIdx -> (work item (bh, slice), feature block): the feature blocks of one work item are
+  // 8 apart in blockIdx so that they land on the same XCD and share its L2 for the K/V tiles.
+  const int nfb = m / 256;
+  const int q8 = blockIdx.x / (8 * nfb), rem = blockIdx.x % (8 * nfb);
+  const int fb = rem / 8, work = q8 * 8 + rem % 8;
+  if (work >= n_work) return;
+  const int bh = work / P, p = work % P;
+  const int h = bh % H;
+  const int tok_begin = p * slice_len;
+  const int tok_end = min(L, tok_begin + slice_len);
+  const int ntile = (tok_end - tok_begin + kTile - 1) / kTile;
+
+  const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+  const int l32 = lane % 32, hf = lane / 32;
+  const int l16 = lane % 16, g16 = lane / 16;
+  const int f0 = fb * 256 + wv * 64;  // first feature of this wave
+
+  // --- resident operands -----------------------------------------------------------------
+  // M' -> LDS
+  for (int ci = tid; ci < R * D / 8; ci += 256) {
+    int row = ci / (D / 8), kc = ci % (D / 8);
+    u32x4 v = *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
+    *reinterpret_cast<u32x4*>(Ms + row * SM::XS + 8 * kc) = v;
+  }
+  // A' fragments (B operand of the projection): feature = f0 + 32 ft + l32, k = 16 s + 8 hf + [0,8)
+  half8 afr[2][D / 16];
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+      afr[ft][s] = *reinterpret_cast<const half8*>(Ah + ((size_t)h * m + f0 + 32 * ft + l32) * D + 16 * s + 8 * hf);
+
+  // --- staging helpers -------------------------------------------------------------------
+  constexpr int KCH = D / 32;   // 16-byte chunks of the K tile per thread
+  constexpr int VCH = DV / 32;  // 16-byte chunks of the V tile per thread
+  u32x4 kreg[KCH], vreg[VCH];
+  const unsigned short* Kb = Kg + (size_t)bh * L * D;
+  const unsigned short* Vb = Vg + (size_t)bh * L * DV;
+  auto load_tile = [&](int t) {
+    const int t0 = tok_begin + t * kTile;
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
+      u32x4 z = {0u, 0u, 0u, 0u};
+      kreg[i] = (t0 + tok < tok_end) ? *reinterpret_cast<const u32x4*>(Kb + (size_t)(t0 + tok) * D + 8 * kc) : z;
+    }
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) {
+      int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
+      u32x4 z = {0u, 0u, 0u, 0u};
+      vreg[i] = (t0 + tok < tok_end) ? *reinterpret_cast<const u32x4*>(Vb + (size_t)(t0 + tok) * DV + 8 * cc) : z;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    _Float16* xs = Xs + buf * kTile * SM::XS;
+    unsigned short* vt = Vt + buf * DV * SM::VS;
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
+      *reinterpret_cast<u32x4*>(xs + tok * SM::XS + 8 * kc) = bf16x8_to_f16x8(kreg[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) {
+      int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vt[(8 * cc + 2 * e) * SM::VS + tok] = (unsigned short)(vreg[i][e] & 0xffffu);
+        vt[(8 * cc + 2 * e + 1) * SM::VS + tok] = (unsigned short)(vreg[i][e] >> 16);
+      }
+    }
+  };
+  // n' of this wave's 16 tokens of the tile in buffer `buf` -> ns[nb]
+  auto norms = [&](int buf, int nb, int t) {
+    const _Float16* xs = Xs + buf * kTile * SM::XS;
+    f32x4 acc[R / 16];
+#pragma unroll
+    for (int rt = 0; rt < R / 16; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+      half8 a = *reinterpret_cast<const half8*>(xs + (16 * wv + l16) * SM::XS + 32 * s + 8 * g16);
+#pragma unroll
+      for (int rt = 0; rt < R / 16; ++rt) {
+        half8 b = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::XS + 32 * s + 8 * g16);
+        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[rt], 0, 0, 0);
+      }
+    }
+    f32x4 ss = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rt = 0; rt < R / 16; ++rt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) ss[v] = fmaf(acc[rt][v], acc[rt][v], ss[v]);
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) ss[v] += __shfl_xor(ss[v], o, 64);
+    if (l16 == 0) {
+      const int t0 = tok_begin + t * kTile + 16 * wv + 4 * g16;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (t0 + v >= tok_end) ss[v] = 1e30f;  // rows past the end contribute exp2(-huge) = 0
+      *reinterpret_cast<f32x4*>(ns + nb * kTile + 16 * wv + 4 * g16) = ss;
+    }
+  };
+
+  // --- accumulators ------------------------------------------------------------------------
+  f32x16 S[2][DV / 32];
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) S[ft][ct][v] = 0.f;
+  float z[2] = {0.f, 0.f};
+  float c = -INFINITY;  // wave-uniform shift of this 64-feature block
+
+  // --- prologue: tile 0 into buffer 0, tile 1 in flight ------------------------------------
+  if (ntile > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  if (ntile > 1) load_tile(1);
+  __syncthreads();
+
+  for (int t = 0; t < ntile; ++t) {
+    const int buf = t % 3, nb = t & 1;
+    norms(buf, nb, t);
+    if (t + 1 < ntile) store_tile((t + 1) % 3);
+    if (t + 2 < ntile) load_tile(t + 2);
+    __syncthreads();
+
+    const _Float16* xs = Xs + buf * kTile * SM::XS;
+    const unsigned short* vt = Vt + buf * DV * SM::VS;
+    // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32
+    f32x16 U[2][2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) U[tt][ft][v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        half8 a = *reinterpret_cast<const half8*>(xs + (32 * tt + l32) * SM::XS + 16 * s + 8 * hf);
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft)
+          U[tt][ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[tt][ft], 0, 0, 0);
+      }
+    // logits (log2 domain) and the tile maximum of this wave's block
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float lg = U[tt][ft][4 * g + e] - nv[e];
+            U[tt][ft][4 * g + e] = lg;
+            mx = fmaxf(mx, lg);
+          }
+      }
+    mx = wave_max64(mx);
+    if (mx > c + kTau) {  // wave-uniform; first tile: c = -inf
+      const float f = fast_exp2(c - mx);
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        z[ft] *= f;
+#pragma unroll
+        for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) S[ft][ct][v] *= f;
+      }
+      c = mx;
+    }
+    // features, packed to bf16 in the operand layout of the second MFMA
+    u32x4 pk[2][2][2];  // [tt][ft][hh]: k-slots s <-> accumulator registers 8 hh + s
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        float zs = 0.f;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float a = fast_exp2(U[tt][ft][8 * hh + 2 * q] - c);
+            float b = fast_exp2(U[tt][ft][8 * hh + 2 * q + 1] - c);
+            pk[tt][ft][hh][q] = pack_bf16(a, b);
+            // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
+            // convex combination of value rows
+            zs = dot2_bf16(pk[tt][ft][hh][q], kOnesBf16x2, zs);
+          }
+        z[ft] += zs;
+      }
+    // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int ct = 0; ct < DV / 32; ++ct) {
+          const unsigned short* vr = vt + (32 * ct + l32) * SM::VS + 32 * tt + 16 * hh + 4 * hf;
+          u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
+          u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
+          u32x4 bv = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+          for (int ft = 0; ft < 2; ++ft)
+            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[tt][ft][hh]),
+                                                                *reinterpret_cast<bf16x8*>(&bv), S[ft][ct], 0, 0, 0);
+        }
+  }
+
+  // --- epilogue: partial state of this slice -------------------------------------------------
+  const size_t pbase = (size_t)bh * P + p;
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft) {
+#pragma unroll
+    for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        int feat = f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
+        Spart[(pbase * m + feat) * DV + 32 * ct + l32] = S[ft][ct][v];
+      }
+    float zt = z[ft] + __shfl_xor(z[ft], 32, 64);
+    if (hf == 0) zpart[pbase * m + f0 + 32 * ft + l32] = zt;
+  }
+  if (lane == 0) cpart[pbase * (m / 64) + f0 / 64] = c;
+}
+
+// ---------------------------------------------------------------------------
+// k_kv_merge: per (b,h, 64-feature block): c* = max_p c_p;  S = sum_p 2^(c_p - c*) S_p (p ascending),
+// same for z.  Writes S^T as bf16 [BH][DV][m] (the readout's MFMA operand), z [BH][m], c* [BH][m/64].
+// ---------------------------------------------------------------------------
+template <int DV>
+__global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spart, const float* __restrict__ zpart,
+                                                  const float* __restrict__ cpart, unsigned short* __restrict__ St,
+                                                  float* __restrict__ zt, float* __restrict__ cf, int m, int P) {
+  __shared__ float tile[64][DV + 1];
+  __shared__ float fac[64];  // up to 64 slices per pass
+  const int nblk = m / 64;
+  const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
+  const int tid = threadIdx.x;
+  float cs = -INFINITY;
+  for (int p = 0; p < P; ++p) cs = fmaxf(cs, cpart[((size_t)bh * P + p) * nblk + blk]);
+  constexpr int PER = 64 * DV / 256;
+  float acc[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+  float zacc = 0.f;
+  for (int p0 = 0; p0 < P; p0 += 64) {
+    const int np = min(64, P - p0);
+    __syncthreads();
+    if (tid < np) {
+      float cp = cpart[((size_t)bh * P + p0 + tid) * nblk + blk];
+      fac[tid] = (cp == -INFINITY) ? 0.f : fast_exp2(cp - cs);
+    }
+    __syncthreads();
+    for (int pi = 0; pi < np; ++pi) {
+      const float f = fac[pi];
+      const float* sp = Spart + (((size_t)bh * P + p0 + pi) * m + 64 * blk) * DV;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) acc[i] = fmaf(f, sp[tid + 256 * i], acc[i]);
+      if (tid < 64) zacc = fmaf(f, zpart[((size_t)bh * P + p0 + pi) * m + 64 * blk + tid], zacc);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int idx = tid + 256 * i;
+    tile[idx / DV][idx % DV] = acc[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    int idx = tid + 256 * i;
+    int cc = idx / 64, f = idx % 64;
+    St[((size_t)bh * DV + cc) * m + 64 * blk + f] = (unsigned short)(pack_bf16(tile[f][cc], 0.f) & 0xffffu);
+  }
+  if (tid < 64) zt[(size_t)bh * m + 64 * blk + tid] = zacc;
+  if (tid == 0) cf[(size_t)bh * nblk + blk] = cs;
+}
+
+// ---------------------------------------------------------------------------
+// k_readout
+// Workgroup = 4 waves; each wave owns 64 tokens per step and sweeps all features in blocks of 64:
+//   U^T[feat][tok] = A' X^T (MFMA f16; A' from LDS, X fragments in registers, converted bf16->fp16)
+//   phi^T = exp2(U^T + c_blk - mu_tok), mu a lazily raised running row shift
+//   out^T[c][tok] += S^T[c][feat] phi^T[feat][tok] (MFMA bf16; S^T from LDS),  den += phi . z
+// No barrier in the main loop.
+// ---------------------------------------------------------------------------
+template <int D, int DV>
+struct RoSmem {
+  static constexpr int AS = D + 8;
+  __host__ __device__ static size_t a_bytes(int m) { return (size_t)m * AS * 2; }
+  __host__ __device__ static size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
+  __host__ __device__ static size_t total(int m) { return a_bytes(m) + s_bytes(m) + (size_t)m * 4 + (size_t)(m / 64) * 4 + 16; }
+};
+
+template <int D, int DV, bool OUT_BF16, int MINW>
+__global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __restrict__ Qg,
+                                                       const _Float16* __restrict__ Ah,
+                                                       const unsigned short* __restrict__ St,
+                                                       const float* __restrict__ zt, const float* __restrict__ cf,
+                                                       void* __restrict__ outp, int H, int L, int m, int tok_per_wg,
+                                                       int wg_per_bh) {
+  using SM = RoSmem<D, DV>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  _Float16* Asl = reinterpret_cast<_Float16*>(smem);
+  unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::a_bytes(m));
+  float* cl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));
+  unsigned short* zl = reinterpret_cast<unsigned short*>(cl + m / 64 + 4);  // z as bf16, 8-byte aligned rows of 4
+  const int SS = m + 4;
+
+  const int bh = blockIdx.x / wg_per_bh, part = blockIdx.x % wg_per_bh;
+  const int h = bh % H;
+  const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+  const int l32 = lane % 32, hf = lane / 32;
+
+  for (int ci = tid; ci < m * D / 8; ci += 256) {
+    int row = ci / (D / 8), kc = ci % (D / 8);
+    *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
+        *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
+  }
+  for (int ci = tid; ci < DV * m / 4; ci += 256) {
+    int row = ci / (m / 4), fc = ci % (m / 4);
+    *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) =
+        *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
+  }
+  for (int i = tid; i < m; i += 256) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
+  for (int i = tid; i < m / 64; i += 256) cl[i] = cf[(size_t)bh * (m / 64) + i];
+  __syncthreads();
+
+  const unsigned short* Qb = Qg + (size_t)bh * L * D;
+  const int wg_begin = part * tok_per_wg;
+  const int wg_end = min(L, wg_begin + tok_per_wg);
+  for (int t0 = wg_begin + 64 * wv; t0 < wg_end; t0 += 256) {
+    // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
+    half8 xf[2][D / 16];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tok = t0 + 32 * tt + l32;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) {
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        if (tok < wg_end) raw = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
+        u32x4 cv = bf16x8_to_f16x8(raw);
+        xf[tt][s] = *reinterpret_cast<half8*>(&cv);
+      }
+    }
+    f32x16 O[DV / 32][2];
+#pragma unroll
+    for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[ct][tt][v] = 0.f;
+    float den[2] = {0.f, 0.f};
+    float mu[2] = {-INFINITY, -INFINITY};
+
+    for (int blk = 0; blk < m / 64; ++blk) {
+      const float cb = cl[blk];
+      // U^T[ft][tt]: rows = features 64 blk + 32 ft + 8 g + 4 hf + e, column = token 32 tt + l32
+      f32x16 U[2][2];
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) U[ft][tt][v] = 0.f;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+          half8 a = *reinterpret_cast<const half8*>(Asl + (64 * blk + 32 * ft + l32) * SM::AS + 16 * s + 8 * hf);
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+            U[ft][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xf[tt][s], U[ft][tt], 0, 0, 0);
+        }
+      // running row shift (per token = per lane column; both halves agree after the exchange)
+      float sh[2];
+      bool changed = false;
+      float fsc[2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        float bm = -INFINITY;
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) bm = fmaxf(bm, U[ft][tt][v]);
+        bm = fmaxf(bm, __shfl_xor(bm, 32, 64)) + cb;
+        fsc[tt] = 1.f;
+        if (bm > mu[tt] + kTau) {
+          fsc[tt] = fast_exp2(mu[tt] - bm);
+          mu[tt] = bm;
+          changed = true;
+        }
+        sh[tt] = mu[tt] - cb;
+      }
+      if (__any(changed)) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          den[tt] *= fsc[tt];
+#pragma unroll
+          for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) O[ct][tt][v] *= fsc[tt];
+        }
+      }
+      // features, denominator, pack
+      u32x4 pk[2][2][2];  // [ft][tt][hh]
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 zv = *reinterpret_cast<const u32x2*>(zl + 64 * blk + 32 * ft + 8 * g + 4 * hf);
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            float a0 = fast_exp2(U[ft][tt][4 * g + 0] - sh[tt]);
+            float a1 = fast_exp2(U[ft][tt][4 * g + 1] - sh[tt]);
+            float a2 = fast_exp2(U[ft][tt][4 * g + 2] - sh[tt]);
+            float a3 = fast_exp2(U[ft][tt][4 * g + 3] - sh[tt]);
+            const unsigned p0 = pack_bf16(a0, a1), p1 = pack_bf16(a2, a3);
+            pk[ft][tt][g / 2][2 * (g % 2)] = p0;
+            pk[ft][tt][g / 2][2 * (g % 2) + 1] = p1;
+            // the denominator weights are the same rounded features that multiply S
+            den[tt] = dot2_bf16(p1, zv[1], dot2_bf16(p0, zv[0], den[tt]));
+          }
+        }
+      // out^T[ct][tt] += S^T phi^T : k-slot s of half hf is feature 64 blk + 32 ft + 16 hh + 8 (s/4) + 4 hf + s%4
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int ct = 0; ct < DV / 32; ++ct) {
+            const unsigned short* sr = Stl + (32 * ct + l32) * SS + 64 * blk + 32 * ft + 16 * hh + 4 * hf;
+            u32x2 lo = *reinterpret_cast<const u32x2*>(sr);
+            u32x2 hi = *reinterpret_cast<const u32x2*>(sr + 8);
+            u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+              O[ct][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av),
+                                                                  *reinterpret_cast<bf16x8*>(&pk[ft][tt][hh]),
+                                                                  O[ct][tt], 0, 0, 0);
+          }
+    }
+    // normalise and store: register v of O[ct][tt] is out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4]
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tok = t0 + 32 * tt + l32;
+      const float inv = 1.f / (den[tt] + __shfl_xor(den[tt], 32, 64));
+      if (tok < wg_end) {
+#pragma unroll
+        for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const size_t o = ((size_t)bh * L + tok) * DV + 32 * ct + 8 * g + 4 * hf;
+            float v0 = O[ct][tt][4 * g] * inv, v1 = O[ct][tt][4 * g + 1] * inv;
+            float v2 = O[ct][tt][4 * g + 2] * inv, v3 = O[ct][tt][4 * g + 3] * inv;
+            if (OUT_BF16) {
+              u32x2 w = {pack_bf16(v0, v1), pack_bf16(v2, v3)};
+              *reinterpret_cast<u32x2*>(reinterpret_cast<unsigned short*>(outp) + o) = w;
+            } else {
+              f32x4 w = {v0, v1, v2, v3};
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + o) = w;
+            }
+          }
+      }
+    }
+  }
+}
+
+int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  int v = std::atoi(s);
+  return v > 0 ? v : dflt;
+}
+
+struct Plan {
+  int P, slice_len, nfb, n_work, kv_grid;
+  int tok_per_wg, wg_per_bh;
+};
+
+Plan make_plan(const Problem& pb) {
+  const dark_params& p = pb.p;
+  Plan pl{};
+  pl.nfb = p.m / 256;
+  const long long BH = pb.BH();
+  // K pass: about two workgroups per CU (256 CUs); slices are whole tiles.
+  int target = env_int("DARK_KV_WGS", 512);
+  long long want = (target + BH * pl.nfb - 1) / (BH * pl.nfb);
+  if (want < 1) want = 1;
+  int sl = (int)((p.L + want - 1) / want);
+  sl = ((sl + kTile - 1) / kTile) * kTile;
+  pl.slice_len = sl;
+  pl.P = (p.L + sl - 1) / sl;
+  pl.n_work = (int)(BH * pl.P);
+  pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
+  // readout: workgroups of a multiple of 256 tokens
+  int tr = env_int("DARK_RO_TOKENS", 512);
+  tr = ((tr + 255) / 256) * 256;
+  pl.tok_per_wg = tr;
+  pl.wg_per_bh = (p.L + tr - 1) / tr;
+  return pl;
+}
+
+struct FusedBufs {
+  _Float16* Ah;
+  _Float16* Mh;
+  float* Spart;
+  float* zpart;
+  float* cpart;
+  unsigned short* St;
+  float* zt;
+  float* cf;
+};
+
+void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
+  const dark_params& p = pb.p;
+  const size_t BH = (size_t)pb.BH();
+  b.Ah = ar.take<_Float16>((size_t)p.H * p.m * p.d);
+  b.Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
+  b.Spart = ar.take<float>(BH * pl.P * p.m * p.dv);
+  b.zpart = ar.take<float>(BH * pl.P * p.m);
+  b.cpart = ar.take<float>(BH * pl.P * (p.m / 64));
+  b.St = ar.take<unsigned short>(BH * p.dv * p.m);
+  b.zt = ar.take<float>(BH * p.m);
+  b.cf = ar.take<float>(BH * (p.m / 64));
+}
+
+template <typename KernelT>
+dark_status allow_lds(KernelT kernel, size_t bytes) {
+  if (bytes > 160 * 1024) return DARK_EUNSUPPORTED;
+  if (bytes > 48 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess)
+      return DARK_EHIP;
+  }
+  return DARK_OK;
+}
+
+template <int D, int DV, int R, int MINW>
+dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* K, const void* V) {
+  const dark_params& p = pb.p;
+  auto kern = k_kv_reduce<D, DV, R, MINW>;
+  const size_t lds = KvSmem<D, DV, R>::total;
+  DARK_TRY(allow_lds(kern, lds));
+  DARK_LAUNCH(KID_KV_REDUCE, pb.st, kern, dim3(pl.kv_grid), dim3(256), lds, (const unsigned short*)K,
+              (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m, pl.P, pl.slice_len,
+              pl.n_work);
+  return DARK_OK;
+}
+
+template <int D, int DV, int MINW>
+dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
+  const dark_params& p = pb.p;
+  const size_t lds = RoSmem<D, DV>::total(p.m);
+  const unsigned grid = (unsigned)(pb.BH() * pl.wg_per_bh);
+  if (p.out_dtype == DARK_BF16) {
+    auto kern = k_readout<D, DV, true, MINW>;
+    DARK_TRY(allow_lds(kern, lds));
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
+                b.cf, out, p.H, p.L, p.m, pl.tok_per_wg, pl.wg_per_bh);
+  } else {
+    auto kern = k_readout<D, DV, false, MINW>;
+    DARK_TRY(allow_lds(kern, lds));
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
+                b.cf, out, p.H, p.L, p.m, pl.tok_per_wg, pl.wg_per_bh);
+  }
+  return DARK_OK;
+}
+
+}  // namespace
+
+bool fused_supported(const Problem& pb, int op, bool causal) {
+  const dark_params& p = pb.p;
+  if (op != DARK_OP_ATTN_FWD || causal) return false;
+  if (p.io_dtype != DARK_BF16) return false;
+  const bool shape64 = p.d == 64 && p.r == 64 && p.dv == 64;
+  const bool shape128 = p.d == 128 && p.r == 128 && p.dv == 128;
+  if (!shape64 && !shape128) return false;
+  if (p.m % 256 != 0) return false;
+  const size_t ro = shape64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
+  if (ro > 160 * 1024) return false;
+  return true;
+}
+
+dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const void* K, const void* V,
+                           const float* M, const float* W, void* out) {
+  const dark_params& p = pb.p;
+  const Plan pl = make_plan(pb);
+  FusedBufs b{};
+  plan_bufs(pb, pl, ar, b);
+  if (ar.base == nullptr) return DARK_OK;
+  if (ar.overflow) return DARK_EWORKSPACE;
+
+  const int nA = (p.m + 3) / 4;
+  DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA + 4, p.H), dim3(256), 0, M, W, b.Ah, b.Mh, p.m, p.r, p.d,
+              p.w_shared, std::sqrt(pb.scale));
+  if (p.d == 64) {
+    DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V)));
+  } else {
+    DARK_TRY((launch_kv<128, 128, 128, 1>(pb, pl, b, K, V)));
+  }
+  const unsigned mgrid = (unsigned)(pb.BH() * (p.m / 64));
+  if (p.dv == 64)
+    DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<64>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
+                b.zt, b.cf, p.m, pl.P);
+  else
+    DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<128>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
+                b.zt, b.cf, p.m, pl.P);
+  if (p.d == 64) {
+    DARK_TRY((launch_ro<64, 64, 2>(pb, pl, b, Q, out)));
+  } else {
+    DARK_TRY((launch_ro<128, 128, 1>(pb, pl, b, Q, out)));
+  }
+  return DARK_OK;
+}
+
 dark_status fused_attn_causal_fwd(const Problem&, Arena&, const void*, const void*, const void*, const float*,
                                   const float*, void*) {
   return DARK_EUNSUPPORTED;
 }
+
 }  // namespace dark

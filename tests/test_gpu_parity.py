@@ -183,3 +183,51 @@ def test_backward_optional_outputs():
     torch.cuda.synchronize()
     assert g["dQ"] is None and g["dV"] is None
     U.assert_close(_np(g["dM"]), U.oracle_bwd(inp, True)[3], 2e-4, "dM only")
+
+
+# ---------------------------------------------------------------------------
+# fused MFMA path (bf16 inputs), forced so that a silent fall-back cannot pass
+# ---------------------------------------------------------------------------
+FUSED_SHAPES = [
+    # B, H, L,    d,   r,   m,   dv
+    (1, 2, 300, 64, 64, 256, 64),      # ragged tail, several tiles
+    (2, 1, 1000, 64, 64, 512, 64),     # two 256-feature blocks
+    (1, 1, 64, 64, 64, 256, 64),       # exactly one tile
+    (1, 1, 7, 64, 64, 256, 64),        # shorter than a tile
+    (1, 2, 333, 128, 128, 256, 128),   # the wide-head instantiation
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_fused_forward(shape, out_f32):
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(11, B, H, L, d, r, m, dv, bf16=True, amp=2.0)
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED,
+                           out_dtype=torch.float32 if out_f32 else None)
+    torch.cuda.synchronize()
+    assert out.dtype == (torch.float32 if out_f32 else torch.bfloat16)
+    e = U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], f"fused {shape}")
+    print(f"fused {shape} out_f32={out_f32}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+
+
+def test_fused_large_logit_range():
+    inp = U.random_problem(12, 1, 1, 500, 64, 64, 256, 64, bf16=True, amp=40.0)
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
+    assert lg.max() - lg.min() > 150
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], "fused, wide logit range")
+
+
+def test_fused_matches_f32_path_and_is_deterministic():
+    inp = U.random_problem(13, 2, 3, 900, 64, 64, 256, 64, bf16=True)
+    dev = U.to_device(inp, True)
+    a = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED).clone()
+    b = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    c = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    U.assert_close(_np(a), _np(c), U.TOL["bf16"], "fused vs fp32 path")
