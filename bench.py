@@ -161,8 +161,8 @@ def main():
             cores = os.cpu_count() or 1
         heads = 0
         t2 = time.perf_counter()
-        while heads < cfg.B * cfg.H and (time.perf_counter() - t2) < args.cpu_seconds:
-            b, h = divmod(heads, cfg.H)
+        while (time.perf_counter() - t2) < args.cpu_seconds:
+            b, h = divmod(heads % (cfg.B * cfg.H), cfg.H)
             Q, K, V, M, W = U.head(inp, b, h)
             Ls = min(cfg.L, 8192)     # causal oracle is a per-token loop: bound the sample length
             if cfg.causal:
@@ -174,8 +174,8 @@ def main():
         el = time.perf_counter() - t2
         line["cpu_baseline"] = {
             "value": (heads * Ls / cfg.H) / el, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{heads} (b,h) slices of {Ls} positions of {cfg.name} (fp64 numpy oracle, forward only), "
-                      f"{el:.1f} s; scaled by 1/H to tokens",
+            "sample": f"{heads} (b,h) slices (cycling over the {cfg.B * cfg.H} of the workload) of {Ls} positions of "
+                      f"{cfg.name}, fp64 numpy oracle, forward only, {el:.1f} s; scaled by 1/H to tokens",
         }
     print(json.dumps(line))
 

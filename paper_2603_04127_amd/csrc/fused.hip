@@ -35,7 +35,11 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kTau = 16.0f;  // a running shift is only raised when exceeded by 2^kTau
+// Running shifts are only raised when a feature value would exceed 2^kTau (rare): fp32 sums of such
+// values over up to 2^20 positions, times the readout's own 2^kTau, stay far below 2^127.
+constexpr float kTau = 40.0f;
+constexpr float kBig = 1.099511627776e12f;  // 2^40
+constexpr float kRaise = 20.0f;             // in the rare path, shifts more than 2^20 too low are raised
 constexpr int kTile = 64;      // tokens per tile in the K pass
 
 __device__ inline unsigned pack_bf16(float a, float b) {
@@ -65,30 +69,72 @@ __device__ inline float dot2_bf16(unsigned a, unsigned b, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&a), *reinterpret_cast<bf16x2*>(&b), acc, false);
 }
 constexpr unsigned kOnesBf16x2 = 0x3f803f80u;
-__device__ inline float wave_max64(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+// max(a, b, c).  This file is compiled with -fno-honor-nans, so the compiler needs no NaN
+// canonicalisation and forms v_max3_f32.  (Not inline asm: the compiler must see the reads of
+// MFMA results to insert the wait states they need.)
+__device__ inline float max3(float a, float b, float c) { return __builtin_fmaxf(a, __builtin_fmaxf(b, c)); }
+// Sum over each row of 16 lanes (result in every lane of the row): four DPP row rotations.
+template <int N>
+__device__ inline float dpp_row_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ inline float row16_sum(float v) {
+  v += dpp_row_ror<8>(v);
+  v += dpp_row_ror<4>(v);
+  v += dpp_row_ror<2>(v);
+  v += dpp_row_ror<1>(v);
   return v;
 }
 
 // ---------------------------------------------------------------------------
 // k_prep: A'[h][j][:] = alpha log2e sum_t W[h][j][t] M[h][t][:]  (fp16),  M' = alpha sqrt(log2e/2) M.
-// One block per (h, 4 feature rows); the last blocks of each head convert M.
+// One block per (h, 16 feature rows): the W rows sit in LDS, every thread owns one column and four
+// rows.  The last blocks of each head convert M.  r <= 128.
 // ---------------------------------------------------------------------------
+constexpr int kPrepRows = 16;
 __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const float* __restrict__ W,
                                               _Float16* __restrict__ Ah, _Float16* __restrict__ Mh, int m, int r,
                                               int d, int w_shared, float alpha) {
+  __shared__ float Ws[kPrepRows][128 + 1];
+  __shared__ float Mt[32][128];  // 32 rows of M at a time
   const int h = blockIdx.y;
-  const int nA = (m + 3) / 4;
+  const int nA = (m + kPrepRows - 1) / kPrepRows;
   const float* Mp = M + (size_t)h * r * d;
   if ((int)blockIdx.x < nA) {
-    const int j = blockIdx.x * 4 + threadIdx.x / 64;
-    if (j >= m) return;
-    const float* w = W + (w_shared ? 0 : (size_t)h * m * r) + (size_t)j * r;
-    for (int c = threadIdx.x % 64; c < d; c += 64) {
-      float s = 0.f;
-      for (int t = 0; t < r; ++t) s = fmaf(w[t], Mp[(size_t)t * d + c], s);
-      Ah[((size_t)h * m + j) * d + c] = (_Float16)(s * alpha * kLog2e);
+    const int j0 = blockIdx.x * kPrepRows;
+    const float* w = W + (w_shared ? 0 : (size_t)h * m * r);
+    for (int i = threadIdx.x; i < kPrepRows * r; i += 256) {
+      int jj = i / r, t = i % r;
+      Ws[jj][t] = (j0 + jj < m) ? w[(size_t)(j0 + jj) * r + t] : 0.f;
+    }
+    const int jq = threadIdx.x / 64, c0 = threadIdx.x % 64;
+    float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};  // columns c0 and c0 + 64
+    for (int tb = 0; tb < r; tb += 32) {
+      __syncthreads();
+      for (int i = threadIdx.x; i < 32 * d; i += 256) {
+        int t = i / d, c = i % d;
+        Mt[t][c] = (tb + t < r) ? Mp[(size_t)(tb + t) * d + c] : 0.f;
+      }
+      __syncthreads();
+#pragma unroll 8
+      for (int t = 0; t < 32; ++t) {
+        const float m0 = Mt[t][c0];
+        const float m1 = d > 64 ? Mt[t][c0 + 64] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float wv = Ws[jq + 4 * i][tb + t];
+          acc[0][i] = fmaf(wv, m0, acc[0][i]);
+          acc[1][i] = fmaf(wv, m1, acc[1][i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = j0 + jq + 4 * i;
+      if (j < m) {
+        if (c0 < d) Ah[((size_t)h * m + j) * d + c0] = (_Float16)(acc[0][i] * alpha * kLog2e);
+        if (c0 + 64 < d) Ah[((size_t)h * m + j) * d + c0 + 64] = (_Float16)(acc[1][i] * alpha * kLog2e);
+      }
     }
   } else {
     const float f = alpha * sqrtf(0.5f * kLog2e);
@@ -171,19 +217,20 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
   u32x4 kreg[KCH], vreg[VCH];
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DV;
+  // Rows past the end of the slice are read from the slice's last row instead (always in
+  // bounds, no predication, so the loads stay in flight across the tile); their features are
+  // forced to zero through the norm term, so what they hold never reaches S or z.
   auto load_tile = [&](int t) {
     const int t0 = tok_begin + t * kTile;
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
-      int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
-      u32x4 z = {0u, 0u, 0u, 0u};
-      kreg[i] = (t0 + tok < tok_end) ? *reinterpret_cast<const u32x4*>(Kb + (size_t)(t0 + tok) * D + 8 * kc) : z;
+      int ci = tid + 256 * i, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
     }
 #pragma unroll
     for (int i = 0; i < VCH; ++i) {
-      int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
-      u32x4 z = {0u, 0u, 0u, 0u};
-      vreg[i] = (t0 + tok < tok_end) ? *reinterpret_cast<const u32x4*>(Vb + (size_t)(t0 + tok) * DV + 8 * cc) : z;
+      int ci = tid + 256 * i, tok = min(t0 + ci / (DV / 8), tok_end - 1), cc = ci % (DV / 8);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DV + 8 * cc);
     }
   };
   auto store_tile = [&](int buf) {
@@ -225,15 +272,13 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 #pragma unroll
       for (int v = 0; v < 4; ++v) ss[v] = fmaf(acc[rt][v], acc[rt][v], ss[v]);
 #pragma unroll
-    for (int o = 1; o < 16; o <<= 1)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) ss[v] += __shfl_xor(ss[v], o, 64);
+    for (int v = 0; v < 4; ++v) ss[v] = row16_sum(ss[v]);
     if (l16 == 0) {
       const int t0 = tok_begin + t * kTile + 16 * wv + 4 * g16;
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        if (t0 + v >= tok_end) ss[v] = 1e30f;  // rows past the end contribute exp2(-huge) = 0
-      *reinterpret_cast<f32x4*>(ns + nb * kTile + 16 * wv + 4 * g16) = ss;
+        ss[v] = (t0 + v >= tok_end) ? -1e30f : -ss[v];  // rows past the end contribute exp2(-huge) = 0
+      *reinterpret_cast<f32x4*>(ns + nb * kTile + 16 * wv + 4 * g16) = ss;  // stored negated
     }
   };
 
@@ -246,13 +291,22 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 #pragma unroll
       for (int v = 0; v < 16; ++v) S[ft][ct][v] = 0.f;
   float z[2] = {0.f, 0.f};
-  float c = -INFINITY;  // wave-uniform shift of this 64-feature block
+  // Per-feature shift (lane = feature column of the projection; both half-waves agree).  It is set
+  // from the first tile and afterwards only raised when a tile exceeds it by more than 2^kTau.
+  float c[2] = {0.f, 0.f};
 
   // --- prologue: tile 0 into buffer 0, tile 1 in flight ------------------------------------
   if (ntile > 0) {
     load_tile(0);
     store_tile(0);
   }
+  // The A' fragments must have arrived before the loop: otherwise the compiler's wait for them sits
+  // inside the loop body, where (the counter being in-order) it would also wait for the tile
+  // prefetch issued a few instructions earlier.
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(afr[ft][s]));
   if (ntile > 1) load_tile(1);
   __syncthreads();
 
@@ -265,14 +319,20 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 
     const _Float16* xs = Xs + buf * kTile * SM::XS;
     const unsigned short* vt = Vt + buf * DV * SM::VS;
-    // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32
+    // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
+    // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
+    // log2-features directly.
     f32x16 U[2][2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-      for (int ft = 0; ft < 2; ++ft)
+      for (int g = 0; g < 4; ++g) {
+        f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) U[tt][ft][v] = 0.f;
+        for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) U[tt][ft][4 * g + e] = nv[e] - c[ft];
+      }
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
 #pragma unroll
@@ -282,55 +342,68 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
         for (int ft = 0; ft < 2; ++ft)
           U[tt][ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[tt][ft], 0, 0, 0);
       }
-    // logits (log2 domain) and the tile maximum of this wave's block
-    float mx = -INFINITY;
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float lg = U[tt][ft][4 * g + e] - nv[e];
-            U[tt][ft][4 * g + e] = lg;
-            mx = fmaxf(mx, lg);
-          }
-      }
-    mx = wave_max64(mx);
-    if (mx > c + kTau) {  // wave-uniform; first tile: c = -inf
-      const float f = fast_exp2(c - mx);
-#pragma unroll
-      for (int ft = 0; ft < 2; ++ft) {
-        z[ft] *= f;
-#pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) S[ft][ct][v] *= f;
-      }
-      c = mx;
-    }
     // features, packed to bf16 in the operand layout of the second MFMA
     u32x4 pk[2][2][2];  // [tt][ft][hh]: k-slots s <-> accumulator registers 8 hh + s
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
+    float zs[2];        // this tile's column sums (this lane's tokens)
+    auto featurize = [&]() {
 #pragma unroll
       for (int ft = 0; ft < 2; ++ft) {
-        float zs = 0.f;
+        float acc = 0.f;
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
+        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float a = fast_exp2(U[tt][ft][8 * hh + 2 * q] - c);
-            float b = fast_exp2(U[tt][ft][8 * hh + 2 * q + 1] - c);
-            pk[tt][ft][hh][q] = pack_bf16(a, b);
-            // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
-            // convex combination of value rows
-            zs = dot2_bf16(pk[tt][ft][hh][q], kOnesBf16x2, zs);
-          }
-        z[ft] += zs;
+          for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              float a = fast_exp2(U[tt][ft][8 * hh + 2 * q]);
+              float b = fast_exp2(U[tt][ft][8 * hh + 2 * q + 1]);
+              pk[tt][ft][hh][q] = pack_bf16(a, b);
+              // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
+              // convex combination of value rows
+              acc = dot2_bf16(pk[tt][ft][hh][q], kOnesBf16x2, acc);
+            }
+        zs[ft] = acc;
       }
+    };
+    // Common path: exponentiate with the current shifts and look at the column sums afterwards;
+    // a sum of 2^kTau or more (or inf) means some shift is far too low for this tile.
+    bool fix = (t == 0);
+    if (!fix) {
+      featurize();
+      fix = __any(!(zs[0] < kBig) || !(zs[1] < kBig));
+    }
+    if (fix) {  // first tile, or rare
+      const bool first = (t == 0);
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        float m0 = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[tt][ft][v], U[tt][ft][v + 1]);
+        m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
+        const float delta = (first || m0 > kRaise) ? m0 : 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) U[tt][ft][v] -= delta;
+        c[ft] += delta;
+        if (!first) {
+          const float f = fast_exp2(-delta);
+          z[ft] *= f;
+          // S rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
+#pragma unroll
+            for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
+          }
+        }
+      }
+      featurize();
+    }
+    z[0] += zs[0];
+    z[1] += zs[1];
     // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
@@ -361,45 +434,67 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
         Spart[(pbase * m + feat) * DV + 32 * ct + l32] = S[ft][ct][v];
       }
     float zt = z[ft] + __shfl_xor(z[ft], 32, 64);
-    if (hf == 0) zpart[pbase * m + f0 + 32 * ft + l32] = zt;
+    if (hf == 0) {
+      zpart[pbase * m + f0 + 32 * ft + l32] = zt;
+      cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
+    }
   }
-  if (lane == 0) cpart[pbase * (m / 64) + f0 / 64] = c;
 }
 
 // ---------------------------------------------------------------------------
-// k_kv_merge: per (b,h, 64-feature block): c* = max_p c_p;  S = sum_p 2^(c_p - c*) S_p (p ascending),
-// same for z.  Writes S^T as bf16 [BH][DV][m] (the readout's MFMA operand), z [BH][m], c* [BH][m/64].
+// k_kv_merge: per (b,h, 64-feature block): c* = max over slices and the block's features of the
+// per-feature shifts;  S_j = sum_p 2^(c_pj - c*) S_pj (p ascending, fixed order), same for z.
+// Writes S^T as bf16 [BH][DV][m] (the readout's MFMA operand), z [BH][m], c* [BH][m/64].
 // ---------------------------------------------------------------------------
 template <int DV>
 __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spart, const float* __restrict__ zpart,
                                                   const float* __restrict__ cpart, unsigned short* __restrict__ St,
                                                   float* __restrict__ zt, float* __restrict__ cf, int m, int P) {
+  constexpr int PP = 16;  // slices per pass
   __shared__ float tile[64][DV + 1];
-  __shared__ float fac[64];  // up to 64 slices per pass
+  __shared__ float fac[PP][64];
+  __shared__ float red[4];
   const int nblk = m / 64;
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x;
   float cs = -INFINITY;
-  for (int p = 0; p < P; ++p) cs = fmaxf(cs, cpart[((size_t)bh * P + p) * nblk + blk]);
+  for (int i = tid; i < P * 64; i += 256) cs = fmaxf(cs, cpart[((size_t)bh * P + i / 64) * m + 64 * blk + i % 64]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
+  if (tid % 64 == 0) red[tid / 64] = cs;
+  __syncthreads();
+  cs = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   constexpr int PER = 64 * DV / 256;
   float acc[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) acc[i] = 0.f;
   float zacc = 0.f;
-  for (int p0 = 0; p0 < P; p0 += 64) {
-    const int np = min(64, P - p0);
+  for (int p0 = 0; p0 < P; p0 += PP) {
+    const int np = min(PP, P - p0);
     __syncthreads();
-    if (tid < np) {
-      float cp = cpart[((size_t)bh * P + p0 + tid) * nblk + blk];
-      fac[tid] = (cp == -INFINITY) ? 0.f : fast_exp2(cp - cs);
-    }
+    for (int i = tid; i < np * 64; i += 256)
+      fac[i / 64][i % 64] = fast_exp2(cpart[((size_t)bh * P + p0 + i / 64) * m + 64 * blk + i % 64] - cs);
     __syncthreads();
-    for (int pi = 0; pi < np; ++pi) {
-      const float f = fac[pi];
-      const float* sp = Spart + (((size_t)bh * P + p0 + pi) * m + 64 * blk) * DV;
+    for (int pi = 0; pi < np; pi += 4) {
+      // up to four slices' loads are issued before any is consumed; the sum order stays p ascending
+      float v[4][PER];
+      float zv[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < PER; ++i) acc[i] = fmaf(f, sp[tid + 256 * i], acc[i]);
-      if (tid < 64) zacc = fmaf(f, zpart[((size_t)bh * P + p0 + pi) * m + 64 * blk + tid], zacc);
+      for (int u = 0; u < 4; ++u) {
+        const int pu = min(pi + u, np - 1);
+        const float* sp = Spart + (((size_t)bh * P + p0 + pu) * m + 64 * blk) * DV;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) v[u][i] = sp[tid + 256 * i];
+        if (tid < 64) zv[u] = zpart[((size_t)bh * P + p0 + pu) * m + 64 * blk + tid];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (pi + u < np) {
+#pragma unroll
+          for (int i = 0; i < PER; ++i) acc[i] = fmaf(fac[pi + u][(tid + 256 * i) / DV], v[u][i], acc[i]);
+          if (tid < 64) zacc = fmaf(fac[pi + u][tid], zv[u], zacc);
+        }
+      }
     }
   }
 #pragma unroll
@@ -439,8 +534,8 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
                                                        const _Float16* __restrict__ Ah,
                                                        const unsigned short* __restrict__ St,
                                                        const float* __restrict__ zt, const float* __restrict__ cf,
-                                                       void* __restrict__ outp, int H, int L, int m, int tok_per_wg,
-                                                       int wg_per_bh) {
+                                                       void* __restrict__ outp, int H, int L, int m,
+                                                       int chunks_per_bh, int n_items, int items_per_wg) {
   using SM = RoSmem<D, DV>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16* Asl = reinterpret_cast<_Float16*>(smem);
@@ -449,38 +544,48 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
   unsigned short* zl = reinterpret_cast<unsigned short*>(cl + m / 64 + 4);  // z as bf16, 8-byte aligned rows of 4
   const int SS = m + 4;
 
-  const int bh = blockIdx.x / wg_per_bh, part = blockIdx.x % wg_per_bh;
-  const int h = bh % H;
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
 
-  for (int ci = tid; ci < m * D / 8; ci += 256) {
-    int row = ci / (D / 8), kc = ci % (D / 8);
-    *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
-        *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
-  }
-  for (int ci = tid; ci < DV * m / 4; ci += 256) {
-    int row = ci / (m / 4), fc = ci % (m / 4);
-    *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) =
-        *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
-  }
-  for (int i = tid; i < m; i += 256) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
-  for (int i = tid; i < m / 64; i += 256) cl[i] = cf[(size_t)bh * (m / 64) + i];
-  __syncthreads();
-
-  const unsigned short* Qb = Qg + (size_t)bh * L * D;
-  const int wg_begin = part * tok_per_wg;
-  const int wg_end = min(L, wg_begin + tok_per_wg);
-  for (int t0 = wg_begin + 64 * wv; t0 < wg_end; t0 += 256) {
+  // Work items are (b,h, 256-token chunk) pairs; a workgroup takes a contiguous run of them, so it
+  // refills its LDS copy of A', S^T, z only when the run crosses into the next (b,h).
+  const int item_begin = blockIdx.x * items_per_wg;
+  const int item_end = min(n_items, item_begin + items_per_wg);
+  int cur_bh = -1;
+  for (int item = item_begin; item < item_end; ++item) {
+    const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
+    if (bh != cur_bh) {
+      const int h = bh % H;
+      if (cur_bh >= 0) __syncthreads();  // everyone is done reading the previous head's operands
+      if (cur_bh < 0 || (cur_bh % H) != h) {
+        for (int ci = tid; ci < m * D / 8; ci += 256) {
+          int row = ci / (D / 8), kc = ci % (D / 8);
+          *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
+              *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
+        }
+      }
+      for (int ci = tid; ci < DV * m / 4; ci += 256) {
+        int row = ci / (m / 4), fc = ci % (m / 4);
+        *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) =
+            *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
+      }
+      for (int i = tid; i < m; i += 256) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
+      for (int i = tid; i < m / 64; i += 256) cl[i] = cf[(size_t)bh * (m / 64) + i];
+      __syncthreads();
+      cur_bh = bh;
+    }
+    const unsigned short* Qb = Qg + (size_t)bh * L * D;
+    const int t0 = chunk * 256 + 64 * wv;
+    const int wg_end = L;
+    if (t0 >= L) continue;  // wave-uniform
     // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
     half8 xf[2][D / 16];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int tok = t0 + 32 * tt + l32;
+      const int tok = min(t0 + 32 * tt + l32, wg_end - 1);  // rows past the end repeat the last row; never stored
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        if (tok < wg_end) raw = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
+        u32x4 raw = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
         u32x4 cv = bf16x8_to_f16x8(raw);
         xf[tt][s] = *reinterpret_cast<half8*>(&cv);
       }
@@ -493,18 +598,23 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
 #pragma unroll
         for (int v = 0; v < 16; ++v) O[ct][tt][v] = 0.f;
     float den[2] = {0.f, 0.f};
-    float mu[2] = {-INFINITY, -INFINITY};
+    // Running per-token shift of the log2-features (lane = token column; both half-waves agree).
+    // Set from the first feature block, afterwards only raised when exceeded by more than 2^kTau.
+    float mu[2] = {0.f, 0.f};
 
     for (int blk = 0; blk < m / 64; ++blk) {
       const float cb = cl[blk];
-      // U^T[ft][tt]: rows = features 64 blk + 32 ft + 8 g + 4 hf + e, column = token 32 tt + l32
+      // U^T[ft][tt]: rows = features 64 blk + 32 ft + 8 g + 4 hf + e, column = token 32 tt + l32.
+      // Accumulators start at c_blk - mu_token, so the MFMA chain delivers shifted log2-features.
       f32x16 U[2][2];
 #pragma unroll
       for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+        for (int tt = 0; tt < 2; ++tt) {
+          const float init = cb - mu[tt];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) U[ft][tt][v] = 0.f;
+          for (int v = 0; v < 16; ++v) U[ft][tt][v] = init;
+        }
 #pragma unroll
       for (int s = 0; s < D / 16; ++s)
 #pragma unroll
@@ -514,34 +624,34 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
           for (int tt = 0; tt < 2; ++tt)
             U[ft][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xf[tt][s], U[ft][tt], 0, 0, 0);
         }
-      // running row shift (per token = per lane column; both halves agree after the exchange)
-      float sh[2];
-      bool changed = false;
-      float fsc[2];
+      float bm[2];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        float bm = -INFINITY;
+        float m0 = -INFINITY;
 #pragma unroll
         for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) bm = fmaxf(bm, U[ft][tt][v]);
-        bm = fmaxf(bm, __shfl_xor(bm, 32, 64)) + cb;
-        fsc[tt] = 1.f;
-        if (bm > mu[tt] + kTau) {
-          fsc[tt] = fast_exp2(mu[tt] - bm);
-          mu[tt] = bm;
-          changed = true;
-        }
-        sh[tt] = mu[tt] - cb;
+          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[ft][tt][v], U[ft][tt][v + 1]);
+        bm[tt] = fmaxf(m0, __shfl_xor(m0, 32, 64));
       }
-      if (__any(changed)) {
+      const bool first = (blk == 0);
+      if (__any(first || bm[0] > kTau || bm[1] > kTau)) {  // rare after the first block
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          den[tt] *= fsc[tt];
+          const float delta = (first || bm[tt] > kTau) ? bm[tt] : 0.f;
+          mu[tt] += delta;
 #pragma unroll
-          for (int ct = 0; ct < DV / 32; ++ct)
+          for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) O[ct][tt][v] *= fsc[tt];
+            for (int v = 0; v < 16; ++v) U[ft][tt][v] -= delta;
+          if (!first) {
+            const float f = fast_exp2(-delta);
+            den[tt] *= f;
+#pragma unroll
+            for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) O[ct][tt][v] *= f;
+          }
         }
       }
       // features, denominator, pack
@@ -553,10 +663,10 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
           u32x2 zv = *reinterpret_cast<const u32x2*>(zl + 64 * blk + 32 * ft + 8 * g + 4 * hf);
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt) {
-            float a0 = fast_exp2(U[ft][tt][4 * g + 0] - sh[tt]);
-            float a1 = fast_exp2(U[ft][tt][4 * g + 1] - sh[tt]);
-            float a2 = fast_exp2(U[ft][tt][4 * g + 2] - sh[tt]);
-            float a3 = fast_exp2(U[ft][tt][4 * g + 3] - sh[tt]);
+            float a0 = fast_exp2(U[ft][tt][4 * g + 0]);
+            float a1 = fast_exp2(U[ft][tt][4 * g + 1]);
+            float a2 = fast_exp2(U[ft][tt][4 * g + 2]);
+            float a3 = fast_exp2(U[ft][tt][4 * g + 3]);
             const unsigned p0 = pack_bf16(a0, a1), p1 = pack_bf16(a2, a3);
             pk[ft][tt][g / 2][2 * (g % 2)] = p0;
             pk[ft][tt][g / 2][2 * (g % 2) + 1] = p1;
@@ -617,7 +727,7 @@ int env_int(const char* name, int dflt) {
 
 struct Plan {
   int P, slice_len, nfb, n_work, kv_grid;
-  int tok_per_wg, wg_per_bh;
+  int chunks_per_bh, n_items, items_per_wg, ro_grid;
 };
 
 Plan make_plan(const Problem& pb) {
@@ -627,7 +737,7 @@ Plan make_plan(const Problem& pb) {
   const long long BH = pb.BH();
   // K pass: about two workgroups per CU (256 CUs); slices are whole tiles.
   int target = env_int("DARK_KV_WGS", 512);
-  long long want = (target + BH * pl.nfb - 1) / (BH * pl.nfb);
+  long long want = target / (BH * pl.nfb);  // rounding down keeps all workgroups co-resident
   if (want < 1) want = 1;
   int sl = (int)((p.L + want - 1) / want);
   sl = ((sl + kTile - 1) / kTile) * kTile;
@@ -635,11 +745,17 @@ Plan make_plan(const Problem& pb) {
   pl.P = (p.L + sl - 1) / sl;
   pl.n_work = (int)(BH * pl.P);
   pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
-  // readout: workgroups of a multiple of 256 tokens
-  int tr = env_int("DARK_RO_TOKENS", 512);
-  tr = ((tr + 255) / 256) * 256;
-  pl.tok_per_wg = tr;
-  pl.wg_per_bh = (p.L + tr - 1) / tr;
+  // readout: (b,h, 256-token chunk) items dealt out in contiguous runs to about as many
+  // workgroups as fit on the chip at once
+  pl.chunks_per_bh = (p.L + 255) / 256;
+  pl.n_items = (int)(BH * pl.chunks_per_bh);
+  int ro_wgs = env_int("DARK_RO_WGS", 0);
+  if (ro_wgs == 0) {
+    const size_t lds = p.d == 64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
+    ro_wgs = 256 * (lds * 2 <= 160 * 1024 && p.d == 64 ? 2 : 1);
+  }
+  pl.items_per_wg = (pl.n_items + ro_wgs - 1) / ro_wgs;
+  pl.ro_grid = (pl.n_items + pl.items_per_wg - 1) / pl.items_per_wg;
   return pl;
 }
 
@@ -661,7 +777,7 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   b.Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
   b.Spart = ar.take<float>(BH * pl.P * p.m * p.dv);
   b.zpart = ar.take<float>(BH * pl.P * p.m);
-  b.cpart = ar.take<float>(BH * pl.P * (p.m / 64));
+  b.cpart = ar.take<float>(BH * pl.P * p.m);
   b.St = ar.take<unsigned short>(BH * p.dv * p.m);
   b.zt = ar.take<float>(BH * p.m);
   b.cf = ar.take<float>(BH * (p.m / 64));
@@ -694,17 +810,17 @@ template <int D, int DV, int MINW>
 dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
   const dark_params& p = pb.p;
   const size_t lds = RoSmem<D, DV>::total(p.m);
-  const unsigned grid = (unsigned)(pb.BH() * pl.wg_per_bh);
+  const unsigned grid = (unsigned)pl.ro_grid;
   if (p.out_dtype == DARK_BF16) {
     auto kern = k_readout<D, DV, true, MINW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, p.m, pl.tok_per_wg, pl.wg_per_bh);
+                b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   } else {
     auto kern = k_readout<D, DV, false, MINW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, p.m, pl.tok_per_wg, pl.wg_per_bh);
+                b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   }
   return DARK_OK;
 }
@@ -733,7 +849,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (ar.base == nullptr) return DARK_OK;
   if (ar.overflow) return DARK_EWORKSPACE;
 
-  const int nA = (p.m + 3) / 4;
+  const int nA = (p.m + kPrepRows - 1) / kPrepRows;
   DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA + 4, p.H), dim3(256), 0, M, W, b.Ah, b.Mh, p.m, p.r, p.d,
               p.w_shared, std::sqrt(pb.scale));
   if (p.d == 64) {
