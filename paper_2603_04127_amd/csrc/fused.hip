@@ -1,23 +1,22 @@
 // Fused MFMA path of the DARK attention library (gfx950): bf16 inputs, fp32 accumulation.
 //
-// Per (b,h), with alpha = sqrt(scale) and everything kept in the log2 domain, the projection is
-// done in the two stages the paper writes (Section 4.1: x~ = M x; Appendix B: omega~^T x = w^T x~):
-//   M'' = alpha M,  W' = log2(e) W          (fp16 MFMA operands, converted in-kernel from fp32)
-//   x~  = M'' x                             (x is bf16, exactly representable in fp16)
-//   n'  = log2(e)/2 |x~|^2                  (fp32, from the MFMA accumulators)
-//   key features    phi_K,lj = exp2(W'_j . x~_l - n'_l - c_j)
-//   query features  phi_Q,ij = exp2(W'_j . x~_i + c - mu_i)
-// c_j is a data-dependent shift (it cancels against the same shift on the query side) and mu_i a
-// per-row shift (cancels in the ratio), so no exponential can overflow.  The query-side norm term
-// is a per-row factor and is dropped.
+// Per (b,h), with alpha = sqrt(scale), A = W M (Appendix B: omega~_j = M^T w_j) and
+// everything kept in the log2 domain:
+//   A' = alpha log2(e) A           (fp16 MFMA operand; x is bf16, exactly representable in fp16)
+//   M' = alpha sqrt(log2(e)/2) M   so that n'(x) = |M' x|^2 = log2(e) * 1/2 |M x'|^2
+//   key features    phi_K,lj = exp2(x_l . A'_j - n'(x_l) - c)      (Section 4.1 feature map)
+//   query features  phi_Q,ij = exp2(x_i . A'_j + c - mu_i)
+// c is a shift shared by a block of 64 features (chosen from the data, it cancels against the
+// same shift on the query side) and mu_i a per-row shift (cancels in the ratio), so no
+// exponential can overflow.  The query-side norm term is a per-row factor and is dropped.
 //
 // Kernels (Section 2, "Efficient attention via random feature kernels": K'^T V first, then Q'):
-//   k_kv_reduce  per (b,h, L-slice, 256-feature block): [S|z] += phi_K^T [V|1]; features never
-//                leave registers: MFMA 1 (W' x~) feeds MFMA 2 (phi^T V) through the accumulator
-//                layout, which is already the operand layout after a bf16 pack.  It also publishes
-//                the fp16 operands M'', W' for the readout.
+//   k_prep       A', M' for every head
+//   k_kv_reduce  per (b,h, L-slice, 256-feature block): [S|z] += phi_K^T [V|1], features never
+//                leave registers; MFMA 1 (projection) feeds MFMA 2 (phi^T V) through the
+//                accumulator layout, which is already the operand layout after a bf16 pack
 //   k_kv_merge   fixed-order merge of the slice states (deterministic), bf16 S^T for the readout
-//   k_readout    per (b,h, 256-token chunk): x~ = M'' q, U = W' x~, out = phi_Q S / phi_Q z
+//   k_readout    per (b,h, token range): out = phi_Q S / phi_Q z
 #include <cmath>
 #include <cstdlib>
 
@@ -88,41 +87,114 @@ __device__ inline float row16_sum(float v) {
 }
 
 // ---------------------------------------------------------------------------
+// k_prep: A'[h][j][:] = alpha log2e sum_t W[h][j][t] M[h][t][:]  (fp16),  M' = alpha sqrt(log2e/2) M.
+// One block per (h, 32 feature rows): the W rows and all of M go to LDS with every global load
+// issued before the first wait, then each thread owns a 2 x (d/16) register tile.  r, d <= 128.
+// ---------------------------------------------------------------------------
+constexpr int kPrepRows = 32;
+__global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const float* __restrict__ W,
+                                              _Float16* __restrict__ Ah, _Float16* __restrict__ Mh, int m, int r,
+                                              int d, int w_shared, float alpha) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* Ws = reinterpret_cast<float*>(smem);   // [32][r + 1]
+  float* Mt = Ws + kPrepRows * (r + 1);         // [r][d]
+  const int h = blockIdx.y;
+  const int j0 = blockIdx.x * kPrepRows;
+  const float* Mp = M + (size_t)h * r * d;
+  const float* w = W + (w_shared ? 0 : (size_t)h * m * r);
+  const int tid = threadIdx.x;
+  // batches of eight independent loads, so that the latencies overlap (the trip counts are not
+  // compile-time constants and the compiler would otherwise serialise load -> LDS store)
+  for (int i0 = tid; i0 < kPrepRows * r; i0 += 256 * 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + 256 * u, jj = i / r, t = i % r;
+      v[u] = (i < kPrepRows * r && j0 + jj < m) ? w[(size_t)(j0 + jj) * r + t] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + 256 * u;
+      if (i < kPrepRows * r) Ws[(i / r) * (r + 1) + i % r] = v[u];
+    }
+  }
+  for (int i0 = tid; i0 < r * d; i0 += 256 * 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (i0 + 256 * u < r * d) ? Mp[i0 + 256 * u] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + 256 * u < r * d) Mt[i0 + 256 * u] = v[u];
+  }
+  __syncthreads();
+  if (blockIdx.x == 0) {
+    const float f = alpha * sqrtf(0.5f * kLog2e);
+    for (int i = tid; i < r * d; i += 256) Mh[(size_t)h * r * d + i] = (_Float16)(Mt[i] * f);
+  }
+  // thread -> rows jq + 16 i (i < 2), columns cq + 16 k (k < d / 16)
+  const int jq = tid / 16, cq = tid % 16;
+  float acc[2][8];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[i][k] = 0.f;
+#pragma unroll 4
+  for (int t = 0; t < r; ++t) {
+    float wv[2], mv[8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wv[i] = Ws[(jq + 16 * i) * (r + 1) + t];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mv[k] = (cq + 16 * k < d) ? Mt[t * d + cq + 16 * k] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[i][k] = fmaf(wv[i], mv[k], acc[i][k]);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int j = j0 + jq + 16 * i;
+    if (j >= m) continue;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (cq + 16 * k < d) Ah[((size_t)h * m + j) * d + cq + 16 * k] = (_Float16)(acc[i][k] * alpha * kLog2e);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // k_kv_reduce
 // Workgroup = 4 waves = 256 features (wave w owns features [64w, 64w+64) of the block) over one
-// L-slice of one (b,h).  Per 64-token tile, software-pipelined over two LDS buffers:
-//   stage A (tile t+1)  wave w takes 16 tokens: K rows straight from HBM in MFMA operand layout,
-//                       x~ = X M''^T (MFMA 16x16x32 f16), n' (DPP row sums) -> LDS, x~ as fp16 -> LDS;
-//                       V tile -> LDS transposed (bf16 [DV][64+4])
-//   stage B (tile t)    per 32-token half: U[tok][feat] = x~ W'^T (MFMA 32x32x16 f16, accumulators
-//                       start at -(n' + c)), phi = exp2(U) packed to bf16 in registers,
-//                       S[feat][dv] += phi^T V (MFMA 32x32x16 bf16), z[feat] += column sums
-// One barrier per tile.
+// L-slice of one (b,h).  Per 64-token tile:
+//   stage   K tile -> LDS as fp16 [64][D+8];  V tile -> LDS transposed bf16 [DV][64+4]
+//   norms   wave w: x~ = X[16w..16w+16) M'^T by MFMA 16x16x32, n' = row sums of squares -> LDS
+//   proj    U[tok][feat] = X A'^T  (MFMA 32x32x16 f16; A' fragments stay in registers)
+//   exp     phi = exp2(U - n' - c) in the accumulator registers, packed to bf16
+//   reduce  S[feat][dv] += phi^T V (MFMA 32x32x16 bf16), z[feat] += column sums of phi
+// Triple-buffered staging, one barrier per tile.
 // ---------------------------------------------------------------------------
 template <int D, int DV, int R>
 struct KvSmem {
-  static constexpr int MS = D + 8;      // fp16 elements per M'' row (pad keeps 16-byte rows off one bank group)
-  static constexpr int XS = R + 8;      // fp16 elements per x~ row
-  static constexpr int VS = kTile + 4;  // bf16 elements per V^T row
-  static constexpr size_t m_bytes = (size_t)R * MS * 2;
-  static constexpr size_t x_bytes = (size_t)2 * kTile * XS * 2;
-  static constexpr size_t v_bytes = (size_t)2 * DV * VS * 2;
+  static constexpr int XS = D + 8;       // fp16 elements per X row (pad keeps 16-byte rows off one bank group)
+  static constexpr int VS = kTile + 4;   // bf16 elements per V^T row
+  static constexpr size_t x_bytes = (size_t)3 * kTile * XS * 2;
+  static constexpr size_t v_bytes = (size_t)3 * DV * VS * 2;
+  static constexpr size_t m_bytes = (size_t)R * XS * 2;
   static constexpr size_t n_bytes = (size_t)2 * kTile * 4;
-  static constexpr size_t total = m_bytes + x_bytes + v_bytes + n_bytes;
+  static constexpr size_t total = x_bytes + v_bytes + m_bytes + n_bytes;
 };
 
 template <int D, int DV, int R, int MINW>
-__global__ __launch_bounds__(256, MINW) void k_kv_reduce(
-    const unsigned short* __restrict__ Kg, const unsigned short* __restrict__ Vg, const float* __restrict__ Mg,
-    const float* __restrict__ Wg, _Float16* __restrict__ Mh, _Float16* __restrict__ Wh, float* __restrict__ Spart,
-    float* __restrict__ zpart, float* __restrict__ cpart, int H, int L, int m, int P, int slice_len, int n_work,
-    int w_shared, float alpha) {
+__global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* __restrict__ Kg,
+                                                         const unsigned short* __restrict__ Vg,
+                                                         const _Float16* __restrict__ Ah,
+                                                         const _Float16* __restrict__ Mh, float* __restrict__ Spart,
+                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
+                                                         int L, int m, int P, int slice_len, int n_work) {
   using SM = KvSmem<D, DV, R>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Ms = reinterpret_cast<_Float16*>(smem);
-  _Float16* Xt = reinterpret_cast<_Float16*>(smem + SM::m_bytes);
-  unsigned short* Vt = reinterpret_cast<unsigned short*>(smem + SM::m_bytes + SM::x_bytes);
-  float* ns = reinterpret_cast<float*>(smem + SM::m_bytes + SM::x_bytes + SM::v_bytes);
+  _Float16* Xs = reinterpret_cast<_Float16*>(smem);
+  unsigned short* Vt = reinterpret_cast<unsigned short*>(smem + SM::x_bytes);
+  _Float16* Ms = reinterpret_cast<_Float16*>(smem + SM::x_bytes + SM::v_bytes);
+  float* ns = reinterpret_cast<float*>(smem + SM::x_bytes + SM::v_bytes + SM::m_bytes);
 
   // blockIdx -> (work item (bh, slice), feature block): the feature blocks of one work item are
   // 8 apart in blockIdx so that they land on the same XCD and share its L2 for the K/V tiles.
@@ -135,7 +207,6 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(
   const int tok_begin = p * slice_len;
   const int tok_end = min(L, tok_begin + slice_len);
   const int ntile = (tok_end - tok_begin + kTile - 1) / kTile;
-  const bool publish = (bh < H) && p == 0;  // batch 0, first slice: writes the fp16 operands of head h
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
@@ -143,96 +214,88 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(
   const int f0 = fb * 256 + wv * 64;  // first feature of this wave
 
   // --- resident operands -----------------------------------------------------------------
-  // M'' = alpha M -> LDS (fp16)
+  // M' -> LDS
   for (int ci = tid; ci < R * D / 8; ci += 256) {
-    const int row = ci / (D / 8), kc = ci % (D / 8);
-    const float* src = Mg + ((size_t)h * R + row) * D + 8 * kc;
-    const f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
-    half8 o = {(_Float16)(a[0] * alpha), (_Float16)(a[1] * alpha), (_Float16)(a[2] * alpha), (_Float16)(a[3] * alpha),
-               (_Float16)(b[0] * alpha), (_Float16)(b[1] * alpha), (_Float16)(b[2] * alpha), (_Float16)(b[3] * alpha)};
-    *reinterpret_cast<half8*>(Ms + row * SM::MS + 8 * kc) = o;
-    if (publish && fb == 0) *reinterpret_cast<half8*>(Mh + ((size_t)h * R + row) * D + 8 * kc) = o;
+    int row = ci / (D / 8), kc = ci % (D / 8);
+    u32x4 v = *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
+    *reinterpret_cast<u32x4*>(Ms + row * SM::XS + 8 * kc) = v;
   }
-  // W' = log2(e) W fragments (B operand of the projection): feature f0 + 32 ft + l32, r = 16 s + 8 hf + [0,8)
-  half8 wfr[2][R / 16];
-  {
-    const float* Wb = Wg + (w_shared ? (size_t)0 : (size_t)h * m * R);
+  // A' fragments (B operand of the projection): feature = f0 + 32 ft + l32, k = 16 s + 8 hf + [0,8)
+  half8 afr[2][D / 16];
 #pragma unroll
-    for (int ft = 0; ft < 2; ++ft)
+  for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-      for (int s = 0; s < R / 16; ++s) {
-        const size_t off = (size_t)(f0 + 32 * ft + l32) * R + 16 * s + 8 * hf;
-        const f32x4 a = *reinterpret_cast<const f32x4*>(Wb + off), b = *reinterpret_cast<const f32x4*>(Wb + off + 4);
-        half8 o = {(_Float16)(a[0] * kLog2e), (_Float16)(a[1] * kLog2e), (_Float16)(a[2] * kLog2e),
-                   (_Float16)(a[3] * kLog2e), (_Float16)(b[0] * kLog2e), (_Float16)(b[1] * kLog2e),
-                   (_Float16)(b[2] * kLog2e), (_Float16)(b[3] * kLog2e)};
-        wfr[ft][s] = o;
-        if (publish) *reinterpret_cast<half8*>(Wh + (size_t)h * m * R + off) = o;
-      }
-  }
+    for (int s = 0; s < D / 16; ++s)
+      afr[ft][s] = *reinterpret_cast<const half8*>(Ah + ((size_t)h * m + f0 + 32 * ft + l32) * D + 16 * s + 8 * hf);
 
-  // --- staging -----------------------------------------------------------------------------
-  constexpr int KCH = D / 32;   // 16-byte pieces of this wave's K rows per lane
+  // --- staging helpers -------------------------------------------------------------------
+  constexpr int KCH = D / 32;   // 16-byte chunks of the K tile per thread
   constexpr int VCH = DV / 32;  // 16-byte chunks of the V tile per thread
   u32x4 kreg[KCH], vreg[VCH];
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DV;
-  // Rows past the end of the slice are read from the slice's last row instead (always in bounds, no
-  // predication, so the loads stay in flight across the tile); their features are forced to zero
-  // through the norm term, so what they hold never reaches S or z.
+  // Rows past the end of the slice are read from the slice's last row instead (always in
+  // bounds, no predication, so the loads stay in flight across the tile); their features are
+  // forced to zero through the norm term, so what they hold never reaches S or z.
   auto load_tile = [&](int t) {
     const int t0 = tok_begin + t * kTile;
-    const int ktok = min(t0 + 16 * wv + l16, tok_end - 1);
 #pragma unroll
-    for (int s = 0; s < KCH; ++s) kreg[s] = *reinterpret_cast<const u32x4*>(Kb + (size_t)ktok * D + 32 * s + 8 * g16);
+    for (int i = 0; i < KCH; ++i) {
+      int ci = tid + 256 * i, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
+    }
 #pragma unroll
     for (int i = 0; i < VCH; ++i) {
-      const int ci = tid + 256 * i, tok = min(t0 + ci / (DV / 8), tok_end - 1), cc = ci % (DV / 8);
+      int ci = tid + 256 * i, tok = min(t0 + ci / (DV / 8), tok_end - 1), cc = ci % (DV / 8);
       vreg[i] = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DV + 8 * cc);
     }
   };
-  auto stage_a = [&](int t, int buf) {
-    // x~ of this wave's 16 tokens: rows = tokens 4 g16 + v, column = r index 16 rt + l16
-    f32x4 acc[R / 16];
-#pragma unroll
-    for (int rt = 0; rt < R / 16; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-      u32x4 cv = bf16x8_to_f16x8(kreg[s]);
-      const half8 a = *reinterpret_cast<half8*>(&cv);
-#pragma unroll
-      for (int rt = 0; rt < R / 16; ++rt) {
-        const half8 b = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::MS + 32 * s + 8 * g16);
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[rt], 0, 0, 0);
-      }
-    }
-    f32x4 ss = {0.f, 0.f, 0.f, 0.f};
-    _Float16* xt = Xt + buf * kTile * SM::XS + (16 * wv + 4 * g16) * SM::XS + l16;
-#pragma unroll
-    for (int rt = 0; rt < R / 16; ++rt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        ss[v] = fmaf(acc[rt][v], acc[rt][v], ss[v]);
-        xt[v * SM::XS + 16 * rt] = (_Float16)acc[rt][v];
-      }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) ss[v] = row16_sum(ss[v]);
-    if (l16 == 0) {
-      const int t0 = tok_begin + t * kTile + 16 * wv + 4 * g16;
-#pragma unroll
-      for (int v = 0; v < 4; ++v)  // stored negated; rows past the end contribute exp2(-huge) = 0
-        ss[v] = (t0 + v >= tok_end) ? -1e30f : -(0.5f * kLog2e) * ss[v];
-      *reinterpret_cast<f32x4*>(ns + buf * kTile + 16 * wv + 4 * g16) = ss;
-    }
+  auto store_tile = [&](int buf) {
+    _Float16* xs = Xs + buf * kTile * SM::XS;
     unsigned short* vt = Vt + buf * DV * SM::VS;
 #pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
+      *reinterpret_cast<u32x4*>(xs + tok * SM::XS + 8 * kc) = bf16x8_to_f16x8(kreg[i]);
+    }
+#pragma unroll
     for (int i = 0; i < VCH; ++i) {
-      const int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
+      int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         vt[(8 * cc + 2 * e) * SM::VS + tok] = (unsigned short)(vreg[i][e] & 0xffffu);
         vt[(8 * cc + 2 * e + 1) * SM::VS + tok] = (unsigned short)(vreg[i][e] >> 16);
       }
+    }
+  };
+  // n' of this wave's 16 tokens of the tile in buffer `buf` -> ns[nb]
+  auto norms = [&](int buf, int nb, int t) {
+    const _Float16* xs = Xs + buf * kTile * SM::XS;
+    f32x4 acc[R / 16];
+#pragma unroll
+    for (int rt = 0; rt < R / 16; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+      half8 a = *reinterpret_cast<const half8*>(xs + (16 * wv + l16) * SM::XS + 32 * s + 8 * g16);
+#pragma unroll
+      for (int rt = 0; rt < R / 16; ++rt) {
+        half8 b = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::XS + 32 * s + 8 * g16);
+        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[rt], 0, 0, 0);
+      }
+    }
+    f32x4 ss = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rt = 0; rt < R / 16; ++rt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) ss[v] = fmaf(acc[rt][v], acc[rt][v], ss[v]);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) ss[v] = row16_sum(ss[v]);
+    if (l16 == 0) {
+      const int t0 = tok_begin + t * kTile + 16 * wv + 4 * g16;
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        ss[v] = (t0 + v >= tok_end) ? -1e30f : -ss[v];  // rows past the end contribute exp2(-huge) = 0
+      *reinterpret_cast<f32x4*>(ns + nb * kTile + 16 * wv + 4 * g16) = ss;  // stored negated
     }
   };
 
@@ -246,130 +309,134 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(
       for (int v = 0; v < 16; ++v) S[ft][ct][v] = 0.f;
   float z[2] = {0.f, 0.f};
   // Per-feature shift (lane = feature column of the projection; both half-waves agree).  It is set
-  // from the first half-tile and afterwards only raised when a column sum says it is far too low.
+  // from the first tile and afterwards only raised when a tile exceeds it by more than 2^kTau.
   float c[2] = {0.f, 0.f};
 
-  // The W' fragments must have arrived before the loop: otherwise the compiler's wait for them sits
+  // --- prologue: tile 0 into buffer 0, tile 1 in flight ------------------------------------
+  if (ntile > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  // The A' fragments must have arrived before the loop: otherwise the compiler's wait for them sits
   // inside the loop body, where (the counter being in-order) it would also wait for the tile
   // prefetch issued a few instructions earlier.
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-    for (int s = 0; s < R / 16; ++s) asm volatile("" ::"v"(wfr[ft][s]));
-  __syncthreads();  // M'' visible
-  if (ntile > 0) {
-    load_tile(0);
-    stage_a(0, 0);
-    if (ntile > 1) load_tile(1);
-  }
+    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(afr[ft][s]));
+  if (ntile > 1) load_tile(1);
   __syncthreads();
 
   for (int t = 0; t < ntile; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < ntile) {
-      stage_a(t + 1, buf ^ 1);
-      if (t + 2 < ntile) load_tile(t + 2);
-    }
-    const _Float16* xt = Xt + buf * kTile * SM::XS;
+    const int buf = t % 3, nb = t & 1;
+    norms(buf, nb, t);
+    if (t + 1 < ntile) store_tile((t + 1) % 3);
+    if (t + 2 < ntile) load_tile(t + 2);
+    __syncthreads();
+
+    const _Float16* xs = Xs + buf * kTile * SM::XS;
     const unsigned short* vt = Vt + buf * DV * SM::VS;
-    const float* nsb = ns + buf * kTile;
+    // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
+    // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
+    // log2-features directly.
+    f32x16 U[2][2];
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      // V fragments of this half (issued early): k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4
-      u32x4 bv[2][DV / 32];
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) U[tt][ft][4 * g + e] = nv[e] - c[ft];
+      }
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        half8 a = *reinterpret_cast<const half8*>(xs + (32 * tt + l32) * SM::XS + 16 * s + 8 * hf);
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft)
+          U[tt][ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[tt][ft], 0, 0, 0);
+      }
+    // features, packed to bf16 in the operand layout of the second MFMA
+    u32x4 pk[2][2][2];  // [tt][ft][hh]: k-slots s <-> accumulator registers 8 hh + s
+    float zs[2];        // this tile's column sums (this lane's tokens)
+    auto featurize = [&]() {
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        float acc = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              float a = fast_exp2(U[tt][ft][8 * hh + 2 * q]);
+              float b = fast_exp2(U[tt][ft][8 * hh + 2 * q + 1]);
+              pk[tt][ft][hh][q] = pack_bf16(a, b);
+              // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
+              // convex combination of value rows
+              acc = dot2_bf16(pk[tt][ft][hh][q], kOnesBf16x2, acc);
+            }
+        zs[ft] = acc;
+      }
+    };
+    // Common path: exponentiate with the current shifts and look at the column sums afterwards;
+    // a sum of 2^kTau or more (or inf) means some shift is far too low for this tile.
+    bool fix = (t == 0);
+    if (!fix) {
+      featurize();
+      fix = __any(!(zs[0] < kBig) || !(zs[1] < kBig));
+    }
+    if (fix) {  // first tile, or rare
+      const bool first = (t == 0);
+#pragma unroll
+      for (int ft = 0; ft < 2; ++ft) {
+        float m0 = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[tt][ft][v], U[tt][ft][v + 1]);
+        m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
+        const float delta = (first || m0 > kRaise) ? m0 : 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) U[tt][ft][v] -= delta;
+        c[ft] += delta;
+        if (!first) {
+          const float f = fast_exp2(-delta);
+          z[ft] *= f;
+          // S rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
+#pragma unroll
+            for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
+          }
+        }
+      }
+      featurize();
+    }
+    z[0] += zs[0];
+    z[1] += zs[1];
+    // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
         for (int ct = 0; ct < DV / 32; ++ct) {
           const unsigned short* vr = vt + (32 * ct + l32) * SM::VS + 32 * tt + 16 * hh + 4 * hf;
-          const u32x2 lo = *reinterpret_cast<const u32x2*>(vr), hi = *reinterpret_cast<const u32x2*>(vr + 8);
-          bv[hh][ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-        }
-      // projection: U[ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32; the
-      // accumulators start at -(n'_token + c_feature), so the MFMA chain delivers shifted log2-features
-      f32x16 U[2];
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 nv = *reinterpret_cast<const f32x4*>(nsb + 32 * tt + 8 * g + 4 * hf);
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) U[ft][4 * g + e] = nv[e] - c[ft];
-      }
-#pragma unroll
-      for (int s = 0; s < R / 16; ++s) {
-        const half8 a = *reinterpret_cast<const half8*>(xt + (32 * tt + l32) * SM::XS + 16 * s + 8 * hf);
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft) U[ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, wfr[ft][s], U[ft], 0, 0, 0);
-      }
-      // features, packed to bf16 in the operand layout of the second MFMA
-      u32x4 pk[2][2];  // [ft][hh]: k-slots s <-> accumulator registers 8 hh + s
-      float zs[2];     // this half-tile's column sums (this lane's tokens)
-      auto featurize = [&]() {
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
-          float acc = 0.f;
-#pragma unroll
-          for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const float a = fast_exp2(U[ft][8 * hh + 2 * q]);
-              const float b = fast_exp2(U[ft][8 * hh + 2 * q + 1]);
-              pk[ft][hh][q] = pack_bf16(a, b);
-              // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
-              // convex combination of value rows
-              acc = dot2_bf16(pk[ft][hh][q], kOnesBf16x2, acc);
-            }
-          zs[ft] = acc;
-        }
-      };
-      // Common path: exponentiate with the current shifts and look at the column sums afterwards; a
-      // sum of 2^kTau or more (or inf) means some shift is far too low for this half-tile.
-      const bool first = (t == 0 && tt == 0);
-      bool fix = first;
-      if (!first) {
-        featurize();
-        fix = __any(!(zs[0] < kBig) || !(zs[1] < kBig));
-      }
-      if (fix) {  // first half-tile, or rare
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
-          float m0 = -INFINITY;
-#pragma unroll
-          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[ft][v], U[ft][v + 1]);
-          m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
-          const float delta = (first || m0 > kRaise) ? m0 : 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) U[ft][v] -= delta;
-          c[ft] += delta;
-          if (!first) {
-            const float f = fast_exp2(-delta);
-            z[ft] *= f;
-            // S rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
-#pragma unroll
-              for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
-            }
-          }
-        }
-        featurize();
-      }
-      z[0] += zs[0];
-      z[1] += zs[1];
-      // S[ft][ct] += phi^T V
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct)
+          u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
+          u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
+          u32x4 bv = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
           for (int ft = 0; ft < 2; ++ft)
-            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[ft][hh]),
-                                                                *reinterpret_cast<bf16x8*>(&bv[hh][ct]), S[ft][ct],
-                                                                0, 0, 0);
-    }
-    __syncthreads();
+            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[tt][ft][hh]),
+                                                                *reinterpret_cast<bf16x8*>(&bv), S[ft][ct], 0, 0, 0);
+        }
   }
 
   // --- epilogue: partial state of this slice -------------------------------------------------
@@ -380,10 +447,10 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(
     for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int feat = f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
+        int feat = f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
         Spart[(pbase * m + feat) * DV + 32 * ct + l32] = S[ft][ct][v];
       }
-    const float zt = z[ft] + __shfl_xor(z[ft], 32, 64);
+    float zt = z[ft] + __shfl_xor(z[ft], 32, 64);
     if (hf == 0) {
       zpart[pbase * m + f0 + 32 * ft + l32] = zt;
       cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
@@ -465,69 +532,42 @@ __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spar
 
 // ---------------------------------------------------------------------------
 // k_readout
-// Workgroup = 4 waves; work items are (b,h, 256-token chunk) pairs dealt out in contiguous runs, each
-// wave owns 64 tokens of an item:
-//   x~^T[r][tok]   = M'' X^T           (MFMA f16; M'' from LDS, X fragments converted bf16->fp16)
-//   U^T[feat][tok] = W' x~^T           (MFMA f16; W' from LDS, x~ packed to fp16 in registers; the
-//                                       accumulator layout of the first product is the operand
-//                                       layout of the second, W' is stored with the matching
-//                                       permutation of r), 32 features at a time
+// Workgroup = 4 waves; each wave owns 64 tokens per step and sweeps all features in blocks of 64:
+//   U^T[feat][tok] = A' X^T (MFMA f16; A' from LDS, X fragments in registers, converted bf16->fp16)
 //   phi^T = exp2(U^T + c_blk - mu_tok), mu a lazily raised running row shift
 //   out^T[c][tok] += S^T[c][feat] phi^T[feat][tok] (MFMA bf16; S^T from LDS),  den += phi . z
-// No barrier in the main loop (only when the run crosses into the next (b,h)).
+// No barrier in the main loop.
 // ---------------------------------------------------------------------------
-template <int D, int DV, int R>
+template <int D, int DV>
 struct RoSmem {
-  static constexpr int MS = D + 8;
-  static constexpr int WS = R + 8;
-  __host__ __device__ static size_t m_bytes() { return (size_t)R * MS * 2; }
-  __host__ __device__ static size_t w_bytes(int m) { return (size_t)m * WS * 2; }
+  static constexpr int AS = D + 8;
+  __host__ __device__ static size_t a_bytes(int m) { return (size_t)m * AS * 2; }
   __host__ __device__ static size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
-  __host__ __device__ static size_t c_bytes(int m) { return (size_t)(m / 64 + 4) * 4; }
-  __host__ __device__ static size_t total(int m) { return m_bytes() + w_bytes(m) + s_bytes(m) + c_bytes(m) + (size_t)m * 2; }
+  __host__ __device__ static size_t total(int m) { return a_bytes(m) + s_bytes(m) + (size_t)m * 4 + (size_t)(m / 64) * 4 + 16; }
 };
 
-template <int D, int DV, int R, bool OUT_BF16, int MINW>
+template <int D, int DV, bool OUT_BF16, int MINW>
 __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __restrict__ Qg,
-                                                       const _Float16* __restrict__ Mh,
-                                                       const _Float16* __restrict__ Wh,
+                                                       const _Float16* __restrict__ Ah,
                                                        const unsigned short* __restrict__ St,
                                                        const float* __restrict__ zt, const float* __restrict__ cf,
                                                        void* __restrict__ outp, int H, int L, int m,
                                                        int chunks_per_bh, int n_items, int items_per_wg) {
-  using SM = RoSmem<D, DV, R>;
+  using SM = RoSmem<D, DV>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Ms = reinterpret_cast<_Float16*>(smem);
-  _Float16* Wp = reinterpret_cast<_Float16*>(smem + SM::m_bytes());
-  unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::m_bytes() + SM::w_bytes(m));
-  float* cl = reinterpret_cast<float*>(smem + SM::m_bytes() + SM::w_bytes(m) + SM::s_bytes(m));
-  unsigned short* zl = reinterpret_cast<unsigned short*>(smem + SM::m_bytes() + SM::w_bytes(m) + SM::s_bytes(m) +
-                                                         SM::c_bytes(m));  // z as bf16
+  _Float16* Asl = reinterpret_cast<_Float16*>(smem);
+  unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::a_bytes(m));
+  float* cl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));
+  unsigned short* zl = reinterpret_cast<unsigned short*>(cl + m / 64 + 4);  // z as bf16, 8-byte aligned rows of 4
   const int SS = m + 4;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
 
+  // Work items are (b,h, 256-token chunk) pairs; a workgroup takes a contiguous run of them, so it
+  // refills its LDS copy of A', S^T, z only when the run crosses into the next (b,h).
   const int item_begin = blockIdx.x * items_per_wg;
   const int item_end = min(n_items, item_begin + items_per_wg);
-  if (item_begin >= item_end) return;
-
-  // X fragments (B operand of the first product): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8).
-  // Rows past the end repeat the last row; they are computed but never stored.
-  u32x4 xraw[2][D / 16];
-  auto load_x = [&](int item) {
-    const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
-    const unsigned short* Qb = Qg + (size_t)bh * L * D;
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int tok = min(chunk * 256 + 64 * wv + 32 * tt + l32, L - 1);
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s)
-        xraw[tt][s] = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
-    }
-  };
-  load_x(item_begin);
-
   int cur_bh = -1;
   for (int item = item_begin; item < item_end; ++item) {
     const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
@@ -535,72 +575,54 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
       const int h = bh % H;
       if (cur_bh >= 0) __syncthreads();  // everyone is done reading the previous head's operands
       if (cur_bh < 0 || (cur_bh % H) != h) {
-        for (int ci = tid; ci < R * D / 8; ci += 256) {
-          const int row = ci / (D / 8), kc = ci % (D / 8);
-          *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) =
-              *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
-        }
-        // W' rows with r permuted so that the eight values of one operand fragment are contiguous:
-        // fragment (rt, hh, half hf) slot s holds r = 32 rt + 16 hh + 8 (s/4) + 4 hf + s%4
-        for (int ci = tid; ci < m * R / 4; ci += 256) {
-          const int row = ci / (R / 4), r0 = 4 * (ci % (R / 4));
-          const int pos = (((r0 / 32) * 2 + (r0 % 32) / 16) * 2 + (r0 % 8) / 4) * 8 + 4 * ((r0 % 16) / 8);
-          *reinterpret_cast<u32x2*>(Wp + row * SM::WS + pos) =
-              *reinterpret_cast<const u32x2*>(Wh + ((size_t)h * m + row) * R + r0);
+        for (int c0 = tid; c0 < m * D / 8; c0 += 256 * 8) {  // m * D / 8 is a multiple of 2048
+          u32x4 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int ci = c0 + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+            v[u] = *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int ci = c0 + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+            *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) = v[u];
+          }
         }
       }
-      for (int ci = tid; ci < DV * m / 4; ci += 256) {
-        const int row = ci / (m / 4), fc = ci % (m / 4);
-        *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) =
-            *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
+      for (int c0 = tid; c0 < DV * m / 4; c0 += 256 * 16) {  // DV * m / 4 is a multiple of 4096
+        u32x2 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int ci = c0 + 256 * u, row = ci / (m / 4), fc = ci % (m / 4);
+          v[u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int ci = c0 + 256 * u, row = ci / (m / 4), fc = ci % (m / 4);
+          *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) = v[u];
+        }
       }
       for (int i = tid; i < m; i += 256) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
       for (int i = tid; i < m / 64; i += 256) cl[i] = cf[(size_t)bh * (m / 64) + i];
       __syncthreads();
       cur_bh = bh;
     }
+    const unsigned short* Qb = Qg + (size_t)bh * L * D;
     const int t0 = chunk * 256 + 64 * wv;
-
-    // x~^T = M'' X^T, then packed to fp16 as the B operand of the projection
-    u32x4 xt[2][R / 16];  // [tt][kk], kk = 2 rt + hh
-    {
-      half8 xq[2][D / 16];
+    const int wg_end = L;
+    if (t0 >= L) continue;  // wave-uniform
+    // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
+    half8 xf[2][D / 16];
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tok = min(t0 + 32 * tt + l32, wg_end - 1);  // rows past the end repeat the last row; never stored
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-          u32x4 cv = bf16x8_to_f16x8(xraw[tt][s]);
-          xq[tt][s] = *reinterpret_cast<half8*>(&cv);
-        }
-      if (item + 1 < item_end) load_x(item + 1);  // prefetch the next item's rows
-#pragma unroll
-      for (int rt = 0; rt < R / 32; ++rt) {
-        f32x16 XT[2];
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) XT[tt][v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-          const half8 a = *reinterpret_cast<const half8*>(Ms + (32 * rt + l32) * SM::MS + 16 * s + 8 * hf);
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) XT[tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xq[tt][s], XT[tt], 0, 0, 0);
-        }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              // round to nearest: a truncating pack would shrink every x~ and bias all logits
-              typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-              f16x2 pr = {(_Float16)XT[tt][8 * hh + 2 * q], (_Float16)XT[tt][8 * hh + 2 * q + 1]};
-              xt[tt][2 * rt + hh][q] = *reinterpret_cast<unsigned*>(&pr);
-            }
+      for (int s = 0; s < D / 16; ++s) {
+        u32x4 raw = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
+        u32x4 cv = bf16x8_to_f16x8(raw);
+        xf[tt][s] = *reinterpret_cast<half8*>(&cv);
       }
     }
-    if (t0 >= L) continue;  // wave-uniform: this wave's 64 tokens are all past the end
-
     f32x16 O[DV / 32][2];
 #pragma unroll
     for (int ct = 0; ct < DV / 32; ++ct)
@@ -610,43 +632,51 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
         for (int v = 0; v < 16; ++v) O[ct][tt][v] = 0.f;
     float den[2] = {0.f, 0.f};
     // Running per-token shift of the log2-features (lane = token column; both half-waves agree).
-    // Set from the first 32 features, afterwards only raised when exceeded by more than 2^kTau.
+    // Set from the first feature block, afterwards only raised when exceeded by more than 2^kTau.
     float mu[2] = {0.f, 0.f};
 
-    for (int fh = 0; fh < m / 32; ++fh) {  // 32 features at a time
-      const float cb = cl[fh / 2];
-      // U^T[tt]: rows = features 32 fh + 8 g + 4 hf + e, column = token 32 tt + l32.  Accumulators
-      // start at c_blk - mu_token, so the MFMA chain delivers shifted log2-features.
-      f32x16 U[2];
+    for (int blk = 0; blk < m / 64; ++blk) {
+      const float cb = cl[blk];
+      // U^T[ft][tt]: rows = features 64 blk + 32 ft + 8 g + 4 hf + e, column = token 32 tt + l32.
+      // Accumulators start at c_blk - mu_token, so the MFMA chain delivers shifted log2-features.
+      f32x16 U[2][2];
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const float init = cb - mu[tt];
+      for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) U[tt][v] = init;
-      }
+        for (int tt = 0; tt < 2; ++tt) {
+          const float init = cb - mu[tt];
 #pragma unroll
-      for (int kk = 0; kk < R / 16; ++kk) {
-        const half8 a = *reinterpret_cast<const half8*>(Wp + (32 * fh + l32) * SM::WS + (2 * kk + hf) * 8);
+          for (int v = 0; v < 16; ++v) U[ft][tt][v] = init;
+        }
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-          U[tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, *reinterpret_cast<half8*>(&xt[tt][kk]), U[tt], 0, 0, 0);
-      }
+      for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+          half8 a = *reinterpret_cast<const half8*>(Asl + (64 * blk + 32 * ft + l32) * SM::AS + 16 * s + 8 * hf);
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+            U[ft][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xf[tt][s], U[ft][tt], 0, 0, 0);
+        }
       float bm[2];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         float m0 = -INFINITY;
 #pragma unroll
-        for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[tt][v], U[tt][v + 1]);
+        for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[ft][tt][v], U[ft][tt][v + 1]);
         bm[tt] = fmaxf(m0, __shfl_xor(m0, 32, 64));
       }
-      const bool first = (fh == 0);
-      if (__any(first || bm[0] > kTau || bm[1] > kTau)) {  // rare after the first 32 features
+      const bool first = (blk == 0);
+      if (__any(first || bm[0] > kTau || bm[1] > kTau)) {  // rare after the first block
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
           const float delta = (first || bm[tt] > kTau) ? bm[tt] : 0.f;
           mu[tt] += delta;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) U[tt][v] -= delta;
+          for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) U[ft][tt][v] -= delta;
           if (!first) {
             const float f = fast_exp2(-delta);
             den[tt] *= f;
@@ -658,51 +688,56 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
         }
       }
       // features, denominator, pack
-      u32x4 pk[2][2];  // [tt][hh]
+      u32x4 pk[2][2][2];  // [ft][tt][hh]
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const u32x2 zv = *reinterpret_cast<const u32x2*>(zl + 32 * fh + 8 * g + 4 * hf);
+      for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const float a0 = fast_exp2(U[tt][4 * g + 0]);
-          const float a1 = fast_exp2(U[tt][4 * g + 1]);
-          const float a2 = fast_exp2(U[tt][4 * g + 2]);
-          const float a3 = fast_exp2(U[tt][4 * g + 3]);
-          const unsigned p0 = pack_bf16(a0, a1), p1 = pack_bf16(a2, a3);
-          pk[tt][g / 2][2 * (g % 2)] = p0;
-          pk[tt][g / 2][2 * (g % 2) + 1] = p1;
-          // the denominator weights are the same rounded features that multiply S
-          den[tt] = dot2_bf16(p1, zv[1], dot2_bf16(p0, zv[0], den[tt]));
+        for (int g = 0; g < 4; ++g) {
+          u32x2 zv = *reinterpret_cast<const u32x2*>(zl + 64 * blk + 32 * ft + 8 * g + 4 * hf);
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            float a0 = fast_exp2(U[ft][tt][4 * g + 0]);
+            float a1 = fast_exp2(U[ft][tt][4 * g + 1]);
+            float a2 = fast_exp2(U[ft][tt][4 * g + 2]);
+            float a3 = fast_exp2(U[ft][tt][4 * g + 3]);
+            const unsigned p0 = pack_bf16(a0, a1), p1 = pack_bf16(a2, a3);
+            pk[ft][tt][g / 2][2 * (g % 2)] = p0;
+            pk[ft][tt][g / 2][2 * (g % 2) + 1] = p1;
+            // the denominator weights are the same rounded features that multiply S
+            den[tt] = dot2_bf16(p1, zv[1], dot2_bf16(p0, zv[0], den[tt]));
+          }
         }
-      }
-      // out^T[ct][tt] += S^T phi^T : k-slot s of half hf is feature 32 fh + 16 hh + 8 (s/4) + 4 hf + s%4
+      // out^T[ct][tt] += S^T phi^T : k-slot s of half hf is feature 64 blk + 32 ft + 16 hh + 8 (s/4) + 4 hf + s%4
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
+      for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct) {
-          const unsigned short* sr = Stl + (32 * ct + l32) * SS + 32 * fh + 16 * hh + 4 * hf;
-          const u32x2 lo = *reinterpret_cast<const u32x2*>(sr), hi = *reinterpret_cast<const u32x2*>(sr + 8);
-          u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+        for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-            O[ct][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av),
-                                                                *reinterpret_cast<bf16x8*>(&pk[tt][hh]), O[ct][tt],
-                                                                0, 0, 0);
-        }
+          for (int ct = 0; ct < DV / 32; ++ct) {
+            const unsigned short* sr = Stl + (32 * ct + l32) * SS + 64 * blk + 32 * ft + 16 * hh + 4 * hf;
+            u32x2 lo = *reinterpret_cast<const u32x2*>(sr);
+            u32x2 hi = *reinterpret_cast<const u32x2*>(sr + 8);
+            u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+              O[ct][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av),
+                                                                  *reinterpret_cast<bf16x8*>(&pk[ft][tt][hh]),
+                                                                  O[ct][tt], 0, 0, 0);
+          }
     }
     // normalise and store: register v of O[ct][tt] is out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4]
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int tok = t0 + 32 * tt + l32;
       const float inv = 1.f / (den[tt] + __shfl_xor(den[tt], 32, 64));
-      if (tok < L) {
+      if (tok < wg_end) {
 #pragma unroll
         for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const size_t o = ((size_t)bh * L + tok) * DV + 32 * ct + 8 * g + 4 * hf;
-            const float v0 = O[ct][tt][4 * g] * inv, v1 = O[ct][tt][4 * g + 1] * inv;
-            const float v2 = O[ct][tt][4 * g + 2] * inv, v3 = O[ct][tt][4 * g + 3] * inv;
+            float v0 = O[ct][tt][4 * g] * inv, v1 = O[ct][tt][4 * g + 1] * inv;
+            float v2 = O[ct][tt][4 * g + 2] * inv, v3 = O[ct][tt][4 * g + 3] * inv;
             if (OUT_BF16) {
               u32x2 w = {pack_bf16(v0, v1), pack_bf16(v2, v3)};
               *reinterpret_cast<u32x2*>(reinterpret_cast<unsigned short*>(outp) + o) = w;
@@ -749,7 +784,8 @@ Plan make_plan(const Problem& pb) {
   pl.n_items = (int)(BH * pl.chunks_per_bh);
   int ro_wgs = env_int("DARK_RO_WGS", 0);
   if (ro_wgs == 0) {
-    ro_wgs = 256 * (RoSmem<64, 64, 64>::total(p.m) * 2 <= 160 * 1024 ? 2 : 1);
+    const size_t lds = p.d == 64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
+    ro_wgs = 256 * (lds * 2 <= 160 * 1024 && p.d == 64 ? 2 : 1);
   }
   pl.items_per_wg = (pl.n_items + ro_wgs - 1) / ro_wgs;
   pl.ro_grid = (pl.n_items + pl.items_per_wg - 1) / pl.items_per_wg;
@@ -757,8 +793,8 @@ Plan make_plan(const Problem& pb) {
 }
 
 struct FusedBufs {
-  _Float16* Wh;  // [H][m][r] fp16, log2(e) W
-  _Float16* Mh;  // [H][r][d] fp16, sqrt(scale) M
+  _Float16* Ah;
+  _Float16* Mh;
   float* Spart;
   float* zpart;
   float* cpart;
@@ -770,7 +806,7 @@ struct FusedBufs {
 void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   const dark_params& p = pb.p;
   const size_t BH = (size_t)pb.BH();
-  b.Wh = ar.take<_Float16>((size_t)p.H * p.m * p.r);
+  b.Ah = ar.take<_Float16>((size_t)p.H * p.m * p.d);
   b.Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
   b.Spart = ar.take<float>(BH * pl.P * p.m * p.dv);
   b.zpart = ar.take<float>(BH * pl.P * p.m);
@@ -780,44 +816,48 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   b.cf = ar.take<float>(BH * (p.m / 64));
 }
 
+// Raises a kernel's dynamic-LDS limit when it needs more than the default 64 KB; done once per
+// kernel and size (the attribute call is host work we do not want on every launch).
 template <typename KernelT>
 dark_status allow_lds(KernelT kernel, size_t bytes) {
   if (bytes > 160 * 1024) return DARK_EUNSUPPORTED;
-  if (bytes > 48 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)bytes) != hipSuccess)
-      return DARK_EHIP;
-  }
+  if (bytes <= 48 * 1024) return DARK_OK;
+  static size_t granted = 0;  // one instance per kernel type
+  static const void* granted_for = nullptr;
+  const void* fn = reinterpret_cast<const void*>(kernel);
+  if (granted_for == fn && granted >= bytes) return DARK_OK;
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return DARK_EHIP;
+  granted = bytes;
+  granted_for = fn;
   return DARK_OK;
 }
 
 template <int D, int DV, int R, int MINW>
-dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* K, const void* V,
-                      const float* M, const float* W) {
+dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* K, const void* V) {
   const dark_params& p = pb.p;
   auto kern = k_kv_reduce<D, DV, R, MINW>;
   const size_t lds = KvSmem<D, DV, R>::total;
   DARK_TRY(allow_lds(kern, lds));
   DARK_LAUNCH(KID_KV_REDUCE, pb.st, kern, dim3(pl.kv_grid), dim3(256), lds, (const unsigned short*)K,
-              (const unsigned short*)V, M, W, b.Mh, b.Wh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m, pl.P,
-              pl.slice_len, pl.n_work, p.w_shared, std::sqrt(pb.scale));
+              (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m, pl.P, pl.slice_len,
+              pl.n_work);
   return DARK_OK;
 }
 
-template <int D, int DV, int R, int MINW>
+template <int D, int DV, int MINW>
 dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
   const dark_params& p = pb.p;
-  const size_t lds = RoSmem<D, DV, R>::total(p.m);
+  const size_t lds = RoSmem<D, DV>::total(p.m);
   const unsigned grid = (unsigned)pl.ro_grid;
   if (p.out_dtype == DARK_BF16) {
-    auto kern = k_readout<D, DV, R, true, MINW>;
+    auto kern = k_readout<D, DV, true, MINW>;
     DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Mh, b.Wh, b.St, b.zt,
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
                 b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   } else {
-    auto kern = k_readout<D, DV, R, false, MINW>;
+    auto kern = k_readout<D, DV, false, MINW>;
     DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Mh, b.Wh, b.St, b.zt,
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
                 b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   }
   return DARK_OK;
@@ -829,9 +869,12 @@ bool fused_supported(const Problem& pb, int op, bool causal) {
   const dark_params& p = pb.p;
   if (op != DARK_OP_ATTN_FWD || causal) return false;
   if (p.io_dtype != DARK_BF16) return false;
-  if (!(p.d == 64 && p.r == 64 && p.dv == 64)) return false;  // wider heads use the fp32 kernels
+  const bool shape64 = p.d == 64 && p.r == 64 && p.dv == 64;
+  const bool shape128 = p.d == 128 && p.r == 128 && p.dv == 128;
+  if (!shape64 && !shape128) return false;
   if (p.m % 256 != 0) return false;
-  if (RoSmem<64, 64, 64>::total(p.m) > 160 * 1024) return false;
+  const size_t ro = shape64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
+  if (ro > 160 * 1024) return false;
   return true;
 }
 
@@ -844,7 +887,16 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (ar.base == nullptr) return DARK_OK;
   if (ar.overflow) return DARK_EWORKSPACE;
 
-  DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V, M, W)));
+  const int nA = (p.m + kPrepRows - 1) / kPrepRows;
+  const size_t prep_lds = ((size_t)kPrepRows * (p.r + 1) + (size_t)p.r * p.d) * sizeof(float);
+  DARK_TRY(allow_lds(k_prep, prep_lds));
+  DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA, p.H), dim3(256), prep_lds, M, W, b.Ah, b.Mh, p.m, p.r, p.d,
+              p.w_shared, std::sqrt(pb.scale));
+  if (p.d == 64) {
+    DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V)));
+  } else {
+    DARK_TRY((launch_kv<128, 128, 128, 1>(pb, pl, b, K, V)));
+  }
   const unsigned mgrid = (unsigned)(pb.BH() * (p.m / 64));
   if (p.dv == 64)
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<64>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
@@ -852,7 +904,11 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   else
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<128>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
                 b.zt, b.cf, p.m, pl.P);
-  DARK_TRY((launch_ro<64, 64, 64, 2>(pb, pl, b, Q, out)));
+  if (p.d == 64) {
+    DARK_TRY((launch_ro<64, 64, 2>(pb, pl, b, Q, out)));
+  } else {
+    DARK_TRY((launch_ro<128, 128, 1>(pb, pl, b, Q, out)));
+  }
   return DARK_OK;
 }
 

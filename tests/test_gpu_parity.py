@@ -194,6 +194,7 @@ FUSED_SHAPES = [
     (2, 1, 1000, 64, 64, 512, 64),     # two 256-feature blocks
     (1, 1, 64, 64, 64, 256, 64),       # exactly one tile
     (1, 1, 7, 64, 64, 256, 64),        # shorter than a tile
+    (1, 2, 333, 128, 128, 256, 128),   # the wide-head instantiation
 ]
 
 
