@@ -1,0 +1,101 @@
+// Device helpers and host-side hooks shared by the fused MFMA translation units (gfx950).
+// Every translation unit that includes this header is compiled with -fno-honor-nans.
+#pragma once
+
+#include "common.h"
+
+namespace dark {
+namespace fz {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __fp16 fp16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+// Running shifts are only raised when a feature value would exceed 2^kTau (rare): fp32 sums of such
+// values over up to 2^20 positions, times the readout's own 2^kTau, stay far below 2^127.
+constexpr float kTau = 40.0f;
+constexpr float kBig = 1.099511627776e12f;  // 2^40
+constexpr float kRaise = 20.0f;             // in the rare path, shifts more than 2^20 too low are raised
+constexpr int kTile = 64;      // tokens per tile in the K pass
+
+__device__ static inline unsigned pack_bf16(float a, float b) {
+  bf16x2 p;
+  p[0] = (__bf16)a;
+  p[1] = (__bf16)b;
+  return *reinterpret_cast<unsigned*>(&p);
+}
+__device__ static inline unsigned pack_f16_from_bf16pair(unsigned w) {
+  // w holds two bf16; both are exactly representable in fp16 unless out of its range
+  float lo = __uint_as_float(w << 16);
+  float hi = __uint_as_float(w & 0xffff0000u);
+  fp16x2 h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  return *reinterpret_cast<unsigned*>(&h);
+}
+__device__ static inline u32x4 bf16x8_to_f16x8(u32x4 r) {
+  u32x4 o;
+  o[0] = pack_f16_from_bf16pair(r[0]);
+  o[1] = pack_f16_from_bf16pair(r[1]);
+  o[2] = pack_f16_from_bf16pair(r[2]);
+  o[3] = pack_f16_from_bf16pair(r[3]);
+  return o;
+}
+__device__ static inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// acc + a.lo * b.lo + a.hi * b.hi on packed bf16 pairs, fp32 arithmetic (v_dot2_f32_bf16)
+__device__ static inline float dot2_bf16(unsigned a, unsigned b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<bf16x2*>(&a), *reinterpret_cast<bf16x2*>(&b), acc, false);
+}
+constexpr unsigned kOnesBf16x2 = 0x3f803f80u;
+// max(a, b, c).  This file is compiled with -fno-honor-nans, so the compiler needs no NaN
+// canonicalisation and forms v_max3_f32.  (Not inline asm: the compiler must see the reads of
+// MFMA results to insert the wait states they need.)
+__device__ static inline float max3(float a, float b, float c) { return __builtin_fmaxf(a, __builtin_fmaxf(b, c)); }
+// Sum over each row of 16 lanes (result in every lane of the row): four DPP row rotations.
+template <int N>
+__device__ static inline float dpp_row_ror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ static inline float row16_sum(float v) {
+  v += dpp_row_ror<8>(v);
+  v += dpp_row_ror<4>(v);
+  v += dpp_row_ror<2>(v);
+  v += dpp_row_ror<1>(v);
+  return v;
+}
+
+
+// Raises a kernel's dynamic-LDS limit when it needs more than the default; done once per kernel
+// and size (the attribute call is host work we do not want on every launch).
+template <typename KernelT>
+static dark_status allow_lds(KernelT kernel, size_t bytes) {
+  if (bytes > 160 * 1024) return DARK_EUNSUPPORTED;
+  if (bytes <= 48 * 1024) return DARK_OK;
+  static size_t granted = 0;  // one instance per kernel type
+  static const void* granted_for = nullptr;
+  const void* fn = reinterpret_cast<const void*>(kernel);
+  if (granted_for == fn && granted >= bytes) return DARK_OK;
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return DARK_EHIP;
+  granted = bytes;
+  granted_for = fn;
+  return DARK_OK;
+}
+
+}  // namespace fz
+
+// Hooks implemented in fused.hip and used by the causal path as well.
+// A' = sqrt(scale) log2(e) W M as fp16 [H][m][d];  M' = sqrt(scale) sqrt(log2(e)/2) M as fp16 [H][r][d].
+dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh);
+// Per-slice states [S|z] = phi_K^T [V|1] with per-feature shifts: Spart [BH][P][m][dv], zpart, cpart [BH][P][m].
+dark_status fused_launch_kv(const Problem& pb, const void* K, const void* V, const _Float16* Ah, const _Float16* Mh,
+                            float* Spart, float* zpart, float* cpart, int P, int slice_len);
+bool fused_kv_shape_ok(const Problem& pb);
+
+// fused_causal.hip
+bool fused_causal_supported(const Problem& pb);
+
+}  // namespace dark
