@@ -104,7 +104,9 @@ __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const
 // k_kv_reduce
 // Workgroup = 4 waves = 256 features (wave w owns features [64w, 64w+64) of the block) over one
 // L-slice of one (b,h).  Per 64-token tile:
-//   stage   K tile -> LDS as fp16 [64][D+8];  V tile -> LDS transposed bf16 [DV][64+4]
+//   stage   K tile -> LDS as fp16 [64][D+8];  V tile -> LDS row-major bf16 [64][DV], the 16-byte
+//           chunks of a row XOR-swizzled with the token index so that the transposing LDS reads
+//           (ds_read_b64_tr_b16) that build the MFMA operand are free of bank conflicts
 //   norms   wave w: x~ = X[16w..16w+16) M'^T by MFMA 16x16x32, n' = row sums of squares -> LDS
 //   proj    U[tok][feat] = X A'^T  (MFMA 32x32x16 f16; A' fragments stay in registers)
 //   exp     phi = exp2(U - n' - c) in the accumulator registers, packed to bf16
@@ -114,9 +116,8 @@ __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const
 template <int D, int DV, int R>
 struct KvSmem {
   static constexpr int XS = D + 8;       // fp16 elements per X row (pad keeps 16-byte rows off one bank group)
-  static constexpr int VS = kTile + 4;   // bf16 elements per V^T row
   static constexpr size_t x_bytes = (size_t)3 * kTile * XS * 2;
-  static constexpr size_t v_bytes = (size_t)3 * DV * VS * 2;
+  static constexpr size_t v_bytes = (size_t)3 * kTile * DV * 2;
   static constexpr size_t m_bytes = (size_t)R * XS * 2;
   static constexpr size_t n_bytes = (size_t)2 * kTile * 4;
   static constexpr size_t total = x_bytes + v_bytes + m_bytes + n_bytes;
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
   };
   auto store_tile = [&](int buf) {
     _Float16* xs = Xs + buf * kTile * SM::XS;
-    unsigned short* vt = Vt + buf * DV * SM::VS;
+    unsigned short* vt = Vt + buf * kTile * DV;
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
@@ -201,11 +202,7 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 #pragma unroll
     for (int i = 0; i < VCH; ++i) {
       int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vt[(8 * cc + 2 * e) * SM::VS + tok] = (unsigned short)(vreg[i][e] & 0xffffu);
-        vt[(8 * cc + 2 * e + 1) * SM::VS + tok] = (unsigned short)(vreg[i][e] >> 16);
-      }
+      *reinterpret_cast<u32x4*>(vt + tok * DV + 8 * (cc ^ (tok & 7))) = vreg[i];
     }
   };
   // n' of this wave's 16 tokens of the tile in buffer `buf` -> ns[nb]
@@ -275,7 +272,7 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
     __syncthreads();
 
     const _Float16* xs = Xs + buf * kTile * SM::XS;
-    const unsigned short* vt = Vt + buf * DV * SM::VS;
+    const unsigned short* vt = Vt + buf * kTile * DV;
     // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
     // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
     // log2-features directly.
@@ -361,16 +358,21 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
     }
     z[0] += zs[0];
     z[1] += zs[1];
-    // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4
+    // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4.
+    // Transposing read: in each group of 16 lanes, lane i points at 4 values V[t + i/4][c0 + 4 (i%4) ...]
+    // and receives V[t .. t+3][c0 + i], i.e. four consecutive tokens of its own column.
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
         for (int ct = 0; ct < DV / 32; ++ct) {
-          const unsigned short* vr = vt + (32 * ct + l32) * SM::VS + 32 * tt + 16 * hh + 4 * hf;
-          u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
-          u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
+          const int j = l32 % 16;
+          const int tok = 32 * tt + 16 * hh + 4 * hf + j / 4;
+          const int chunk = 4 * ct + 2 * (l32 / 16) + (j % 4) / 2;
+          const unsigned short* vr = vt + tok * DV + 8 * (chunk ^ (tok & 7)) + 4 * (j % 2);
+          u32x2 lo = lds_read_tr16(vr);
+          u32x2 hi = lds_read_tr16(vr + 8 * DV);
           u32x4 bv = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
           for (int ft = 0; ft < 2; ++ft)
@@ -476,18 +478,22 @@ __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spar
 //   U^T[feat][tok] = A' X^T (MFMA f16; A' from LDS, X fragments in registers, converted bf16->fp16)
 //   phi^T = exp2(U^T + c_blk - mu_tok), mu a lazily raised running row shift
 //   out^T[c][tok] += S^T[c][feat] phi^T[feat][tok] (MFMA bf16; S^T from LDS),  den += phi . z
-// No barrier in the main loop.
+// No barrier in the main loop.  The accumulators hold out^T (lane = token); each wave turns its
+// tile through a private LDS stage so that the global stores are whole 128-byte rows.
 // ---------------------------------------------------------------------------
 template <int D, int DV>
 struct RoSmem {
   static constexpr int AS = D + 8;
+  static constexpr int stage_row = 128 + 8;                   // bytes: 64 bf16 or 32 fp32, plus pad
+  static constexpr size_t stage_bytes = 32 * stage_row;       // per wave: 32 tokens
   __host__ __device__ static size_t a_bytes(int m) { return (size_t)m * AS * 2; }
   __host__ __device__ static size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
-  __host__ __device__ static size_t total(int m) { return a_bytes(m) + s_bytes(m) + (size_t)m * 4 + (size_t)(m / 64) * 4 + 16; }
+  __host__ __device__ static size_t misc_bytes(int m) { return (((size_t)m * 2 + (size_t)(m / 64) * 4 + 16) + 15) & ~(size_t)15; }
+  __host__ __device__ static size_t total(int m, int nw) { return a_bytes(m) + s_bytes(m) + misc_bytes(m) + nw * stage_bytes; }
 };
 
-template <int D, int DV, bool OUT_BF16, int MINW>
-__global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __restrict__ Qg,
+template <int D, int DV, bool OUT_BF16, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __restrict__ Qg,
                                                        const _Float16* __restrict__ Ah,
                                                        const unsigned short* __restrict__ St,
                                                        const float* __restrict__ zt, const float* __restrict__ cf,
@@ -500,11 +506,13 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
   float* cl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));
   unsigned short* zl = reinterpret_cast<unsigned short*>(cl + m / 64 + 4);  // z as bf16, 8-byte aligned rows of 4
   const int SS = m + 4;
+  constexpr int NT = 64 * NW;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+  unsigned char* stage = smem + SM::a_bytes(m) + SM::s_bytes(m) + SM::misc_bytes(m) + wv * SM::stage_bytes;
   const int l32 = lane % 32, hf = lane / 32;
 
-  // Work items are (b,h, 256-token chunk) pairs; a workgroup takes a contiguous run of them, so it
+  // Work items are (b,h, 64 NW-token chunk) pairs; a workgroup takes a contiguous run of them, so it
   // refills its LDS copy of A', S^T, z only when the run crosses into the next (b,h).
   const int item_begin = blockIdx.x * items_per_wg;
   const int item_end = min(n_items, item_begin + items_per_wg);
@@ -515,40 +523,40 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
       const int h = bh % H;
       if (cur_bh >= 0) __syncthreads();  // everyone is done reading the previous head's operands
       if (cur_bh < 0 || (cur_bh % H) != h) {
-        for (int c0 = tid; c0 < m * D / 8; c0 += 256 * 8) {  // m * D / 8 is a multiple of 2048
-          u32x4 v[8];
+        for (int c0 = tid; c0 < m * D / 8; c0 += NT * 4) {  // m * D / 8 is a multiple of 2048
+          u32x4 v[4];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int ci = c0 + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+          for (int u = 0; u < 4; ++u) {
+            const int ci = c0 + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
             v[u] = *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
           }
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int ci = c0 + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+          for (int u = 0; u < 4; ++u) {
+            const int ci = c0 + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
             *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) = v[u];
           }
         }
       }
-      for (int c0 = tid; c0 < DV * m / 4; c0 += 256 * 16) {  // DV * m / 4 is a multiple of 4096
-        u32x2 v[16];
+      for (int c0 = tid; c0 < DV * m / 4; c0 += NT * 8) {  // DV * m / 4 is a multiple of 4096
+        u32x2 v[8];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const int ci = c0 + 256 * u, row = ci / (m / 4), fc = ci % (m / 4);
+        for (int u = 0; u < 8; ++u) {
+          const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
           v[u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
         }
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const int ci = c0 + 256 * u, row = ci / (m / 4), fc = ci % (m / 4);
+        for (int u = 0; u < 8; ++u) {
+          const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
           *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) = v[u];
         }
       }
-      for (int i = tid; i < m; i += 256) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
-      for (int i = tid; i < m / 64; i += 256) cl[i] = cf[(size_t)bh * (m / 64) + i];
+      for (int i = tid; i < m; i += NT) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
+      for (int i = tid; i < m / 64; i += NT) cl[i] = cf[(size_t)bh * (m / 64) + i];
       __syncthreads();
       cur_bh = bh;
     }
     const unsigned short* Qb = Qg + (size_t)bh * L * D;
-    const int t0 = chunk * 256 + 64 * wv;
+    const int t0 = chunk * NT + 64 * wv;
     const int wg_end = L;
     if (t0 >= L) continue;  // wave-uniform
     // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
@@ -665,31 +673,64 @@ __global__ __launch_bounds__(256, MINW) void k_readout(const unsigned short* __r
                                                                   O[ct][tt], 0, 0, 0);
           }
     }
-    // normalise and store: register v of O[ct][tt] is out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4]
+    // normalise, turn through the wave's LDS stage, store whole rows.  Register v of O[ct][tt] is
+    // out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4].
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int tok = t0 + 32 * tt + l32;
       const float inv = 1.f / (den[tt] + __shfl_xor(den[tt], 32, 64));
-      if (tok < wg_end) {
+      const int row = lane / 8, ch = lane % 8;  // read side: 8 lanes per token row, 16 bytes each
+      if (OUT_BF16) {
 #pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct)
+        for (int c64 = 0; c64 < DV / 64; ++c64) {  // 64 output columns (one 128-byte row piece) at a time
+#pragma unroll
+          for (int cl2 = 0; cl2 < 2; ++cl2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int ct = 2 * c64 + cl2;
+              u32x2 w = {pack_bf16(O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv),
+                         pack_bf16(O[ct][tt][4 * g + 2] * inv, O[ct][tt][4 * g + 3] * inv)};
+              *reinterpret_cast<u32x2*>(stage + l32 * SM::stage_row + (32 * cl2 + 8 * g + 4 * hf) * 2) = w;
+            }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int ps = 0; ps < 4; ++ps) {
+            const int tok = t0 + 32 * tt + 8 * ps + row;
+            u32x4 w = *reinterpret_cast<const u32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
+            if (tok < wg_end)
+              *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned short*>(outp) + ((size_t)bh * L + tok) * DV + 64 * c64 +
+                                        8 * ch) = w;
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+        }
+      } else {
+#pragma unroll
+        for (int ct = 0; ct < DV / 32; ++ct) {
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const size_t o = ((size_t)bh * L + tok) * DV + 32 * ct + 8 * g + 4 * hf;
-            float v0 = O[ct][tt][4 * g] * inv, v1 = O[ct][tt][4 * g + 1] * inv;
-            float v2 = O[ct][tt][4 * g + 2] * inv, v3 = O[ct][tt][4 * g + 3] * inv;
-            if (OUT_BF16) {
-              u32x2 w = {pack_bf16(v0, v1), pack_bf16(v2, v3)};
-              *reinterpret_cast<u32x2*>(reinterpret_cast<unsigned short*>(outp) + o) = w;
-            } else {
-              f32x4 w = {v0, v1, v2, v3};
-              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + o) = w;
-            }
+            f32x4 w = {O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv, O[ct][tt][4 * g + 2] * inv,
+                       O[ct][tt][4 * g + 3] * inv};
+            *reinterpret_cast<f32x4*>(stage + l32 * SM::stage_row + (8 * g + 4 * hf) * 4) = w;
           }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int ps = 0; ps < 4; ++ps) {
+            const int tok = t0 + 32 * tt + 8 * ps + row;
+            f32x4 w = *reinterpret_cast<const f32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
+            if (tok < wg_end)
+              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + ((size_t)bh * L + tok) * DV + 32 * ct + 4 * ch) = w;
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+        }
       }
     }
   }
 }
+
+constexpr size_t kLdsMax = 160 * 1024;
 
 int env_int(const char* name, int dflt) {
   const char* s = std::getenv(name);
@@ -700,7 +741,7 @@ int env_int(const char* name, int dflt) {
 
 struct Plan {
   int P, slice_len, nfb, n_work, kv_grid;
-  int chunks_per_bh, n_items, items_per_wg, ro_grid;
+  int ro_nw, chunks_per_bh, n_items, items_per_wg, ro_grid;
 };
 
 Plan make_plan(const Problem& pb) {
@@ -720,13 +761,12 @@ Plan make_plan(const Problem& pb) {
   pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
   // readout: (b,h, 256-token chunk) items dealt out in contiguous runs to about as many
   // workgroups as fit on the chip at once
-  pl.chunks_per_bh = (p.L + 255) / 256;
+  // one workgroup per CU: eight waves when the registers (d = 64) and the LDS allow, else four
+  pl.ro_nw = (p.d == 64 && RoSmem<64, 64>::total(p.m, 8) <= kLdsMax) ? 8 : 4;
+  const int ro_tok = 64 * pl.ro_nw;
+  pl.chunks_per_bh = (p.L + ro_tok - 1) / ro_tok;
   pl.n_items = (int)(BH * pl.chunks_per_bh);
-  int ro_wgs = env_int("DARK_RO_WGS", 0);
-  if (ro_wgs == 0) {
-    const size_t lds = p.d == 64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
-    ro_wgs = 256 * (lds * 2 <= 160 * 1024 && p.d == 64 ? 2 : 1);
-  }
+  const int ro_wgs = env_int("DARK_RO_WGS", 256);
   pl.items_per_wg = (pl.n_items + ro_wgs - 1) / ro_wgs;
   pl.ro_grid = (pl.n_items + pl.items_per_wg - 1) / pl.items_per_wg;
   return pl;
@@ -768,20 +808,20 @@ dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, con
   return DARK_OK;
 }
 
-template <int D, int DV, int MINW>
+template <int D, int DV, int NW>
 dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
   const dark_params& p = pb.p;
-  const size_t lds = RoSmem<D, DV>::total(p.m);
+  const size_t lds = RoSmem<D, DV>::total(p.m, NW);
   const unsigned grid = (unsigned)pl.ro_grid;
   if (p.out_dtype == DARK_BF16) {
-    auto kern = k_readout<D, DV, true, MINW>;
+    auto kern = k_readout<D, DV, true, NW>;
     DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
                 b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   } else {
-    auto kern = k_readout<D, DV, false, MINW>;
+    auto kern = k_readout<D, DV, false, NW>;
     DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
+    DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
                 b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   }
   return DARK_OK;
@@ -797,8 +837,8 @@ bool fused_supported(const Problem& pb, int op, bool causal) {
   const bool shape128 = p.d == 128 && p.r == 128 && p.dv == 128;
   if (!shape64 && !shape128) return false;
   if (p.m % 256 != 0) return false;
-  const size_t ro = shape64 ? RoSmem<64, 64>::total(p.m) : RoSmem<128, 128>::total(p.m);
-  if (ro > 160 * 1024) return false;
+  const size_t ro = shape64 ? RoSmem<64, 64>::total(p.m, 4) : RoSmem<128, 128>::total(p.m, 4);
+  if (ro > kLdsMax) return false;
   return true;
 }
 
@@ -828,10 +868,12 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   else
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<128>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
                 b.zt, b.cf, p.m, pl.P);
-  if (p.d == 64) {
-    DARK_TRY((launch_ro<64, 64, 2>(pb, pl, b, Q, out)));
+  if (p.d == 64 && pl.ro_nw == 8) {
+    DARK_TRY((launch_ro<64, 64, 8>(pb, pl, b, Q, out)));
+  } else if (p.d == 64) {
+    DARK_TRY((launch_ro<64, 64, 4>(pb, pl, b, Q, out)));
   } else {
-    DARK_TRY((launch_ro<128, 128, 1>(pb, pl, b, Q, out)));
+    DARK_TRY((launch_ro<128, 128, 4>(pb, pl, b, Q, out)));
   }
   return DARK_OK;
 }

@@ -69,6 +69,17 @@ __device__ static inline float row16_sum(float v) {
 }
 
 
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i supplies the LDS address of four
+// consecutive 16-bit values r_i[0..3]; lane l of the group receives r_{4e + l/4}[l % 4] for
+// e = 0..3.  With lane i pointing at row i/4, columns 4 (i%4) .. 4 (i%4) + 3 of a row-major tile,
+// lane l receives column l of rows 0..3: a 4 x 16 transpose.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ static inline u32x2 lds_read_tr16(const unsigned short* p) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(const_cast<unsigned short*>(p)));
+  return *reinterpret_cast<u32x2*>(&v);
+}
+
 // Raises a kernel's dynamic-LDS limit when it needs more than the default; done once per kernel
 // and size (the attribute call is host work we do not want on every launch).
 template <typename KernelT>
