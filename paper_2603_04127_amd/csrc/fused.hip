@@ -401,8 +401,9 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 }
 
 // ---------------------------------------------------------------------------
-// k_kv_merge: per (b,h, 64-feature block): c* = max over slices and the block's features of the
-// per-feature shifts;  S_j = sum_p 2^(c_pj - c*) S_pj (p ascending, fixed order), same for z.
+// k_kv_merge: per (b,h, 64-feature block): c* = max over the slices and all features of the (b,h)
+// of the per-feature shifts (one scalar per (b,h): on the query side it is a per-row factor that
+// cancels);  S_j = sum_p 2^(c_pj - c*) S_pj (p ascending, fixed order), same for z.
 // Writes S^T as bf16 [BH][DV][m] (the readout's MFMA operand), z [BH][m], c* [BH][m/64].
 // ---------------------------------------------------------------------------
 template <int DV>
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spar
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x;
   float cs = -INFINITY;
-  for (int i = tid; i < P * 64; i += 256) cs = fmaxf(cs, cpart[((size_t)bh * P + i / 64) * m + 64 * blk + i % 64]);
+  for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[(size_t)bh * P * m + i]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
   if (tid % 64 == 0) red[tid / 64] = cs;
@@ -492,14 +493,15 @@ struct RoSmem {
   __host__ __device__ static size_t total(int m, int nw) { return a_bytes(m) + s_bytes(m) + misc_bytes(m) + nw * stage_bytes; }
 };
 
-template <int D, int DV, bool OUT_BF16, int NW>
+template <int D, int DV, int NFB, bool OUT_BF16, int NW>
 __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __restrict__ Qg,
                                                        const _Float16* __restrict__ Ah,
                                                        const unsigned short* __restrict__ St,
                                                        const float* __restrict__ zt, const float* __restrict__ cf,
-                                                       void* __restrict__ outp, int H, int L, int m,
+                                                       void* __restrict__ outp, int H, int L,
                                                        int chunks_per_bh, int n_items, int items_per_wg) {
   using SM = RoSmem<D, DV>;
+  constexpr int m = 256 * NFB;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16* Asl = reinterpret_cast<_Float16*>(smem);
   unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::a_bytes(m));
@@ -517,6 +519,24 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   const int item_begin = blockIdx.x * items_per_wg;
   const int item_end = min(n_items, item_begin + items_per_wg);
   int cur_bh = -1;
+  // X fragments (B operand of the projection): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8).
+  // The raw bf16 rows of the next tile are fetched into these registers during the last slot of
+  // the current one (their last use is the projection of the last unit), so the fetch latency
+  // hides behind the rest of the tile.
+  half8 xf[2][D / 16];
+  bool have_x = false;
+  auto fetch_x = [&](int fbh, int ft0) {
+    const unsigned short* Qf = Qg + (size_t)fbh * L * D;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tok = min(ft0 + 32 * tt + l32, L - 1);  // rows past the end repeat the last row; never stored
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) {
+        u32x4 raw = *reinterpret_cast<const u32x4*>(Qf + (size_t)tok * D + 16 * s + 8 * hf);
+        xf[tt][s] = *reinterpret_cast<half8*>(&raw);
+      }
+    }
+  };
   for (int item = item_begin; item < item_end; ++item) {
     const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
     if (bh != cur_bh) {
@@ -555,30 +575,164 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       __syncthreads();
       cur_bh = bh;
     }
-    const unsigned short* Qb = Qg + (size_t)bh * L * D;
     const int t0 = chunk * NT + 64 * wv;
     const int wg_end = L;
-    if (t0 >= L) continue;  // wave-uniform
-    // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
-    half8 xf[2][D / 16];
+    if (t0 >= L) {  // wave-uniform
+      have_x = false;
+      continue;
+    }
+    // the tile fetched ahead: the next one, or this one again when there is none (never used then)
+    const bool more = item + 1 < item_end;
+    const int nitem = more ? item + 1 : item;
+    const int nbh = nitem / chunks_per_bh, nt0 = (nitem % chunks_per_bh) * NT + 64 * wv;
+    if (!have_x) fetch_x(bh, t0);
+    have_x = false;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int tok = min(t0 + 32 * tt + l32, wg_end - 1);  // rows past the end repeat the last row; never stored
+    for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        u32x4 raw = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 16 * s + 8 * hf);
-        u32x4 cv = bf16x8_to_f16x8(raw);
+        u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<u32x4*>(&xf[tt][s]));
         xf[tt][s] = *reinterpret_cast<half8*>(&cv);
       }
+    constexpr int CT = DV / 32;
+    f32x16 O[CT][2];
+    float den[2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // ---- fast path -----------------------------------------------------------------------
+    // Units of 32 features.  For unit g:  P(g) projection MFMAs -> U,  E(g) exp2/pack/denominator
+    // (vector ALU) -> pk,  S(g) second MFMAs -> O.  Slot g of the schedule issues S(g-1), then
+    // P(g+1), with the 16 pieces of E(g) spread between the MFMAs, so the matrix pipe and the
+    // vector ALU work on different units at the same time.  The per-token shift mu is taken from
+    // unit 0 only and never raised; a token whose later features exceed it by more than the fp32
+    // range shows up as a non-finite or out-of-range denominator, and then the whole tile is
+    // redone by the careful path below.
+    {
+      constexpr int NS = 4 * CT;        // S MFMAs per unit
+      constexpr int NP = 2 * (D / 16);  // P MFMAs per unit
+      constexpr int STEPS = NS + NP, PER = STEPS / 16;
+      static_assert(STEPS % 16 == 0, "schedule assumes 16 exp pieces per slot");
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) O[ct][tt] = zero16;
+      den[0] = den[1] = 0.f;
+      float sh[2] = {0.f, 0.f};
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb) {
+        const _Float16* Ab = Asl + (size_t)(256 * fb + l32) * SM::AS + 8 * hf;
+        const unsigned short* Sb = Stl + (size_t)l32 * SS + 256 * fb + 4 * hf;
+        const unsigned short* zb = zl + 256 * fb + 4 * hf;
+        f32x16 U[2][2];        // [unit parity][tt]
+        u32x4 pk[2][2][2];     // [unit parity][tt][hh]
+        half8 af[D / 16];      // A' fragments of the unit being projected
+        u32x4 sf[2][CT];       // S^T fragments of the unit being accumulated
+        u32x2 zf[2][4];        // z of the unit being exponentiated: [parity][2 hh + q/2]
+        // prologue: P(0)
+#pragma unroll
+        for (int s2 = 0; s2 < D / 16; ++s2) af[s2] = *reinterpret_cast<const half8*>(Ab + 16 * s2);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) zf[0][k] = *reinterpret_cast<const u32x2*>(zb + 8 * k);
+#pragma unroll
+        for (int s2 = 0; s2 < D / 16; ++s2)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+            U[0][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s2], xf[tt][s2], s2 == 0 ? zero16 : U[0][tt], 0, 0, 0);
+        if (fb == 0) {
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            float m0 = U[0][tt][0];
+#pragma unroll
+            for (int v = 1; v < 16; v += 2) m0 = max3(m0, U[0][tt][v], U[0][tt][(v + 1) % 16]);
+            m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
+            sh[tt] = -m0;  // the key shift c* is one scalar per (b,h): it cancels against the row maximum
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+          const int cur = g & 1, nxt = cur ^ 1;
+          if (g == 7 && fb == NFB - 1) {
+            fetch_x(nbh, nt0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+          for (int i = 0; i < STEPS; ++i) {
+            if (i < NS) {
+              if (g >= 1) {  // S(g-1)
+                const int hh = i / (2 * CT), ct = (i / 2) % CT, tt = i % 2;
+                O[ct][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&sf[hh][ct]),
+                                                                    *reinterpret_cast<bf16x8*>(&pk[nxt][tt][hh]),
+                                                                    O[ct][tt], 0, 0, 0);
+              }
+              // A' fragments for P(g+1), one every other step
+              if (g < 7 && i % 2 == 0 && i / 2 < D / 16)
+                af[i / 2] = *reinterpret_cast<const half8*>(Ab + (size_t)32 * (g + 1) * SM::AS + 16 * (i / 2));
+              if (g < 7 && i == 1) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) zf[nxt][k] = *reinterpret_cast<const u32x2*>(zb + 32 * (g + 1) + 8 * k);
+              }
+            } else {
+              const int ip = i - NS;
+              if (g < 7) {  // P(g+1)
+                const int s2 = ip / 2, tt = ip % 2;
+                U[nxt][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s2], xf[tt][s2], s2 == 0 ? zero16 : U[nxt][tt], 0, 0, 0);
+              }
+              // S^T fragments for S(g), one every other step
+              if (ip % 2 == 0 && ip / 2 < 2 * CT) {
+                const int hh = (ip / 2) / CT, ct = (ip / 2) % CT;
+                const unsigned short* sr = Sb + (size_t)32 * ct * SS + 32 * g + 16 * hh;
+                u32x2 lo = *reinterpret_cast<const u32x2*>(sr);
+                u32x2 hi = *reinterpret_cast<const u32x2*>(sr + 8);
+                sf[hh][ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (i % PER == PER - 1) {  // piece e of E(g): registers 8 hh + 2 q, + 1 of tile tt
+              const int e = i / PER, tt = e / 8, hh = (e % 8) / 4, q = e % 4;
+              const float a = fast_exp2(U[cur][tt][8 * hh + 2 * q] + sh[tt]);
+              const float b = fast_exp2(U[cur][tt][8 * hh + 2 * q + 1] + sh[tt]);
+              const unsigned pq = pack_bf16(a, b);
+              pk[cur][tt][hh][q] = pq;
+              // the denominator weights are the same rounded features that multiply S
+              den[tt] = dot2_bf16(pq, zf[cur][2 * hh + q / 2][q % 2], den[tt]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+        // drain: S(7)
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+          const int hh = i / (2 * CT), ct = (i / 2) % CT, tt = i % 2;
+          O[ct][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&sf[hh][ct]),
+                                                              *reinterpret_cast<bf16x8*>(&pk[1][tt][hh]), O[ct][tt], 0, 0, 0);
+        }
+      }
     }
-    f32x16 O[DV / 32][2];
+    have_x = more;
+    const float dt0 = den[0] + __shfl_xor(den[0], 32, 64), dt1 = den[1] + __shfl_xor(den[1], 32, 64);
+    const bool redo = __any(!(dt0 > kDenLo && dt0 < kDenHi) || !(dt1 > kDenLo && dt1 < kDenHi));
+
+    // ---- careful path: running per-token shift, raised whenever a block exceeds it by 2^kTau ---
+    if (redo) {
+    if (have_x) {  // the fragments already hold the next tile: fetch this one again
+      fetch_x(bh, t0);
+      have_x = false;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+          u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<u32x4*>(&xf[tt][s]));
+          xf[tt][s] = *reinterpret_cast<half8*>(&cv);
+        }
+    }
 #pragma unroll
     for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) O[ct][tt][v] = 0.f;
-    float den[2] = {0.f, 0.f};
+    den[0] = den[1] = 0.f;
     // Running per-token shift of the log2-features (lane = token column; both half-waves agree).
     // Set from the first feature block, afterwards only raised when exceeded by more than 2^kTau.
     float mu[2] = {0.f, 0.f};
@@ -673,6 +827,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
                                                                   O[ct][tt], 0, 0, 0);
           }
     }
+    }  // careful path
     // normalise, turn through the wave's LDS stage, store whole rows.  Register v of O[ct][tt] is
     // out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4].
 #pragma unroll
@@ -762,7 +917,7 @@ Plan make_plan(const Problem& pb) {
   // readout: (b,h, 256-token chunk) items dealt out in contiguous runs to about as many
   // workgroups as fit on the chip at once
   // one workgroup per CU: eight waves when the registers (d = 64) and the LDS allow, else four
-  pl.ro_nw = (p.d == 64 && RoSmem<64, 64>::total(p.m, 8) <= kLdsMax) ? 8 : 4;
+  pl.ro_nw = (p.d == 64 && p.m == 256) ? 8 : 4;
   const int ro_tok = 64 * pl.ro_nw;
   pl.chunks_per_bh = (p.L + ro_tok - 1) / ro_tok;
   pl.n_items = (int)(BH * pl.chunks_per_bh);
@@ -808,21 +963,21 @@ dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, con
   return DARK_OK;
 }
 
-template <int D, int DV, int NW>
+template <int D, int DV, int NFB, int NW>
 dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
   const dark_params& p = pb.p;
   const size_t lds = RoSmem<D, DV>::total(p.m, NW);
   const unsigned grid = (unsigned)pl.ro_grid;
   if (p.out_dtype == DARK_BF16) {
-    auto kern = k_readout<D, DV, true, NW>;
+    auto kern = k_readout<D, DV, NFB, true, NW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
+                b.cf, out, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   } else {
-    auto kern = k_readout<D, DV, false, NW>;
+    auto kern = k_readout<D, DV, NFB, false, NW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, p.m, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
+                b.cf, out, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   }
   return DARK_OK;
 }
@@ -836,9 +991,8 @@ bool fused_supported(const Problem& pb, int op, bool causal) {
   const bool shape64 = p.d == 64 && p.r == 64 && p.dv == 64;
   const bool shape128 = p.d == 128 && p.r == 128 && p.dv == 128;
   if (!shape64 && !shape128) return false;
-  if (p.m % 256 != 0) return false;
-  const size_t ro = shape64 ? RoSmem<64, 64>::total(p.m, 4) : RoSmem<128, 128>::total(p.m, 4);
-  if (ro > kLdsMax) return false;
+  // feature counts the readout is instantiated for (its operands must fit the 160 KB of LDS)
+  if (!(p.m == 256 || (shape64 && p.m == 512))) return false;
   return true;
 }
 
@@ -868,12 +1022,12 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   else
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<128>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
                 b.zt, b.cf, p.m, pl.P);
-  if (p.d == 64 && pl.ro_nw == 8) {
-    DARK_TRY((launch_ro<64, 64, 8>(pb, pl, b, Q, out)));
+  if (p.d == 64 && p.m == 256) {
+    DARK_TRY((launch_ro<64, 64, 1, 8>(pb, pl, b, Q, out)));
   } else if (p.d == 64) {
-    DARK_TRY((launch_ro<64, 64, 4>(pb, pl, b, Q, out)));
+    DARK_TRY((launch_ro<64, 64, 2, 4>(pb, pl, b, Q, out)));
   } else {
-    DARK_TRY((launch_ro<128, 128, 4>(pb, pl, b, Q, out)));
+    DARK_TRY((launch_ro<128, 128, 1, 4>(pb, pl, b, Q, out)));
   }
   return DARK_OK;
 }

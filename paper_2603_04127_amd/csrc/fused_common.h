@@ -23,6 +23,10 @@ constexpr float kTau = 40.0f;
 constexpr float kBig = 1.099511627776e12f;  // 2^40
 constexpr float kRaise = 20.0f;             // in the rare path, shifts more than 2^20 too low are raised
 constexpr int kTile = 64;      // tokens per tile in the K pass
+// The readout's fast path accepts a tile when every denominator lies in this range: numerators are
+// bounded by max|v| times the denominator, so nothing has overflowed, and nothing was flushed.
+constexpr float kDenLo = 7.888609052210118e-31f;  // 2^-100
+constexpr float kDenHi = 7.922816251426434e28f;   // 2^96
 
 __device__ static inline unsigned pack_bf16(float a, float b) {
   bf16x2 p;
