@@ -28,75 +28,74 @@ namespace {
 
 // ---------------------------------------------------------------------------
 // k_prep: A'[h][j][:] = alpha log2e sum_t W[h][j][t] M[h][t][:]  (fp16),  M' = alpha sqrt(log2e/2) M.
-// One block per (h, 32 feature rows): the W rows and all of M go to LDS with every global load
-// issued before the first wait, then each thread owns a 2 x (d/16) register tile.  r, d <= 128.
+// One block per (h, 256 / (d/4) feature rows).  Every global load of the block (its W rows and all
+// of M, as float4) is issued before the first wait, so the block pays the memory latency once;
+// then thread (row, column group) accumulates four adjacent outputs over t from LDS.
+// Requires r, d multiples of 4, d <= 256.
 // ---------------------------------------------------------------------------
-constexpr int kPrepRows = 32;
+constexpr int kPrepMaxLoads = 16;  // float4 loads of M per thread: r * d / 4 / 256 <= 16 for r, d <= 128
 __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const float* __restrict__ W,
                                               _Float16* __restrict__ Ah, _Float16* __restrict__ Mh, int m, int r,
                                               int d, int w_shared, float alpha) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* Ws = reinterpret_cast<float*>(smem);   // [32][r + 1]
-  float* Mt = Ws + kPrepRows * (r + 1);         // [r][d]
+  const int cg = d / 4, rows = 256 / cg;          // column groups of 4; feature rows per block
+  float* Ws = reinterpret_cast<float*>(smem);     // [rows][r + 4]
+  float* Mt = Ws + rows * (r + 4);                // [r][d]
   const int h = blockIdx.y;
-  const int j0 = blockIdx.x * kPrepRows;
-  const float* Mp = M + (size_t)h * r * d;
+  const int j0 = blockIdx.x * rows;
+  const f32x4* Mp = reinterpret_cast<const f32x4*>(M + (size_t)h * r * d);
   const float* w = W + (w_shared ? 0 : (size_t)h * m * r);
   const int tid = threadIdx.x;
-  // batches of eight independent loads, so that the latencies overlap (the trip counts are not
-  // compile-time constants and the compiler would otherwise serialise load -> LDS store)
-  for (int i0 = tid; i0 < kPrepRows * r; i0 += 256 * 8) {
-    float v[8];
+  const int nM = r * d / 4, nW = rows * r / 4;    // float4 counts
+  f32x4 mv[kPrepMaxLoads], wv[2];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int i = i0 + 256 * u, jj = i / r, t = i % r;
-      v[u] = (i < kPrepRows * r && j0 + jj < m) ? w[(size_t)(j0 + jj) * r + t] : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int i = i0 + 256 * u;
-      if (i < kPrepRows * r) Ws[(i / r) * (r + 1) + i % r] = v[u];
-    }
+  for (int u = 0; u < kPrepMaxLoads; ++u) {
+    const int i = tid + 256 * u;
+    mv[u] = i < nM ? Mp[i] : f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  for (int i0 = tid; i0 < r * d; i0 += 256 * 8) {
-    float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = (i0 + 256 * u < r * d) ? Mp[i0 + 256 * u] : 0.f;
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (i0 + 256 * u < r * d) Mt[i0 + 256 * u] = v[u];
+  for (int u = 0; u < 2; ++u) {
+    const int i = tid + 256 * u, jj = i / (r / 4), t4 = i % (r / 4);
+    wv[u] = (i < nW && j0 + jj < m) ? *reinterpret_cast<const f32x4*>(w + (size_t)(j0 + jj) * r + 4 * t4)
+                                    : f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kPrepMaxLoads; ++u) {
+    const int i = tid + 256 * u;
+    if (i < nM) *reinterpret_cast<f32x4*>(Mt + 4 * i) = mv[u];
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int i = tid + 256 * u, jj = i / (r / 4), t4 = i % (r / 4);
+    if (i < nW) *reinterpret_cast<f32x4*>(Ws + jj * (r + 4) + 4 * t4) = wv[u];
+  }
   if (blockIdx.x == 0) {
     const float f = alpha * sqrtf(0.5f * kLog2e);
-    for (int i = tid; i < r * d; i += 256) Mh[(size_t)h * r * d + i] = (_Float16)(Mt[i] * f);
+#pragma unroll
+    for (int u = 0; u < kPrepMaxLoads; ++u) {
+      const int i = tid + 256 * u;
+      if (i < nM) {
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 o = {(_Float16)(mv[u][0] * f), (_Float16)(mv[u][1] * f), (_Float16)(mv[u][2] * f), (_Float16)(mv[u][3] * f)};
+        *reinterpret_cast<h4*>(Mh + (size_t)h * r * d + 4 * i) = o;
+      }
+    }
   }
-  // thread -> rows jq + 16 i (i < 2), columns cq + 16 k (k < d / 16)
-  const int jq = tid / 16, cq = tid % 16;
-  float acc[2][8];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int k = 0; k < 8; ++k) acc[i][k] = 0.f;
-#pragma unroll 4
+  __syncthreads();
+  const int jj = tid / cg, cq = tid % cg;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
   for (int t = 0; t < r; ++t) {
-    float wv[2], mv[8];
+    const float wt = Ws[jj * (r + 4) + t];
+    const f32x4 mt = *reinterpret_cast<const f32x4*>(Mt + t * d + 4 * cq);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) wv[i] = Ws[(jq + 16 * i) * (r + 1) + t];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) mv[k] = (cq + 16 * k < d) ? Mt[t * d + cq + 16 * k] : 0.f;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc[i][k] = fmaf(wv[i], mv[k], acc[i][k]);
+    for (int x = 0; x < 4; ++x) acc[x] = fmaf(wt, mt[x], acc[x]);
   }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int j = j0 + jq + 16 * i;
-    if (j >= m) continue;
-#pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (cq + 16 * k < d) Ah[((size_t)h * m + j) * d + cq + 16 * k] = (_Float16)(acc[i][k] * alpha * kLog2e);
+  if (jj < rows && j0 + jj < m) {
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    const float f = alpha * kLog2e;
+    h4 o = {(_Float16)(acc[0] * f), (_Float16)(acc[1] * f), (_Float16)(acc[2] * f), (_Float16)(acc[3] * f)};
+    *reinterpret_cast<h4*>(Ah + ((size_t)h * m + j0 + jj) * d + 4 * cq) = o;
   }
 }
 
@@ -410,50 +409,52 @@ template <int DV>
 __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spart, const float* __restrict__ zpart,
                                                   const float* __restrict__ cpart, unsigned short* __restrict__ St,
                                                   float* __restrict__ zt, float* __restrict__ cf, int m, int P) {
-  constexpr int PP = 16;  // slices per pass
+  constexpr int PP = 8;  // slices per pass
   __shared__ float tile[64][DV + 1];
   __shared__ float fac[PP][64];
   __shared__ float red[4];
   const int nblk = m / 64;
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x;
-  float cs = -INFINITY;
-  for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[(size_t)bh * P * m + i]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
-  if (tid % 64 == 0) red[tid / 64] = cs;
-  __syncthreads();
-  cs = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   constexpr int PER = 64 * DV / 256;
   float acc[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) acc[i] = 0.f;
   float zacc = 0.f;
+  float cs = -INFINITY;
   for (int p0 = 0; p0 < P; p0 += PP) {
     const int np = min(PP, P - p0);
-    __syncthreads();
+    // the pass's loads of the partial states are issued first: they do not depend on the shifts,
+    // so their latency overlaps the reduction that finds c*
+    float v[PP][PER];
+    float zv[PP];
+#pragma unroll
+    for (int u = 0; u < PP; ++u) {
+      const int pu = min(u, np - 1);
+      const float* sp = Spart + (((size_t)bh * P + p0 + pu) * m + 64 * blk) * DV;
+#pragma unroll
+      for (int i = 0; i < PER; ++i) v[u][i] = sp[tid + 256 * i];
+      zv[u] = tid < 64 ? zpart[((size_t)bh * P + p0 + pu) * m + 64 * blk + tid] : 0.f;
+    }
+    if (p0 == 0) {
+      for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[(size_t)bh * P * m + i]);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
+      if (tid % 64 == 0) red[tid / 64] = cs;
+      __syncthreads();
+      cs = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    } else {
+      __syncthreads();  // the previous pass is done with fac
+    }
     for (int i = tid; i < np * 64; i += 256)
       fac[i / 64][i % 64] = fast_exp2(cpart[((size_t)bh * P + p0 + i / 64) * m + 64 * blk + i % 64] - cs);
     __syncthreads();
-    for (int pi = 0; pi < np; pi += 4) {
-      // up to four slices' loads are issued before any is consumed; the sum order stays p ascending
-      float v[4][PER];
-      float zv[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int pu = min(pi + u, np - 1);
-        const float* sp = Spart + (((size_t)bh * P + p0 + pu) * m + 64 * blk) * DV;
+    for (int u = 0; u < PP; ++u) {  // p ascending: the order of summation is fixed
+      if (u < np) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = sp[tid + 256 * i];
-        if (tid < 64) zv[u] = zpart[((size_t)bh * P + p0 + pu) * m + 64 * blk + tid];
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (pi + u < np) {
-#pragma unroll
-          for (int i = 0; i < PER; ++i) acc[i] = fmaf(fac[pi + u][(tid + 256 * i) / DV], v[u][i], acc[i]);
-          if (tid < 64) zacc = fmaf(fac[pi + u][tid], zv[u], zacc);
-        }
+        for (int i = 0; i < PER; ++i) acc[i] = fmaf(fac[u][(tid + 256 * i) / DV], v[u][i], acc[i]);
+        if (tid < 64) zacc = fmaf(fac[u][tid], zv[u], zacc);
       }
     }
   }
@@ -489,7 +490,7 @@ struct RoSmem {
   static constexpr size_t stage_bytes = 32 * stage_row;       // per wave: 32 tokens
   __host__ __device__ static size_t a_bytes(int m) { return (size_t)m * AS * 2; }
   __host__ __device__ static size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
-  __host__ __device__ static size_t misc_bytes(int m) { return (((size_t)m * 2 + (size_t)(m / 64) * 4 + 16) + 15) & ~(size_t)15; }
+  __host__ __device__ static size_t misc_bytes(int m) { return (size_t)m * 4 + 16 * (size_t)((m / 64 + 3) / 4); }  // z, shifts
   __host__ __device__ static size_t total(int m, int nw) { return a_bytes(m) + s_bytes(m) + misc_bytes(m) + nw * stage_bytes; }
 };
 
@@ -505,8 +506,8 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16* Asl = reinterpret_cast<_Float16*>(smem);
   unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::a_bytes(m));
-  float* cl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));
-  unsigned short* zl = reinterpret_cast<unsigned short*>(cl + m / 64 + 4);  // z as bf16, 8-byte aligned rows of 4
+  float* zl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));  // z, 16-byte aligned
+  float* cl = zl + m;
   const int SS = m + 4;
   constexpr int NT = 64 * NW;
 
@@ -570,7 +571,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
           *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) = v[u];
         }
       }
-      for (int i = tid; i < m; i += NT) zl[i] = (unsigned short)(pack_bf16(zt[(size_t)bh * m + i], 0.f) & 0xffffu);
+      for (int i = tid; i < m; i += NT) zl[i] = zt[(size_t)bh * m + i];
       for (int i = tid; i < m / 64; i += NT) cl[i] = cf[(size_t)bh * (m / 64) + i];
       __syncthreads();
       cur_bh = bh;
@@ -622,17 +623,16 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       for (int fb = 0; fb < NFB; ++fb) {
         const _Float16* Ab = Asl + (size_t)(256 * fb + l32) * SM::AS + 8 * hf;
         const unsigned short* Sb = Stl + (size_t)l32 * SS + 256 * fb + 4 * hf;
-        const unsigned short* zb = zl + 256 * fb + 4 * hf;
+        const float* zb = zl + 256 * fb + 4 * hf;
         f32x16 U[2][2];        // [unit parity][tt]
         u32x4 pk[2][2][2];     // [unit parity][tt][hh]
         half8 af[D / 16];      // A' fragments of the unit being projected
         u32x4 sf[2][CT];       // S^T fragments of the unit being accumulated
-        u32x2 zf[2][4];        // z of the unit being exponentiated: [parity][2 hh + q/2]
+        f32x4 zf[2];           // z of the features of the current and the next pair of pieces
         // prologue: P(0)
 #pragma unroll
         for (int s2 = 0; s2 < D / 16; ++s2) af[s2] = *reinterpret_cast<const half8*>(Ab + 16 * s2);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) zf[0][k] = *reinterpret_cast<const u32x2*>(zb + 8 * k);
+        zf[0] = *reinterpret_cast<const f32x4*>(zb);
 #pragma unroll
         for (int s2 = 0; s2 < D / 16; ++s2)
 #pragma unroll
@@ -668,10 +668,6 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
               // A' fragments for P(g+1), one every other step
               if (g < 7 && i % 2 == 0 && i / 2 < D / 16)
                 af[i / 2] = *reinterpret_cast<const half8*>(Ab + (size_t)32 * (g + 1) * SM::AS + 16 * (i / 2));
-              if (g < 7 && i == 1) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) zf[nxt][k] = *reinterpret_cast<const u32x2*>(zb + 32 * (g + 1) + 8 * k);
-              }
             } else {
               const int ip = i - NS;
               if (g < 7) {  // P(g+1)
@@ -689,13 +685,20 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
             }
             __builtin_amdgcn_sched_barrier(0);
             if (i % PER == PER - 1) {  // piece e of E(g): registers 8 hh + 2 q, + 1 of tile tt
-              const int e = i / PER, tt = e / 8, hh = (e % 8) / 4, q = e % 4;
+              // order (hh, q, tt), tt fastest: four consecutive pieces share one f32x4 of z
+              const int e = i / PER, tt = e % 2, hh = e / 8, q = (e / 2) % 4;
+              const int k = e / 4;  // = 2 hh + q / 2: features 8 k + 4 hf + [0,4) of the unit
+              if (e % 4 == 0) {     // fetch the next group's z (the next unit's first group at the end)
+                const int kn = (k + 1) % 4, gn = g + (k + 1) / 4;
+                zf[(k + 1) % 2] = *reinterpret_cast<const f32x4*>(zb + 32 * (gn % 8) + 8 * kn);
+              }
               const float a = fast_exp2(U[cur][tt][8 * hh + 2 * q] + sh[tt]);
               const float b = fast_exp2(U[cur][tt][8 * hh + 2 * q + 1] + sh[tt]);
-              const unsigned pq = pack_bf16(a, b);
-              pk[cur][tt][hh][q] = pq;
-              // the denominator weights are the same rounded features that multiply S
-              den[tt] = dot2_bf16(pq, zf[cur][2 * hh + q / 2][q % 2], den[tt]);
+              pk[cur][tt][hh][q] = pack_bf16(a, b);
+              // plain fmas: a dot2 instruction stalls behind the MFMAs in flight (measured: one
+              // v_dot2c per MFMA costs as much as six ordinary vector instructions)
+              den[tt] = fmaf(a, zf[k % 2][2 * (q % 2)], den[tt]);
+              den[tt] = fmaf(b, zf[k % 2][2 * (q % 2) + 1], den[tt]);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
@@ -795,7 +798,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          u32x2 zv = *reinterpret_cast<const u32x2*>(zl + 64 * blk + 32 * ft + 8 * g + 4 * hf);
+          f32x4 zv = *reinterpret_cast<const f32x4*>(zl + 64 * blk + 32 * ft + 8 * g + 4 * hf);
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt) {
             float a0 = fast_exp2(U[ft][tt][4 * g + 0]);
@@ -805,8 +808,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
             const unsigned p0 = pack_bf16(a0, a1), p1 = pack_bf16(a2, a3);
             pk[ft][tt][g / 2][2 * (g % 2)] = p0;
             pk[ft][tt][g / 2][2 * (g % 2) + 1] = p1;
-            // the denominator weights are the same rounded features that multiply S
-            den[tt] = dot2_bf16(p1, zv[1], dot2_bf16(p0, zv[0], den[tt]));
+            den[tt] = fmaf(a3, zv[3], fmaf(a2, zv[2], fmaf(a1, zv[1], fmaf(a0, zv[0], den[tt]))));
           }
         }
       // out^T[ct][tt] += S^T phi^T : k-slot s of half hf is feature 64 blk + 32 ft + 16 hh + 8 (s/4) + 4 hf + s%4
@@ -1005,8 +1007,9 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (ar.base == nullptr) return DARK_OK;
   if (ar.overflow) return DARK_EWORKSPACE;
 
-  const int nA = (p.m + kPrepRows - 1) / kPrepRows;
-  const size_t prep_lds = ((size_t)kPrepRows * (p.r + 1) + (size_t)p.r * p.d) * sizeof(float);
+  const int prep_rows = 256 / (p.d / 4);
+  const int nA = (p.m + prep_rows - 1) / prep_rows;
+  const size_t prep_lds = ((size_t)prep_rows * (p.r + 4) + (size_t)p.r * p.d) * sizeof(float);
   DARK_TRY(allow_lds(k_prep, prep_lds));
   DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA, p.H), dim3(256), prep_lds, M, W, b.Ah, b.Mh, p.m, p.r, p.d,
               p.w_shared, std::sqrt(pb.scale));
