@@ -38,7 +38,7 @@ const char* kernel_name(int k) {
   static const char* names[KID_COUNT] = {
       "f32_gemm",     "f32_load",   "f32_rowstat",  "f32_headmax",  "f32_exp",      "f32_sum_slices",
       "f32_finish",   "f32_scan",   "f32_bwd_elem", "fused_prep",   "fused_kv_reduce", "fused_kv_merge",
-      "fused_readout", "fused_causal_state", "fused_causal_scan", "fused_causal_out"};
+      "fused_readout", "fused_causal_state", "fused_causal_scan", "fused_causal_out", "fused_featurize"};
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }
@@ -98,7 +98,7 @@ static dark_status check_ws(const void* ws, size_t ws_bytes, size_t need) {
 static bool use_fused(const Problem& pb, int op, bool causal, dark_status* err) {
   *err = DARK_OK;
   if (pb.p.path == DARK_PATH_F32) return false;
-  bool ok = fused_supported(pb, op, causal);
+  bool ok = op == DARK_OP_FEATURIZE ? fused_featurize_supported(pb) : fused_supported(pb, op, causal);
   if (!ok && pb.p.path == DARK_PATH_FUSED) *err = DARK_EUNSUPPORTED;
   return ok;
 }
@@ -111,7 +111,8 @@ static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const 
   if (err != DARK_OK) return err;
   switch (op) {
     case DARK_OP_FEATURIZE:
-      return f32_featurize(pb, ar, Q, M, W, is_query, out, stab);
+      return fused ? fused_featurize(pb, ar, Q, M, W, is_query, out, stab)
+                   : f32_featurize(pb, ar, Q, M, W, is_query, out, stab);
     case DARK_OP_ATTN_FWD:
       return fused ? fused_attn_fwd(pb, ar, Q, K, V, M, W, out) : f32_attn_fwd(pb, ar, false, Q, K, V, M, W, out);
     case DARK_OP_ATTN_CAUSAL_FWD:
@@ -168,7 +169,11 @@ dark_status dark_featurize(const dark_params* p, const void* X, const float* M, 
   if (X == nullptr || M == nullptr || W == nullptr || phi == nullptr) return DARK_EINVAL;
   if (!aligned(X, 16) || !aligned(M, 16) || !aligned(W, 16) || !aligned(phi, 16) || !aligned(stab, 4))
     return DARK_EALIGN;
-  if (pb.p.path == DARK_PATH_FUSED) return DARK_EUNSUPPORTED;
+  {
+    dark_status err;
+    (void)use_fused(pb, DARK_OP_FEATURIZE, false, &err);
+    if (err != DARK_OK) return err;
+  }
   DARK_TRY(check_ws(ws, ws_bytes, measure(pb, DARK_OP_FEATURIZE, false)));
   pb.st = static_cast<hipStream_t>(hip_stream);
   Arena ar(ws, ws_bytes);

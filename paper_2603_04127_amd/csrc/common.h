@@ -30,6 +30,7 @@ enum KernelId : int {
   KID_CAUSAL_STATE,    // fused causal path: per-chunk state
   KID_CAUSAL_SCAN,     // fused causal path: exclusive scan over chunk states
   KID_CAUSAL_OUT,      // fused causal path: inter + intra chunk readout
+  KID_FEATURIZE,       // fused path: feature map written to memory (dark_featurize)
   KID_COUNT
 };
 
@@ -98,6 +99,11 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
 dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K,
                          const void* V, const float* M, const float* W, const void* dOut, float* dQ,
                          float* dK, float* dV, float* dM);
+
+// fused MFMA feature map (fused_feat.hip).
+bool fused_featurize_supported(const Problem& pb);
+dark_status fused_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,
+                            int is_query, void* phi, float* stab);
 
 // fused MFMA path (fused.hip).
 bool fused_supported(const Problem& pb, int op, bool causal);

@@ -986,6 +986,17 @@ dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, con
 
 }  // namespace
 
+dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh) {
+  const dark_params& p = pb.p;
+  const int prep_rows = 256 / (p.d / 4);
+  const int nA = (p.m + prep_rows - 1) / prep_rows;
+  const size_t prep_lds = ((size_t)prep_rows * (p.r + 4) + (size_t)p.r * p.d) * sizeof(float);
+  DARK_TRY(allow_lds(k_prep, prep_lds));
+  DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA, p.H), dim3(256), prep_lds, M, W, Ah, Mh, p.m, p.r, p.d, p.w_shared,
+              std::sqrt(pb.scale));
+  return DARK_OK;
+}
+
 bool fused_supported(const Problem& pb, int op, bool causal) {
   const dark_params& p = pb.p;
   if (op != DARK_OP_ATTN_FWD || causal) return false;
@@ -1007,12 +1018,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (ar.base == nullptr) return DARK_OK;
   if (ar.overflow) return DARK_EWORKSPACE;
 
-  const int prep_rows = 256 / (p.d / 4);
-  const int nA = (p.m + prep_rows - 1) / prep_rows;
-  const size_t prep_lds = ((size_t)prep_rows * (p.r + 4) + (size_t)p.r * p.d) * sizeof(float);
-  DARK_TRY(allow_lds(k_prep, prep_lds));
-  DARK_LAUNCH(KID_PREP, pb.st, k_prep, dim3(nA, p.H), dim3(256), prep_lds, M, W, b.Ah, b.Mh, p.m, p.r, p.d,
-              p.w_shared, std::sqrt(pb.scale));
+  DARK_TRY(fused_launch_prep(pb, M, W, b.Ah, b.Mh));
   if (p.d == 64) {
     DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V)));
   } else {

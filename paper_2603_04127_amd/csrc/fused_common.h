@@ -102,15 +102,9 @@ static dark_status allow_lds(KernelT kernel, size_t bytes) {
 
 }  // namespace fz
 
-// Hooks implemented in fused.hip and used by the causal path as well.
+// Implemented in fused.hip, used by the other fused translation units as well.
 // A' = sqrt(scale) log2(e) W M as fp16 [H][m][d];  M' = sqrt(scale) sqrt(log2(e)/2) M as fp16 [H][r][d].
+// Requires r, d multiples of 4, d <= 256, r * d <= 16384.
 dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh);
-// Per-slice states [S|z] = phi_K^T [V|1] with per-feature shifts: Spart [BH][P][m][dv], zpart, cpart [BH][P][m].
-dark_status fused_launch_kv(const Problem& pb, const void* K, const void* V, const _Float16* Ah, const _Float16* Mh,
-                            float* Spart, float* zpart, float* cpart, int P, int slice_len);
-bool fused_kv_shape_ok(const Problem& pb);
-
-// fused_causal.hip
-bool fused_causal_supported(const Problem& pb);
 
 }  // namespace dark

@@ -46,6 +46,28 @@ def test_featurize(bf16, is_query):
                 assert np.abs(lg - ref)[big].max() < 2e-4
 
 
+@pytest.mark.parametrize("is_query", [True, False])
+@pytest.mark.parametrize("shape", [(2, 2, 300, 64, 64, 256), (1, 2, 700, 64, 64, 512), (1, 2, 130, 128, 128, 128)])
+def test_featurize_fused(shape, is_query):
+    """MFMA feature-map kernel (bf16 in and out, fp16 projection operands)."""
+    B, H, L, d, r, m = shape
+    inp = U.random_problem(3, B=B, H=H, L=L, d=d, r=r, m=m, dv=8, bf16=True, amp=1.5)
+    dev = U.to_device(inp, True)
+    phi, stab = dk.dark_featurize(dev["Q"], dev["M"], dev["W"], is_query, path=dk.PATH_FUSED)
+    torch.cuda.synchronize()
+    phi, stab = _np(phi), _np(stab)
+    assert np.all(np.isfinite(phi)) and phi.max() <= 1.0 / np.sqrt(m) * (1 + 1e-2)
+    for b in range(B):
+        for h in range(H):
+            want, c = O.featurize(inp["Q"][b, h], inp["M"][h], inp["W"][h], is_query)
+            got_c = stab[b, h]
+            # the shift is itself a logit computed from fp16-rounded operands
+            assert np.abs(got_c - c).max() <= 2e-2
+            # phi * exp(shift) is the unstabilised feature vector: compare that, shift-independently
+            adj = phi[b, h] * np.exp((got_c - c)[:, None] if is_query else (got_c - c))
+            U.assert_close(adj, want, U.TOL["bf16"], f"fused phi[{b},{h}]")
+
+
 # ---------------------------------------------------------------------------
 # forward, small shapes spanning several tiles with ragged tails
 # ---------------------------------------------------------------------------
