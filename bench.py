@@ -51,6 +51,20 @@ def algorithmic_work(cfg):
     return th * f_tok, th * b_tok, per_kernel
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known
+    size), or None when no such measurement is on file."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel and parts[1].startswith("hbm_bytes_per_launch="):
+            return float(parts[1].split("=", 1)[1])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +75,10 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (read 256 MiB, write 256 MiB) three times before the "
+                         "timed region: under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its counter value gives the "
+                         "scale factor between the counters and real HBM bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every GPU box has one GPU); use --gpus 1", file=sys.stderr)
@@ -102,6 +120,13 @@ def main():
         if cfg.backward:
             dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], cfg.causal, chunk=cfg.chunk)
 
+    if args.calibrate_copy:
+        src = torch.full((64 * 1024 * 1024,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(copies[i % len(copies)])
     torch.cuda.synchronize()
@@ -130,8 +155,8 @@ def main():
     peak, unit = PEAK[bound]
     achieved = units / (us_step * 1e-6) / (1e9 if bound == "hbm" else 1e12)
     roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None, "avg_kernel_us": kernels[dom]["avg_us"],
-                "launches_per_step": kernels[dom]["launches"] / args.steps}
+                "frac": achieved / peak, "traffic": measured_traffic(cfg.name, dom),
+                "avg_kernel_us": kernels[dom]["avg_us"], "launches_per_step": kernels[dom]["launches"] / args.steps}
 
     line = {
         "metric": "DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)",
