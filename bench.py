@@ -44,8 +44,8 @@ def algorithmic_work(cfg):
         # kernel name -> (bound, algorithmic units per launch) ; bytes for hbm, flops otherwise
         "fused_kv_reduce": ("hbm", th * (d + dv) * s_in),
         "fused_readout": ("hbm", th * (d + dv) * s_in),
-        "fused_causal_state": ("hbm", th * (d + dv) * s_in),
-        "fused_causal_out": ("mfma", th * (2 * d * m + 2 * m * (dv + 1) + m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1))),
+        # the scan's MFMA work: both projections, the state read-out and update, the tile triangle
+        "fused_causal_scan": ("mfma", th * (4 * d * m + 4 * m * (dv + 1) + m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1))),
         "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
     }
     return th * f_tok, th * b_tok, per_kernel

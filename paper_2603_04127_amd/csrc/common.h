@@ -27,9 +27,9 @@ enum KernelId : int {
   KID_KV_REDUCE,       // fused path: phi(K)^T [V|1] per L-slice
   KID_KV_MERGE,        // fused path: fixed-order merge of slice states
   KID_READOUT,         // fused path: phi(Q) S / phi(Q) z
-  KID_CAUSAL_STATE,    // fused causal path: per-chunk state
-  KID_CAUSAL_SCAN,     // fused causal path: exclusive scan over chunk states
-  KID_CAUSAL_OUT,      // fused causal path: inter + intra chunk readout
+  KID_KEY_NORMS,       // fused causal path: norm term of every key
+  KID_CAUSAL_PREFIX,   // fused causal path: exclusive prefix over the slice states
+  KID_CAUSAL_SCAN,     // fused causal path: tile-by-tile scan inside a slice (inter + intra term)
   KID_FEATURIZE,       // fused path: feature map written to memory (dark_featurize)
   KID_COUNT
 };

@@ -999,6 +999,7 @@ dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W,
 
 bool fused_supported(const Problem& pb, int op, bool causal) {
   const dark_params& p = pb.p;
+  if (op == DARK_OP_ATTN_CAUSAL_FWD) return fused_causal_supported(pb);
   if (op != DARK_OP_ATTN_FWD || causal) return false;
   if (p.io_dtype != DARK_BF16) return false;
   const bool shape64 = p.d == 64 && p.r == 64 && p.dv == 64;
@@ -1041,9 +1042,24 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   return DARK_OK;
 }
 
-dark_status fused_attn_causal_fwd(const Problem&, Arena&, const void*, const void*, const void*, const float*,
-                                  const float*, void*) {
-  return DARK_EUNSUPPORTED;
+dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
+                                   const _Float16* Mh, float* Spart, float* zpart, float* cpart, int P,
+                                   int slice_len) {
+  const dark_params& p = pb.p;
+  Plan pl{};
+  pl.nfb = p.m / 256;
+  pl.P = P;
+  pl.slice_len = slice_len;
+  pl.n_work = (int)(pb.BH() * P);
+  pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
+  FusedBufs b{};
+  b.Ah = const_cast<_Float16*>(Ah);
+  b.Mh = const_cast<_Float16*>(Mh);
+  b.Spart = Spart;
+  b.zpart = zpart;
+  b.cpart = cpart;
+  if (p.d == 64) return launch_kv<64, 64, 64, 2>(pb, pl, b, K, V);
+  return launch_kv<128, 128, 128, 1>(pb, pl, b, K, V);
 }
 
 }  // namespace dark

@@ -253,3 +253,67 @@ def test_fused_matches_f32_path_and_is_deterministic():
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     U.assert_close(_np(a), _np(c), U.TOL["bf16"], "fused vs fp32 path")
+
+
+# ---------------------------------------------------------------------------
+# fused MFMA causal path (bf16 inputs), forced
+# ---------------------------------------------------------------------------
+FUSED_CAUSAL_SHAPES = [
+    # B, H, L,    d,   r,   m,   dv
+    (1, 2, 300, 64, 64, 256, 64),      # several slices, ragged tail inside the last tile
+    (2, 3, 1000, 64, 64, 256, 64),     # slices of more than one key tile
+    (1, 1, 32, 64, 64, 256, 64),       # exactly one scan tile
+    (1, 1, 7, 64, 64, 256, 64),        # shorter than a tile
+    (1, 1, 1, 64, 64, 256, 64),        # a single position: out == v
+    (1, 1, 2100, 64, 64, 256, 64),     # many slices for one head: long prefix chain
+    (1, 2, 333, 128, 128, 256, 128),   # wide head: two workgroups per slice, one per half of the value columns
+    (2, 2, 900, 128, 128, 256, 128),
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_CAUSAL_SHAPES)
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_fused_causal_forward(shape, out_f32):
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(21, B, H, L, d, r, m, dv, bf16=True, amp=2.0)
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED,
+                                  out_dtype=torch.float32 if out_f32 else None)
+    torch.cuda.synchronize()
+    assert out.dtype == (torch.float32 if out_f32 else torch.bfloat16)
+    e = U.assert_close(_np(out), U.oracle_attn(inp, True), U.TOL["bf16"], f"fused causal {shape}")
+    print(f"fused causal {shape} out_f32={out_f32}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+
+
+def test_fused_causal_first_row_and_last_row():
+    inp = U.random_problem(22, 1, 2, 500, 64, 64, 256, 64, bf16=True)
+    dev = U.to_device(inp, True)
+    c = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED,
+                                out_dtype=torch.float32)
+    b = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED,
+                         out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    # position 0 sees only itself; the last position sees everything (bidirectional result)
+    np.testing.assert_allclose(_np(c)[:, :, 0], inp["V"][:, :, 0], rtol=1e-5, atol=1e-5)
+    U.assert_close(_np(c)[:, :, -1], _np(b)[:, :, -1], U.TOL["bf16"], "last row")
+
+
+def test_fused_causal_matches_f32_path_and_is_deterministic():
+    inp = U.random_problem(23, 2, 3, 900, 64, 64, 256, 64, bf16=True)
+    dev = U.to_device(inp, True)
+    a = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED).clone()
+    b = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    c = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    U.assert_close(_np(a), _np(c), U.TOL["bf16"], "fused causal vs fp32 path")
+
+
+def test_fused_causal_wide_logit_range():
+    inp = U.random_problem(24, 1, 1, 700, 64, 64, 256, 64, bf16=True, amp=8.0)
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
+    assert lg.max() - lg.min() > 40
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, True), U.TOL["bf16"], "fused causal, wide logit range")
