@@ -38,7 +38,7 @@ const char* kernel_name(int k) {
   static const char* names[KID_COUNT] = {
       "f32_gemm",     "f32_load",   "f32_rowstat",  "f32_headmax",  "f32_exp",      "f32_sum_slices",
       "f32_finish",   "f32_scan",   "f32_bwd_elem", "fused_prep",   "fused_kv_reduce", "fused_kv_merge",
-      "fused_readout", "fused_key_norms", "fused_causal_prefix", "fused_causal_scan", "fused_featurize"};
+      "fused_readout", "fused_key_norms", "fused_causal_state", "fused_causal_prefix", "fused_causal_scan", "fused_featurize"};
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }

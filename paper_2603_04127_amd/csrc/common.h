@@ -28,6 +28,7 @@ enum KernelId : int {
   KID_KV_MERGE,        // fused path: fixed-order merge of slice states
   KID_READOUT,         // fused path: phi(Q) S / phi(Q) z
   KID_KEY_NORMS,       // fused causal path: norm term of every key
+  KID_CAUSAL_STATE,    // fused causal path: state of every slice
   KID_CAUSAL_PREFIX,   // fused causal path: exclusive prefix over the slice states
   KID_CAUSAL_SCAN,     // fused causal path: tile-by-tile scan inside a slice (inter + intra term)
   KID_FEATURIZE,       // fused path: feature map written to memory (dark_featurize)

@@ -161,6 +161,210 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const float* __restrict__ Spa
 }
 
 // ---------------------------------------------------------------------------
+// k_slice_state: [S|z] = phi_K^T [V|1] over one slice of one (b,h), all dv columns.
+// Workgroup = 8 waves: wave (fg, hv) = (w % 4, w / 4) projects the 32 features 64 fg + 32 hv + [0,32)
+// of each 32-token tile (tokens as MFMA columns), exponentiates, and leaves the packed features in
+// an LDS patch shared with its partner (fg, 1 - hv); after the tile's barrier both waves read the
+// patch with transposing loads and add phi_K^T V for all 64 features of the group to their own
+// half of the value columns.  z comes from an MFMA against ones in the hv = 0 waves.
+// Shifts: one per wave (32 features), set from the first tile, raised only when a logit exceeds
+// it by more than kRaise; a raise is published with the features so that both waves rescale the
+// rows concerned.  K tiles are double-buffered, V tiles triple-buffered (they are still being
+// read after the barrier), one barrier per tile.
+// ---------------------------------------------------------------------------
+template <int D>
+struct SsSmem {
+  static constexpr int AS = D + 8;
+  static constexpr size_t a_bytes = (size_t)256 * AS * 2;
+  static constexpr size_t x_bytes = (size_t)kCT * AS * 2;
+  static constexpr size_t v_bytes = (size_t)kCT * D * 2;
+  static constexpr int TBS = 64 * 2 + 8;
+  static constexpr size_t tb_bytes = (size_t)kCT * TBS;  // per feature group
+  static constexpr size_t ns_bytes = (size_t)kCT * 4;
+  static constexpr size_t dl_bytes = (size_t)8 * 4;
+  static constexpr size_t total = a_bytes + 2 * x_bytes + 3 * v_bytes + 2 * 4 * tb_bytes + 2 * ns_bytes + 2 * dl_bytes;
+};
+
+template <int D>
+__global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __restrict__ Kg,
+                                                        const unsigned short* __restrict__ Vg,
+                                                        const _Float16* __restrict__ Ah,
+                                                        const float* __restrict__ nrm, float* __restrict__ Spart,
+                                                        float* __restrict__ zpart, float* __restrict__ cpart, int H,
+                                                        int L, int P, int slice_len) {
+  using SM = SsSmem<D>;
+  constexpr int DVT = D, DVW = D / 2, NCT = DVW / 32, m = 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  _Float16* Asl = reinterpret_cast<_Float16*>(smem);
+  unsigned char* xb = smem + SM::a_bytes;
+  unsigned char* vb = xb + 2 * SM::x_bytes;
+  unsigned char* tbb = vb + 3 * SM::v_bytes;
+  float* nsb = reinterpret_cast<float*>(tbb + 2 * 4 * SM::tb_bytes);
+  float* dlb = nsb + 2 * kCT;
+
+  const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
+  const int l32 = lane % 32, hf = lane / 32;
+  const int j16 = l32 % 16, g2 = l32 / 16;
+  const int fg = wv % 4, hv = wv / 4;
+  const int bh = blockIdx.x / P, p = blockIdx.x % P;
+  const int h = bh % H;
+  const int tok_begin = p * slice_len;
+  const int tok_end = min(L, tok_begin + slice_len);
+  const int ntile = (tok_end - tok_begin + kCT - 1) / kCT;
+  if (ntile <= 0) return;
+
+  for (int ci = tid; ci < m * D / 8; ci += 512) {
+    const int row = ci / (D / 8), kc = ci % (D / 8);
+    *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
+        *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
+  }
+
+  constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a K (or V) tile
+  const bool stager = tid < NCH;
+  u32x4 kreg = {0u, 0u, 0u, 0u}, vreg = {0u, 0u, 0u, 0u};
+  float nreg = 0.f;
+  const unsigned short* Kb = Kg + (size_t)bh * L * D;
+  const unsigned short* Vb = Vg + (size_t)bh * L * DVT;
+  auto load_tile = [&](int t) {
+    const int t0 = tok_begin + t * kCT;
+    if (stager) {
+      const int tok = min(t0 + tid / (D / 8), tok_end - 1), kc = tid % (D / 8);
+      kreg = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
+      vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * kc);
+    }
+    if (tid < kCT) {
+      const int tok = t0 + tid;
+      nreg = tok < tok_end ? -nrm[(size_t)bh * L + tok] : -1e30f;  // keys past the end: features exactly zero
+    }
+  };
+  auto store_tile = [&](int t) {
+    _Float16* xs = reinterpret_cast<_Float16*>(xb + (t % 2) * SM::x_bytes);
+    unsigned short* vt = reinterpret_cast<unsigned short*>(vb + (t % 3) * SM::v_bytes);
+    if (stager) {
+      const int tok = tid / (D / 8), kc = tid % (D / 8);
+      *reinterpret_cast<u32x4*>(xs + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg);
+      *reinterpret_cast<u32x4*>(vt + tok * DVT + 8 * (kc ^ (tok & 7))) = vreg;
+    }
+    if (tid < kCT) nsb[(t % 2) * kCT + tid] = nreg;
+  };
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 S[2][NCT], zacc[2];
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb) {
+    zacc[fb] = zero16;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) S[fb][ct] = zero16;
+  }
+  float c = 0.f;  // this wave's shift (log2 domain), wave-uniform
+
+  load_tile(0);
+  store_tile(0);
+  if (ntile > 1) load_tile(1);
+  __syncthreads();
+
+  for (int t = 0; t < ntile; ++t) {
+    if (t + 1 < ntile) store_tile(t + 1);
+    if (t + 2 < ntile) load_tile(t + 2);
+    const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 2) * SM::x_bytes);
+    const unsigned short* vt = reinterpret_cast<const unsigned short*>(vb + (t % 3) * SM::v_bytes);
+    unsigned char* tb = tbb + ((t % 2) * 4 + fg) * SM::tb_bytes;
+    // --- this wave's 32 features of the tile ----------------------------------------------
+    const float nk = nsb[(t % 2) * kCT + l32] - c;
+    f32x16 U;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) U[v] = nk;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) {
+      const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * fg + 32 * hv + l32) * SM::AS + 16 * s + 8 * hf);
+      const half8 b = *reinterpret_cast<const half8*>(xs + l32 * SM::AS + 16 * s + 8 * hf);
+      U = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, U, 0, 0, 0);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) mx = max3(mx, U[v], U[v + 1]);
+    float delta = 0.f;
+    if (t == 0 || __any(mx > kRaise)) {  // wave-uniform; after the first tile this is rare
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+      delta = mx;
+      c += delta;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) U[v] -= delta;
+    }
+    if (lane == 0) dlb[(t % 2) * 8 + wv] = delta;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x2 w = {pack_bf16(fast_exp2(U[4 * g]), fast_exp2(U[4 * g + 1])),
+                 pack_bf16(fast_exp2(U[4 * g + 2]), fast_exp2(U[4 * g + 3]))};
+      *reinterpret_cast<u32x2*>(tb + l32 * SM::TBS + (32 * hv + 8 * g + 4 * hf) * 2) = w;
+    }
+    __syncthreads();
+    // --- a raise by either wave of the pair rescales the rows of its 32 features (rare) ------
+    if (t > 0) {
+      const float d0 = dlb[(t % 2) * 8 + fg], d1 = dlb[(t % 2) * 8 + 4 + fg];
+      if (d0 != 0.f || d1 != 0.f) {
+        const float f0 = fast_exp2(-d0), f1 = fast_exp2(-d1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          zacc[0][v] *= f0;
+          zacc[1][v] *= f1;
+#pragma unroll
+          for (int ct = 0; ct < NCT; ++ct) {
+            S[0][ct][v] *= f0;
+            S[1][ct][v] *= f1;
+          }
+        }
+      }
+    }
+    // --- S += phi_K^T V, z += phi_K^T 1: k-slot s of half hf is token 16 hh + 8 (s/4) + 4 hf + s%4 ---
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      u32x4 bv[NCT];
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct) {
+        const int tok = 16 * hh + 4 * hf + j16 / 4;
+        const int chunk = (DVW * hv) / 8 + 4 * ct + 2 * g2 + (j16 % 4) / 2;
+        const unsigned short* vr = vt + tok * DVT + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
+        u32x2 lo = lds_read_tr16(vr);
+        u32x2 hi = lds_read_tr16(vr + 8 * DVT);
+        bv[ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb) {
+        const unsigned short* tr = reinterpret_cast<const unsigned short*>(tb + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
+                                   32 * fb + 16 * g2 + 4 * (j16 % 4);
+        u32x2 lo = lds_read_tr16(tr);
+        u32x2 hi = lds_read_tr16(tr + 8 * (SM::TBS / 2));
+        u32x4 ak = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+          S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
+                                                              *reinterpret_cast<bf16x8*>(&bv[ct]), S[fb][ct], 0, 0, 0);
+        if (hv == 0) {
+          u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
+          zacc[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
+                                                             *reinterpret_cast<bf16x8*>(&o4), zacc[fb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // --- the slice's state ---------------------------------------------------------------------
+  const size_t srow0 = ((size_t)bh * P + p) * m;
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int feat = 64 * fg + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct) Spart[(srow0 + feat) * DVT + DVW * hv + 32 * ct + l32] = S[fb][ct][v];
+      if (hv == 0 && l32 == 0) zpart[srow0 + feat] = zacc[fb][v];
+    }
+  if (hf == 0) cpart[srow0 + 64 * fg + 32 * hv + l32] = c;
+}
+
+// ---------------------------------------------------------------------------
 // k_causal_scan
 // Workgroup = 4 waves over one slice of one (b,h) and 64 of the value columns; wave w owns
 // features [64w, 64w+64) (m = 256) and carries their rows of the state in accumulators:
@@ -196,7 +400,7 @@ struct CsSmem {
 };
 
 template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(256, 1) void k_causal_scan(const unsigned short* __restrict__ Qg,
+__global__ __launch_bounds__(256, 2) void k_causal_scan(const unsigned short* __restrict__ Qg,
                                                         const unsigned short* __restrict__ Kg,
                                                         const unsigned short* __restrict__ Vg,
                                                         const _Float16* __restrict__ Ah,
@@ -298,52 +502,74 @@ __global__ __launch_bounds__(256, 1) void k_causal_scan(const unsigned short* __
 
   load_tile(0);
   store_tile();
-  if (ntile > 1) load_tile(1);
   __syncthreads();
 
   for (int t = 0; t < ntile; ++t) {
-    // --- projections: tokens are columns, so lane = token -----------------------------------
-    const float nk = ns[l32];
-    f32x16 UK[2], UQ[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb) {
-      UQ[fb] = zero16;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) UK[fb][v] = nk;
-    }
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      const half8 bk = *reinterpret_cast<const half8*>(Xk + l32 * SM::AS + 16 * s + 8 * hf);
-      const half8 bq = *reinterpret_cast<const half8*>(Xq + l32 * SM::AS + 16 * s + 8 * hf);
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb) {
-        const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * wv + 32 * fb + l32) * SM::AS + 16 * s + 8 * hf);
-        UK[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bk, UK[fb], 0, 0, 0);
-        UQ[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, UQ[fb], 0, 0, 0);
-      }
-    }
-    // --- features ----------------------------------------------------------------------------
-    float mu = -INFINITY;
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int v = 0; v < 16; v += 2) mu = max3(mu, UQ[fb][v], UQ[fb][v + 1]);
-    mu = fmaxf(mu, __shfl_xor(mu, 32, 64));
+    // --- projections: tokens are columns, so lane = token.  Queries first, then keys, so that
+    // only one set of projection accumulators is alive at a time. ----------------------------
     u32x4 pq[2][2], pkk[2][2];  // [fb][hh]: k-slot s <-> accumulator register 8 hh + s
-    float den = 0.f;
+    float mu, den = 0.f;
+    {
+      f32x16 UQ[2] = {zero16, zero16};
 #pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
+      for (int s = 0; s < D / 16; ++s) {
+        const half8 bq = *reinterpret_cast<const half8*>(Xq + l32 * SM::AS + 16 * s + 8 * hf);
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int v = 8 * hh + 2 * q;
-          const float a = fast_exp2(UQ[fb][v] - mu), b = fast_exp2(UQ[fb][v + 1] - mu);
-          den = fmaf(a, zacc[fb][v], den);
-          den = fmaf(b, zacc[fb][v + 1], den);
-          pq[fb][hh][q] = pack_bf16(a, b);
-          pkk[fb][hh][q] = pack_bf16(fast_exp2(UK[fb][v]), fast_exp2(UK[fb][v + 1]));
+        for (int fb = 0; fb < 2; ++fb) {
+          const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * wv + 32 * fb + l32) * SM::AS + 16 * s + 8 * hf);
+          UQ[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, UQ[fb], 0, 0, 0);
         }
+        if (s % 4 == 3) __builtin_amdgcn_sched_barrier(0);  // bounds how far operand reads run ahead
+      }
+      mu = -INFINITY;
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) mu = max3(mu, UQ[fb][v], UQ[fb][v + 1]);
+      mu = fmaxf(mu, __shfl_xor(mu, 32, 64));
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int v = 8 * hh + 2 * q;
+            const float a = fast_exp2(UQ[fb][v] - mu), b = fast_exp2(UQ[fb][v + 1] - mu);
+            den = fmaf(a, zacc[fb][v], den);
+            den = fmaf(b, zacc[fb][v + 1], den);
+            pq[fb][hh][q] = pack_bf16(a, b);
+          }
+    }
+    {
+      const float nk = ns[l32];
+      f32x16 UK[2];
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) UK[fb][v] = nk;
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) {
+        const half8 bk = *reinterpret_cast<const half8*>(Xk + l32 * SM::AS + 16 * s + 8 * hf);
+#pragma unroll
+        for (int fb = 0; fb < 2; ++fb) {
+          const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * wv + 32 * fb + l32) * SM::AS + 16 * s + 8 * hf);
+          UK[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bk, UK[fb], 0, 0, 0);
+        }
+        if (s % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int v = 8 * hh + 2 * q;
+            pkk[fb][hh][q] = pack_bf16(fast_exp2(UK[fb][v]), fast_exp2(UK[fb][v + 1]));
+          }
+    }
+    // The next tile's rows are requested here, after the projections (whose accumulators have just
+    // died), and are parked in LDS at the end of this tile.
+    if (t + 1 < ntile) load_tile(t + 1);
     // phi_K of this wave, row-major [tok][feat], for the transposing reads below
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb)
@@ -478,7 +704,6 @@ __global__ __launch_bounds__(256, 1) void k_causal_scan(const unsigned short* __
       }
     }
     if (t + 1 < ntile) store_tile();
-    if (t + 2 < ntile) load_tile(t + 2);
     __syncthreads();
   }
 }
@@ -496,10 +721,17 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
                           float* cpre, float* nrm, void* out, int P, int slice_len) {
   const dark_params& p = pb.p;
   const unsigned BH = (unsigned)pb.BH();
-  DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
   const int chunks_per_bh = (p.L + 255) / 256;
   DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms<D, D>), dim3(BH * chunks_per_bh), dim3(256), 0,
               (const unsigned short*)K, Mh, nrm, p.H, p.L, chunks_per_bh);
+  if (env_int("DARK_CS_STATE", D == 128 ? 1 : 2) == 1) {
+    auto kern = k_slice_state<D>;
+    DARK_TRY(allow_lds(kern, SsSmem<D>::total));
+    DARK_LAUNCH(KID_CAUSAL_STATE, pb.st, kern, dim3(BH * P), dim3(512), SsSmem<D>::total, (const unsigned short*)K,
+                (const unsigned short*)V, Ah, nrm, Spart, zpart, cpart, p.H, p.L, P, slice_len);
+  } else {
+    DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
+  }
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
               Spre, zpre, cpre, p.m, P);
   const size_t lds = CsSmem<D>::total;
