@@ -7,12 +7,14 @@
 // keys of the tile itself, which enter through the masked 32 x 32 block of estimated kernel values.
 //
 // The sequence of every (b,h) is cut into P slices so that the chip is filled:
-//   k_kv_reduce (fused.hip)   state of every slice, per-feature shifts
+//   k_kv_reduce (fused.hip) or k_slice_state   state of every slice, per-feature shifts
 //   k_key_norms               n'(k_l) = |M' k_l|^2 for every key (log2 domain)
 //   k_kv_prefix               exclusive prefix of the slice states, brought to one running scalar
 //                             shift c*_p = max of the shifts of slices 0..p
 //   k_causal_scan             per (b,h, slice, 64 value columns): starts from the prefix state and
 //                             walks the slice in tiles of 32 tokens
+// (k_kv_reduce serves d = 64; the wide head uses k_slice_state, which keeps its accumulators within
+// the register file.)
 // Everything is in the log2 domain with the fp16 operands A', M' of the bidirectional path.
 #include <cmath>
 #include <cstdlib>
@@ -34,52 +36,61 @@ constexpr int kMaxP = 64;  // slices per (b,h) at most
 template <int D, int R>
 __global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restrict__ Kg,
                                                    const _Float16* __restrict__ Mh, float* __restrict__ nrm, int H,
-                                                   int L, int chunks_per_bh) {
+                                                   int L, int blocks_per_bh, int chunks_per_block) {
   constexpr int AS = D + 8;
   __shared__ __attribute__((aligned(16))) _Float16 Ms[R * AS];
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
-  const int bh = blockIdx.x / chunks_per_bh, chunk = blockIdx.x % chunks_per_bh;
+  const int bh = blockIdx.x / blocks_per_bh, blk = blockIdx.x % blocks_per_bh;
   const int h = bh % H;
+  const unsigned short* Xb = Kg + (size_t)bh * L * D;
+  // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8); rows past the end
+  // repeat the last row and are never stored
+  u32x4 xr[2][D / 16];
+  auto fetch = [&](int chunk, int tt) {
+    const int tok = min(chunk * 256 + 64 * wv + 32 * tt + l32, L - 1);
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) xr[tt][s] = *reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf);
+  };
+  const int c_begin = blk * chunks_per_block;
+  const int c_end = min(c_begin + chunks_per_block, (L + 255) / 256);
+  if (c_begin < c_end) {  // in flight while M' is copied
+    fetch(c_begin, 0);
+    fetch(c_begin, 1);
+  }
   for (int ci = tid; ci < R * D / 8; ci += 256) {
     const int row = ci / (D / 8), kc = ci % (D / 8);
     *reinterpret_cast<u32x4*>(Ms + row * AS + 8 * kc) =
         *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
   }
-  const int t0 = chunk * 256 + 64 * wv;
-  const unsigned short* Xb = Kg + (size_t)bh * L * D;
-  half8 xf[2][D / 16];
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    const int tok = min(t0 + 32 * tt + l32, L - 1);
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf));
-      xf[tt][s] = *reinterpret_cast<half8*>(&cv);
-    }
-  }
   __syncthreads();
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float n2[2] = {0.f, 0.f};
+  for (int chunk = c_begin; chunk < c_end; ++chunk) {
 #pragma unroll
-  for (int rt = 0; rt < R / 32; ++rt) {
-    f32x16 xt[2] = {zero16, zero16};
+    for (int tt = 0; tt < 2; ++tt) {
+      half8 xf[D / 16];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      half8 a = *reinterpret_cast<const half8*>(Ms + (32 * rt + l32) * AS + 16 * s + 8 * hf);
+      for (int s = 0; s < D / 16; ++s) {
+        u32x4 cv = bf16x8_to_f16x8(xr[tt][s]);
+        xf[s] = *reinterpret_cast<half8*>(&cv);
+      }
+      if (chunk + 1 < c_end) fetch(chunk + 1, tt);  // the next chunk's rows, while these are projected
+      float n2 = 0.f;
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) xt[tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xf[tt][s], xt[tt], 0, 0, 0);
+      for (int rt = 0; rt < R / 32; ++rt) {
+        f32x16 xt = zero16;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+          half8 a = *reinterpret_cast<const half8*>(Ms + (32 * rt + l32) * AS + 16 * s + 8 * hf);
+          xt = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, xf[s], xt, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) n2 = fmaf(xt[v], xt[v], n2);
+      }
+      n2 += __shfl_xor(n2, 32, 64);
+      const int tok = chunk * 256 + 64 * wv + 32 * tt + l32;
+      if (hf == 0 && tok < L) nrm[(size_t)bh * L + tok] = n2;
     }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) n2[tt] = fmaf(xt[tt][v], xt[tt][v], n2[tt]);
-  }
-#pragma unroll
-  for (int tt = 0; tt < 2; ++tt) {
-    n2[tt] += __shfl_xor(n2[tt], 32, 64);
-    const int tok = t0 + 32 * tt + l32;
-    if (hf == 0 && tok < L) nrm[(size_t)bh * L + tok] = n2[tt];
   }
 }
 
@@ -232,10 +243,8 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       kreg = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
       vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * kc);
     }
-    if (tid < kCT) {
-      const int tok = t0 + tid;
-      nreg = tok < tok_end ? -nrm[(size_t)bh * L + tok] : -1e30f;  // keys past the end: features exactly zero
-    }
+    // no arithmetic on the loaded value here: it would make the wave wait for everything above
+    nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
   };
   auto store_tile = [&](int t) {
     _Float16* xs = reinterpret_cast<_Float16*>(xb + (t % 2) * SM::x_bytes);
@@ -245,7 +254,9 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       *reinterpret_cast<u32x4*>(xs + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg);
       *reinterpret_cast<u32x4*>(vt + tok * DVT + 8 * (kc ^ (tok & 7))) = vreg;
     }
-    if (tid < kCT) nsb[(t % 2) * kCT + tid] = nreg;
+    // keys past the end of the slice: features exactly zero
+    const float nsv = tok_begin + t * kCT + tid % kCT < tok_end ? -nreg : -1e30f;
+    if (tid < kCT) nsb[(t % 2) * kCT + tid] = nsv;
   };
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -366,68 +377,59 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
 
 // ---------------------------------------------------------------------------
 // k_causal_scan
-// Workgroup = 4 waves over one slice of one (b,h) and 64 of the value columns; wave w owns
-// features [64w, 64w+64) (m = 256) and carries their rows of the state in accumulators:
-// S[feat][col] as MFMA accumulators, z[feat] as the accumulators of an MFMA against ones (all 32
-// columns equal, so every lane holds the z of exactly the features its phi_Q registers hold).
-// Per tile of 32 tokens, with tokens as MFMA columns in both projections
-// (U^T[feat][tok] = A' X^T, lane = token):
-//   phi_K = exp2(U_K - n' - c*), phi_Q = exp2(U_Q - mu), mu the row maximum over the wave's features
-//   P^T[k][q] = phi_K phi_Q^T over the wave's features, masked to k <= q      (intra-tile scores)
-//   N[q][col] = P V  +  phi_Q S                                               (before S is updated)
-//   D[q]      = row sums of P  +  phi_Q . z
-//   S += phi_K^T V,  z += phi_K^T 1   (phi_K is turned through a per-wave LDS patch with
-//                                      transposing reads: this contraction runs over tokens)
-// Every MFMA operand that is not read from LDS is the bf16 pack of an accumulator: the 32x32
-// accumulator layout (lane = column, registers = rows 8 (v/4) + 4 (lane/32) + v%4) is an operand
-// layout with the contraction index permuted, and both operands of a product use the same
-// permutation.  The four waves' partial (N, D, mu) meet in LDS; 256 threads combine them with the
-// factors 2^(mu_w - max mu), normalise and store 16-byte pieces of whole rows.
+// Workgroup = 8 waves over one slice of one (b,h) and 64 of the value columns.  Wave (fg, role) =
+// (w % 4, w / 4): the pair (fg, 0), (fg, 1) shares the features [64 fg, 64 fg + 64) and sits on
+// the same SIMD, where the matrix work of one overlaps the vector work of the other.
+//   role 0 projects and exponentiates the tile's queries, role 1 its keys (tokens are MFMA columns,
+//   lane = token); each leaves its packed features in an LDS patch for the partner;
+//   both then form the masked intra-tile scores P^T[k][q] over the pair's features and, for their
+//   own 32 value columns (32 role + [0,32)):  N = phi_Q S_old + P V,  S += phi_K^T V.
+//   role 0 owns the denominator (phi_Q . z + row sums of P) and the row shift mu, role 1 owns z.
+// The A' rows of the pair stay in registers for the whole slice; S is 64 x 32 per wave.
+// The eight waves' partial numerators meet in LDS; 512 threads combine them with the factors
+// 2^(mu_fg - max mu), normalise and store 8-byte pieces of whole rows.  Three barriers per tile.
 // ---------------------------------------------------------------------------
 template <int D>
 struct CsSmem {
-  static constexpr int AS = D + 8;                       // fp16 elements per row of A' and of an X tile
-  static constexpr size_t a_bytes = (size_t)256 * AS * 2;
-  static constexpr size_t x_bytes = (size_t)kCT * AS * 2;   // one tile of Q or of K
+  static constexpr int AS = D + 8;
+  static constexpr size_t x_bytes = (size_t)kCT * AS * 2;
   static constexpr size_t v_bytes = (size_t)kCT * kDVH * 2;
-  static constexpr int TBS = 64 * 2 + 8;                 // bytes per token row of the transpose patch
-  static constexpr size_t tb_bytes = (size_t)kCT * TBS;  // per wave
-  static constexpr int NBS = kDVH + 4;                   // floats per row of a partial-N tile
-  static constexpr size_t nb_bytes = (size_t)kCT * NBS * 4;  // per wave
-  static constexpr size_t dm_bytes = (size_t)2 * kCT * 4;    // per wave: D, mu
+  static constexpr int TBS = 64 * 2 + 8;
+  static constexpr size_t tb_bytes = (size_t)kCT * TBS;      // per wave: its packed features [tok][64]
+  static constexpr int NBS = 32 + 4;
+  static constexpr size_t nb_bytes = (size_t)kCT * NBS * 4;  // per wave: partial numerator [q][32]
+  static constexpr size_t dm_bytes = (size_t)4 * 2 * kCT * 4;  // per feature group: D, mu
+  static constexpr size_t zl_bytes = (size_t)4 * 64 * 4;       // per feature group: z
   static constexpr size_t ns_bytes = (size_t)kCT * 4;
-  static constexpr size_t total = a_bytes + 2 * x_bytes + v_bytes + 4 * (tb_bytes + nb_bytes + dm_bytes) + ns_bytes;
+  static constexpr size_t total = 2 * x_bytes + 2 * v_bytes + 8 * (tb_bytes + nb_bytes) + dm_bytes + zl_bytes + ns_bytes;
 };
 
 template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(256, 2) void k_causal_scan(const unsigned short* __restrict__ Qg,
-                                                        const unsigned short* __restrict__ Kg,
-                                                        const unsigned short* __restrict__ Vg,
-                                                        const _Float16* __restrict__ Ah,
-                                                        const float* __restrict__ nrm,
-                                                        const float* __restrict__ Spre,
-                                                        const float* __restrict__ zpre,
-                                                        const float* __restrict__ cpre, void* __restrict__ outp, int H,
-                                                        int L, int P, int slice_len) {
+__global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __restrict__ Qg,
+                                                         const unsigned short* __restrict__ Kg,
+                                                         const unsigned short* __restrict__ Vg,
+                                                         const _Float16* __restrict__ Ah,
+                                                         const float* __restrict__ nrm,
+                                                         const float* __restrict__ Spre,
+                                                         const float* __restrict__ zpre,
+                                                         const float* __restrict__ cpre, void* __restrict__ outp, int H,
+                                                         int L, int P, int slice_len) {
   using SM = CsSmem<D>;
-  constexpr int DVT = D;           // value width (dv = d)
-  constexpr int NH = DVT / kDVH;   // workgroups per (b,h, slice)
-  constexpr int m = 256;
+  constexpr int DVT = D, NH = DVT / kDVH, m = 256, NS = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Asl = reinterpret_cast<_Float16*>(smem);
-  _Float16* Xq = reinterpret_cast<_Float16*>(smem + SM::a_bytes);
-  _Float16* Xk = reinterpret_cast<_Float16*>(smem + SM::a_bytes + SM::x_bytes);
-  unsigned short* Vt = reinterpret_cast<unsigned short*>(smem + SM::a_bytes + 2 * SM::x_bytes);
-  unsigned char* wbase = smem + SM::a_bytes + 2 * SM::x_bytes + SM::v_bytes;
-  constexpr size_t wave_bytes = SM::tb_bytes + SM::nb_bytes + SM::dm_bytes;
-  float* ns = reinterpret_cast<float*>(wbase + 4 * wave_bytes);
+  _Float16* Xq = reinterpret_cast<_Float16*>(smem);
+  _Float16* Xk = reinterpret_cast<_Float16*>(smem + SM::x_bytes);
+  unsigned short* Vt2 = reinterpret_cast<unsigned short*>(smem + 2 * SM::x_bytes);
+  unsigned char* patch0 = smem + 2 * SM::x_bytes + 2 * SM::v_bytes;
+  float* nb0 = reinterpret_cast<float*>(patch0 + 8 * SM::tb_bytes);
+  float* dm0 = reinterpret_cast<float*>(patch0 + 8 * (SM::tb_bytes + SM::nb_bytes));
+  float* zl0 = dm0 + 4 * 2 * kCT;
+  float* ns = zl0 + 4 * 64;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
-  unsigned char* tb = wbase + wv * wave_bytes;
-  float* nbw = reinterpret_cast<float*>(wbase + wv * wave_bytes + SM::tb_bytes);
-  float* dmw = reinterpret_cast<float*>(wbase + wv * wave_bytes + SM::tb_bytes + SM::nb_bytes);
-
+  const int j16 = l32 % 16, g2 = l32 / 16;
+  const int fg = wv % 4, role = wv / 4;
   const int half = blockIdx.x % NH;
   const int p = (blockIdx.x / NH) % P;
   const int bh = blockIdx.x / (NH * P);
@@ -437,273 +439,269 @@ __global__ __launch_bounds__(256, 2) void k_causal_scan(const unsigned short* __
   const int ntile = (tok_end - tok_begin + kCT - 1) / kCT;
   if (ntile <= 0) return;
 
-  // --- resident operands ---------------------------------------------------------------------
-  for (int ci = tid; ci < m * D / 8; ci += 256) {
-    const int row = ci / (D / 8), kc = ci % (D / 8);
-    *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
-        *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
-  }
+  unsigned char* my_patch = patch0 + wv * SM::tb_bytes;
+  const unsigned char* other_patch = patch0 + (wv ^ 4) * SM::tb_bytes;
+  const unsigned char* k_patch = patch0 + (4 + fg) * SM::tb_bytes;
+  float* nbw = nb0 + wv * (SM::nb_bytes / 4);
+  float* dmg = dm0 + fg * 2 * kCT;
+  float* zl = zl0 + fg * 64;
+
+  // --- resident operands: the pair's rows of A' (A operand of the projection: lane = feature) ---
+  half8 afr[2][NS];
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      afr[fb][s] = *reinterpret_cast<const half8*>(Ah + ((size_t)h * m + 64 * fg + 32 * fb + l32) * D + 16 * s + 8 * hf);
   const size_t srow0 = ((size_t)bh * P + p) * m;
   const float cs = cpre[(size_t)bh * P + p];
-  f32x16 S[2][2], zacc[2];
+  f32x16 S[2];
 #pragma unroll
   for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int feat = 64 * wv + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
-      zacc[fb][v] = zpre[srow0 + feat];
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) S[fb][ct][v] = Spre[(srow0 + feat) * DVT + half * kDVH + 32 * ct + l32];
+      const int feat = 64 * fg + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
+      S[fb][v] = Spre[(srow0 + feat) * DVT + half * kDVH + 32 * role + l32];
     }
+  if (role == 1) zl[lane] = zpre[srow0 + 64 * fg + lane];
 
-  // --- staging ---------------------------------------------------------------------------------
-  constexpr int KCH = D / 64;  // 16-byte pieces of a Q (or K) tile per thread
-  u32x4 qreg[KCH], kreg[KCH], vreg;
+  // --- staging: V straight to LDS, Q and K through registers (bf16 -> fp16) --------------------
+  constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a Q (or K) tile: 512 or 256
+  u32x4 qreg = {0u, 0u, 0u, 0u}, kreg = {0u, 0u, 0u, 0u};
   float nreg = 0.f;
   const unsigned short* Qb = Qg + (size_t)bh * L * D;
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DVT + half * kDVH;
-  // Rows past the end of the slice repeat its last row (in bounds, no predication); such keys get
-  // the norm term -1e30, so their features are exactly zero, and such queries are never stored.
-  auto load_tile = [&](int t) {
+  auto load_tile = [&](int t, int tid) {
     const int t0 = tok_begin + t * kCT;
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int ci = tid + 256 * i, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
-      qreg[i] = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 8 * kc);
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
+    if (tid < 256) {  // waves 0..3: one 1 KB run of eight rows each, swizzle applied on the source side
+      const int ln = tid % 64, r = 8 * (tid / 64) + ln / 8, pos = ln % 8;
+      const int tok = min(t0 + r, tok_end - 1), cc = pos ^ (r & 7);
+      dma16_to_lds(Vb + (size_t)tok * DVT + 8 * cc, Vt2 + (t % 2) * kCT * kDVH + (tid / 64) * 512);
     }
-    {
-      const int tok = min(t0 + tid / 8, tok_end - 1), cc = tid % 8;
-      vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * cc);
+    const int ci = tid % NCH, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
+    if (NCH == 512) {
+      qreg = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 8 * kc);
+      kreg = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
+    } else {  // threads 0..255 fetch Q, the others K
+      qreg = *reinterpret_cast<const u32x4*>((tid < NCH ? Qb : Kb) + (size_t)tok * D + 8 * kc);
     }
-    if (tid < kCT) {
-      const int tok = t0 + tid;
-      nreg = tok < tok_end ? -(nrm[(size_t)bh * L + tok] + cs) : -1e30f;
-    }
+    nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
   };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
-      *reinterpret_cast<u32x4*>(Xq + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(qreg[i]);
-      *reinterpret_cast<u32x4*>(Xk + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg[i]);
+  auto store_tile = [&](int t, int tid) {
+    const int ci = tid % NCH, tok = ci / (D / 8), kc = ci % (D / 8);
+    if (NCH == 512) {
+      *reinterpret_cast<u32x4*>(Xq + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(qreg);
+      *reinterpret_cast<u32x4*>(Xk + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg);
+    } else {
+      *reinterpret_cast<u32x4*>((tid < NCH ? Xq : Xk) + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(qreg);
     }
-    {
-      const int tok = tid / 8, cc = tid % 8;
-      *reinterpret_cast<u32x4*>(Vt + tok * kDVH + 8 * (cc ^ (tok & 7))) = vreg;
-    }
-    if (tid < kCT) ns[tid] = nreg;
+    const float nsv = tok_begin + t * kCT + tid % kCT < tok_end ? -(nreg + cs) : -1e30f;
+    if (tid < kCT) ns[tid] = nsv;
+    wait_vmcnt0();  // the V tile written by dma16_to_lds has landed
   };
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const u32x4 ones4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
-  const int j16 = l32 % 16, g2 = l32 / 16;
 
-  load_tile(0);
-  store_tile();
+  load_tile(0, tid);
+  store_tile(0, tid);
   __syncthreads();
 
   for (int t = 0; t < ntile; ++t) {
-    // --- projections: tokens are columns, so lane = token.  Queries first, then keys, so that
-    // only one set of projection accumulators is alive at a time. ----------------------------
-    u32x4 pq[2][2], pkk[2][2];  // [fb][hh]: k-slot s <-> accumulator register 8 hh + s
-    float mu, den = 0.f;
-    {
-      f32x16 UQ[2] = {zero16, zero16};
+    int tid_o = threadIdx.x;
+    asm volatile("" : "+v"(tid_o));  // thread-derived addresses are recomputed per tile, not kept
+    const unsigned short* Vt = Vt2 + (t % 2) * kCT * kDVH;
+    load_tile(min(t + 1, ntile - 1), tid_o);  // a whole tile ahead; unconditional (the last one twice)
+
+    // --- phase A: this wave's side of the feature map ---------------------------------------
+    const _Float16* X = role == 0 ? Xq : Xk;
+    const float init = role == 0 ? 0.f : ns[l32];
+    f32x16 U[2];
 #pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        const half8 bq = *reinterpret_cast<const half8*>(Xq + l32 * SM::AS + 16 * s + 8 * hf);
+    for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-        for (int fb = 0; fb < 2; ++fb) {
-          const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * wv + 32 * fb + l32) * SM::AS + 16 * s + 8 * hf);
-          UQ[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq, UQ[fb], 0, 0, 0);
-        }
-        if (s % 4 == 3) __builtin_amdgcn_sched_barrier(0);  // bounds how far operand reads run ahead
-      }
+      for (int v = 0; v < 16; ++v) U[fb][v] = init;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const half8 b = *reinterpret_cast<const half8*>(X + l32 * SM::AS + 16 * s + 8 * hf);
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb) U[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[fb][s], b, U[fb], 0, 0, 0);
+    }
+    u32x4 pw[2][2];  // own packed features, [fb][hh]: k-slot s <-> accumulator register 8 hh + s
+    float mu = 0.f, den = 0.f;
+    if (role == 0) {
       mu = -INFINITY;
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-        for (int v = 0; v < 16; v += 2) mu = max3(mu, UQ[fb][v], UQ[fb][v + 1]);
+        for (int v = 0; v < 16; v += 2) mu = max3(mu, U[fb][v], U[fb][v + 1]);
       mu = fmaxf(mu, __shfl_xor(mu, 32, 64));
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
+        for (int g = 0; g < 4; ++g) {
+          // z of the features this lane's registers hold: rows 8 g + 4 hf + [0,4) of block fb
+          const f32x4 zq = *reinterpret_cast<const f32x4*>(zl + 32 * fb + 8 * g + 4 * hf);
+          float e[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int v = 8 * hh + 2 * q;
-            const float a = fast_exp2(UQ[fb][v] - mu), b = fast_exp2(UQ[fb][v + 1] - mu);
-            den = fmaf(a, zacc[fb][v], den);
-            den = fmaf(b, zacc[fb][v + 1], den);
-            pq[fb][hh][q] = pack_bf16(a, b);
+          for (int i = 0; i < 4; ++i) {
+            e[i] = fast_exp2(U[fb][4 * g + i] - mu);
+            den = fmaf(e[i], zq[i], den);
           }
-    }
-    {
-      const float nk = ns[l32];
-      f32x16 UK[2];
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) UK[fb][v] = nk;
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        const half8 bk = *reinterpret_cast<const half8*>(Xk + l32 * SM::AS + 16 * s + 8 * hf);
-#pragma unroll
-        for (int fb = 0; fb < 2; ++fb) {
-          const half8 a = *reinterpret_cast<const half8*>(Asl + (64 * wv + 32 * fb + l32) * SM::AS + 16 * s + 8 * hf);
-          UK[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bk, UK[fb], 0, 0, 0);
+          pw[fb][g / 2][2 * (g % 2)] = pack_bf16(e[0], e[1]);
+          pw[fb][g / 2][2 * (g % 2) + 1] = pack_bf16(e[2], e[3]);
         }
-        if (s % 4 == 3) __builtin_amdgcn_sched_barrier(0);
-      }
+    } else {
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int v = 8 * hh + 2 * q;
-            pkk[fb][hh][q] = pack_bf16(fast_exp2(UK[fb][v]), fast_exp2(UK[fb][v + 1]));
-          }
+          for (int q = 0; q < 4; ++q)
+            pw[fb][hh][q] = pack_bf16(fast_exp2(U[fb][8 * hh + 2 * q]), fast_exp2(U[fb][8 * hh + 2 * q + 1]));
     }
-    // The next tile's rows are requested here, after the projections (whose accumulators have just
-    // died), and are parked in LDS at the end of this tile.
-    if (t + 1 < ntile) load_tile(t + 1);
-    // phi_K of this wave, row-major [tok][feat], for the transposing reads below
+    // own features, row-major [tok][feat], for the partner
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        u32x2 w = {pkk[fb][g / 2][2 * (g % 2)], pkk[fb][g / 2][2 * (g % 2) + 1]};
-        *reinterpret_cast<u32x2*>(tb + l32 * SM::TBS + (32 * fb + 8 * g + 4 * hf) * 2) = w;
+        u32x2 w = {pw[fb][g / 2][2 * (g % 2)], pw[fb][g / 2][2 * (g % 2) + 1]};
+        *reinterpret_cast<u32x2*>(my_patch + l32 * SM::TBS + (32 * fb + 8 * g + 4 * hf) * 2) = w;
       }
-    // --- intra-tile scores P^T[k][q], masked to k <= q --------------------------------------
-    f32x16 Pt = zero16;
+    __syncthreads();
+
+    // --- phase B ------------------------------------------------------------------------------
+    // The partner's features as operand fragments with the accumulator's permutation of the
+    // contraction index: k-slots 0..3 <-> features 16 hh + 4 hf + [0,4), slots 4..7 <-> those + 8.
+    u32x4 po[2][2];
 #pragma unroll
     for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-        Pt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pkk[fb][hh]),
-                                                     *reinterpret_cast<bf16x8*>(&pq[fb][hh]), Pt, 0, 0, 0);
+      for (int hh = 0; hh < 2; ++hh) {
+        const unsigned char* pr = other_patch + l32 * SM::TBS + (32 * fb + 16 * hh + 4 * hf) * 2;
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(pr), hi = *reinterpret_cast<const u32x2*>(pr + 16);
+        po[fb][hh] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+    // V fragments of this wave's 32 columns: k-slot s of half hf is token 16 hh + 8 (s/4) + 4 hf + s%4
+    u32x4 bv[2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int krow = 8 * (v / 4) + 4 * hf + (v % 4);
-      Pt[v] = krow <= l32 ? Pt[v] : 0.f;
+    for (int hh = 0; hh < 2; ++hh) {
+      const int tok = 16 * hh + 4 * hf + j16 / 4;
+      const int chunk = 4 * role + 2 * g2 + (j16 % 4) / 2;
+      const unsigned short* vr = Vt + tok * kDVH + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
+      const u32x2 lo = lds_read_tr16(vr), hi = lds_read_tr16(vr + 8 * kDVH);
+      bv[hh] = u32x4{lo[0], lo[1], hi[0], hi[1]};
     }
-    // The denominator sums the same bf16-rounded kernel values that multiply V, so the intra-tile
-    // part of N / D is an exact convex combination of value rows.
+    // phi_K^T fragments (rows = the pair's features, contraction over tokens)
+    auto k_frag = [&](int fb, int hh) {
+      const unsigned short* tr = reinterpret_cast<const unsigned short*>(k_patch + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
+                                 32 * fb + 16 * g2 + 4 * (j16 % 4);
+      const u32x2 l2 = lds_read_tr16(tr), h2 = lds_read_tr16(tr + 8 * (SM::TBS / 2));
+      return u32x4{l2[0], l2[1], h2[0], h2[1]};
+    };
+    f32x16 N, Pt;
+    auto scores_and_state_term = [&](u32x4 (&pq)[2][2], u32x4 (&pk)[2][2]) {
+      // numerator from the state as it was before this tile
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          u32x4 sb;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) sb[q] = pack_bf16(S[fb][8 * hh + 2 * q], S[fb][8 * hh + 2 * q + 1]);
+          N = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pq[fb][hh]),
+                                                      *reinterpret_cast<bf16x8*>(&sb),
+                                                      (fb == 0 && hh == 0) ? zero16 : N, 0, 0, 0);
+          Pt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[fb][hh]),
+                                                       *reinterpret_cast<bf16x8*>(&pq[fb][hh]),
+                                                       (fb == 0 && hh == 0) ? zero16 : Pt, 0, 0, 0);
+        }
+    };
+    if (role == 0) scores_and_state_term(pw, po);
+    else scores_and_state_term(po, pw);
+    // state update (after the read-out above): S += phi_K^T V; role 1 also sums phi_K over the tile
+    // (every column of that MFMA result is equal: one lane per half holds every sum of its rows)
+#pragma unroll
+    for (int fb = 0; fb < 2; ++fb) {
+      u32x4 ak0 = k_frag(fb, 0), ak1 = k_frag(fb, 1);
+      S[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak0), *reinterpret_cast<bf16x8*>(&bv[0]),
+                                                      S[fb], 0, 0, 0);
+      S[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1), *reinterpret_cast<bf16x8*>(&bv[1]),
+                                                      S[fb], 0, 0, 0);
+      if (role == 1) {
+        u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
+        f32x16 dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak0),
+                                                            *reinterpret_cast<bf16x8*>(&o4), zero16, 0, 0, 0);
+        dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1), *reinterpret_cast<bf16x8*>(&o4), dz,
+                                                     0, 0, 0);
+        if (l32 == 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) zl[32 * fb + 8 * (v / 4) + 4 * hf + (v % 4)] += dz[v];
+        }
+      }
+    }
+    // masked scores (k <= q), packed; the denominator sums the same bf16-rounded kernel values that
+    // multiply V, so the intra-tile part of N / D is an exact convex combination of value rows
     u32x4 pp[2];
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const unsigned w = pack_bf16(Pt[8 * hh + 2 * q], Pt[8 * hh + 2 * q + 1]);
+        const int v = 8 * hh + 2 * q;
+        const int krow = 8 * (v / 4) + 4 * hf + (v % 4);
+        const float x0 = krow <= l32 ? Pt[v] : 0.f, x1 = krow + 1 <= l32 ? Pt[v + 1] : 0.f;
+        const unsigned w = pack_bf16(x0, x1);
         pp[hh][q] = w;
-        den += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
+        if (role == 0) den += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
       }
-    den += __shfl_xor(den, 32, 64);
-    // --- V fragments: k-slot s of half hf is token 16 hh + 8 (s/4) + 4 hf + s%4 -------------
-    u32x4 bv[2][2];
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh)
+      N = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pp[hh]), *reinterpret_cast<bf16x8*>(&bv[hh]), N,
+                                                  0, 0, 0);
+    // partial results
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const int tok = 16 * hh + 4 * hf + j16 / 4;
-        const int chunk = 4 * ct + 2 * g2 + (j16 % 4) / 2;
-        const unsigned short* vr = Vt + tok * kDVH + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
-        u32x2 lo = lds_read_tr16(vr);
-        u32x2 hi = lds_read_tr16(vr + 8 * kDVH);
-        bv[hh][ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+    for (int v = 0; v < 16; ++v) nbw[(8 * (v / 4) + 4 * hf + (v % 4)) * SM::NBS + l32] = N[v];
+    if (role == 0) {
+      den += __shfl_xor(den, 32, 64);
+      if (hf == 0) {
+        dmg[l32] = den;
+        dmg[kCT + l32] = mu;
       }
-    // --- numerator: intra-tile term, then the state as it was before this tile --------------
-    f32x16 N[2] = {zero16, zero16};
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
-        N[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pp[hh]),
-                                                        *reinterpret_cast<bf16x8*>(&bv[hh][ct]), N[ct], 0, 0, 0);
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          u32x4 sb;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) sb[q] = pack_bf16(S[fb][ct][8 * hh + 2 * q], S[fb][ct][8 * hh + 2 * q + 1]);
-          N[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pq[fb][hh]),
-                                                          *reinterpret_cast<bf16x8*>(&sb), N[ct], 0, 0, 0);
-        }
-    // --- state update: contraction over the tile's tokens -----------------------------------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        const unsigned short* tr = reinterpret_cast<const unsigned short*>(tb + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
-                                   32 * fb + 16 * g2 + 4 * (j16 % 4);
-        u32x2 lo = lds_read_tr16(tr);
-        u32x2 hi = lds_read_tr16(tr + 8 * (SM::TBS / 2));
-        u32x4 ak = {lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-          S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
-                                                              *reinterpret_cast<bf16x8*>(&bv[hh][ct]), S[fb][ct], 0, 0, 0);
-        u32x4 o4 = ones4;
-        zacc[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
-                                                           *reinterpret_cast<bf16x8*>(&o4), zacc[fb], 0, 0, 0);
-      }
-    // --- partial results of this wave --------------------------------------------------------
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) nbw[(8 * (v / 4) + 4 * hf + (v % 4)) * SM::NBS + 32 * ct + l32] = N[ct][v];
-    if (hf == 0) {
-      dmw[l32] = den;
-      dmw[kCT + l32] = mu;
     }
     __syncthreads();
-    // --- combine the four waves, normalise, store --------------------------------------------
+    // --- combine the four feature groups, normalise, store ------------------------------------
     {
-      const int q = tid / 8, dg = tid % 8;
+      const int q = tid_o / 16, cg = tid_o % 16;  // row, group of 4 columns
       float muw[4], mx = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        muw[w] = reinterpret_cast<const float*>(wbase + w * wave_bytes + SM::tb_bytes + SM::nb_bytes)[kCT + q];
-        mx = fmaxf(mx, muw[w]);
+      for (int g = 0; g < 4; ++g) {
+        muw[g] = dm0[g * 2 * kCT + kCT + q];
+        mx = fmaxf(mx, muw[g]);
       }
-      float dsum = 0.f, num[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      float dsum = 0.f;
+      f32x4 num = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float f = fast_exp2(muw[w] - mx);
-        dsum = fmaf(f, reinterpret_cast<const float*>(wbase + w * wave_bytes + SM::tb_bytes + SM::nb_bytes)[q], dsum);
-        const float* np = reinterpret_cast<const float*>(wbase + w * wave_bytes + SM::tb_bytes) + q * SM::NBS + 8 * dg;
-        const f32x4 a = *reinterpret_cast<const f32x4*>(np), b = *reinterpret_cast<const f32x4*>(np + 4);
+      for (int g = 0; g < 4; ++g) {
+        const float f = fast_exp2(muw[g] - mx);
+        dsum = fmaf(f, dm0[g * 2 * kCT + q], dsum);
+        const f32x4 a = *reinterpret_cast<const f32x4*>(nb0 + (g + 4 * (cg / 8)) * (SM::nb_bytes / 4) + q * SM::NBS + 4 * (cg % 8));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          num[e] = fmaf(f, a[e], num[e]);
-          num[4 + e] = fmaf(f, b[e], num[4 + e]);
-        }
+        for (int e = 0; e < 4; ++e) num[e] = fmaf(f, a[e], num[e]);
       }
-      const float inv = 1.0f / dsum;
+      const float inv = __builtin_amdgcn_rcpf(dsum);
       const int tok = tok_begin + t * kCT + q;
       if (tok < tok_end) {
-        const size_t o = ((size_t)bh * L + tok) * DVT + half * kDVH + 8 * dg;
+        const size_t o = ((size_t)bh * L + tok) * DVT + half * kDVH + 4 * cg;
         if (OUT_BF16) {
-          u32x4 w = {pack_bf16(num[0] * inv, num[1] * inv), pack_bf16(num[2] * inv, num[3] * inv),
-                     pack_bf16(num[4] * inv, num[5] * inv), pack_bf16(num[6] * inv, num[7] * inv)};
-          *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned short*>(outp) + o) = w;
+          u32x2 w = {pack_bf16(num[0] * inv, num[1] * inv), pack_bf16(num[2] * inv, num[3] * inv)};
+          *reinterpret_cast<u32x2*>(reinterpret_cast<unsigned short*>(outp) + o) = w;
         } else {
-          float* op = reinterpret_cast<float*>(outp) + o;
-          *reinterpret_cast<f32x4*>(op) = f32x4{num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
-          *reinterpret_cast<f32x4*>(op + 4) = f32x4{num[4] * inv, num[5] * inv, num[6] * inv, num[7] * inv};
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + o) =
+              f32x4{num[0] * inv, num[1] * inv, num[2] * inv, num[3] * inv};
         }
       }
     }
-    if (t + 1 < ntile) store_tile();
+    store_tile(min(t + 1, ntile - 1), tid_o);
     __syncthreads();
   }
 }
@@ -721,9 +719,17 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
                           float* cpre, float* nrm, void* out, int P, int slice_len) {
   const dark_params& p = pb.p;
   const unsigned BH = (unsigned)pb.BH();
-  const int chunks_per_bh = (p.L + 255) / 256;
-  DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms<D, D>), dim3(BH * chunks_per_bh), dim3(256), 0,
-              (const unsigned short*)K, Mh, nrm, p.H, p.L, chunks_per_bh);
+  {
+    // about 1024 workgroups, each over a run of 256-token chunks of one (b,h): M' is copied to LDS once
+    // per workgroup and the rows of the next chunk are in flight while the current one is projected
+    const int chunks_per_bh = (p.L + 255) / 256;
+    int blocks_per_bh = (int)(1024 / BH);
+    blocks_per_bh = blocks_per_bh < 1 ? 1 : (blocks_per_bh > chunks_per_bh ? chunks_per_bh : blocks_per_bh);
+    const int chunks_per_block = (chunks_per_bh + blocks_per_bh - 1) / blocks_per_bh;
+    blocks_per_bh = (chunks_per_bh + chunks_per_block - 1) / chunks_per_block;
+    DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms<D, D>), dim3(BH * blocks_per_bh), dim3(256), 0,
+                (const unsigned short*)K, Mh, nrm, p.H, p.L, blocks_per_bh, chunks_per_block);
+  }
   if (env_int("DARK_CS_STATE", D == 128 ? 1 : 2) == 1) {
     auto kern = k_slice_state<D>;
     DARK_TRY(allow_lds(kern, SsSmem<D>::total));
@@ -734,21 +740,13 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
   }
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
               Spre, zpre, cpre, p.m, P);
-  const size_t lds = CsSmem<D>::total;
   const unsigned grid = BH * P * (D / kDVH);
-  if (p.out_dtype == DARK_BF16) {
-    auto kern = k_causal_scan<D, true>;
-    DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_CAUSAL_SCAN, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q,
-                (const unsigned short*)K, (const unsigned short*)V, Ah, nrm, Spre, zpre, cpre, out, p.H, p.L, P,
-                slice_len);
-  } else {
-    auto kern = k_causal_scan<D, false>;
-    DARK_TRY(allow_lds(kern, lds));
-    DARK_LAUNCH(KID_CAUSAL_SCAN, pb.st, kern, dim3(grid), dim3(256), lds, (const unsigned short*)Q,
-                (const unsigned short*)K, (const unsigned short*)V, Ah, nrm, Spre, zpre, cpre, out, p.H, p.L, P,
-                slice_len);
-  }
+  const unsigned short *Qp = (const unsigned short*)Q, *Kp = (const unsigned short*)K, *Vp = (const unsigned short*)V;
+  const size_t lds = CsSmem<D>::total;
+  auto kern = p.out_dtype == DARK_BF16 ? k_causal_scan<D, true> : k_causal_scan<D, false>;
+  DARK_TRY(allow_lds(kern, lds));
+  DARK_LAUNCH(KID_CAUSAL_SCAN, pb.st, kern, dim3(grid), dim3(512), lds, Qp, Kp, Vp, Ah, nrm, Spre, zpre, cpre, out, p.H,
+              p.L, P, slice_len);
   return DARK_OK;
 }
 

@@ -84,6 +84,17 @@ __device__ static inline u32x2 lds_read_tr16(const unsigned short* p) {
   return *reinterpret_cast<u32x2*>(&v);
 }
 
+// Direct global -> LDS load of 16 bytes per lane (global_load_lds_dwordx4): lane i of the wave
+// writes the 16 bytes at gsrc (its own address) to LDS at lds_wave_base + 16 i.  The load is
+// counted by vmcnt like any global load, but it is issued from inline assembly so that the
+// compiler does not serialise later LDS reads behind it: the caller waits (wait_vmcnt0) and
+// synchronises before anyone reads the destination.
+__device__ static inline void dma16_to_lds(const void* gsrc, void* lds_wave_base) {
+  const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(base) : "memory", "m0");
+}
+__device__ static inline void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
+
 // Raises a kernel's dynamic-LDS limit when it needs more than the default; done once per kernel
 // and size (the attribute call is host work we do not want on every launch).
 template <typename KernelT>
