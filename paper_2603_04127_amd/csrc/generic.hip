@@ -67,11 +67,96 @@ struct Gemm {
 };
 
 constexpr int GT = 64;  // C tile edge
-constexpr int GK = 16;  // K step
+constexpr int GK = 32;  // K step
+
+// How one operand tile (64 x GK, element (x, k) at P[x * sx + k * sk]) is fetched: 16-byte loads
+// along k or along x when that index is contiguous and everything is 16-byte aligned, else scalars.
+enum { GL_SCALAR = 0, GL_VEC_K = 1, GL_VEC_X = 2 };
+
+__device__ inline int gemm_load_mode(const float* P, long long sx, long long sk, long long s0, long long s1,
+                                     long long s2) {
+  const bool al = ((reinterpret_cast<uintptr_t>(P) | (uintptr_t)(s0 * 4) | (uintptr_t)(s1 * 4) | (uintptr_t)(s2 * 4)) & 15) == 0;
+  if (al && sk == 1 && (sx & 3) == 0) return GL_VEC_K;
+  if (al && sx == 1 && (sk & 3) == 0) return GL_VEC_X;
+  return GL_SCALAR;
+}
+
+// Fetches this thread's 8 elements of an operand tile into registers (zero outside the matrix).
+__device__ inline void gemm_fetch(float (&r)[8], int mode, const float* P, long long sx, long long sk, int x0, int Xe,
+                                  int k0, int Ke, int tid) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int idx = tid + 256 * t;
+    if (mode == GL_VEC_K) {
+      const int k4 = idx % (GK / 4), x = idx / (GK / 4);
+      const int gx = x0 + x, gk = k0 + 4 * k4;
+      if (gx < Xe && gk + 3 < Ke) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(P + gx * sx + gk);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[4 * t + j] = v[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[4 * t + j] = (gx < Xe && gk + j < Ke) ? P[gx * sx + gk + j] : 0.f;
+      }
+    } else if (mode == GL_VEC_X) {
+      const int x4 = idx % (GT / 4), k = idx / (GT / 4);
+      const int gx = x0 + 4 * x4, gk = k0 + k;
+      if (gk < Ke && gx + 3 < Xe) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(P + gx + gk * sk);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[4 * t + j] = v[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[4 * t + j] = (gk < Ke && gx + j < Xe) ? P[gx + j + gk * sk] : 0.f;
+      }
+    } else {
+      // consecutive threads walk the smaller stride
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int e = tid + 256 * (4 * t + j);
+        int x, k;
+        if (sk <= sx) {
+          k = e % GK;
+          x = e / GK;
+        } else {
+          x = e % GT;
+          k = e / GT;
+        }
+        const int gx = x0 + x, gk = k0 + k;
+        r[4 * t + j] = (gx < Xe && gk < Ke) ? P[gx * sx + gk * sk] : 0.f;
+      }
+    }
+  }
+}
+
+// Parks the fetched elements in the LDS tile T[k][x].
+__device__ inline void gemm_park(float (*T)[GT + 4], const float (&r)[8], int mode, long long sx, long long sk, int tid) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int idx = tid + 256 * t;
+    if (mode == GL_VEC_K) {
+      const int k4 = idx % (GK / 4), x = idx / (GK / 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) T[4 * k4 + j][x] = r[4 * t + j];
+    } else if (mode == GL_VEC_X) {
+      const int x4 = idx % (GT / 4), k = idx / (GT / 4);
+      *reinterpret_cast<f32x4*>(&T[k][4 * x4]) = f32x4{r[4 * t], r[4 * t + 1], r[4 * t + 2], r[4 * t + 3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int e = tid + 256 * (4 * t + j);
+        if (sk <= sx) T[e % GK][e / GK] = r[4 * t + j];
+        else T[e / GT][e % GT] = r[4 * t + j];
+      }
+    }
+  }
+}
 
 __global__ __launch_bounds__(256) void k_gemm(Gemm g) {
-  __shared__ float As[GK][GT + 4];
-  __shared__ float Bs[GK][GT + 4];
+  __shared__ __attribute__((aligned(16))) float As[GK][GT + 4];
+  __shared__ __attribute__((aligned(16))) float Bs[GK][GT + 4];
   const int tilesN = (g.N + GT - 1) / GT;
   const int tilesM = (g.M + GT - 1) / GT;
   long long bid = blockIdx.x;
@@ -94,73 +179,49 @@ __global__ __launch_bounds__(256) void k_gemm(Gemm g) {
   const float* A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
   const float* B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
   float* C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
+  const int modeA = gemm_load_mode(g.A, g.sAm, g.sAk, g.sA0, g.sA1, g.sA2);
+  const int modeB = gemm_load_mode(g.B, g.sBn, g.sBk, g.sB0, g.sB1, g.sB2);
 
   const int tid = threadIdx.x;
-  const int tx = tid % 16, ty = tid / 16;
-  float acc[4][4];
+  // Wave w owns the 32 x 32 block (w / 2, w % 2) of the tile and accumulates it with fp32 MFMAs
+  // (32x32x2: lane = (row or column, k mod 2)); the accumulator holds column lane % 32, rows
+  // 8 (v / 4) + 4 (lane / 32) + v % 4.
+  typedef float f32x16 __attribute__((ext_vector_type(16)));
+  const int lane = tid % 64, wv = tid / 64, l32 = lane % 32, hf = lane / 32;
+  const int wm = wv / 2, wn = wv % 2;
+  f32x16 acc;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 
-  const bool a_k_fast = g.sAk <= g.sAm;  // make consecutive threads walk the smaller stride
-  const bool b_k_fast = g.sBk <= g.sBn;
-
+  // The next K step's elements are fetched into registers while the current one is multiplied.
+  float ra[8], rb[8];
+  if (Ke > 0) {
+    gemm_fetch(ra, modeA, A, g.sAm, g.sAk, m0, Me, 0, Ke, tid);
+    gemm_fetch(rb, modeB, B, g.sBn, g.sBk, n0, Ne, 0, Ke, tid);
+  }
   for (int k0 = 0; k0 < Ke; k0 += GK) {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      int idx = tid + t * 256;
-      int ki, mi;
-      if (a_k_fast) {
-        ki = idx % GK;
-        mi = idx / GK;
-      } else {
-        mi = idx % GT;
-        ki = idx / GT;
-      }
-      int gm = m0 + mi, gk = k0 + ki;
-      As[ki][mi] = (gm < Me && gk < Ke) ? A[gm * g.sAm + gk * g.sAk] : 0.f;
-      int ni;
-      if (b_k_fast) {
-        ki = idx % GK;
-        ni = idx / GK;
-      } else {
-        ni = idx % GT;
-        ki = idx / GT;
-      }
-      int gn = n0 + ni;
-      gk = k0 + ki;
-      Bs[ki][ni] = (gn < Ne && gk < Ke) ? B[gk * g.sBk + gn * g.sBn] : 0.f;
-    }
+    gemm_park(As, ra, modeA, g.sAm, g.sAk, tid);
+    gemm_park(Bs, rb, modeB, g.sBn, g.sBk, tid);
     __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < GK; ++kk) {
-      float a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    if (k0 + GK < Ke) {
+      gemm_fetch(ra, modeA, A, g.sAm, g.sAk, m0, Me, k0 + GK, Ke, tid);
+      gemm_fetch(rb, modeB, B, g.sBn, g.sBk, n0, Ne, k0 + GK, Ke, tid);
     }
+#pragma unroll
+    for (int kk = 0; kk < GK; kk += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk + hf][32 * wm + l32], Bs[kk + hf][32 * wn + l32], acc, 0, 0, 0);
     __syncthreads();
   }
+  const int gn = n0 + 32 * wn + l32;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int gm = m0 + ty * 4 + i;
-    if (gm >= Me) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int gn = n0 + tx * 4 + j;
-      if (gn >= Ne) continue;
-      float* c = C + gm * g.sCm + gn * g.sCn;
-      float v = g.alpha * acc[i][j];
-      if (g.beta != 0.f) v += g.beta * (*c);
-      if (g.mask == 1 && gn > gm) v = 0.f;
-      *c = v;
-    }
+  for (int v = 0; v < 16; ++v) {
+    const int gm = m0 + 32 * wm + 8 * (v / 4) + 4 * hf + (v % 4);
+    if (gm >= Me || gn >= Ne) continue;
+    float* c = C + gm * g.sCm + gn * g.sCn;
+    float x = g.alpha * acc[v];
+    if (g.beta != 0.f) x += g.beta * (*c);
+    if (g.mask == 1 && gn > gm) x = 0.f;
+    *c = x;
   }
 }
 
