@@ -46,6 +46,8 @@ def algorithmic_work(cfg):
         "fused_readout": ("hbm", th * (d + dv) * s_in),
         # the scan's MFMA work: both projections, the state read-out and update, the tile triangle
         "fused_causal_scan": ("mfma", th * (4 * d * m + 4 * m * (dv + 1) + m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1))),
+        "fused_causal_state": ("hbm", th * (d + dv) * s_in),
+        "fused_key_norms": ("hbm", th * d * s_in),
         "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
     }
     return th * f_tok, th * b_tok, per_kernel
