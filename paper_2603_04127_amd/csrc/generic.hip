@@ -282,10 +282,11 @@ __global__ __launch_bounds__(256) void k_headmax(const float* __restrict__ rowma
 }
 
 // Per-feature maximum over the L rows of each (b,h): colmax[bh][j] = max_l logit[bh][l][j].
-// One block per (bh, 64-column group); threads = 64 columns x 4 row phases.
-__global__ __launch_bounds__(256) void k_colmax(const float* __restrict__ logit, float* __restrict__ colmax, int L,
-                                                int m) {
-  __shared__ float sm[4][64];
+// One block per (bh, 64-column group); threads = 64 columns x 16 row phases, eight loads in flight.
+constexpr int kColmaxPhases = 16;
+__global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __restrict__ logit,
+                                                               float* __restrict__ colmax, int L, int m) {
+  __shared__ float sm[kColmaxPhases][64];
   const int groups = (m + 63) / 64;
   const long long bh = blockIdx.x / groups;
   const int j = (blockIdx.x % groups) * 64 + threadIdx.x % 64;
@@ -293,12 +294,23 @@ __global__ __launch_bounds__(256) void k_colmax(const float* __restrict__ logit,
   float mx = -INFINITY;
   if (j < m) {
     const float* p = logit + bh * L * (long long)m + j;
-    for (int l = ph; l < L; l += 4) mx = fmaxf(mx, p[(long long)l * m]);
+    int l = ph;
+    for (; l + 7 * kColmaxPhases < L; l += 8 * kColmaxPhases) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(long long)(l + u * kColmaxPhases) * m];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) mx = fmaxf(mx, v[u]);
+    }
+    for (; l < L; l += kColmaxPhases) mx = fmaxf(mx, p[(long long)l * m]);
   }
   sm[ph][threadIdx.x % 64] = mx;
   __syncthreads();
-  if (ph == 0 && j < m)
-    colmax[bh * m + j] = fmaxf(fmaxf(sm[0][threadIdx.x], sm[1][threadIdx.x]), fmaxf(sm[2][threadIdx.x], sm[3][threadIdx.x]));
+  if (ph == 0 && j < m) {
+#pragma unroll
+    for (int u = 1; u < kColmaxPhases; ++u) mx = fmaxf(mx, sm[u][threadIdx.x]);
+    colmax[bh * m + j] = mx;
+  }
 }
 
 // Phi = exp(logit - c) * mult.  mode 0: c = cvec[row];  1: c = cvec[row / L] (per head);
@@ -508,7 +520,7 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
   if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
   if (mode == STAB_KEY_FEATURE)
-    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(256), 0, fb.Phi,
+    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(64 * kColmaxPhases), 0, fb.Phi,
                 fb.colmax, p.L, p.m);
   return DARK_OK;
 }
@@ -521,7 +533,18 @@ dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
   return DARK_OK;
 }
 
-int slice_len(const Problem&) { return 4096; }
+// Length of the L-slices whose partial states are summed in a fixed order: short enough that a
+// states GEMM (four 64-row tiles per (b,h, slice)) has about a thousand workgroups, whole 64-token
+// multiples, at most 4096.  A function of the shape only, so results stay reproducible.
+int slice_len(const Problem& pb) {
+  long long want = 1024 / (pb.BH() * 4 > 0 ? pb.BH() * 4 : 1);
+  if (want < 1) want = 1;
+  long long sl = (pb.p.L + want - 1) / want;
+  sl = ((sl + 63) / 64) * 64;
+  if (sl < 256) sl = 256;
+  if (sl > 4096) sl = 4096;
+  return (int)sl;
+}
 
 }  // namespace
 
