@@ -126,7 +126,7 @@ template <int D, int DV, int R, int MINW>
 __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* __restrict__ Kg,
                                                          const unsigned short* __restrict__ Vg,
                                                          const _Float16* __restrict__ Ah,
-                                                         const _Float16* __restrict__ Mh, float* __restrict__ Spart,
+                                                         const _Float16* __restrict__ Mh, unsigned short* __restrict__ Spart,
                                                          float* __restrict__ zpart, float* __restrict__ cpart, int H,
                                                          int L, int m, int P, int slice_len, int n_work) {
   using SM = KvSmem<D, DV, R>;
@@ -243,9 +243,16 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
     for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll
       for (int v = 0; v < 16; ++v) S[ft][ct][v] = 0.f;
-  float z[2] = {0.f, 0.f};
+  // z[feat] = column sums of phi, accumulated by an MFMA against ones (every column of the result is
+  // equal): the same bf16-rounded features that enter S, so S_j / z_j stays an exact convex
+  // combination of value rows.  (Summing with v_dot2c_f32_bf16 instead stalls behind the MFMAs in flight.)
+  f32x16 zacc[2];
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zacc[ft][v] = 0.f;
   // Per-feature shift (lane = feature column of the projection; both half-waves agree).  It is set
-  // from the first tile and afterwards only raised when a tile exceeds it by more than 2^kTau.
+  // from the first 32 tokens and afterwards only raised when a logit exceeds it by more than kTau.
   float c[2] = {0.f, 0.f};
 
   // --- prologue: tile 0 into buffer 0, tile 1 in flight ------------------------------------
@@ -263,6 +270,7 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
   if (ntile > 1) load_tile(1);
   __syncthreads();
 
+  const u32x4 ones4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
   for (int t = 0; t < ntile; ++t) {
     const int buf = t % 3, nb = t & 1;
     norms(buf, nb, t);
@@ -272,98 +280,73 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 
     const _Float16* xs = Xs + buf * kTile * SM::XS;
     const unsigned short* vt = Vt + buf * kTile * DV;
-    // projection: U[tt][ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
-    // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
-    // log2-features directly.
-    f32x16 U[2][2];
+    // The tile is worked in two halves of 32 tokens, so that only one half's logits are alive.
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
+    for (int tt = 0; tt < 2; ++tt) {
+      // projection: U[ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
+      // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
+      // log2-features directly.
+      f32x16 U[2];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
 #pragma unroll
         for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) U[tt][ft][4 * g + e] = nv[e] - c[ft];
+          for (int e = 0; e < 4; ++e) U[ft][4 * g + e] = nv[e] - c[ft];
       }
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
+      for (int s = 0; s < D / 16; ++s) {
         half8 a = *reinterpret_cast<const half8*>(xs + (32 * tt + l32) * SM::XS + 16 * s + 8 * hf);
 #pragma unroll
-        for (int ft = 0; ft < 2; ++ft)
-          U[tt][ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[tt][ft], 0, 0, 0);
+        for (int ft = 0; ft < 2; ++ft) U[ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[ft], 0, 0, 0);
       }
-    // features, packed to bf16 in the operand layout of the second MFMA
-    u32x4 pk[2][2][2];  // [tt][ft][hh]: k-slots s <-> accumulator registers 8 hh + s
-    float zs[2];        // this tile's column sums (this lane's tokens)
-    auto featurize = [&]() {
+      // Common path: look at the largest shifted logit; more than kTau (or the very first half tile,
+      // whose shifts are still zero) means some shift has to be set or raised.
+      float mall = -INFINITY;
 #pragma unroll
-      for (int ft = 0; ft < 2; ++ft) {
-        float acc = 0.f;
+      for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+        for (int v = 0; v < 16; v += 2) mall = max3(mall, U[ft][v], U[ft][v + 1]);
+      const bool first = (t == 0 && tt == 0);
+      if (first || __any(mall > kTau)) {  // first half tile, or rare
 #pragma unroll
-          for (int hh = 0; hh < 2; ++hh)
+        for (int ft = 0; ft < 2; ++ft) {
+          float m0 = -INFINITY;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              float a = fast_exp2(U[tt][ft][8 * hh + 2 * q]);
-              float b = fast_exp2(U[tt][ft][8 * hh + 2 * q + 1]);
-              pk[tt][ft][hh][q] = pack_bf16(a, b);
-              // z sums the same bf16-rounded features that enter S, so S_j / z_j stays an exact
-              // convex combination of value rows
-              acc = dot2_bf16(pk[tt][ft][hh][q], kOnesBf16x2, acc);
+          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[ft][v], U[ft][v + 1]);
+          m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
+          const float delta = (first || m0 > kRaise) ? m0 : 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) U[ft][v] -= delta;
+          c[ft] += delta;
+          if (!first) {
+            const float f = fast_exp2(-delta);
+            // S and z rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
+              zacc[ft][v] *= fr;
+#pragma unroll
+              for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
             }
-        zs[ft] = acc;
-      }
-    };
-    // Common path: exponentiate with the current shifts and look at the column sums afterwards;
-    // a sum of 2^kTau or more (or inf) means some shift is far too low for this tile.
-    bool fix = (t == 0);
-    if (!fix) {
-      featurize();
-      fix = __any(!(zs[0] < kBig) || !(zs[1] < kBig));
-    }
-    if (fix) {  // first tile, or rare
-      const bool first = (t == 0);
-#pragma unroll
-      for (int ft = 0; ft < 2; ++ft) {
-        float m0 = -INFINITY;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[tt][ft][v], U[tt][ft][v + 1]);
-        m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
-        const float delta = (first || m0 > kRaise) ? m0 : 0.f;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) U[tt][ft][v] -= delta;
-        c[ft] += delta;
-        if (!first) {
-          const float f = fast_exp2(-delta);
-          z[ft] *= f;
-          // S rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
-#pragma unroll
-            for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
           }
         }
       }
-      featurize();
-    }
-    z[0] += zs[0];
-    z[1] += zs[1];
-    // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4.
-    // Transposing read: in each group of 16 lanes, lane i points at 4 values V[t + i/4][c0 + 4 (i%4) ...]
-    // and receives V[t .. t+3][c0 + i], i.e. four consecutive tokens of its own column.
+      // features, packed to bf16 in the operand layout of the second MFMA
+      u32x4 pk[2][2];  // [ft][hh]: k-slots s <-> accumulator registers 8 hh + s
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
+      for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            pk[ft][hh][q] = pack_bf16(fast_exp2(U[ft][8 * hh + 2 * q]), fast_exp2(U[ft][8 * hh + 2 * q + 1]));
+      // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4.
+      // Transposing read: in each group of 16 lanes, lane i points at 4 values V[t + i/4][c0 + 4 (i%4) ...]
+      // and receives V[t .. t+3][c0 + i], i.e. four consecutive tokens of its own column.
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
         for (int ct = 0; ct < DV / 32; ++ct) {
           const int j = l32 % 16;
@@ -375,27 +358,55 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
           u32x4 bv = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
           for (int ft = 0; ft < 2; ++ft)
-            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[tt][ft][hh]),
+            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[ft][hh]),
                                                                 *reinterpret_cast<bf16x8*>(&bv), S[ft][ct], 0, 0, 0);
         }
+#pragma unroll
+        for (int ft = 0; ft < 2; ++ft) {
+          u32x4 o4 = ones4;
+          zacc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[ft][hh]),
+                                                             *reinterpret_cast<bf16x8*>(&o4), zacc[ft], 0, 0, 0);
+        }
+      }
+    }
   }
 
-  // --- epilogue: partial state of this slice -------------------------------------------------
+  // --- epilogue: partial state of this slice (bf16 in memory: half the bytes on the way to the merge;
+  // the merged state is rounded to bf16 for the readout's MFMA anyway).  Each wave turns its 64 x DV
+  // block through LDS (the tile buffers are free now) so that the stores are 16-byte pieces of whole rows.
   const size_t pbase = (size_t)bh * P + p;
+  __syncthreads();  // every wave is done with the tile buffers
+  {
+    constexpr int ROWB = DV * 2 + 16;  // bytes per staged feature row, padded
+    static_assert(4 * 64 * ROWB <= SM::x_bytes + SM::v_bytes, "stage does not fit the tile buffers");
+    unsigned char* stg = smem + wv * 64 * ROWB;
+#pragma unroll
+    for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+      for (int ct = 0; ct < DV / 32; ++ct)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
+          *reinterpret_cast<unsigned short*>(stg + row * ROWB + (32 * ct + l32) * 2) =
+              (unsigned short)(pack_bf16(S[ft][ct][v], 0.f) & 0xffffu);
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CPR = DV / 8;  // 16-byte pieces per row
+#pragma unroll
+    for (int k = 0; k < 64 * CPR / 64; ++k) {
+      const int i = lane + 64 * k, row = i / CPR, ch = i % CPR;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(stg + row * ROWB + 16 * ch);
+      *reinterpret_cast<u32x4*>(Spart + (pbase * m + f0 + row) * DV + 8 * ch) = w;
+    }
+  }
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft) {
+    if (l32 == 0) {  // every column of zacc is equal: one lane per half writes its rows
 #pragma unroll
-    for (int ct = 0; ct < DV / 32; ++ct)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        int feat = f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
-        Spart[(pbase * m + feat) * DV + 32 * ct + l32] = S[ft][ct][v];
-      }
-    float zt = z[ft] + __shfl_xor(z[ft], 32, 64);
-    if (hf == 0) {
-      zpart[pbase * m + f0 + 32 * ft + l32] = zt;
-      cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
+      for (int v = 0; v < 16; ++v) zpart[pbase * m + f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4)] = zacc[ft][v];
     }
+    if (hf == 0) cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
   }
 }
 
@@ -406,9 +417,10 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
 // Writes S^T as bf16 [BH][DV][m] (the readout's MFMA operand), z [BH][m], c* [BH][m/64].
 // ---------------------------------------------------------------------------
 template <int DV>
-__global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spart, const float* __restrict__ zpart,
-                                                  const float* __restrict__ cpart, unsigned short* __restrict__ St,
-                                                  float* __restrict__ zt, float* __restrict__ cf, int m, int P) {
+__global__ __launch_bounds__(256) void k_kv_merge(const unsigned short* __restrict__ Spart,
+                                                  const float* __restrict__ zpart, const float* __restrict__ cpart,
+                                                  unsigned short* __restrict__ St, float* __restrict__ zt,
+                                                  float* __restrict__ cf, int m, int P) {
   constexpr int PP = 8;  // slices per pass
   __shared__ float tile[64][DV + 1];
   __shared__ float fac[PP][64];
@@ -416,24 +428,26 @@ __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spar
   const int nblk = m / 64;
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x;
-  constexpr int PER = 64 * DV / 256;
-  float acc[PER];
+  constexpr int NV = 64 * DV / 8 / 256;  // 16-byte pieces (8 bf16 of one feature row) per thread and slice
+  float acc[NV][8];
 #pragma unroll
-  for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
   float zacc = 0.f;
   float cs = -INFINITY;
   for (int p0 = 0; p0 < P; p0 += PP) {
     const int np = min(PP, P - p0);
     // the pass's loads of the partial states are issued first: they do not depend on the shifts,
     // so their latency overlaps the reduction that finds c*
-    float v[PP][PER];
+    u32x4 v[PP][NV];
     float zv[PP];
 #pragma unroll
     for (int u = 0; u < PP; ++u) {
       const int pu = min(u, np - 1);
-      const float* sp = Spart + (((size_t)bh * P + p0 + pu) * m + 64 * blk) * DV;
+      const unsigned short* sp = Spart + (((size_t)bh * P + p0 + pu) * m + 64 * blk) * DV;
 #pragma unroll
-      for (int i = 0; i < PER; ++i) v[u][i] = sp[tid + 256 * i];
+      for (int i = 0; i < NV; ++i) v[u][i] = *reinterpret_cast<const u32x4*>(sp + 8 * (tid + 256 * i));
       zv[u] = tid < 64 ? zpart[((size_t)bh * P + p0 + pu) * m + 64 * blk + tid] : 0.f;
     }
     if (p0 == 0) {
@@ -453,17 +467,27 @@ __global__ __launch_bounds__(256) void k_kv_merge(const float* __restrict__ Spar
     for (int u = 0; u < PP; ++u) {  // p ascending: the order of summation is fixed
       if (u < np) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] = fmaf(fac[u][(tid + 256 * i) / DV], v[u][i], acc[i]);
+        for (int i = 0; i < NV; ++i) {
+          const float f = fac[u][8 * (tid + 256 * i) / DV];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const unsigned w = v[u][i][j];
+            acc[i][2 * j] = fmaf(f, __uint_as_float(w << 16), acc[i][2 * j]);
+            acc[i][2 * j + 1] = fmaf(f, __uint_as_float(w & 0xffff0000u), acc[i][2 * j + 1]);
+          }
+        }
         if (tid < 64) zacc = fmaf(fac[u][tid], zv[u], zacc);
       }
     }
   }
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    int idx = tid + 256 * i;
-    tile[idx / DV][idx % DV] = acc[i];
+  for (int i = 0; i < NV; ++i) {
+    const int e = 8 * (tid + 256 * i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tile[e / DV][e % DV + j] = acc[i][j];
   }
   __syncthreads();
+  constexpr int PER = 64 * DV / 256;
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     int idx = tid + 256 * i;
@@ -932,7 +956,7 @@ Plan make_plan(const Problem& pb) {
 struct FusedBufs {
   _Float16* Ah;
   _Float16* Mh;
-  float* Spart;
+  unsigned short* Spart;  // per-slice partial states, bf16
   float* zpart;
   float* cpart;
   unsigned short* St;
@@ -945,7 +969,7 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   const size_t BH = (size_t)pb.BH();
   b.Ah = ar.take<_Float16>((size_t)p.H * p.m * p.d);
   b.Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
-  b.Spart = ar.take<float>(BH * pl.P * p.m * p.dv);
+  b.Spart = ar.take<unsigned short>(BH * pl.P * p.m * p.dv);
   b.zpart = ar.take<float>(BH * pl.P * p.m);
   b.cpart = ar.take<float>(BH * pl.P * p.m);
   b.St = ar.take<unsigned short>(BH * p.dv * p.m);
@@ -1043,7 +1067,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
 }
 
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
-                                   const _Float16* Mh, float* Spart, float* zpart, float* cpart, int P,
+                                   const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
                                    int slice_len) {
   const dark_params& p = pb.p;
   Plan pl{};

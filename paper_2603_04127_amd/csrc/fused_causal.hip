@@ -102,7 +102,8 @@ __global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restr
 // Workgroup = (b,h, 8 features); a thread owns 8 DV / 256 adjacent state entries.
 // ---------------------------------------------------------------------------
 template <int DV>
-__global__ __launch_bounds__(256) void k_kv_prefix(const float* __restrict__ Spart, const float* __restrict__ zpart,
+__global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restrict__ Spart,
+                                                   const float* __restrict__ zpart,
                                                    const float* __restrict__ cpart, float* __restrict__ Spre,
                                                    float* __restrict__ zpre, float* __restrict__ cpre, int m, int P) {
   constexpr int EPT = 8 * DV / 256;  // 2 or 4
@@ -127,7 +128,15 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const float* __restrict__ Spa
     for (int u = 0; u < PB; ++u) {
       const int p = min(p0 + u, P - 1);
       const size_t row = ((size_t)bh * P + p) * m + feat;
-      v[u] = *reinterpret_cast<const fvec*>(Spart + row * DV + col);
+      {  // EPT bf16 values of the slice state
+        typedef unsigned uvec __attribute__((ext_vector_type(EPT / 2)));
+        const uvec w = *reinterpret_cast<const uvec*>(Spart + row * DV + col);
+#pragma unroll
+        for (int e = 0; e < EPT / 2; ++e) {
+          v[u][2 * e] = __uint_as_float(w[e] << 16);
+          v[u][2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+        }
+      }
       cj[u] = cpart[row];
       zv[u] = zpart[row];
     }
@@ -200,7 +209,8 @@ template <int D>
 __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __restrict__ Kg,
                                                         const unsigned short* __restrict__ Vg,
                                                         const _Float16* __restrict__ Ah,
-                                                        const float* __restrict__ nrm, float* __restrict__ Spart,
+                                                        const float* __restrict__ nrm,
+                                                        unsigned short* __restrict__ Spart,
                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
                                                         int L, int P, int slice_len) {
   using SM = SsSmem<D>;
@@ -369,7 +379,8 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
     for (int v = 0; v < 16; ++v) {
       const int feat = 64 * fg + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) Spart[(srow0 + feat) * DVT + DVW * hv + 32 * ct + l32] = S[fb][ct][v];
+      for (int ct = 0; ct < NCT; ++ct)
+        Spart[(srow0 + feat) * DVT + DVW * hv + 32 * ct + l32] = (unsigned short)(pack_bf16(S[fb][ct][v], 0.f) & 0xffffu);
       if (hv == 0 && l32 == 0) zpart[srow0 + feat] = zacc[fb][v];
     }
   if (hf == 0) cpart[srow0 + 64 * fg + 32 * hv + l32] = c;
@@ -715,7 +726,7 @@ int env_int(const char* name, int dflt) {
 
 template <int D>
 dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const void* V, const _Float16* Ah,
-                          const _Float16* Mh, float* Spart, float* zpart, float* cpart, float* Spre, float* zpre,
+                          const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, float* Spre, float* zpre,
                           float* cpre, float* nrm, void* out, int P, int slice_len) {
   const dark_params& p = pb.p;
   const unsigned BH = (unsigned)pb.BH();
@@ -776,7 +787,7 @@ dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, c
   const size_t nstate = (size_t)BH * P * p.m;
   _Float16* Ah = ar.take<_Float16>((size_t)p.H * p.m * p.d);
   _Float16* Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
-  float* Spart = ar.take<float>(nstate * p.dv);
+  unsigned short* Spart = ar.take<unsigned short>(nstate * p.dv);
   float* zpart = ar.take<float>(nstate);
   float* cpart = ar.take<float>(nstate);
   float* Spre = ar.take<float>(nstate * p.dv);

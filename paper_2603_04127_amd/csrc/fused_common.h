@@ -118,10 +118,10 @@ static dark_status allow_lds(KernelT kernel, size_t bytes) {
 // Requires r, d multiples of 4, d <= 256, r * d <= 16384.
 dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh);
 // Key/value pass over P slices of slice_len tokens (a multiple of 64) per (b,h):
-// Spart [BH][P][m][dv], zpart and cpart [BH][P][m] (per-slice, per-feature shifts, log2 domain).
+// Spart [BH][P][m][dv] (bf16), zpart and cpart [BH][P][m] (per-slice, per-feature shifts, log2 domain).
 // Requires the shapes of fused_supported().
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
-                                   const _Float16* Mh, float* Spart, float* zpart, float* cpart, int P,
+                                   const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
                                    int slice_len);
 // Implemented in fused_causal.hip.
 bool fused_causal_supported(const Problem& pb);
