@@ -931,7 +931,8 @@ Plan make_plan(const Problem& pb) {
   pl.nfb = p.m / 256;
   const long long BH = pb.BH();
   // K pass: about two workgroups per CU (256 CUs); slices are whole tiles.
-  int target = env_int("DARK_KV_WGS", 512);
+  // (d = 128: the 8-wave slice-state kernel, one workgroup per CU)
+  int target = env_int("DARK_KV_WGS", p.d == 128 ? 256 : 512);
   long long want = target / (BH * pl.nfb);  // rounding down keeps all workgroups co-resident
   if (want < 1) want = 1;
   int sl = (int)((p.L + want - 1) / want);
@@ -962,6 +963,7 @@ struct FusedBufs {
   unsigned short* St;
   float* zt;
   float* cf;
+  float* nrm;  // key norms [BH][L], d = 128 only
 };
 
 void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
@@ -975,6 +977,7 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   b.St = ar.take<unsigned short>(BH * p.dv * p.m);
   b.zt = ar.take<float>(BH * p.m);
   b.cf = ar.take<float>(BH * (p.m / 64));
+  b.nrm = p.d == 128 ? ar.take<float>(BH * (size_t)(p.L > 0 ? p.L : 1)) : nullptr;
 }
 
 template <int D, int DV, int R, int MINW>
@@ -1047,7 +1050,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (p.d == 64) {
     DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V)));
   } else {
-    DARK_TRY((launch_kv<128, 128, 128, 1>(pb, pl, b, K, V)));
+    DARK_TRY(fused_launch_slice_state128(pb, K, V, b.Ah, b.Mh, b.nrm, b.Spart, b.zpart, b.cpart, pl.P, pl.slice_len));
   }
   const unsigned mgrid = (unsigned)(pb.BH() * (p.m / 64));
   if (p.dv == 64)
@@ -1082,8 +1085,8 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
   b.Spart = Spart;
   b.zpart = zpart;
   b.cpart = cpart;
-  if (p.d == 64) return launch_kv<64, 64, 64, 2>(pb, pl, b, K, V);
-  return launch_kv<128, 128, 128, 1>(pb, pl, b, K, V);
+  if (p.d != 64) return DARK_EUNSUPPORTED;
+  return launch_kv<64, 64, 64, 2>(pb, pl, b, K, V);
 }
 
 }  // namespace dark

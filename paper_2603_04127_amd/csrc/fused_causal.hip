@@ -725,28 +725,44 @@ int env_int(const char* name, int dflt) {
 }
 
 template <int D>
+dark_status launch_key_norms(const Problem& pb, const void* K, const _Float16* Mh, float* nrm) {
+  const dark_params& p = pb.p;
+  const long long BH = pb.BH();
+  // about 1024 workgroups, each over a run of 256-token chunks of one (b,h): M' is copied to LDS once
+  // per workgroup and the rows of the next chunk are in flight while the current one is projected
+  const int chunks_per_bh = (p.L + 255) / 256;
+  int blocks_per_bh = (int)(1024 / BH);
+  blocks_per_bh = blocks_per_bh < 1 ? 1 : (blocks_per_bh > chunks_per_bh ? chunks_per_bh : blocks_per_bh);
+  const int chunks_per_block = (chunks_per_bh + blocks_per_bh - 1) / blocks_per_bh;
+  blocks_per_bh = (chunks_per_bh + chunks_per_block - 1) / chunks_per_block;
+  DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms<D, D>), dim3((unsigned)(BH * blocks_per_bh)), dim3(256), 0,
+              (const unsigned short*)K, Mh, nrm, p.H, p.L, blocks_per_bh, chunks_per_block);
+  return DARK_OK;
+}
+
+// Key norms, then the state of every slice by k_slice_state.
+template <int D>
+dark_status launch_slice_state(const Problem& pb, const void* K, const void* V, const _Float16* Ah, const _Float16* Mh,
+                               float* nrm, unsigned short* Spart, float* zpart, float* cpart, int P, int slice_len) {
+  const dark_params& p = pb.p;
+  DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
+  auto kern = k_slice_state<D>;
+  DARK_TRY(allow_lds(kern, SsSmem<D>::total));
+  DARK_LAUNCH(KID_CAUSAL_STATE, pb.st, kern, dim3((unsigned)(pb.BH() * P)), dim3(512), SsSmem<D>::total,
+              (const unsigned short*)K, (const unsigned short*)V, Ah, nrm, Spart, zpart, cpart, p.H, p.L, P, slice_len);
+  return DARK_OK;
+}
+
+template <int D>
 dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const void* V, const _Float16* Ah,
                           const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, float* Spre, float* zpre,
                           float* cpre, float* nrm, void* out, int P, int slice_len) {
   const dark_params& p = pb.p;
   const unsigned BH = (unsigned)pb.BH();
-  {
-    // about 1024 workgroups, each over a run of 256-token chunks of one (b,h): M' is copied to LDS once
-    // per workgroup and the rows of the next chunk are in flight while the current one is projected
-    const int chunks_per_bh = (p.L + 255) / 256;
-    int blocks_per_bh = (int)(1024 / BH);
-    blocks_per_bh = blocks_per_bh < 1 ? 1 : (blocks_per_bh > chunks_per_bh ? chunks_per_bh : blocks_per_bh);
-    const int chunks_per_block = (chunks_per_bh + blocks_per_bh - 1) / blocks_per_bh;
-    blocks_per_bh = (chunks_per_bh + chunks_per_block - 1) / chunks_per_block;
-    DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms<D, D>), dim3(BH * blocks_per_bh), dim3(256), 0,
-                (const unsigned short*)K, Mh, nrm, p.H, p.L, blocks_per_bh, chunks_per_block);
-  }
-  if (env_int("DARK_CS_STATE", D == 128 ? 1 : 2) == 1) {
-    auto kern = k_slice_state<D>;
-    DARK_TRY(allow_lds(kern, SsSmem<D>::total));
-    DARK_LAUNCH(KID_CAUSAL_STATE, pb.st, kern, dim3(BH * P), dim3(512), SsSmem<D>::total, (const unsigned short*)K,
-                (const unsigned short*)V, Ah, nrm, Spart, zpart, cpart, p.H, p.L, P, slice_len);
+  if (D == 128 || env_int("DARK_CS_STATE", 2) == 1) {
+    DARK_TRY((launch_slice_state<D>(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, P, slice_len)));
   } else {
+    DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
     DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
   }
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
@@ -762,6 +778,12 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
 }
 
 }  // namespace
+
+dark_status fused_launch_slice_state128(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
+                                        const _Float16* Mh, float* nrm, unsigned short* Spart, float* zpart,
+                                        float* cpart, int P, int slice_len) {
+  return launch_slice_state<128>(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, P, slice_len);
+}
 
 bool fused_causal_supported(const Problem& pb) {
   const dark_params& p = pb.p;

@@ -119,11 +119,16 @@ static dark_status allow_lds(KernelT kernel, size_t bytes) {
 dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh);
 // Key/value pass over P slices of slice_len tokens (a multiple of 64) per (b,h):
 // Spart [BH][P][m][dv] (bf16), zpart and cpart [BH][P][m] (per-slice, per-feature shifts, log2 domain).
-// Requires the shapes of fused_supported().
+// Requires d = r = dv = 64.
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
                                    const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
                                    int slice_len);
 // Implemented in fused_causal.hip.
 bool fused_causal_supported(const Problem& pb);
+// The same states for d = r = dv = 128 (whose accumulators do not fit k_kv_reduce's register budget):
+// key norms into nrm [BH][L], then an 8-wave kernel per (b,h, slice).
+dark_status fused_launch_slice_state128(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
+                                        const _Float16* Mh, float* nrm, unsigned short* Spart, float* zpart,
+                                        float* cpart, int P, int slice_len);
 
 }  // namespace dark
