@@ -117,8 +117,9 @@ dark_status dark_attn_fwd(const dark_params* p, const void* Q, const void* K, co
 
 /*
  * Causal form: out_i uses only keys l <= i (prefix sums of S and z).  The
- * sequence is processed in chunks of p->chunk positions; the result does not
- * depend on the chunk length.  L need not be a multiple of the chunk length.
+ * fp32 kernels process the sequence in chunks of p->chunk positions, the fused
+ * MFMA kernels in slices and tiles of their own choosing; the result does not
+ * depend on either, and L need not be a multiple of anything.
  * Same arguments as dark_attn_fwd.
  */
 dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void* K, const void* V,
