@@ -29,13 +29,13 @@ constexpr int kCT = 32;    // tokens per tile of the scan
 constexpr int kMaxP = 64;  // slices per (b,h) at most
 
 // ---------------------------------------------------------------------------
-// k_key_norms: nrm[bh][l] = |M' k_l|^2.  Workgroup = 4 waves x 64 tokens; x~^T[r][tok] = M' X^T by
+// k_key_norms: nrm[bh][l] = |M' k_l|^2.  Workgroup = 4 waves x 64 tokens per chunk; x~^T[r][tok] = M' X^T by
 // MFMA with the tokens as columns, so a token's sum of squares is a sum over registers.
 // ---------------------------------------------------------------------------
 template <int D, int R>
-__global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restrict__ Kg,
-                                                   const _Float16* __restrict__ Mh, float* __restrict__ nrm, int H,
-                                                   int L, int blocks_per_bh, int chunks_per_block) {
+__global__ __launch_bounds__(256, 4) void k_key_norms(const unsigned short* __restrict__ Kg,
+                                                      const _Float16* __restrict__ Mh, float* __restrict__ nrm, int H,
+                                                      int L, int blocks_per_bh, int chunks_per_block) {
   constexpr int AS = D + 8;
   __shared__ __attribute__((aligned(16))) _Float16 Ms[R * AS];
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
@@ -43,20 +43,6 @@ __global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restr
   const int bh = blockIdx.x / blocks_per_bh, blk = blockIdx.x % blocks_per_bh;
   const int h = bh % H;
   const unsigned short* Xb = Kg + (size_t)bh * L * D;
-  // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8); rows past the end
-  // repeat the last row and are never stored
-  u32x4 xr[2][D / 16];
-  auto fetch = [&](int chunk, int tt) {
-    const int tok = min(chunk * 256 + 64 * wv + 32 * tt + l32, L - 1);
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) xr[tt][s] = *reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf);
-  };
-  const int c_begin = blk * chunks_per_block;
-  const int c_end = min(c_begin + chunks_per_block, (L + 255) / 256);
-  if (c_begin < c_end) {  // in flight while M' is copied
-    fetch(c_begin, 0);
-    fetch(c_begin, 1);
-  }
   for (int ci = tid; ci < R * D / 8; ci += 256) {
     const int row = ci / (D / 8), kc = ci % (D / 8);
     *reinterpret_cast<u32x4*>(Ms + row * AS + 8 * kc) =
@@ -64,16 +50,24 @@ __global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restr
   }
   __syncthreads();
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int c_begin = blk * chunks_per_block;
+  const int c_end = min(c_begin + chunks_per_block, (L + 255) / 256);
+  // A wave walks its 64 tokens of every 256-token chunk in blocks of 32; few registers, so that four
+  // workgroups share a CU and their memory waits overlap.
   for (int chunk = c_begin; chunk < c_end; ++chunk) {
-#pragma unroll
+#pragma unroll 1
     for (int tt = 0; tt < 2; ++tt) {
+      const int tok0 = chunk * 256 + 64 * wv + 32 * tt;
+      if (tok0 >= L) break;  // wave-uniform
+      // X fragments (B operand): token = tok0 + l32, k = 16 s + 8 hf + [0,8); rows past the end repeat
+      // the last row and are never stored
+      const int tok = min(tok0 + l32, L - 1);
       half8 xf[D / 16];
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        u32x4 cv = bf16x8_to_f16x8(xr[tt][s]);
+        u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf));
         xf[s] = *reinterpret_cast<half8*>(&cv);
       }
-      if (chunk + 1 < c_end) fetch(chunk + 1, tt);  // the next chunk's rows, while these are projected
       float n2 = 0.f;
 #pragma unroll
       for (int rt = 0; rt < R / 32; ++rt) {
@@ -87,8 +81,7 @@ __global__ __launch_bounds__(256) void k_key_norms(const unsigned short* __restr
         for (int v = 0; v < 16; ++v) n2 = fmaf(xt[v], xt[v], n2);
       }
       n2 += __shfl_xor(n2, 32, 64);
-      const int tok = chunk * 256 + 64 * wv + 32 * tt + l32;
-      if (hf == 0 && tok < L) nrm[(size_t)bh * L + tok] = n2;
+      if (hf == 0 && tok0 + l32 < L) nrm[(size_t)bh * L + tok0 + l32] = n2;
     }
   }
 }
@@ -748,8 +741,8 @@ template <int D>
 dark_status launch_key_norms(const Problem& pb, const void* K, const _Float16* Mh, float* nrm) {
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
-  // about 1024 workgroups, each over a run of 256-token chunks of one (b,h): M' is copied to LDS once
-  // per workgroup and the rows of the next chunk are in flight while the current one is projected
+  // about 1024 workgroups (four fit a CU), each over a run of 256-token chunks of one (b,h): M' is copied
+  // to LDS once per workgroup
   const int chunks_per_bh = (p.L + 255) / 256;
   int blocks_per_bh = (int)(1024 / BH);
   blocks_per_bh = blocks_per_bh < 1 ? 1 : (blocks_per_bh > chunks_per_bh ? chunks_per_bh : blocks_per_bh);
