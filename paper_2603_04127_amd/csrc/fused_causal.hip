@@ -387,7 +387,8 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
 //   lane = token); each leaves its packed features in an LDS patch for the partner;
 //   both then form the masked intra-tile scores P^T[k][q] over the pair's features and, for their
 //   own half of the value columns (one or two blocks of 32):  N = phi_Q S_old + P V,  S += phi_K^T V.
-//   role 0 owns the denominator (phi_Q . z + row sums of P) and the row shift mu, role 1 owns z.
+//   role 0 owns the denominator (phi_Q . z + row sums of P), the row shift mu and z (read before the
+//   tile's first barrier, updated after it by the same wave).
 // The A' rows of the pair stay in registers for the whole slice; S is 64 x dv/2 per wave.
 // The eight waves' partial numerators meet in LDS; 512 threads combine them with the factors
 // 2^(mu_fg - max mu), normalise and store 8-byte pieces of whole rows.  Three barriers per tile.
@@ -467,7 +468,7 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
 #pragma unroll
       for (int ct = 0; ct < CTW; ++ct) S[fb][ct][v] = Spre[(srow0 + feat) * DVT + WCOLS * role + 32 * ct + l32];
     }
-  if (role == 1) zl[lane] = zpre[srow0 + 64 * fg + lane];
+  if (role == 0) zl[lane] = zpre[srow0 + 64 * fg + lane];
 
   // --- staging: V straight to LDS, Q and K through registers (bf16 -> fp16) --------------------
   constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a Q (or K) tile: 512 or 256
@@ -549,9 +550,9 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          // z of the features this lane's registers hold: rows 8 g + 4 hf + [0,4) of block fb.  (Read here,
-          // before the tile's barrier: role 1 updates z after it.)  phi_Q . z uses the bf16-rounded
-          // features that enter N.
+          // z of the features this lane's registers hold: rows 8 g + 4 hf + [0,4) of block fb (as it was
+          // before this tile: it is updated in phase B).  phi_Q . z uses the bf16-rounded features
+          // that enter N.
           const f32x4 zq = *reinterpret_cast<const f32x4*>(zl + 32 * fb + 8 * g + 4 * hf);
           const unsigned w0 = pack_bf16(fast_exp2(U[fb][4 * g] - mu), fast_exp2(U[fb][4 * g + 1] - mu));
           const unsigned w1 = pack_bf16(fast_exp2(U[fb][4 * g + 2] - mu), fast_exp2(U[fb][4 * g + 3] - mu));
@@ -651,7 +652,7 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
       for (int hh = 0; hh < 2; ++hh)
         N = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pp[hh]), *reinterpret_cast<bf16x8*>(&bv[hh]),
                                                     N, 0, 0, 0);
-      // state update (after the read-out above): S += phi_K^T V; role 1 also sums phi_K over the tile
+      // state update (after the read-out above): S += phi_K^T V; role 0 also sums phi_K over the tile
       // (every column of that MFMA result is equal: one lane per half holds every sum of its rows)
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb) {
@@ -660,15 +661,21 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
                                                             *reinterpret_cast<bf16x8*>(&bv[0]), S[fb][ct], 0, 0, 0);
         S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1),
                                                             *reinterpret_cast<bf16x8*>(&bv[1]), S[fb][ct], 0, 0, 0);
-        if (role == 1 && ct == 0) {
+        if (role == 0 && ct == 0) {
           u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
           f32x16 dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak0),
                                                               *reinterpret_cast<bf16x8*>(&o4), zero16, 0, 0, 0);
           dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1), *reinterpret_cast<bf16x8*>(&o4),
                                                        dz, 0, 0, 0);
-          if (l32 == 0) {
+          if (l32 == 0) {  // rows 8 g + 4 hf + [0,4) are four adjacent floats of z
 #pragma unroll
-            for (int v = 0; v < 16; ++v) zl[32 * fb + 8 * (v / 4) + 4 * hf + (v % 4)] += dz[v];
+            for (int g = 0; g < 4; ++g) {
+              f32x4* zp = reinterpret_cast<f32x4*>(zl + 32 * fb + 8 * g + 4 * hf);
+              f32x4 zv = *zp;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) zv[i] += dz[4 * g + i];
+              *zp = zv;
+            }
           }
         }
       }
