@@ -100,44 +100,55 @@ __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const
 }
 
 // ---------------------------------------------------------------------------
-// k_kv_reduce
-// Workgroup = 4 waves = 256 features (wave w owns features [64w, 64w+64) of the block) over one
-// L-slice of one (b,h).  Per 64-token tile:
-//   stage   K tile -> LDS as fp16 [64][D+8];  V tile -> LDS row-major bf16 [64][DV], the 16-byte
-//           chunks of a row XOR-swizzled with the token index so that the transposing LDS reads
-//           (ds_read_b64_tr_b16) that build the MFMA operand are free of bank conflicts
-//   norms   wave w: x~ = X[16w..16w+16) M'^T by MFMA 16x16x32, n' = row sums of squares -> LDS
-//   proj    U[tok][feat] = X A'^T  (MFMA 32x32x16 f16; A' fragments stay in registers)
-//   exp     phi = exp2(U - n' - c) in the accumulator registers, packed to bf16
-//   reduce  S[feat][dv] += phi^T V (MFMA 32x32x16 bf16), z[feat] += column sums of phi
-// Triple-buffered staging, one barrier per tile.
+// k_kv_reduce  (d = r = dv = 64): [S|z] of one L-slice of one (b,h), software-pipelined.
+// Workgroup = 4 waves x 64 features (wave w owns features [64w, 64w+64) of a 256-feature block); two
+// workgroups per CU.  Features never leave registers: the projection's accumulators, packed to bf16,
+// are an operand of the second MFMA.
+//
+// The unit of work is a block: 32 tokens x 32 features of one wave.  For block b
+//   A(b)  projection  U = [x | n'_hi n'_lo 1 1] . [A'_j | -1 -1 -c_hi -c_lo]   (5 MFMA 32x32x16 f16:
+//         the norm term of the token and the shift of the feature enter through eight extra
+//         contraction slots, each as an fp16 pair hi + lo, so the accumulators start from the
+//         constant zero and no vector instruction touches the logits before the exponential)
+//   B(b)  max check, exp2, pack to bf16                                         (vector ALU)
+//   C(b)  S += phi^T V (4 MFMA 32x32x16 bf16);  z is summed by the vector ALU beside the exponentials
+// and iteration b issues C(b-1) and A(b+1) between the pieces of B(b), pinned by sched_barrier, so
+// the matrix pipe and the vector ALU always have independent work from the same wave.
+//
+// Staging: thread (wave w, l16, g16) owns the 16-byte pieces g16 and 4 + g16 of key row 16 w + l16 of
+// a tile: it loads them a tile ahead, converts bf16 -> fp16, stores them to LDS and, from the same
+// registers, feeds the 16x16x32 MFMAs that give x~ = M' x of its wave's 16 rows; n' = |x~|^2 goes to
+// the row's extra slots.  V tiles go global -> LDS directly (XOR-swizzled on the source side for the
+// transposing reads).  One barrier per 64-token tile; X tiles are triple-buffered (tile t+1 is read
+// by the last block of tile t, tile t+2 is being written), V tiles too (the last block of tile t-1
+// still reads V(t-1) after the barrier).
 // ---------------------------------------------------------------------------
-template <int D, int DV, int R>
 struct KvSmem {
-  static constexpr int XS = D + 8;       // fp16 elements per X row (pad keeps 16-byte rows off one bank group)
-  static constexpr size_t x_bytes = (size_t)3 * kTile * XS * 2;
-  static constexpr size_t v_bytes = (size_t)3 * kTile * DV * 2;
-  static constexpr size_t m_bytes = (size_t)R * XS * 2;
-  static constexpr size_t n_bytes = (size_t)2 * kTile * 4;
-  static constexpr size_t total = x_bytes + v_bytes + m_bytes + n_bytes;
+  static constexpr int XS = 88;  // fp16 per staged key row: 64 coordinates, 8 extra slots, pad (conflict-free 16-byte reads)
+  static constexpr int MS = 72;
+  static constexpr size_t x_buf = (size_t)kTile * XS * 2;
+  static constexpr size_t v_buf = (size_t)kTile * 64 * 2;
+  static constexpr size_t x_bytes = 4 * x_buf;
+  static constexpr size_t v_bytes = 3 * v_buf;
+  static constexpr size_t m_bytes = (size_t)64 * MS * 2;
+  static constexpr size_t total = x_bytes + v_bytes + m_bytes;
 };
+constexpr float kF16Max = 65504.f;
 
-template <int D, int DV, int R, int MINW>
-__global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* __restrict__ Kg,
-                                                         const unsigned short* __restrict__ Vg,
-                                                         const _Float16* __restrict__ Ah,
-                                                         const _Float16* __restrict__ Mh, unsigned short* __restrict__ Spart,
-                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
-                                                         int L, int m, int P, int slice_len, int n_work) {
-  using SM = KvSmem<D, DV, R>;
+__global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __restrict__ Kg,
+                                                    const unsigned short* __restrict__ Vg,
+                                                    const _Float16* __restrict__ Ah, const _Float16* __restrict__ Mh,
+                                                    unsigned short* __restrict__ Spart, float* __restrict__ zpart,
+                                                    float* __restrict__ cpart, int H, int L, int m, int P,
+                                                    int slice_len, int n_work) {
+  using SM = KvSmem;
+  constexpr int D = 64, DV = 64, R = 64;
+  constexpr int XROW = SM::XS * 2;  // bytes per staged key row
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Xs = reinterpret_cast<_Float16*>(smem);
-  unsigned short* Vt = reinterpret_cast<unsigned short*>(smem + SM::x_bytes);
+  unsigned char* Xs = smem;
+  unsigned char* Vt = smem + SM::x_bytes;
   _Float16* Ms = reinterpret_cast<_Float16*>(smem + SM::x_bytes + SM::v_bytes);
-  float* ns = reinterpret_cast<float*>(smem + SM::x_bytes + SM::v_bytes + SM::m_bytes);
 
-  // blockIdx -> (work item (bh, slice), feature block): the feature blocks of one work item are
-  // 8 apart in blockIdx so that they land on the same XCD and share its L2 for the K/V tiles.
   const int nfb = m / 256;
   const int q8 = blockIdx.x / (8 * nfb), rem = blockIdx.x % (8 * nfb);
   const int fb = rem / 8, work = q8 * 8 + rem % 8;
@@ -151,239 +162,336 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
   const int l16 = lane % 16, g16 = lane / 16;
-  const int f0 = fb * 256 + wv * 64;  // first feature of this wave
+  const int f0 = fb * 256 + wv * 64;
 
-  // --- resident operands -----------------------------------------------------------------
-  // M' -> LDS
   for (int ci = tid; ci < R * D / 8; ci += 256) {
     int row = ci / (D / 8), kc = ci % (D / 8);
     u32x4 v = *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
-    *reinterpret_cast<u32x4*>(Ms + row * SM::XS + 8 * kc) = v;
+    *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) = v;
   }
-  // A' fragments (B operand of the projection): feature = f0 + 32 ft + l32, k = 16 s + 8 hf + [0,8)
-  half8 afr[2][D / 16];
+  // A' fragments: feature = f0 + 32 ft + l32, k = 16 s + 8 hf + [0,8); fragment 4 holds the extra slots
+  half8 afr[2][5];
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
+    for (int s = 0; s < 4; ++s)
       afr[ft][s] = *reinterpret_cast<const half8*>(Ah + ((size_t)h * m + f0 + 32 * ft + l32) * D + 16 * s + 8 * hf);
+  // extra slots of the feature side: -1, -1 (times n'_hi, n'_lo of the token), -c_hi, -c_lo (times 1, 1);
+  // only the lower half-wave's eight slots are used.  Returns the shift the pair really represents.
+  auto fold_frag = [&](float cc, float& c_eff) {
+    cc = fminf(fmaxf(cc, -kF16Max), kF16Max);
+    const _Float16 hi = (_Float16)cc;
+    const _Float16 lo = (_Float16)(cc - (float)hi);
+    c_eff = (float)hi + (float)lo;
+    half8 f = {(_Float16)-1.f, (_Float16)-1.f, -hi, -lo, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+    if (hf) f = half8{(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+    return f;
+  };
+  float c[2] = {0.f, 0.f};
+  {
+    float ce;
+    afr[0][4] = fold_frag(0.f, ce);
+    afr[1][4] = afr[0][4];
+  }
 
-  // --- staging helpers -------------------------------------------------------------------
-  constexpr int KCH = D / 32;   // 16-byte chunks of the K tile per thread
-  constexpr int VCH = DV / 32;  // 16-byte chunks of the V tile per thread
-  u32x4 kreg[KCH], vreg[VCH];
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DV;
-  // Rows past the end of the slice are read from the slice's last row instead (always in
-  // bounds, no predication, so the loads stay in flight across the tile); their features are
-  // forced to zero through the norm term, so what they hold never reaches S or z.
-  auto load_tile = [&](int t) {
-    const int t0 = tok_begin + t * kTile;
+  auto load_k = [&](u32x4(&kr)[2], int tile) {
+    const int tok = min(tok_begin + tile * kTile + 16 * wv + l16, tok_end - 1);
+    const unsigned short* src = Kb + (size_t)tok * D + 8 * g16;
+    kr[0] = *reinterpret_cast<const u32x4*>(src);
+    kr[1] = *reinterpret_cast<const u32x4*>(src + 32);
+  };
+  // V tile -> LDS: lane i of a wave fills position i % 8 of row r0 + i / 8 with the row's 16-byte piece
+  // (i % 8) ^ (row & 7).  Rows past the end of the slice repeat its last row (their features are zero).
+  auto dma_v = [&](int tile, int vb) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      int ci = tid + 256 * i, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
-    }
-#pragma unroll
-    for (int i = 0; i < VCH; ++i) {
-      int ci = tid + 256 * i, tok = min(t0 + ci / (DV / 8), tok_end - 1), cc = ci % (DV / 8);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DV + 8 * cc);
+    for (int u = 0; u < 2; ++u) {
+      const int row = 16 * wv + 8 * u + lane / 8;
+      const int tok = min(tok_begin + tile * kTile + row, tok_end - 1);
+      dma16_to_lds(Vb + (size_t)tok * DV + 8 * ((lane % 8) ^ (row & 7)), Vt + vb * SM::v_buf + (16 * wv + 8 * u) * 128);
     }
   };
-  auto store_tile = [&](int buf) {
-    _Float16* xs = Xs + buf * kTile * SM::XS;
-    unsigned short* vt = Vt + buf * kTile * DV;
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      int ci = tid + 256 * i, tok = ci / (D / 8), kc = ci % (D / 8);
-      *reinterpret_cast<u32x4*>(xs + tok * SM::XS + 8 * kc) = bf16x8_to_f16x8(kreg[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < VCH; ++i) {
-      int ci = tid + 256 * i, tok = ci / (DV / 8), cc = ci % (DV / 8);
-      *reinterpret_cast<u32x4*>(vt + tok * DV + 8 * (cc ^ (tok & 7))) = vreg[i];
-    }
-  };
-  // n' of this wave's 16 tokens of the tile in buffer `buf` -> ns[nb]
-  auto norms = [&](int buf, int nb, int t) {
-    const _Float16* xs = Xs + buf * kTile * SM::XS;
+  // Convert the fetched key rows, store them, and write n' of this wave's 16 rows into their extra slots.
+  // x~^T = M' X^T by 16x16x32 MFMAs with the tokens as columns (lane l16 = token, registers = rows of M'),
+  // so the sum of squares runs over registers; the four lane groups are added by one fp32 MFMA against ones.
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  auto stage = [&](const u32x4(&kr)[2], int tile, int xb) {
+    unsigned char* xs = Xs + xb * SM::x_buf;
     f32x4 acc[R / 16];
 #pragma unroll
-    for (int rt = 0; rt < R / 16; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < 2; ++s) {
+      half8 mf[R / 16];
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-      half8 a = *reinterpret_cast<const half8*>(xs + (16 * wv + l16) * SM::XS + 32 * s + 8 * g16);
+      for (int rt = 0; rt < R / 16; ++rt)
+        mf[rt] = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::MS + 32 * s + 8 * g16);
+      u32x4 cv = bf16x8_to_f16x8(kr[s]);
+      *reinterpret_cast<u32x4*>(xs + (16 * wv + l16) * XROW + (32 * s + 8 * g16) * 2) = cv;
 #pragma unroll
-      for (int rt = 0; rt < R / 16; ++rt) {
-        half8 b = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::XS + 32 * s + 8 * g16);
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[rt], 0, 0, 0);
-      }
+      for (int rt = 0; rt < R / 16; ++rt)
+        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[rt], *reinterpret_cast<half8*>(&cv), s == 0 ? zero4 : acc[rt], 0, 0, 0);
     }
-    f32x4 ss = {0.f, 0.f, 0.f, 0.f};
+    float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-    for (int rt = 0; rt < R / 16; ++rt)
+    for (int rt = 0; rt < R / 16; rt += 2)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) ss[v] = fmaf(acc[rt][v], acc[rt][v], ss[v]);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) ss[v] = row16_sum(ss[v]);
-    if (l16 == 0) {
-      const int t0 = tok_begin + t * kTile + 16 * wv + 4 * g16;
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        ss[v] = (t0 + v >= tok_end) ? -1e30f : -ss[v];  // rows past the end contribute exp2(-huge) = 0
-      *reinterpret_cast<f32x4*>(ns + nb * kTile + 16 * wv + 4 * g16) = ss;  // stored negated
+      for (int v = 0; v < 4; ++v) {
+        s0 = fmaf(acc[rt][v], acc[rt][v], s0);
+        s1 = fmaf(acc[rt + 1][v], acc[rt + 1][v], s1);
+      }
+    // D[i][tok] = sum over the four lane groups of their partial sums: every lane ends with n' of token l16
+    const f32x4 tot = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, s0 + s1, zero4, 0, 0, 0);
+    if (g16 == 0) {
+      // rows past the end get the largest norm fp16 holds: their features are exp2(-65504 ...) = 0
+      const float n = (tok_begin + tile * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(tot[0], kF16Max);
+      const _Float16 hi = (_Float16)n;
+      const _Float16 lo = (_Float16)(n - (float)hi);
+      fp16x2 hl;
+      hl[0] = hi;
+      hl[1] = lo;
+      const u32x4 w = {*reinterpret_cast<unsigned*>(&hl), 0x3c003c00u, 0u, 0u};  // n'_hi, n'_lo, 1, 1, 0 x 4
+      *reinterpret_cast<u32x4*>(xs + (16 * wv + l16) * XROW + 128) = w;
     }
   };
 
-  // --- accumulators ------------------------------------------------------------------------
-  f32x16 S[2][DV / 32];
-#pragma unroll
-  for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-    for (int ct = 0; ct < DV / 32; ++ct)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) S[ft][ct][v] = 0.f;
-  // z[feat] = column sums of phi, accumulated by an MFMA against ones (every column of the result is
-  // equal): the same bf16-rounded features that enter S, so S_j / z_j stays an exact convex
-  // combination of value rows.  (Summing with v_dot2c_f32_bf16 instead stalls behind the MFMAs in flight.)
-  f32x16 zacc[2];
-#pragma unroll
-  for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) zacc[ft][v] = 0.f;
-  // Per-feature shift (lane = feature column of the projection; both half-waves agree).  It is set
-  // from the first 32 tokens and afterwards only raised when a logit exceeds it by more than kTau.
-  float c[2] = {0.f, 0.f};
+  // per-lane byte offsets of the operand fetches
+  const unsigned xoff = l32 * XROW + 16 * hf;   // + 32 s: fragment s < 4 of a key row
+  const unsigned xoff4 = l32 * XROW + 128;      // the extra slots (both half-waves read the same eight)
+  const int jj = l32 % 16, tl = 4 * hf + jj / 4, kq = 2 * (l32 / 16) + (jj % 4) / 2;
+  unsigned voff[2];
+  voff[0] = tl * 128 + 16 * (kq ^ (tl & 7)) + 8 * (jj % 2);
+  voff[1] = tl * 128 + 16 * ((kq + 4) ^ (tl & 7)) + 8 * (jj % 2);
 
-  // --- prologue: tile 0 into buffer 0, tile 1 in flight ------------------------------------
-  if (ntile > 0) {
-    load_tile(0);
-    store_tile(0);
+  f32x16 S[2][2], U[2];
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) S[ft][ct] = zero16;
+  float zl[2] = {0.f, 0.f};  // z of feature f0 + 32 ft + l32 over this half-wave's token rows
+  u32x4 pk[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) pk[a][b] = u32x4{0u, 0u, 0u, 0u};
+  half8 xa[5];
+
+  auto fetch_xa = [&](const unsigned char* xrows) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) xa[s] = *reinterpret_cast<const half8*>(xrows + xoff + 32 * s);
+    xa[4] = *reinterpret_cast<const half8*>(xrows + xoff4);
+  };
+  auto fetch_bv = [&](u32x4(&bv)[2], const unsigned char* vrows, int hh) {
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const unsigned char* vr = vrows + voff[ct] + hh * 16 * 128;
+      u32x2 lo = lds_read_tr16(reinterpret_cast<const unsigned short*>(vr));
+      u32x2 hi = lds_read_tr16(reinterpret_cast<const unsigned short*>(vr + 8 * 128));
+      bv[ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+    }
+  };
+
+  // --- prologue: tiles 0 and 1 staged, tile 2 in flight, V(0) on its way, A(block 0) -------------
+  u32x4 kreg[2];
+  u32x4 cvh[2];  // converted rows of the tile whose norms are being computed (this thread's two 16-byte pieces)
+  {
+    u32x4 k1[2];
+    load_k(kreg, 0);
+    load_k(k1, 1);
+    load_k(cvh, 2);
+    dma_v(0, 0);
+    stage(kreg, 0, 0);
+    stage(k1, 1, 1);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      cvh[s2] = bf16x8_to_f16x8(cvh[s2]);
+      *reinterpret_cast<u32x4*>(Xs + 2 * SM::x_buf + (16 * wv + l16) * XROW + (32 * s2 + 8 * g16) * 2) = cvh[s2];
+    }
+    load_k(kreg, 3);
   }
   // The A' fragments must have arrived before the loop: otherwise the compiler's wait for them sits
-  // inside the loop body, where (the counter being in-order) it would also wait for the tile
-  // prefetch issued a few instructions earlier.
+  // inside the loop body, where (the counter being in-order) it would also wait for the loads in flight.
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(afr[ft][s]));
-  if (ntile > 1) load_tile(1);
+    for (int s = 0; s < 4; ++s) asm volatile("" ::"v"(afr[ft][s]));
+  __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2): everything but the two loads of tile 2
   __syncthreads();
+  fetch_xa(Xs);
+#pragma unroll
+  for (int s = 0; s < 5; ++s)
+    U[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[s], afr[0][s], s == 0 ? zero16 : U[0], 0, 0, 0);
+  u32x4 bva[2];  // V fragments (first 16 token rows) of the block whose C runs next; the first C adds zeros
+  fetch_bv(bva, Vt, 0);
 
-  const u32x4 ones4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
+  // Staging of the following tiles, cut into pieces that ride along the 32 pieces of a tile's four
+  // blocks (slot = 8 k + i):  norms of tile t+2 (its rows were converted during the previous tile):
+  //   slots 0,4,8,12: fetch the M' fragments of 16 rows;  3,7,11,15: their two MFMAs;  6,10,14,18: squares;
+  //   19: sum over the lane groups;  22: n' -> extra slots of X(t+2);
+  // slots 24..31: convert the rows of tile t+3 word by word, store them, fetch tile t+4.
+  half8 mf[2];
+  f32x4 nacc = zero4, ntot = zero4;
+  float sq0 = 0.f, sq1 = 0.f;
+  int b0 = 0, b1 = 1, b2 = 2, b3 = 3;   // X buffers of tiles t .. t+3
+  int v0 = 0, v1 = 1, v2 = 2;           // V buffers of tiles t, t+1, t-1
+  auto stg = [&](int slot, int t) {
+    if (slot < 16 && slot % 4 == 0) {
+      const int rt = slot / 4;
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+        mf[s2] = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::MS + 32 * s2 + 8 * g16);
+    }
+    if (slot < 16 && slot % 4 == 3) {
+      nacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[0], *reinterpret_cast<half8*>(&cvh[0]), zero4, 0, 0, 0);
+      nacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[1], *reinterpret_cast<half8*>(&cvh[1]), nacc, 0, 0, 0);
+    }
+    if (slot >= 6 && slot <= 18 && slot % 4 == 2) {
+#pragma unroll
+      for (int v = 0; v < 4; v += 2) {
+        sq0 = fmaf(nacc[v], nacc[v], sq0);
+        sq1 = fmaf(nacc[v + 1], nacc[v + 1], sq1);
+      }
+    }
+    if (slot == 19) {
+      ntot = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, sq0 + sq1, zero4, 0, 0, 0);
+      sq0 = sq1 = 0.f;
+    }
+    if (slot == 22) {  // all four lane groups hold the same n' and write the same 16 bytes: no branch
+      const float n = (tok_begin + (t + 2) * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(ntot[0], kF16Max);
+      const _Float16 hi = (_Float16)n;
+      const _Float16 lo = (_Float16)(n - (float)hi);
+      fp16x2 hl;
+      hl[0] = hi;
+      hl[1] = lo;
+      const u32x4 w = {*reinterpret_cast<unsigned*>(&hl), 0x3c003c00u, 0u, 0u};
+      *reinterpret_cast<u32x4*>(Xs + b2 * SM::x_buf + (16 * wv + l16) * XROW + 128) = w;
+    }
+    if (slot >= 24) {
+      const int s2 = (slot - 24) / 4, q = (slot - 24) % 4;
+      cvh[s2][q] = pack_f16_from_bf16pair(kreg[s2][q]);
+      if (q == 3)
+        *reinterpret_cast<u32x4*>(Xs + b3 * SM::x_buf + (16 * wv + l16) * XROW + (32 * s2 + 8 * g16) * 2) = cvh[s2];
+      if (slot == 31) load_k(kreg, t + 4);
+    }
+  };
   for (int t = 0; t < ntile; ++t) {
-    const int buf = t % 3, nb = t & 1;
-    norms(buf, nb, t);
-    if (t + 1 < ntile) store_tile((t + 1) % 3);
-    if (t + 2 < ntile) load_tile(t + 2);
-    __syncthreads();
-
-    const _Float16* xs = Xs + buf * kTile * SM::XS;
-    const unsigned short* vt = Vt + buf * kTile * DV;
-    // The tile is worked in two halves of 32 tokens, so that only one half's logits are alive.
+    // the buffer indices are rotated at the end of the body and kept in scalar registers;
+    // bp: buffer of V(t-1); the very first block adds zero features times V(0)
+    const int bp = (t == 0) ? 0 : v2;
+    dma_v(t + 1, v1);  // V(t+1) -> LDS; the key side of the staging rides along the blocks (stg)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      // projection: U[ft], rows = tokens 32 tt + 8 g + 4 hf + e, column = feature 32 ft + l32.
-      // The accumulators start at -(n'_token + c_feature), so the MFMA chain delivers the shifted
-      // log2-features directly.
-      f32x16 U[2];
+    for (int k = 0; k < 4; ++k) {
+      const int ft = k % 2, pft = ft ^ 1, nft = ft ^ 1, cur = k & 1, nxt = cur ^ 1;
+      const unsigned char* vprev = Vt + ((k == 0) ? bp : v0) * SM::v_buf + ((k == 0) ? 32 : 32 * ((k - 1) / 2)) * 128;
+      u32x4 bvb[2];
+      fetch_bv(bvb, vprev, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      // B(k), first part: largest shifted logit of the block; the first half of C(k-1) runs meanwhile
+      float mall = U[cur][0];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 nv = *reinterpret_cast<const f32x4*>(ns + nb * kTile + 32 * tt + 8 * g + 4 * hf);
+      for (int v = 1; v < 9; v += 2) mall = max3(mall, U[cur][v], U[cur][v + 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      S[pft][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[nxt][0]),
+                                                          *reinterpret_cast<bf16x8*>(&bva[0]), S[pft][0], 0, 0, 0);
 #pragma unroll
-        for (int ft = 0; ft < 2; ++ft)
+      for (int v = 9; v < 15; v += 2) mall = max3(mall, U[cur][v], U[cur][v + 1]);
+      mall = fmaxf(mall, U[cur][15]);
+      __builtin_amdgcn_sched_barrier(0);
+      S[pft][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[nxt][0]),
+                                                          *reinterpret_cast<bf16x8*>(&bva[1]), S[pft][1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      const bool first = (t == 0 && k < 2);
+      if (first || __any(mall > kTau)) {
+        float m0 = fmaxf(mall, __shfl_xor(mall, 32, 64));
+        const float delta = (first || m0 > kRaise) ? m0 : 0.f;
+        float ceff;
+        afr[ft][4] = fold_frag(c[ft] + delta, ceff);
+        const float deff = ceff - c[ft];
+        c[ft] = ceff;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) U[ft][4 * g + e] = nv[e] - c[ft];
-      }
+        for (int v = 0; v < 16; ++v) U[cur][v] -= deff;
+        if (!first) {
+          const float f = fast_exp2(-deff);
+          zl[ft] *= f;
 #pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        half8 a = *reinterpret_cast<const half8*>(xs + (32 * tt + l32) * SM::XS + 16 * s + 8 * hf);
+          for (int v = 0; v < 16; ++v) {
+            const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
 #pragma unroll
-        for (int ft = 0; ft < 2; ++ft) U[ft] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, afr[ft][s], U[ft], 0, 0, 0);
-      }
-      // Common path: look at the largest shifted logit; more than kTau (or the very first half tile,
-      // whose shifts are still zero) means some shift has to be set or raised.
-      float mall = -INFINITY;
-#pragma unroll
-      for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) mall = max3(mall, U[ft][v], U[ft][v + 1]);
-      const bool first = (t == 0 && tt == 0);
-      if (first || __any(mall > kTau)) {  // first half tile, or rare
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
-          float m0 = -INFINITY;
-#pragma unroll
-          for (int v = 0; v < 16; v += 2) m0 = max3(m0, U[ft][v], U[ft][v + 1]);
-          m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
-          const float delta = (first || m0 > kRaise) ? m0 : 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) U[ft][v] -= delta;
-          c[ft] += delta;
-          if (!first) {
-            const float f = fast_exp2(-delta);
-            // S and z rows are features: row 8 g + 4 hf + e of tile ft takes the factor held by that lane
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
-              zacc[ft][v] *= fr;
-#pragma unroll
-              for (int ct = 0; ct < DV / 32; ++ct) S[ft][ct][v] *= fr;
-            }
+            for (int ct = 0; ct < 2; ++ct) S[ft][ct][v] *= fr;
           }
         }
       }
-      // features, packed to bf16 in the operand layout of the second MFMA
-      u32x4 pk[2][2];  // [ft][hh]: k-slots s <-> accumulator registers 8 hh + s
+      __builtin_amdgcn_sched_barrier(0);
+      // B(k), second part, in eight pieces; piece i follows MFMA i of A(k+1) (i < 5) or of C(k-1)
 #pragma unroll
-      for (int ft = 0; ft < 2; ++ft)
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            pk[ft][hh][q] = pack_bf16(fast_exp2(U[ft][8 * hh + 2 * q]), fast_exp2(U[ft][8 * hh + 2 * q + 1]));
-      // S[ft][ct] += phi^T V : k-slot s of half hf is token 32 tt + 16 hh + 8 (s/4) + 4 hf + s%4.
-      // Transposing read: in each group of 16 lanes, lane i points at 4 values V[t + i/4][c0 + 4 (i%4) ...]
-      // and receives V[t .. t+3][c0 + i], i.e. four consecutive tokens of its own column.
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-#pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct) {
-          const int j = l32 % 16;
-          const int tok = 32 * tt + 16 * hh + 4 * hf + j / 4;
-          const int chunk = 4 * ct + 2 * (l32 / 16) + (j % 4) / 2;
-          const unsigned short* vr = vt + tok * DV + 8 * (chunk ^ (tok & 7)) + 4 * (j % 2);
-          u32x2 lo = lds_read_tr16(vr);
-          u32x2 hi = lds_read_tr16(vr + 8 * DV);
-          u32x4 bv = {lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-          for (int ft = 0; ft < 2; ++ft)
-            S[ft][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[ft][hh]),
-                                                                *reinterpret_cast<bf16x8*>(&bv), S[ft][ct], 0, 0, 0);
+      for (int i = 0; i < 8; ++i) {
+        if (i < 5) {
+          U[nxt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[i], afr[nft][i], i == 0 ? zero16 : U[nxt], 0, 0, 0);
+        } else if (i < 7) {
+          S[pft][i - 5] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[nxt][1]),
+                                                                  *reinterpret_cast<bf16x8*>(&bvb[i - 5]), S[pft][i - 5], 0, 0, 0);
         }
-#pragma unroll
-        for (int ft = 0; ft < 2; ++ft) {
-          u32x4 o4 = ones4;
-          zacc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[ft][hh]),
-                                                             *reinterpret_cast<bf16x8*>(&o4), zacc[ft], 0, 0, 0);
-        }
+        const float ea = fast_exp2(U[cur][2 * i]), eb = fast_exp2(U[cur][2 * i + 1]);
+        pk[cur][i / 4][i % 4] = pack_bf16(ea, eb);
+        zl[ft] = (zl[ft] + ea) + eb;
+        // operand fetches for the next iteration, behind the last MFMAs that read the old ones
+        if (i == 5 && k == 0) fetch_xa(Xs + b0 * SM::x_buf + 32 * XROW);  // second half of this tile
+        if (i == 5 && k == 2) fetch_xa(Xs + b1 * SM::x_buf);              // first half of the next tile
+        if (i == 6) fetch_bv(bva, Vt + v0 * SM::v_buf + 32 * (k / 2) * 128, 0);  // V rows of this block
+        stg(8 * k + i, t);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // keep this block's results on this side of the next block's branch (the compiler would otherwise
+      // sink the last exponentials to their first use, behind it)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(pk[cur][hh][q]));
+      asm volatile("" : "+v"(zl[ft]));
     }
+    __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2): V(t+1) has landed; the two key loads may still fly
+    __syncthreads();
+    {
+      const int r0 = b0, r2 = v2;
+      b0 = __builtin_amdgcn_readfirstlane(b1);
+      b1 = __builtin_amdgcn_readfirstlane(b2);
+      b2 = __builtin_amdgcn_readfirstlane(b3);
+      b3 = __builtin_amdgcn_readfirstlane(r0);
+      v2 = __builtin_amdgcn_readfirstlane(v0);
+      v0 = __builtin_amdgcn_readfirstlane(v1);
+      v1 = __builtin_amdgcn_readfirstlane(r2);
+    }
+  }
+  // drain: C of the last block (second half of the last tile, feature tile 1)
+  {
+    const unsigned char* vlast = Vt + v2 * SM::v_buf + 32 * 128;  // after the last rotation v2 is the last tile's buffer
+    u32x4 bvb[2];
+    fetch_bv(bvb, vlast, 1);
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+      S[1][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[1][0]),
+                                                         *reinterpret_cast<bf16x8*>(&bva[ct]), S[1][ct], 0, 0, 0);
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+      S[1][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[1][1]),
+                                                         *reinterpret_cast<bf16x8*>(&bvb[ct]), S[1][ct], 0, 0, 0);
   }
 
   // --- epilogue: partial state of this slice (bf16 in memory: half the bytes on the way to the merge;
-  // the merged state is rounded to bf16 for the readout's MFMA anyway).  Each wave turns its 64 x DV
+  // the merged state is rounded to bf16 for the readout's MFMA anyway).  Each wave turns its 64 x dv
   // block through LDS (the tile buffers are free now) so that the stores are 16-byte pieces of whole rows.
   const size_t pbase = (size_t)bh * P + p;
+  wait_vmcnt0();   // the key loads issued for tiles past the end
   __syncthreads();  // every wave is done with the tile buffers
   {
-    constexpr int ROWB = DV * 2 + 16;  // bytes per staged feature row, padded
+    constexpr int ROWB = DV * 2 + 16;
     static_assert(4 * 64 * ROWB <= SM::x_bytes + SM::v_bytes, "stage does not fit the tile buffers");
     unsigned char* stg = smem + wv * 64 * ROWB;
 #pragma unroll
     for (int ft = 0; ft < 2; ++ft)
 #pragma unroll
-      for (int ct = 0; ct < DV / 32; ++ct)
+      for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4);
@@ -392,7 +500,7 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
         }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    constexpr int CPR = DV / 8;  // 16-byte pieces per row
+    constexpr int CPR = DV / 8;
 #pragma unroll
     for (int k = 0; k < 64 * CPR / 64; ++k) {
       const int i = lane + 64 * k, row = i / CPR, ch = i % CPR;
@@ -402,12 +510,12 @@ __global__ __launch_bounds__(256, MINW) void k_kv_reduce(const unsigned short* _
   }
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft) {
-    if (l32 == 0) {  // every column of zacc is equal: one lane per half writes its rows
-#pragma unroll
-      for (int v = 0; v < 16; ++v) zpart[pbase * m + f0 + 32 * ft + 8 * (v / 4) + 4 * hf + (v % 4)] = zacc[ft][v];
-    }
-    if (hf == 0) cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
+    const float zs = zl[ft] + __shfl_xor(zl[ft], 32, 64);
+    if (hf == 0) zpart[pbase * m + f0 + 32 * ft + l32] = zs;
   }
+#pragma unroll
+  for (int ft = 0; ft < 2; ++ft)
+    if (hf == 0) cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
 }
 
 // ---------------------------------------------------------------------------
@@ -980,13 +1088,10 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
   b.nrm = p.d == 128 ? ar.take<float>(BH * (size_t)(p.L > 0 ? p.L : 1)) : nullptr;
 }
 
-template <int D, int DV, int R, int MINW>
 dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* K, const void* V) {
   const dark_params& p = pb.p;
-  auto kern = k_kv_reduce<D, DV, R, MINW>;
-  const size_t lds = KvSmem<D, DV, R>::total;
-  DARK_TRY(allow_lds(kern, lds));
-  DARK_LAUNCH(KID_KV_REDUCE, pb.st, kern, dim3(pl.kv_grid), dim3(256), lds, (const unsigned short*)K,
+  DARK_TRY(allow_lds(k_kv_reduce, KvSmem::total));
+  DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce, dim3(pl.kv_grid), dim3(256), KvSmem::total, (const unsigned short*)K,
               (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m, pl.P, pl.slice_len,
               pl.n_work);
   return DARK_OK;
@@ -1048,7 +1153,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
 
   DARK_TRY(fused_launch_prep(pb, M, W, b.Ah, b.Mh));
   if (p.d == 64) {
-    DARK_TRY((launch_kv<64, 64, 64, 2>(pb, pl, b, K, V)));
+    DARK_TRY(launch_kv(pb, pl, b, K, V));
   } else {
     DARK_TRY(fused_launch_slice_state128(pb, K, V, b.Ah, b.Mh, b.nrm, b.Spart, b.zpart, b.cpart, pl.P, pl.slice_len));
   }
@@ -1086,7 +1191,7 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
   b.zpart = zpart;
   b.cpart = cpart;
   if (p.d != 64) return DARK_EUNSUPPORTED;
-  return launch_kv<64, 64, 64, 2>(pb, pl, b, K, V);
+  return launch_kv(pb, pl, b, K, V);
 }
 
 }  // namespace dark
