@@ -164,10 +164,12 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
   const int l16 = lane % 16, g16 = lane / 16;
   const int f0 = fb * 256 + wv * 64;
 
-  for (int ci = tid; ci < R * D / 8; ci += 256) {
-    int row = ci / (D / 8), kc = ci % (D / 8);
-    u32x4 v = *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
-    *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) = v;
+  // M' -> registers now, -> LDS in the prologue (after the tile fetches have been issued)
+  u32x4 mreg[R * D / 8 / 256];
+#pragma unroll
+  for (int u = 0; u < R * D / 8 / 256; ++u) {
+    const int ci = tid + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+    mreg[u] = *reinterpret_cast<const u32x4*>(Mh + ((size_t)h * R + row) * D + 8 * kc);
   }
   // A' fragments: feature = f0 + 32 ft + l32, k = 16 s + 8 hf + [0,8); fragment 4 holds the extra slots
   half8 afr[2][5];
@@ -300,6 +302,12 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
     load_k(k1, 1);
     load_k(cvh, 2);
     dma_v(0, 0);
+#pragma unroll
+    for (int u = 0; u < R * D / 8 / 256; ++u) {
+      const int ci = tid + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
+      *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) = mreg[u];
+    }
+    __syncthreads();  // M' is read by every wave's norm MFMAs
     stage(kreg, 0, 0);
     stage(k1, 1, 1);
 #pragma unroll
