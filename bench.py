@@ -141,8 +141,9 @@ def main():
     tokens = cfg.B * cfg.L
     flops, nbytes, per_kernel = algorithmic_work(cfg)
 
-    # Per-kernel device time: a second loop with HIP events around every launch, recorded by the
-    # library on the launch stream.
+    # Per-kernel device time: a second loop in which the library attaches start/stop events to every
+    # launch (stamped with the kernel's own begin and end on the launch stream; the stream is drained
+    # before each timed launch, so this loop is slower than the timed region above).
     dk.timing_reset()
     dk.timing_enable(True)
     for i in range(args.steps):

@@ -144,7 +144,10 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
 
 /*
  * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel
- * launch of the library is bracketed by HIP events on the launch stream.
+ * launch of the library carries a start and a stop event that the launch itself
+ * stamps with the kernel's begin and end on the device, and the launch stream is
+ * synchronised before each such launch (so the entry points block the host and
+ * the kernels no longer run back to back: enable it for measurement only).
  * dark_timing_read() synchronises with the recorded events, adds their elapsed
  * times into per-kernel totals and returns, for kernel slot `k`
  * (0 <= k < dark_timing_slots()), its name (static storage), the number of

@@ -20,7 +20,6 @@ std::vector<Pending> g_pending;
 std::vector<hipEvent_t> g_free;
 double g_total_ms[KID_COUNT];
 int64_t g_launches[KID_COUNT];
-hipEvent_t g_cur_start;
 
 hipEvent_t get_event() {
   if (!g_free.empty()) {
@@ -42,14 +41,11 @@ const char* kernel_name(int k) {
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }
-void timing_before(int, hipStream_t st) {
-  g_cur_start = get_event();
-  (void)hipEventRecord(g_cur_start, st);
-}
-void timing_after(int kid, hipStream_t st) {
-  hipEvent_t e = get_event();
-  (void)hipEventRecord(e, st);
-  g_pending.push_back({kid, g_cur_start, e});
+void timing_events(int kid, hipStream_t st, hipEvent_t* start, hipEvent_t* stop) {
+  (void)hipStreamSynchronize(st);
+  *start = get_event();
+  *stop = get_event();
+  g_pending.push_back({kid, *start, *stop});
 }
 
 static void drain() {

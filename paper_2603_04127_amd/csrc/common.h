@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <hip/hip_bf16.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -37,16 +38,23 @@ enum KernelId : int {
 
 const char* kernel_name(int k);
 bool timing_on();
-void timing_before(int kid, hipStream_t st);
-void timing_after(int kid, hipStream_t st);
+// A pair of events for one launch: hipExtLaunchKernelGGL stamps them with the kernel's own begin and end
+// on the device, so their difference is the kernel's duration without the launch gap around it.  The
+// stream is drained first: a dispatch queued behind running work is stamped when it is picked up, not
+// when its first wave starts.
+void timing_events(int kid, hipStream_t st, hipEvent_t* start, hipEvent_t* stop);
 
-// Launch helper: optional event bracketing, launch-error check.
-#define DARK_LAUNCH(kid, st, kernel, grid, block, shmem, ...)                    \
-  do {                                                                           \
-    if (::dark::timing_on()) ::dark::timing_before((kid), (st));                 \
-    hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (st), __VA_ARGS__);     \
-    if (::dark::timing_on()) ::dark::timing_after((kid), (st));                  \
-    if (hipGetLastError() != hipSuccess) return DARK_EHIP;                       \
+// Launch helper: optional per-kernel timing, launch-error check.
+#define DARK_LAUNCH(kid, st, kernel, grid, block, shmem, ...)                                       \
+  do {                                                                                              \
+    if (::dark::timing_on()) {                                                                      \
+      hipEvent_t _ea, _eb;                                                                          \
+      ::dark::timing_events((kid), (st), &_ea, &_eb);                                                  \
+      hipExtLaunchKernelGGL(kernel, (grid), (block), (shmem), (st), _ea, _eb, 0, __VA_ARGS__);      \
+    } else {                                                                                        \
+      hipLaunchKernelGGL(kernel, (grid), (block), (shmem), (st), __VA_ARGS__);                      \
+    }                                                                                               \
+    if (hipGetLastError() != hipSuccess) return DARK_EHIP;                                          \
   } while (0)
 
 #define DARK_TRY(expr)                       \
