@@ -678,6 +678,14 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       }
     }
   };
+  // The first tile's rows are requested before the first LDS fill, so that the two cold fetches overlap.
+  if (item_begin < item_end) {
+    const int t00 = (item_begin % chunks_per_bh) * NT + 64 * wv;
+    if (t00 < L) {
+      fetch_x(item_begin / chunks_per_bh, t00);
+      have_x = true;
+    }
+  }
   for (int item = item_begin; item < item_end; ++item) {
     const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
     if (bh != cur_bh) {
