@@ -218,41 +218,51 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
   // x~^T = M' X^T by 16x16x32 MFMAs with the tokens as columns (lane l16 = token, registers = rows of M'),
   // so the sum of squares runs over registers; the four lane groups are added by one fp32 MFMA against ones.
   const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  auto stage = [&](const u32x4(&kr)[2], int tile, int xb) {
-    unsigned char* xs = Xs + xb * SM::x_buf;
-    f32x4 acc[R / 16];
+  // (prologue only: tiles 0 and 1 together, so that their two dependent chains interleave)
+  auto stage01 = [&](const u32x4(&kr0)[2], const u32x4(&kr1)[2]) {
+    f32x4 acc[2][R / 16];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       half8 mf[R / 16];
 #pragma unroll
       for (int rt = 0; rt < R / 16; ++rt)
         mf[rt] = *reinterpret_cast<const half8*>(Ms + (16 * rt + l16) * SM::MS + 32 * s + 8 * g16);
-      u32x4 cv = bf16x8_to_f16x8(kr[s]);
-      *reinterpret_cast<u32x4*>(xs + (16 * wv + l16) * XROW + (32 * s + 8 * g16) * 2) = cv;
 #pragma unroll
-      for (int rt = 0; rt < R / 16; ++rt)
-        acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[rt], *reinterpret_cast<half8*>(&cv), s == 0 ? zero4 : acc[rt], 0, 0, 0);
-    }
-    float s0 = 0.f, s1 = 0.f;
+      for (int tl2 = 0; tl2 < 2; ++tl2) {
+        u32x4 cv = bf16x8_to_f16x8(tl2 ? kr1[s] : kr0[s]);
+        *reinterpret_cast<u32x4*>(Xs + tl2 * SM::x_buf + (16 * wv + l16) * XROW + (32 * s + 8 * g16) * 2) = cv;
 #pragma unroll
-    for (int rt = 0; rt < R / 16; rt += 2)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        s0 = fmaf(acc[rt][v], acc[rt][v], s0);
-        s1 = fmaf(acc[rt + 1][v], acc[rt + 1][v], s1);
+        for (int rt = 0; rt < R / 16; ++rt)
+          acc[tl2][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[rt], *reinterpret_cast<half8*>(&cv),
+                                                                s == 0 ? zero4 : acc[tl2][rt], 0, 0, 0);
       }
-    // D[i][tok] = sum over the four lane groups of their partial sums: every lane ends with n' of token l16
-    const f32x4 tot = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, s0 + s1, zero4, 0, 0, 0);
-    if (g16 == 0) {
-      // rows past the end get the largest norm fp16 holds: their features are exp2(-65504 ...) = 0
-      const float n = (tok_begin + tile * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(tot[0], kF16Max);
+    }
+    f32x4 tot[2];
+#pragma unroll
+    for (int tl2 = 0; tl2 < 2; ++tl2) {
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < R / 16; rt += 2)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          s0 = fmaf(acc[tl2][rt][v], acc[tl2][rt][v], s0);
+          s1 = fmaf(acc[tl2][rt + 1][v], acc[tl2][rt + 1][v], s1);
+        }
+      // D[i][tok] = sum over the four lane groups of their partial sums: every lane ends with n' of token l16
+      tot[tl2] = __builtin_amdgcn_mfma_f32_16x16x4f32(1.0f, s0 + s1, zero4, 0, 0, 0);
+    }
+#pragma unroll
+    for (int tl2 = 0; tl2 < 2; ++tl2) {
+      // rows past the end get the largest norm fp16 holds: their features are exp2(-65504 ...) = 0;
+      // all four lane groups hold the same n' and write the same 16 bytes
+      const float n = (tok_begin + tl2 * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(tot[tl2][0], kF16Max);
       const _Float16 hi = (_Float16)n;
       const _Float16 lo = (_Float16)(n - (float)hi);
       fp16x2 hl;
       hl[0] = hi;
       hl[1] = lo;
       const u32x4 w = {*reinterpret_cast<unsigned*>(&hl), 0x3c003c00u, 0u, 0u};  // n'_hi, n'_lo, 1, 1, 0 x 4
-      *reinterpret_cast<u32x4*>(xs + (16 * wv + l16) * XROW + 128) = w;
+      *reinterpret_cast<u32x4*>(Xs + tl2 * SM::x_buf + (16 * wv + l16) * XROW + 128) = w;
     }
   };
 
@@ -308,8 +318,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) = mreg[u];
     }
     __syncthreads();  // M' is read by every wave's norm MFMAs
-    stage(kreg, 0, 0);
-    stage(k1, 1, 1);
+    stage01(kreg, k1);
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
       cvh[s2] = bf16x8_to_f16x8(cvh[s2]);
