@@ -154,31 +154,48 @@ __device__ inline void gemm_park(float (*T)[GT + 4], const float (&r)[8], int mo
   }
 }
 
-__global__ __launch_bounds__(256) void k_gemm(Gemm g) {
-  __shared__ __attribute__((aligned(16))) float As[GK][GT + 4];
-  __shared__ __attribute__((aligned(16))) float Bs[GK][GT + 4];
+// One output tile of the batched problem, as seen by the whole workgroup (all fields uniform).
+struct GemmTile {
+  const float* A;
+  const float* B;
+  float* C;
+  int m0, n0, Me, Ne, Ke;
+};
+
+// Tile t -> its operands and effective sizes; false if the tile lies outside the (ragged) problem.
+__device__ inline bool gemm_tile(const Gemm& g, int t, int tilesM, int tilesN, GemmTile& o) {
+  const int tn = t % tilesN;
+  t /= tilesN;
+  const int tm = t % tilesM;
+  t /= tilesM;
+  const int b2 = t % g.nb2;
+  t /= g.nb2;
+  const int b1 = t % g.nb1;
+  const int b0 = t / g.nb1;
+  o.Me = g.M;
+  o.Ne = g.N;
+  o.Ke = g.K;
+  if (g.mlim > 0) o.Me = max(0, min(g.M, g.mlim - b2 * g.mstep));
+  if (g.nlim > 0) o.Ne = max(0, min(g.N, g.nlim - b2 * g.nstep));
+  if (g.klim > 0) o.Ke = max(0, min(g.K, g.klim - b2 * g.kstep));
+  o.m0 = tm * GT;
+  o.n0 = tn * GT;
+  o.A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
+  o.B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
+  o.C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
+  return o.m0 < o.Me && o.n0 < o.Ne;
+}
+
+// Persistent workgroups: each walks the output tiles blockIdx.x, blockIdx.x + gridDim.x, ... and treats
+// their K steps as one stream: while step s is multiplied out of one LDS buffer, the elements of step
+// s + 1 (of the same tile, or the first step of the next tile) are on their way into registers, and
+// they are parked in the other buffer, so there is one barrier per step and a tile's stores overlap the
+// next tile's loads.
+__global__ __launch_bounds__(256, 4) void k_gemm(Gemm g, int total_tiles) {
+  __shared__ __attribute__((aligned(16))) float As[2][GK][GT + 4];
+  __shared__ __attribute__((aligned(16))) float Bs[2][GK][GT + 4];
   const int tilesN = (g.N + GT - 1) / GT;
   const int tilesM = (g.M + GT - 1) / GT;
-  long long bid = blockIdx.x;
-  const int tn = (int)(bid % tilesN);
-  bid /= tilesN;
-  const int tm = (int)(bid % tilesM);
-  bid /= tilesM;
-  const int b2 = (int)(bid % g.nb2);
-  bid /= g.nb2;
-  const int b1 = (int)(bid % g.nb1);
-  const int b0 = (int)(bid / g.nb1);
-
-  int Me = g.M, Ne = g.N, Ke = g.K;
-  if (g.mlim > 0) Me = max(0, min(g.M, g.mlim - b2 * g.mstep));
-  if (g.nlim > 0) Ne = max(0, min(g.N, g.nlim - b2 * g.nstep));
-  if (g.klim > 0) Ke = max(0, min(g.K, g.klim - b2 * g.kstep));
-  const int m0 = tm * GT, n0 = tn * GT;
-  if (m0 >= Me || n0 >= Ne) return;
-
-  const float* A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
-  const float* B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
-  float* C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
   const int modeA = gemm_load_mode(g.A, g.sAm, g.sAk, g.sA0, g.sA1, g.sA2);
   const int modeB = gemm_load_mode(g.B, g.sBn, g.sBk, g.sB0, g.sB1, g.sB2);
 
@@ -189,39 +206,63 @@ __global__ __launch_bounds__(256) void k_gemm(Gemm g) {
   typedef float f32x16 __attribute__((ext_vector_type(16)));
   const int lane = tid % 64, wv = tid / 64, l32 = lane % 32, hf = lane / 32;
   const int wm = wv / 2, wn = wv % 2;
+
+  GemmTile cur, nxt;
+  int t = blockIdx.x;
+  while (t < total_tiles && !gemm_tile(g, t, tilesM, tilesN, cur)) t += gridDim.x;
+  if (t >= total_tiles) return;
+  // Every tile has at least one step (an empty contraction fetches zeros), so the stream is uniform.
+  float ra[8], rb[8];
+  gemm_fetch(ra, modeA, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, 0, cur.Ke, tid);
+  gemm_fetch(rb, modeB, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, 0, cur.Ke, tid);
+  int buf = 0, k0 = 0;
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-
-  // The next K step's elements are fetched into registers while the current one is multiplied.
-  float ra[8], rb[8];
-  if (Ke > 0) {
-    gemm_fetch(ra, modeA, A, g.sAm, g.sAk, m0, Me, 0, Ke, tid);
-    gemm_fetch(rb, modeB, B, g.sBn, g.sBk, n0, Ne, 0, Ke, tid);
-  }
-  for (int k0 = 0; k0 < Ke; k0 += GK) {
-    gemm_park(As, ra, modeA, g.sAm, g.sAk, tid);
-    gemm_park(Bs, rb, modeB, g.sBn, g.sBk, tid);
-    __syncthreads();
-    if (k0 + GK < Ke) {
-      gemm_fetch(ra, modeA, A, g.sAm, g.sAk, m0, Me, k0 + GK, Ke, tid);
-      gemm_fetch(rb, modeB, B, g.sBn, g.sBk, n0, Ne, k0 + GK, Ke, tid);
+  while (true) {
+    gemm_park(As[buf], ra, modeA, g.sAm, g.sAk, tid);
+    gemm_park(Bs[buf], rb, modeB, g.sBn, g.sBk, tid);
+    // what to fetch while this step is multiplied: the tile's next step, or the next tile's first
+    const bool last = k0 + GK >= cur.Ke;
+    int tn = t;
+    bool more = true;
+    if (last) {
+      tn = t + gridDim.x;
+      while (tn < total_tiles && !gemm_tile(g, tn, tilesM, tilesN, nxt)) tn += gridDim.x;
+      more = tn < total_tiles;
     }
+    if (more) {
+      const GemmTile& f = last ? nxt : cur;
+      const int fk = last ? 0 : k0 + GK;
+      gemm_fetch(ra, modeA, f.A, g.sAm, g.sAk, f.m0, f.Me, fk, f.Ke, tid);
+      gemm_fetch(rb, modeB, f.B, g.sBn, g.sBk, f.n0, f.Ne, fk, f.Ke, tid);
+    }
+    __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < GK; kk += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk + hf][32 * wm + l32], Bs[kk + hf][32 * wn + l32], acc, 0, 0, 0);
-    __syncthreads();
-  }
-  const int gn = n0 + 32 * wn + l32;
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][kk + hf][32 * wm + l32], Bs[buf][kk + hf][32 * wn + l32], acc, 0, 0, 0);
+    buf ^= 1;
+    if (!last) {
+      k0 += GK;
+      continue;
+    }
+    const int gn = cur.n0 + 32 * wn + l32;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int gm = m0 + 32 * wm + 8 * (v / 4) + 4 * hf + (v % 4);
-    if (gm >= Me || gn >= Ne) continue;
-    float* c = C + gm * g.sCm + gn * g.sCn;
-    float x = g.alpha * acc[v];
-    if (g.beta != 0.f) x += g.beta * (*c);
-    if (g.mask == 1 && gn > gm) x = 0.f;
-    *c = x;
+    for (int v = 0; v < 16; ++v) {
+      const int gm = cur.m0 + 32 * wm + 8 * (v / 4) + 4 * hf + (v % 4);
+      if (gm < cur.Me && gn < cur.Ne) {
+        float* c = cur.C + gm * g.sCm + gn * g.sCn;
+        float x = g.alpha * acc[v];
+        if (g.beta != 0.f) x += g.beta * (*c);
+        if (g.mask == 1 && gn > gm) x = 0.f;
+        *c = x;
+      }
+      acc[v] = 0.f;
+    }
+    if (!more) break;
+    cur = nxt;
+    t = tn;
+    k0 = 0;
   }
 }
 
@@ -447,7 +488,9 @@ dark_status run_gemm(const Gemm& g, hipStream_t st) {
   long long blocks = tiles * g.nb0 * g.nb1 * g.nb2;
   if (blocks <= 0) return DARK_OK;
   if (blocks > 0x7fffffffLL) return DARK_EUNSUPPORTED;
-  DARK_LAUNCH(KID_GEMM, st, k_gemm, dim3((unsigned)blocks), dim3(256), 0, g);
+  // persistent workgroups, four per CU
+  const unsigned grid = (unsigned)(blocks < 1024 ? blocks : 1024);
+  DARK_LAUNCH(KID_GEMM, st, k_gemm, dim3(grid), dim3(256), 0, g, (int)blocks);
   return DARK_OK;
 }
 
