@@ -238,9 +238,13 @@ __global__ __launch_bounds__(256, 4) void k_gemm(Gemm g, int total_tiles) {
       gemm_fetch(rb, modeB, f.B, g.sBn, g.sBk, f.n0, f.Ne, fk, f.Ke, tid);
     }
     __syncthreads();
+    // a wave whose 32 x 32 block lies outside the matrix (the 65th column of [V|1] opens a tile of its own)
+    // leaves the matrix pipe to the other workgroups of the CU
+    if (cur.m0 + 32 * wm < cur.Me && cur.n0 + 32 * wn < cur.Ne) {
 #pragma unroll
-    for (int kk = 0; kk < GK; kk += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][kk + hf][32 * wm + l32], Bs[buf][kk + hf][32 * wn + l32], acc, 0, 0, 0);
+      for (int kk = 0; kk < GK; kk += 2)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[buf][kk + hf][32 * wm + l32], Bs[buf][kk + hf][32 * wn + l32], acc, 0, 0, 0);
+    }
     buf ^= 1;
     if (!last) {
       k0 += GK;
@@ -384,13 +388,13 @@ __global__ void k_sum_slices(const float* __restrict__ in, float* __restrict__ o
 
 // out[row][c] = ND[row][c] / ND[row][dv]
 template <typename T>
-__global__ void k_finish(const float* __restrict__ ND, T* __restrict__ out, long long rows, int dv) {
+__global__ void k_finish(const float* __restrict__ ND, T* __restrict__ out, long long rows, int dv, int ld) {
   long long total = rows * dv;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
     long long row = i / dv;
     int c = (int)(i % dv);
-    const float* nd = ND + row * (dv + 1);
+    const float* nd = ND + row * ld;
     store_from_f32(out, i, nd[c] / nd[dv]);
   }
 }
@@ -423,13 +427,13 @@ __global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long lo
 // Backward, per row (one wave): from ND = [N | D] and G = dOut,
 //   dN = G / D,  dD = -(G . out) / D  with out = N / D;  written as dND = [dN | dD].
 __global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const float* __restrict__ G,
-                                             float* __restrict__ dND, long long rows, int dv) {
+                                             float* __restrict__ dND, long long rows, int dv, int ld) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
-  const float* nd = ND + row * (dv + 1);
+  const float* nd = ND + row * ld;
   const float* gp = G + row * dv;
-  float* o = dND + row * (dv + 1);
+  float* o = dND + row * ld;
   float invD = 1.f / nd[dv];
   float dot = 0.f;
   for (int c = lane; c < dv; c += kWave) {
@@ -635,6 +639,10 @@ dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const flo
 // ===========================================================================
 namespace {
 
+// [V|1], [N|D], their gradients and the states have dv + 1 columns; their rows are padded to a multiple of
+// four floats so that the GEMM can fetch them with 16-byte loads (the padding is never read as data).
+inline int padded_ld(int cols) { return (cols + 3) & ~3; }
+
 struct AttnBufs {
   float* As;
   FeatBufs q, k;
@@ -649,7 +657,7 @@ struct AttnBufs {
 void plan_attn(const Problem& pb, Arena& ar, bool causal, bool keep_xt, AttnBufs& b) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
-  const int dv1 = p.dv + 1;
+  const int ldv = padded_ld(p.dv + 1);
   const bool conv = p.io_dtype == DARK_BF16;
   b.As = ar.take<float>((size_t)p.H * p.m * p.d);
   b.q.Xf = conv ? ar.take<float>((size_t)rows * p.d) : nullptr;
@@ -662,17 +670,17 @@ void plan_attn(const Problem& pb, Arena& ar, bool causal, bool keep_xt, AttnBufs
   b.k.rowmax = ar.take<float>((size_t)rows);
   b.q.headmax = b.k.headmax = nullptr;
   b.q.colmax = b.k.colmax = ar.take<float>((size_t)pb.BH() * p.m);
-  b.Vx = ar.take<float>((size_t)rows * dv1);
-  b.ND = ar.take<float>((size_t)rows * dv1);
+  b.Vx = ar.take<float>((size_t)rows * ldv);
+  b.ND = ar.take<float>((size_t)rows * ldv);
   b.P = (p.L + slice_len(pb) - 1) / slice_len(pb);
   b.nchunk = (p.L + pb.chunk - 1) / pb.chunk;
   if (causal) {
     b.part = nullptr;
-    b.SZ = ar.take<float>((size_t)pb.BH() * b.nchunk * p.m * dv1);
+    b.SZ = ar.take<float>((size_t)pb.BH() * b.nchunk * p.m * ldv);
     b.Pm = ar.take<float>((size_t)pb.BH() * b.nchunk * pb.chunk * pb.chunk);
   } else {
-    b.part = ar.take<float>((size_t)pb.BH() * b.P * p.m * dv1);
-    b.SZ = ar.take<float>((size_t)pb.BH() * p.m * dv1);
+    b.part = ar.take<float>((size_t)pb.BH() * b.P * p.m * ldv);
+    b.SZ = ar.take<float>((size_t)pb.BH() * p.m * ldv);
     b.Pm = nullptr;
   }
 }
@@ -684,16 +692,16 @@ inline void bhl(long long& s0, long long& s1, long long& s2, const dark_params& 
   s2 = (long long)piece * cols;
 }
 
-// States: per piece (slice or chunk) of the sequence, Phi_piece^T X_piece  ->  dst[bh][piece][mm][nn].
+// States: per piece (slice or chunk) of the sequence, Phi_piece^T X_piece  ->  dst[bh][piece][mm][ldd] (nn columns used).
 dark_status piece_states(const Problem& pb, const float* Phi, int mm, const float* X, int nn, int ldx, float* dst,
-                         int piece, int npiece, float beta) {
+                         int ldd, int piece, int npiece, float beta) {
   const dark_params& p = pb.p;
   Gemm g = gemm_base(Phi, X, dst, mm, nn, piece);
-  g.sAm = 1; g.sAk = mm; g.sBk = ldx; g.sBn = 1; g.sCm = nn; g.sCn = 1;
+  g.sAm = 1; g.sAk = mm; g.sBk = ldx; g.sBn = 1; g.sCm = ldd; g.sCn = 1;
   g.nb0 = p.B; g.nb1 = p.H; g.nb2 = npiece;
   bhl(g.sA0, g.sA1, g.sA2, p, mm, piece);
   bhl(g.sB0, g.sB1, g.sB2, p, ldx, piece);
-  g.sC2 = (long long)mm * nn;
+  g.sC2 = (long long)mm * ldd;
   g.sC1 = g.sC2 * npiece;
   g.sC0 = g.sC1 * p.H;
   g.klim = p.L; g.kstep = piece;
@@ -762,7 +770,7 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
                          const float* M, const float* W) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
-  const int dv1 = p.dv + 1;
+  const int dv1 = p.dv + 1, ldv = padded_ld(dv1);
   if (p.io_dtype == DARK_BF16) {
     DARK_TRY(to_f32(pb, Q, b.q.Xf, rows, p.d, p.d, 0));
     DARK_TRY(to_f32(pb, K, b.k.Xf, rows, p.d, p.d, 0));
@@ -770,7 +778,7 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
     b.q.Xf = const_cast<float*>(static_cast<const float*>(Q));
     b.k.Xf = const_cast<float*>(static_cast<const float*>(K));
   }
-  DARK_TRY(to_f32(pb, V, b.Vx, rows, p.dv, dv1, 1));
+  DARK_TRY(to_f32(pb, V, b.Vx, rows, p.dv, ldv, 1));
   DARK_TRY(make_As(pb, M, W, b.As));
   // Keys first: phi_K,lj = exp(logit_lj - c_j), c_j the per-feature maximum over the head.  The
   // queries add c_j back (phi_Q,ij = exp(logit_ij + c_j - rowmax_i)), so every product
@@ -779,25 +787,25 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
   DARK_TRY(exp_inplace(pb, b.k, STAB_KEY_FEATURE));
   DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax));
   DARK_TRY(exp_inplace(pb, b.q, STAB_QUERY_ROW));
-  const long long st_elems = (long long)p.m * dv1;
+  const long long st_elems = (long long)p.m * ldv;
   if (!causal) {
     // [S|z] = Phi_K^T [V|1]: per-slice partial states, then a fixed-order sum (Section 2: K'^T V first).
-    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, dv1, b.part, slice_len(pb), b.P, 0.f));
+    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, ldv, b.part, ldv, slice_len(pb), b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.part, b.SZ,
                 pb.BH(), b.P, st_elems, st_elems * b.P, st_elems);
     // [N|D] = Phi_Q [S|z]   (then left-multiplying by Q')
-    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, dv1, false, false, st_elems, b.ND, dv1, dv1, p.L, 1, 1.f,
+    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, ldv, false, false, st_elems, b.ND, dv1, ldv, p.L, 1, 1.f,
                               0.f));
   } else {
     const int C = pb.chunk;
-    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, dv1, b.SZ, C, b.nchunk, 0.f));
+    DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, ldv, b.SZ, ldv, C, b.nchunk, 0.f));
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.SZ, pb.BH(), b.nchunk,
                 st_elems, 0);
     // inter-chunk: Phi_Q,c [S|z]_{<c};  intra-chunk: tril(Phi_Q,c Phi_K,c^T) [V_c|1]
-    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, dv1, false, true, st_elems, b.ND, dv1, dv1, C, b.nchunk,
+    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, ldv, false, true, st_elems, b.ND, dv1, ldv, C, b.nchunk,
                               1.f, 0.f));
     DARK_TRY(chunk_tiles(pb, b.q.Phi, p.m, b.k.Phi, p.m, p.m, b.Pm));
-    DARK_TRY(tile_times_rows(pb, b.Pm, false, b.Vx, dv1, b.ND, dv1, dv1));
+    DARK_TRY(tile_times_rows(pb, b.Pm, false, b.Vx, ldv, b.ND, dv1, ldv));
   }
   return DARK_OK;
 }
@@ -814,10 +822,10 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
   const long long rows = pb.rows();
   if (pb.p.out_dtype == DARK_BF16)
     DARK_LAUNCH(KID_FINISH, pb.st, k_finish<__hip_bfloat16>, dim3(grid_for(rows * pb.p.dv)), dim3(256), 0, b.ND,
-                (__hip_bfloat16*)out, rows, pb.p.dv);
+                (__hip_bfloat16*)out, rows, pb.p.dv, padded_ld(pb.p.dv + 1));
   else
     DARK_LAUNCH(KID_FINISH, pb.st, k_finish<float>, dim3(grid_for(rows * pb.p.dv)), dim3(256), 0, b.ND, (float*)out,
-                rows, pb.p.dv);
+                rows, pb.p.dv, padded_ld(pb.p.dv + 1));
   return DARK_OK;
 }
 
@@ -838,13 +846,13 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
                          float* dM) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
-  const int dv1 = p.dv + 1;
+  const int dv1 = p.dv + 1, ldv = padded_ld(dv1);
   const int C = pb.chunk;
   AttnBufs b{};
   plan_attn(pb, ar, causal, true, b);
-  const long long st_elems = (long long)p.m * dv1;
+  const long long st_elems = (long long)p.m * ldv;
   float* Gf = p.io_dtype == DARK_BF16 ? ar.take<float>((size_t)rows * p.dv) : nullptr;
-  float* dND = ar.take<float>((size_t)rows * dv1);
+  float* dND = ar.take<float>((size_t)rows * ldv);
   float* dPq = ar.take<float>((size_t)rows * p.m);
   float* dPk = ar.take<float>((size_t)rows * p.m);
   float* R = ar.take<float>((size_t)pb.BH() * (causal ? b.nchunk : 1) * st_elems);
@@ -862,32 +870,32 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
     DARK_TRY(to_f32(pb, dOut, Gf, rows, p.dv, p.dv, 0));
   else
     Gf = const_cast<float*>(static_cast<const float*>(dOut));
-  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND, Gf, dND, rows, p.dv);
+  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND, Gf, dND, rows, p.dv, ldv);
   float* dVo = dV;
 
   if (!causal) {
-    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, dv1, Rpart, slice_len(pb), b.P, 0.f));
+    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, ldv, Rpart, ldv, slice_len(pb), b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, Rpart, R,
                 pb.BH(), b.P, st_elems, st_elems * b.P, st_elems);
-    DARK_TRY(rows_times_state(pb, dND, dv1, dv1, b.SZ, dv1, true, false, st_elems, dPq, p.m, p.m, p.L, 1, 1.f, 0.f));
-    DARK_TRY(rows_times_state(pb, b.Vx, dv1, dv1, R, dv1, true, false, st_elems, dPk, p.m, p.m, p.L, 1, 1.f, 0.f));
-    if (dV) DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, dv1, false, false, st_elems, dVo, p.dv, p.dv, p.L, 1,
+    DARK_TRY(rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, false, st_elems, dPq, p.m, p.m, p.L, 1, 1.f, 0.f));
+    DARK_TRY(rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, false, st_elems, dPk, p.m, p.m, p.L, 1, 1.f, 0.f));
+    if (dV) DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, false, st_elems, dVo, p.dv, p.dv, p.L, 1,
                                       1.f, 0.f));
   } else {
-    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, dv1, R, C, b.nchunk, 0.f));
+    DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, ldv, R, ldv, C, b.nchunk, 0.f));
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, R, pb.BH(), b.nchunk,
                 st_elems, 1);
-    DARK_TRY(chunk_tiles(pb, dND, dv1, b.Vx, dv1, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
+    DARK_TRY(chunk_tiles(pb, dND, ldv, b.Vx, ldv, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
     // b.Pm = tril(Phi_Q Phi_K^T) is left over from forward_core.
-    DARK_TRY(rows_times_state(pb, dND, dv1, dv1, b.SZ, dv1, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,
+    DARK_TRY(rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,
                               0.f));
     DARK_TRY(tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m));
-    DARK_TRY(rows_times_state(pb, b.Vx, dv1, dv1, R, dv1, true, true, st_elems, dPk, p.m, p.m, C, b.nchunk, 1.f, 0.f));
+    DARK_TRY(rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, true, st_elems, dPk, p.m, p.m, C, b.nchunk, 1.f, 0.f));
     DARK_TRY(tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m));
     if (dV) {
-      DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, dv1, false, true, st_elems, dVo, p.dv, p.dv, C, b.nchunk,
+      DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, true, st_elems, dVo, p.dv, p.dv, C, b.nchunk,
                                 1.f, 0.f));
-      DARK_TRY(tile_times_rows(pb, b.Pm, true, dND, dv1, dVo, p.dv, p.dv));
+      DARK_TRY(tile_times_rows(pb, b.Pm, true, dND, ldv, dVo, p.dv, p.dv));
     }
   }
   // dlogit (in dPq / dPk), dXt (in Xt buffers)
@@ -916,12 +924,12 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   }
   if (dM) {
     const int SL = slice_len(pb);
-    DARK_TRY(piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, SL, b.P, 0.f));
-    DARK_TRY(piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, SL, b.P, 1.f));
+    DARK_TRY(piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 0.f));
+    DARK_TRY(piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 1.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * as_elems)), dim3(256), 0, Tpart, T,
                 pb.BH(), b.P, as_elems, as_elems * b.P, as_elems);
-    DARK_TRY(piece_states(pb, b.q.Xt, p.r, b.q.Xf, p.d, p.d, T2part, SL, b.P, 0.f));
-    DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, SL, b.P, 1.f));
+    DARK_TRY(piece_states(pb, b.q.Xt, p.r, b.q.Xf, p.d, p.d, T2part, p.d, SL, b.P, 0.f));
+    DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, p.d, SL, b.P, 1.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * m_elems)), dim3(256), 0, T2part, T2,
                 pb.BH(), b.P, m_elems, m_elems * b.P, m_elems);
     // T2_bh = alpha * W_h^T T_bh + alpha * T2_bh
