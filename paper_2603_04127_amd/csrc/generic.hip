@@ -64,6 +64,7 @@ struct Gemm {
   float alpha, beta;
   int mask;
   int mlim, mstep, nlim, nstep, klim, kstep;
+  int modeA, modeB;  // GL_* fetch modes, set by run_gemm
 };
 
 constexpr int GT = 64;  // C tile edge
@@ -71,86 +72,70 @@ constexpr int GK = 32;  // K step
 
 // How one operand tile (64 x GK, element (x, k) at P[x * sx + k * sk]) is fetched: 16-byte loads
 // along k or along x when that index is contiguous and everything is 16-byte aligned, else scalars.
+// A 16-byte load that straddles the matrix edge is issued whole and its tail zeroed afterwards, so the
+// vector modes also require that the contiguous extent, rounded up to four, fits under every other
+// stride of the operand (rows padded to a multiple of four floats): the over-read then stays inside
+// the row's own span.
 enum { GL_SCALAR = 0, GL_VEC_K = 1, GL_VEC_X = 2 };
 
-__device__ inline int gemm_load_mode(const float* P, long long sx, long long sk, long long s0, long long s1,
-                                     long long s2) {
+inline int gemm_load_mode(const float* P, long long sx, long long sk, int X, int K, long long s0, long long s1,
+                          long long s2) {
   const bool al = ((reinterpret_cast<uintptr_t>(P) | (uintptr_t)(s0 * 4) | (uintptr_t)(s1 * 4) | (uintptr_t)(s2 * 4)) & 15) == 0;
-  if (al && sk == 1 && (sx & 3) == 0) return GL_VEC_K;
-  if (al && sx == 1 && (sk & 3) == 0) return GL_VEC_X;
+  if (!al) return GL_SCALAR;
+  auto fits = [&](int extent, long long other) {
+    const long long up = ((long long)extent + 3) & ~3LL;
+    for (long long st : {other, s0, s1, s2})
+      if (st != 0 && st < up) return false;
+    return true;
+  };
+  if (sk == 1 && (sx & 3) == 0 && fits(K, sx)) return GL_VEC_K;
+  if (sx == 1 && (sk & 3) == 0 && fits(X, sk)) return GL_VEC_X;
   return GL_SCALAR;
 }
 
-// Fetches this thread's 8 elements of an operand tile into registers (zero outside the matrix).
-__device__ inline void gemm_fetch(float (&r)[8], int mode, const float* P, long long sx, long long sk, int x0, int Xe,
-                                  int k0, int Ke, int tid) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
+// A thread's fetch of the register-blocked kernel: two groups of four consecutive floats (q[u][j])
+// and how many of each lie inside the matrix (n[u]).  A group is fetched with one 16-byte load
+// whenever its first element is inside (see gemm_load_mode for why that is safe) and the elements
+// past the edge are zeroed before the group is used, so a fetch is a single predicated load: no
+// second path whose loads would have to wait for the first to return.
+// The groups stay 4-vectors from the load to the park: scalarised, the register allocator would load
+// into a spare tuple and copy, which again means waiting for the load right behind its issue.
+typedef float quad_t __attribute__((ext_vector_type(4)));
+struct Fetch {
+  quad_t q[2];
+  int n[2];
+};
+
+__device__ __forceinline__ void load_quad(Fetch& f, int u, const float* p, int n) {
+  quad_t x = {0.f, 0.f, 0.f, 0.f};
+  if (n > 0) x = *reinterpret_cast<const quad_t*>(p);
+  f.q[u] = x;
+  f.n[u] = n;
+}
+
+// Scalar fetch of the general kernel: this thread's 8 elements of an operand tile (64 x GK, element
+// (x, k) at P[x * sx + k * sk]) into registers, zero outside the matrix or when `on` is false.
+// Consecutive threads walk the smaller stride.  Every element is one predicated load into a register
+// of its own, so all of them are in flight together.
+__device__ __forceinline__ void gemm_fetch(float (&r)[8], const float* P, long long sx, long long sk, int x0, int Xe, int k0,
+                                  int Ke, int tid, bool on) {
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int idx = tid + 256 * t;
-    if (mode == GL_VEC_K) {
-      const int k4 = idx % (GK / 4), x = idx / (GK / 4);
-      const int gx = x0 + x, gk = k0 + 4 * k4;
-      if (gx < Xe && gk + 3 < Ke) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(P + gx * sx + gk);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[4 * t + j] = v[j];
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[4 * t + j] = (gx < Xe && gk + j < Ke) ? P[gx * sx + gk + j] : 0.f;
-      }
-    } else if (mode == GL_VEC_X) {
-      const int x4 = idx % (GT / 4), k = idx / (GT / 4);
-      const int gx = x0 + 4 * x4, gk = k0 + k;
-      if (gk < Ke && gx + 3 < Xe) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(P + gx + gk * sk);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[4 * t + j] = v[j];
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r[4 * t + j] = (gk < Ke && gx + j < Xe) ? P[gx + j + gk * sk] : 0.f;
-      }
-    } else {
-      // consecutive threads walk the smaller stride
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int e = tid + 256 * (4 * t + j);
-        int x, k;
-        if (sk <= sx) {
-          k = e % GK;
-          x = e / GK;
-        } else {
-          x = e % GT;
-          k = e / GT;
-        }
-        const int gx = x0 + x, gk = k0 + k;
-        r[4 * t + j] = (gx < Xe && gk < Ke) ? P[gx * sx + gk * sk] : 0.f;
-      }
-    }
+  for (int i = 0; i < 8; ++i) {
+    const int e = tid + 256 * i;
+    const int k = sk <= sx ? e % GK : e / GT;
+    const int x = sk <= sx ? e / GK : e % GT;
+    const int gx = x0 + x, gk = k0 + k;
+    r[i] = (on && gx < Xe && gk < Ke) ? P[gx * sx + gk * sk] : 0.f;
   }
 }
 
 // Parks the fetched elements in the LDS tile T[k][x].
-__device__ inline void gemm_park(float (*T)[GT + 4], const float (&r)[8], int mode, long long sx, long long sk, int tid) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void gemm_park(float (*T)[GT + 4], const float (&r)[8], long long sx, long long sk, int tid) {
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int idx = tid + 256 * t;
-    if (mode == GL_VEC_K) {
-      const int k4 = idx % (GK / 4), x = idx / (GK / 4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) T[4 * k4 + j][x] = r[4 * t + j];
-    } else if (mode == GL_VEC_X) {
-      const int x4 = idx % (GT / 4), k = idx / (GT / 4);
-      *reinterpret_cast<f32x4*>(&T[k][4 * x4]) = f32x4{r[4 * t], r[4 * t + 1], r[4 * t + 2], r[4 * t + 3]};
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int e = tid + 256 * (4 * t + j);
-        if (sk <= sx) T[e % GK][e / GK] = r[4 * t + j];
-        else T[e / GT][e % GT] = r[4 * t + j];
-      }
-    }
+  for (int i = 0; i < 8; ++i) {
+    const int e = tid + 256 * i;
+    if (sk <= sx) T[e % GK][e / GK] = r[i];
+    else T[e / GT][e % GT] = r[i];
   }
 }
 
@@ -162,8 +147,22 @@ struct GemmTile {
   int m0, n0, Me, Ne, Ke;
 };
 
+// Field by field, so that both tiles stay in scalar registers.
+__device__ __forceinline__ GemmTile pick_tile(bool second, const GemmTile& a, const GemmTile& b) {
+  GemmTile o;
+  o.A = second ? b.A : a.A;
+  o.B = second ? b.B : a.B;
+  o.C = second ? b.C : a.C;
+  o.m0 = second ? b.m0 : a.m0;
+  o.n0 = second ? b.n0 : a.n0;
+  o.Me = second ? b.Me : a.Me;
+  o.Ne = second ? b.Ne : a.Ne;
+  o.Ke = second ? b.Ke : a.Ke;
+  return o;
+}
+
 // Tile t -> its operands and effective sizes; false if the tile lies outside the (ragged) problem.
-__device__ inline bool gemm_tile(const Gemm& g, int t, int tilesM, int tilesN, GemmTile& o) {
+__device__ __forceinline__ bool gemm_tile(const Gemm& g, int t, int tilesM, int tilesN, int tile_m, int tile_n, GemmTile& o) {
   const int tn = t % tilesN;
   t /= tilesN;
   const int tm = t % tilesM;
@@ -178,12 +177,59 @@ __device__ inline bool gemm_tile(const Gemm& g, int t, int tilesM, int tilesN, G
   if (g.mlim > 0) o.Me = max(0, min(g.M, g.mlim - b2 * g.mstep));
   if (g.nlim > 0) o.Ne = max(0, min(g.N, g.nlim - b2 * g.nstep));
   if (g.klim > 0) o.Ke = max(0, min(g.K, g.klim - b2 * g.kstep));
-  o.m0 = tm * GT;
-  o.n0 = tn * GT;
+  o.m0 = tm * tile_m;
+  o.n0 = tn * tile_n;
   o.A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
   o.B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
   o.C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
   return o.m0 < o.Me && o.n0 < o.Ne;
+}
+
+// Epilogue of one 32 x 32 accumulator block whose corner is (bm0, bn0): this lane holds column
+// bn0 + l32, rows bm0 + 4 hf + 8 (v / 4) + v % 4.  The old values of C (beta != 0) are fetched first,
+// all in flight together, then everything is stored; the offset is laundered in between so that the
+// sixteen addresses are recomputed rather than kept in registers.  A block that lies wholly inside
+// the matrix takes a path without per-element branches: behind a branch the compiler can no longer
+// count the stores in flight and would wait for each one to finish.  Clears the accumulator.
+typedef float gemm_acc_t __attribute__((ext_vector_type(16)));
+template <bool kFull, bool kBeta>
+__device__ __forceinline__ void gemm_store_block_as(const Gemm& g, float* C, int m_first, int Me, int gn, int Ne,
+                                                    gemm_acc_t& acc) {
+  long long off = m_first * g.sCm + gn * g.sCn;
+  const float* cb = C + off;
+  const bool col = gn < Ne;
+  float cv[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int r = 8 * (v / 4) + (v % 4);
+    cv[v] = kBeta ? ((kFull || (col && m_first + r < Me)) ? cb[r * g.sCm] : 0.f) : 0.f;
+  }
+  asm volatile("" : "+v"(off));
+  float* cs = C + off;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int r = 8 * (v / 4) + (v % 4);
+    if (kFull || (col && m_first + r < Me)) {
+      float x = g.alpha * acc[v];
+      if (kBeta) x += g.beta * cv[v];
+      if (g.mask == 1 && gn > m_first + r) x = 0.f;
+      cs[r * g.sCm] = x;
+    }
+    acc[v] = 0.f;
+  }
+}
+
+__device__ __forceinline__ void gemm_store_block(const Gemm& g, float* C, int bm0, int hf, int Me, int bn0, int l32,
+                                                 int Ne, gemm_acc_t& acc) {
+  const bool full = bm0 + 32 <= Me && bn0 + 32 <= Ne;
+  const int m_first = bm0 + 4 * hf, gn = bn0 + l32;
+  if (g.beta != 0.f) {
+    if (full) gemm_store_block_as<true, true>(g, C, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, true>(g, C, m_first, Me, gn, Ne, acc);
+  } else {
+    if (full) gemm_store_block_as<true, false>(g, C, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, false>(g, C, m_first, Me, gn, Ne, acc);
+  }
 }
 
 // Persistent workgroups: each walks the output tiles blockIdx.x, blockIdx.x + gridDim.x, ... and treats
@@ -191,13 +237,11 @@ __device__ inline bool gemm_tile(const Gemm& g, int t, int tilesM, int tilesN, G
 // s + 1 (of the same tile, or the first step of the next tile) are on their way into registers, and
 // they are parked in the other buffer, so there is one barrier per step and a tile's stores overlap the
 // next tile's loads.
-__global__ __launch_bounds__(256, 4) void k_gemm(Gemm g, int total_tiles) {
+__global__ __launch_bounds__(256, 3) void k_gemm(Gemm g, int total_tiles) {
   __shared__ __attribute__((aligned(16))) float As[2][GK][GT + 4];
   __shared__ __attribute__((aligned(16))) float Bs[2][GK][GT + 4];
   const int tilesN = (g.N + GT - 1) / GT;
   const int tilesM = (g.M + GT - 1) / GT;
-  const int modeA = gemm_load_mode(g.A, g.sAm, g.sAk, g.sA0, g.sA1, g.sA2);
-  const int modeB = gemm_load_mode(g.B, g.sBn, g.sBk, g.sB0, g.sB1, g.sB2);
 
   const int tid = threadIdx.x;
   // Wave w owns the 32 x 32 block (w / 2, w % 2) of the tile and accumulates it with fp32 MFMAs
@@ -209,33 +253,34 @@ __global__ __launch_bounds__(256, 4) void k_gemm(Gemm g, int total_tiles) {
 
   GemmTile cur, nxt;
   int t = blockIdx.x;
-  while (t < total_tiles && !gemm_tile(g, t, tilesM, tilesN, cur)) t += gridDim.x;
+  while (t < total_tiles && !gemm_tile(g, t, tilesM, tilesN, GT, GT, cur)) t += gridDim.x;
   if (t >= total_tiles) return;
+  nxt = cur;
   // Every tile has at least one step (an empty contraction fetches zeros), so the stream is uniform.
   float ra[8], rb[8];
-  gemm_fetch(ra, modeA, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, 0, cur.Ke, tid);
-  gemm_fetch(rb, modeB, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, 0, cur.Ke, tid);
+  gemm_fetch(ra, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, 0, cur.Ke, tid, true);
+  gemm_fetch(rb, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, 0, cur.Ke, tid, true);
   int buf = 0, k0 = 0;
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   while (true) {
-    gemm_park(As[buf], ra, modeA, g.sAm, g.sAk, tid);
-    gemm_park(Bs[buf], rb, modeB, g.sBn, g.sBk, tid);
+    gemm_park(As[buf], ra, g.sAm, g.sAk, tid);
+    gemm_park(Bs[buf], rb, g.sBn, g.sBk, tid);
     // what to fetch while this step is multiplied: the tile's next step, or the next tile's first
     const bool last = k0 + GK >= cur.Ke;
     int tn = t;
     bool more = true;
     if (last) {
       tn = t + gridDim.x;
-      while (tn < total_tiles && !gemm_tile(g, tn, tilesM, tilesN, nxt)) tn += gridDim.x;
+      while (tn < total_tiles && !gemm_tile(g, tn, tilesM, tilesN, GT, GT, nxt)) tn += gridDim.x;
       more = tn < total_tiles;
     }
-    if (more) {
-      const GemmTile& f = last ? nxt : cur;
+    {
+      const GemmTile f = pick_tile(last, cur, nxt);
       const int fk = last ? 0 : k0 + GK;
-      gemm_fetch(ra, modeA, f.A, g.sAm, g.sAk, f.m0, f.Me, fk, f.Ke, tid);
-      gemm_fetch(rb, modeB, f.B, g.sBn, g.sBk, f.n0, f.Ne, fk, f.Ke, tid);
+      gemm_fetch(ra, f.A, g.sAm, g.sAk, f.m0, f.Me, fk, f.Ke, tid, more);
+      gemm_fetch(rb, f.B, g.sBn, g.sBk, f.n0, f.Ne, fk, f.Ke, tid, more);
     }
     __syncthreads();
     // a wave whose 32 x 32 block lies outside the matrix (the 65th column of [V|1] opens a tile of its own)
@@ -250,24 +295,202 @@ __global__ __launch_bounds__(256, 4) void k_gemm(Gemm g, int total_tiles) {
       k0 += GK;
       continue;
     }
-    const int gn = cur.n0 + 32 * wn + l32;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int gm = cur.m0 + 32 * wm + 8 * (v / 4) + 4 * hf + (v % 4);
-      if (gm < cur.Me && gn < cur.Ne) {
-        float* c = cur.C + gm * g.sCm + gn * g.sCn;
-        float x = g.alpha * acc[v];
-        if (g.beta != 0.f) x += g.beta * (*c);
-        if (g.mask == 1 && gn > gm) x = 0.f;
-        *c = x;
-      }
-      acc[v] = 0.f;
-    }
+    gemm_store_block(g, cur.C, cur.m0 + 32 * wm, hf, cur.Me, cur.n0 + 32 * wn, l32, cur.Ne, acc);
     if (!more) break;
     cur = nxt;
     t = tn;
     k0 = 0;
   }
+}
+
+// ---------------------------------------------------------------------------
+// Register-blocked variant of the same GEMM for operands that 16-byte loads can fetch (both in a
+// GL_VEC_* mode).  The workgroup's four waves form a WM x WN grid; each wave accumulates BM x BN blocks
+// of 32 x 32, so one operand fragment read from LDS feeds BN (or BM) MFMAs and a fetched element is
+// reused over a tile of (32 BM WM) x (32 BN WN) instead of 64 x 64.
+// ---------------------------------------------------------------------------
+constexpr int RK = 16;  // K step
+
+// LDS image of the K step of an operand tile with TX rows (A) or columns (B): element (x, k),
+// k = 8 g + hf + 2 s, sits at v[g][hf][x][s].  A lane of half hf feeds k = hf, hf + 2, hf + 4, hf + 6 of
+// a group of eight to four consecutive 32x32x2 MFMAs, and finds them in one 16-byte read.
+template <int TX>
+struct RbTile {
+  float v[RK / 8][2][TX + 1][4];
+};
+
+// How the threads split an operand tile's K step (TX x RK elements, two groups of four per thread).
+// along_x (x contiguous): a thread takes four neighbouring x at NS values of s of one (g, hf);
+// else (k contiguous): a thread takes the eight k of one group g for one x.
+template <int TX>
+struct RbSplit {
+  static constexpr int combos = (TX / 4) * (RK / 8) * 2;
+  static constexpr int split = 256 / combos >= 4 ? 4 : (256 / combos >= 2 ? 2 : 1);
+  static constexpr int NS = 4 / split;
+  static constexpr int items = TX * (RK / 8);
+  static_assert(NS <= 2 && items <= 256, "a thread holds at most eight elements");
+};
+
+// What a thread fetches of every K step of an operand, fixed for the whole launch: for each of its two
+// groups the position along the contiguous index (c) and along the strided one (s), relative to the
+// first element of the tile's K step, the element offset from there, and whether the group exists.
+struct RbLane {
+  long long off[2];
+  int c[2], s[2];
+  bool act[2];
+};
+
+template <int TX>
+__device__ __forceinline__ RbLane rb_lane(bool along_x, long long sx, long long sk, int tid) {
+  typedef RbSplit<TX> S;
+  const int cb = tid % S::combos, sh = tid / S::combos;
+  const int xq = cb % (TX / 4), ghf = cb / (TX / 4);
+  const int gq = tid % (RK / 8), xk = tid / (RK / 8);
+  RbLane L;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    L.c[u] = along_x ? 4 * xq : 8 * gq + 4 * u;
+    L.s[u] = along_x ? 8 * (ghf / 2) + (ghf % 2) + 2 * (S::NS * sh + u) : xk;
+    L.act[u] = along_x ? (sh < S::split && u < S::NS) : tid < S::items;
+    L.off[u] = L.s[u] * (along_x ? sk : sx) + L.c[u];
+  }
+  return L;
+}
+
+// This thread's share of an operand tile's K step, into registers (zero outside the matrix or when
+// `on` is false).  Both orientations run through the same two loads: only the addresses differ.
+// Everything but the last few operations is uniform and stays on the scalar unit.  Returns whether
+// the step is cut by the matrix edge inside a group of four (then the park has to zero the tails).
+template <int TX>
+__device__ __forceinline__ bool rb_fetch(Fetch& r, const RbLane& L, bool along_x, const float* P, long long sx, long long sk,
+                                int x0, int Xe, int k0, int Ke, bool on) {
+  const float* base = P + x0 * (along_x ? 1LL : sx) + k0 * (along_x ? sk : 1LL);
+  const int cleft = along_x ? Xe - x0 : Ke - k0;          // extent left along the contiguous index
+  const int sleft = on ? (along_x ? Ke - k0 : Xe - x0) : 0;  // and along the strided one
+#pragma unroll
+  for (int u = 0; u < 2; ++u) load_quad(r, u, base + L.off[u], (L.act[u] && L.s[u] < sleft) ? cleft - L.c[u] : 0);
+  return (cleft & 3) != 0 && cleft < (along_x ? TX : RK);
+}
+
+// Zeroes the elements past the matrix edge of a fetched pair of groups.
+__device__ __forceinline__ void trim_fetch(Fetch& r) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r.q[u][j] = j < r.n[u] ? r.q[u][j] : 0.f;
+}
+
+template <int TX>
+__device__ __forceinline__ void rb_park(RbTile<TX>& T, const Fetch& r, bool along_x, int tid) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef RbSplit<TX> S;
+  if (along_x) {
+    const int c = tid % S::combos, sh = tid / S::combos;
+    if (sh < S::split) {
+      const int xq = c % (TX / 4), ghf = c / (TX / 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float* dst = &T.v[ghf / 2][ghf % 2][4 * xq + j][S::NS * sh];
+        if (S::NS == 2) *reinterpret_cast<f32x2*>(dst) = f32x2{r.q[0][j], r.q[1][j]};
+        else *dst = r.q[0][j];
+      }
+    }
+  } else {
+    if (tid < S::items) {
+      const int gq = tid % (RK / 8), x = tid / (RK / 8);
+      *reinterpret_cast<f32x4*>(&T.v[gq][0][x][0]) = f32x4{r.q[0][0], r.q[0][2], r.q[1][0], r.q[1][2]};
+      *reinterpret_cast<f32x4*>(&T.v[gq][1][x][0]) = f32x4{r.q[0][1], r.q[0][3], r.q[1][1], r.q[1][3]};
+    }
+  }
+}
+
+template <int WM, int WN, int BM, int BN>
+struct RbShape {
+  static constexpr int TM = 32 * BM * WM, TN = 32 * BN * WN;
+  static constexpr size_t lds = 2 * (sizeof(RbTile<TM>) + sizeof(RbTile<TN>));
+  static constexpr int per_cu = BM * BN >= 3 ? 3 : 4;  // resident workgroups the registers allow
+};
+
+// One output tile per workgroup (the hardware queue keeps three or four of them on a CU, so one tile's
+// epilogue overlaps its neighbours' products).  The K steps are double-buffered: while step s is
+// multiplied out of one LDS buffer, the elements of step s + 1 are on their way into registers, and they
+// are parked in the other buffer, so there is one barrier per step.  Inside the loop nothing but the
+// step's first-element pointers and remaining extents changes, all of it on the scalar unit.
+template <int WM, int WN, int BM, int BN>
+__global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm_rb(Gemm g) {
+  static_assert(WM * WN == 4, "four waves");
+  constexpr int TM = RbShape<WM, WN, BM, BN>::TM, TN = RbShape<WM, WN, BM, BN>::TN;
+  extern __shared__ __attribute__((aligned(16))) unsigned char rb_smem[];
+  RbTile<TM>* As = reinterpret_cast<RbTile<TM>*>(rb_smem);
+  RbTile<TN>* Bs = reinterpret_cast<RbTile<TN>*>(rb_smem + 2 * sizeof(RbTile<TM>));
+  const bool ax = g.modeA == GL_VEC_X, bx = g.modeB == GL_VEC_X;  // else GL_VEC_K
+
+  GemmTile cur;
+  if (!gemm_tile(g, blockIdx.x, (g.M + TM - 1) / TM, (g.N + TN - 1) / TN, TM, TN, cur)) return;
+
+  typedef float f32x16 __attribute__((ext_vector_type(16)));
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x;
+  const int lane = tid % 64, wv = tid / 64, l32 = lane % 32, hf = lane / 32;
+  const int rbase = 32 * BM * (wv / WN), cbase = 32 * BN * (wv % WN);  // the wave's corner inside the tile
+  const RbLane la = rb_lane<TM>(ax, g.sAm, g.sAk, tid), lb = rb_lane<TN>(bx, g.sBn, g.sBk, tid);
+
+  // which of the wave's blocks do any work: inside the matrix and, for a triangular result, not
+  // wholly above the diagonal
+  bool work[BM][BN];
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int j = 0; j < BN; ++j)
+      work[i][j] = cur.m0 + rbase + 32 * i < cur.Me && cur.n0 + cbase + 32 * j < cur.Ne &&
+                   !(g.mask == 1 && cur.n0 + cbase + 32 * j > cur.m0 + rbase + 32 * i + 31);
+
+  f32x16 acc[BM][BN];
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int j = 0; j < BN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  Fetch ra, rb;
+  bool edge_a = rb_fetch<TM>(ra, la, ax, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, 0, cur.Ke, true);
+  bool edge_b = rb_fetch<TN>(rb, lb, bx, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, 0, cur.Ke, true);
+  int buf = 0;
+  // at least one step, so that an empty contraction still stores beta * C
+  for (int k0 = 0; k0 == 0 || k0 < cur.Ke; k0 += RK) {
+    if (edge_a) trim_fetch(ra);
+    if (edge_b) trim_fetch(rb);
+    rb_park<TM>(As[buf], ra, ax, tid);
+    rb_park<TN>(Bs[buf], rb, bx, tid);
+    const bool more = k0 + RK < cur.Ke;
+    edge_a = rb_fetch<TM>(ra, la, ax, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, k0 + RK, cur.Ke, more);
+    edge_b = rb_fetch<TN>(rb, lb, bx, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, k0 + RK, cur.Ke, more);
+    __syncthreads();
+    const int ng = min(RK / 8, (cur.Ke - k0 + 7) / 8);  // groups of eight k that hold data
+    for (int gq = 0; gq < ng; ++gq) {
+      f32x4 a[BM], b[BN];
+#pragma unroll
+      for (int i = 0; i < BM; ++i) a[i] = *reinterpret_cast<const f32x4*>(&As[buf].v[gq][hf][rbase + 32 * i + l32][0]);
+#pragma unroll
+      for (int j = 0; j < BN; ++j) b[j] = *reinterpret_cast<const f32x4*>(&Bs[buf].v[gq][hf][cbase + 32 * j + l32][0]);
+#pragma unroll
+      for (int i = 0; i < BM; ++i)
+#pragma unroll
+        for (int j = 0; j < BN; ++j)
+          if (work[i][j]) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
+          }
+    }
+    buf ^= 1;
+  }
+#pragma unroll
+  for (int i = 0; i < BM; ++i)
+#pragma unroll
+    for (int j = 0; j < BN; ++j)
+      gemm_store_block(g, cur.C, cur.m0 + rbase + 32 * i, hf, cur.Me, cur.n0 + cbase + 32 * j, l32, cur.Ne, acc[i][j]);
 }
 
 // dst[row][0..cols) = (float)src[row][0..cols);  dst[row][cols] = 1 if ones.
@@ -487,13 +710,46 @@ Gemm gemm_base(const float* A, const float* B, float* C, int M, int N, int K) {
   return g;
 }
 
-dark_status run_gemm(const Gemm& g, hipStream_t st) {
+template <int WM, int WN, int BM, int BN>
+dark_status launch_gemm_rb(const Gemm& g, hipStream_t st) {
+  typedef RbShape<WM, WN, BM, BN> S;
+  static bool granted = false;
+  if (!granted) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_rb<WM, WN, BM, BN>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::lds) != hipSuccess)
+      return DARK_EHIP;
+    granted = true;
+  }
+  const long long blocks = (long long)((g.M + S::TM - 1) / S::TM) * ((g.N + S::TN - 1) / S::TN) * g.nb0 * g.nb1 * g.nb2;
+  if (blocks > 0x7fffffffLL) return DARK_EUNSUPPORTED;
+  DARK_LAUNCH(KID_GEMM, st, (k_gemm_rb<WM, WN, BM, BN>), dim3((unsigned)blocks), dim3(256), S::lds, g);
+  return DARK_OK;
+}
+
+dark_status run_gemm(const Gemm& g_in, hipStream_t st) {
+  if ((long long)g_in.M * g_in.N * g_in.nb0 * g_in.nb1 * g_in.nb2 <= 0) return DARK_OK;
+  Gemm g = g_in;
+  g.modeA = gemm_load_mode(g.A, g.sAm, g.sAk, g.M, g.K, g.sA0, g.sA1, g.sA2);
+  g.modeB = gemm_load_mode(g.B, g.sBn, g.sBk, g.N, g.K, g.sB0, g.sB1, g.sB2);
+  const bool vec = g.modeA != GL_SCALAR && g.modeB != GL_SCALAR;
+  if (vec) {
+    // The largest tile that still gives about as many tiles as the chip holds workgroups.
+    const long long nb = (long long)g.nb0 * g.nb1 * g.nb2;
+    auto enough = [&](int tm, int tn, int per_cu) {
+      const long long tiles = (long long)((g.M + tm - 1) / tm) * ((g.N + tn - 1) / tn) * nb;
+      return 4 * tiles >= 3 * 256LL * per_cu;
+    };
+    if (g.M > 64 && g.N > 96 && enough(128, 128, 3)) return launch_gemm_rb<2, 2, 2, 2>(g, st);
+    if (g.M > 64 && g.N > 64 && g.N <= 96 && enough(128, 96, 3)) return launch_gemm_rb<4, 1, 1, 3>(g, st);
+    if (g.M > 64 && enough(128, 64, 4)) return launch_gemm_rb<2, 2, 2, 1>(g, st);
+    return launch_gemm_rb<2, 2, 1, 1>(g, st);
+  }
   long long tiles = (long long)((g.M + GT - 1) / GT) * ((g.N + GT - 1) / GT);
   long long blocks = tiles * g.nb0 * g.nb1 * g.nb2;
   if (blocks <= 0) return DARK_OK;
   if (blocks > 0x7fffffffLL) return DARK_EUNSUPPORTED;
-  // persistent workgroups, four per CU
-  const unsigned grid = (unsigned)(blocks < 1024 ? blocks : 1024);
+  // persistent workgroups, three per CU
+  const unsigned grid = (unsigned)(blocks < 768 ? blocks : 768);
   DARK_LAUNCH(KID_GEMM, st, k_gemm, dim3(grid), dim3(256), 0, g, (int)blocks);
   return DARK_OK;
 }
