@@ -312,12 +312,16 @@ __global__ __launch_bounds__(256, 3) void k_gemm(Gemm g, int total_tiles) {
 constexpr int RK = 16;  // K step
 
 // LDS image of the K step of an operand tile with TX rows (A) or columns (B): element (x, k),
-// k = 8 g + hf + 2 s, sits at v[g][hf][x][s].  A lane of half hf feeds k = hf, hf + 2, hf + 4, hf + 6 of
-// a group of eight to four consecutive 32x32x2 MFMAs, and finds them in one 16-byte read.
+// k = 8 g + hf + 2 s, sits at v[g][hf][rb_row(x)][s].  A lane of half hf feeds k = hf, hf + 2, hf + 4,
+// hf + 6 of a group of eight to four consecutive 32x32x2 MFMAs, and finds them in one 16-byte read.
+// rb_row rotates the rows of every group of eight by the group's number: the MFMA reads (32
+// consecutive x) still cover eight different 16-byte bank groups per eight lanes, and so do the
+// stores of a thread that fetched along x and therefore holds x = 4 q + j (stride four rows).
 template <int TX>
 struct RbTile {
-  float v[RK / 8][2][TX + 1][4];
+  float v[RK / 8][2][TX + 2][4];
 };
+__device__ __forceinline__ int rb_row(int x) { return (x & ~7) | ((x + ((x >> 3) & 3)) & 7); }
 
 // How the threads split an operand tile's K step (TX x RK elements, two groups of four per thread).
 // along_x (x contiguous): a thread takes four neighbouring x at NS values of s of one (g, hf);
@@ -391,7 +395,7 @@ __device__ __forceinline__ void rb_park(RbTile<TX>& T, const Fetch& r, bool alon
       const int xq = c % (TX / 4), ghf = c / (TX / 4);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        float* dst = &T.v[ghf / 2][ghf % 2][4 * xq + j][S::NS * sh];
+        float* dst = &T.v[ghf / 2][ghf % 2][rb_row(4 * xq + j)][S::NS * sh];
         if (S::NS == 2) *reinterpret_cast<f32x2*>(dst) = f32x2{r.q[0][j], r.q[1][j]};
         else *dst = r.q[0][j];
       }
@@ -399,8 +403,8 @@ __device__ __forceinline__ void rb_park(RbTile<TX>& T, const Fetch& r, bool alon
   } else {
     if (tid < S::items) {
       const int gq = tid % (RK / 8), x = tid / (RK / 8);
-      *reinterpret_cast<f32x4*>(&T.v[gq][0][x][0]) = f32x4{r.q[0][0], r.q[0][2], r.q[1][0], r.q[1][2]};
-      *reinterpret_cast<f32x4*>(&T.v[gq][1][x][0]) = f32x4{r.q[0][1], r.q[0][3], r.q[1][1], r.q[1][3]};
+      *reinterpret_cast<f32x4*>(&T.v[gq][0][rb_row(x)][0]) = f32x4{r.q[0][0], r.q[0][2], r.q[1][0], r.q[1][2]};
+      *reinterpret_cast<f32x4*>(&T.v[gq][1][rb_row(x)][0]) = f32x4{r.q[0][1], r.q[0][3], r.q[1][1], r.q[1][3]};
     }
   }
 }
@@ -432,8 +436,9 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
   typedef float f32x16 __attribute__((ext_vector_type(16)));
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   const int tid = threadIdx.x;
-  const int lane = tid % 64, wv = tid / 64, l32 = lane % 32, hf = lane / 32;
+  const int lane = tid % 64, wv = __builtin_amdgcn_readfirstlane(tid / 64), l32 = lane % 32, hf = lane / 32;
   const int rbase = 32 * BM * (wv / WN), cbase = 32 * BN * (wv % WN);  // the wave's corner inside the tile
+  const int row32 = rb_row(l32);
   const RbLane la = rb_lane<TM>(ax, g.sAm, g.sAk, tid), lb = rb_lane<TN>(bx, g.sBn, g.sBk, tid);
 
   // which of the wave's blocks do any work: inside the matrix and, for a triangular result, not
@@ -472,9 +477,9 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
     for (int gq = 0; gq < ng; ++gq) {
       f32x4 a[BM], b[BN];
 #pragma unroll
-      for (int i = 0; i < BM; ++i) a[i] = *reinterpret_cast<const f32x4*>(&As[buf].v[gq][hf][rbase + 32 * i + l32][0]);
+      for (int i = 0; i < BM; ++i) a[i] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&As[buf].v[gq][hf][rbase + 32 * i + row32][0], 16));
 #pragma unroll
-      for (int j = 0; j < BN; ++j) b[j] = *reinterpret_cast<const f32x4*>(&Bs[buf].v[gq][hf][cbase + 32 * j + l32][0]);
+      for (int j = 0; j < BN; ++j) b[j] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&Bs[buf].v[gq][hf][cbase + 32 * j + row32][0], 16));
 #pragma unroll
       for (int i = 0; i < BM; ++i)
 #pragma unroll
