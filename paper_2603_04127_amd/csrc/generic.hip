@@ -519,9 +519,12 @@ __global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, 
 // One wave per row: n = 1/2 |x~|^2, logits = U - n (+ bias_j) in place, rowmax.
 // bias (optional) is a per-(b,h) vector of m per-feature shifts (the key-side stabilisers,
 // which the query side adds back so that every product phi_Q,j * phi_K,j is unchanged).
+// exp_rows != 0: the row is left as exp(logit - rowmax) instead (the query features), the logits of up
+// to 512 features staying in registers in between, so the row is read and written once.
 __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const float* __restrict__ Xt,
                                                  float* __restrict__ rowmax, const float* __restrict__ bias,
-                                                 long long rows, int m, int r, int L) {
+                                                 long long rows, int m, int r, int L, int exp_rows) {
+  constexpr int kKeep = 8;
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
@@ -532,7 +535,20 @@ __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const fl
   s = 0.5f * wave_sum(s);
   float* u = U + row * m;
   float mx = -INFINITY;
-  for (int j = lane; j < m; j += kWave) {
+  float keep[kKeep];
+#pragma unroll
+  for (int t = 0; t < kKeep; ++t) {
+    const int j = lane + kWave * t;
+    float v = -INFINITY;
+    if (j < m) {
+      v = u[j] - s;
+      if (bs) v += bs[j];
+      if (!exp_rows) u[j] = v;
+    }
+    keep[t] = v;
+    mx = fmaxf(mx, v);
+  }
+  for (int j = lane + kWave * kKeep; j < m; j += kWave) {
     float v = u[j] - s;
     if (bs) v += bs[j];
     u[j] = v;
@@ -540,6 +556,14 @@ __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const fl
   }
   mx = wave_max(mx);
   if (lane == 0) rowmax[row] = mx;
+  if (exp_rows) {
+#pragma unroll
+    for (int t = 0; t < kKeep; ++t) {
+      const int j = lane + kWave * t;
+      if (j < m) u[j] = expf(keep[t] - mx);
+    }
+    for (int j = lane + kWave * kKeep; j < m; j += kWave) u[j] = expf(u[j] - mx);
+  }
 }
 
 // One block per (b,h): maximum of L row maxima.
@@ -800,7 +824,7 @@ dark_status make_As(const Problem& pb, const float* M, const float* W, float* As
 // (b,h) slice (STAB_KEY_HEAD, the dark_featurize contract) or per feature over the slice
 // (STAB_KEY_FEATURE, used inside attention where the query side adds the shifts back).
 dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, const float* As, StabMode mode,
-                     const float* qbias = nullptr) {
+                     const float* qbias = nullptr, bool exp_rows = false) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
   const float alpha = std::sqrt(pb.scale);
@@ -824,7 +848,7 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
     DARK_TRY(run_gemm(g, pb.st));
   }
   DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
-              fb.rowmax, mode == STAB_QUERY_ROW ? qbias : nullptr, rows, p.m, p.r, p.L);
+              fb.rowmax, mode == STAB_QUERY_ROW ? qbias : nullptr, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
   if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
   if (mode == STAB_KEY_FEATURE)
@@ -1046,8 +1070,7 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
   // phi_Q,ij phi_K,lj is the unshifted one times a per-row factor that cancels in N / D.
   DARK_TRY(features(pb, b.k, M, b.As, STAB_KEY_FEATURE));
   DARK_TRY(exp_inplace(pb, b.k, STAB_KEY_FEATURE));
-  DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax));
-  DARK_TRY(exp_inplace(pb, b.q, STAB_QUERY_ROW));
+  DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax, true));  // leaves the query features
   const long long st_elems = (long long)p.m * ldv;
   if (!causal) {
     // [S|z] = Phi_K^T [V|1]: per-slice partial states, then a fixed-order sum (Section 2: K'^T V first).
