@@ -55,17 +55,30 @@ __global__ __launch_bounds__(256, 4) void k_key_norms(const unsigned short* __re
   // A wave walks its 64 tokens of every 256-token chunk in blocks of 32; few registers, so that four
   // workgroups share a CU and their memory waits overlap.
   for (int chunk = c_begin; chunk < c_end; ++chunk) {
-#pragma unroll 1
+    // X fragments (B operand) of both 32-token blocks: token = tok0 + l32, k = 16 s + 8 hf + [0,8); rows
+    // past the end repeat the last row and are never stored.  All loads are issued before the first is
+    // converted, so the wave waits for memory once per chunk.
+    constexpr int NB = D <= 64 ? 2 : 1;  // blocks fetched together (registers)
+    u32x4 raw[2][D / 16];
+#pragma unroll
+    for (int tt = 0; tt < NB; ++tt) {
+      const int tok = min(chunk * 256 + 64 * wv + 32 * tt + l32, L - 1);
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) raw[tt][s] = *reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf);
+    }
+#pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int tok0 = chunk * 256 + 64 * wv + 32 * tt;
       if (tok0 >= L) break;  // wave-uniform
-      // X fragments (B operand): token = tok0 + l32, k = 16 s + 8 hf + [0,8); rows past the end repeat
-      // the last row and are never stored
-      const int tok = min(tok0 + l32, L - 1);
+      if (tt >= NB) {
+        const int tok = min(tok0 + l32, L - 1);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) raw[tt][s] = *reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf);
+      }
       half8 xf[D / 16];
 #pragma unroll
       for (int s = 0; s < D / 16; ++s) {
-        u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf));
+        u32x4 cv = bf16x8_to_f16x8(raw[tt][s]);
         xf[s] = *reinterpret_cast<half8*>(&cv);
       }
       float n2 = 0.f;

@@ -87,16 +87,22 @@ __global__ __launch_bounds__(256, 2) void k_featurize(const unsigned short* __re
     if (active) {
       const unsigned short* Xb = Xg + (size_t)bh * L * D;
       // X fragments (B operand): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8)
+      // (all loads are issued before the first is converted: one wait for memory, not one per load)
       half8 xf[2][D / 16];
+      u32x4 raw[2][D / 16];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
         const int tok = min(t0 + 32 * tt + l32, L - 1);  // rows past the end repeat the last row; never stored
 #pragma unroll
+        for (int s = 0; s < D / 16; ++s) raw[tt][s] = *reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf);
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
         for (int s = 0; s < D / 16; ++s) {
-          u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<const u32x4*>(Xb + (size_t)tok * D + 16 * s + 8 * hf));
+          u32x4 cv = bf16x8_to_f16x8(raw[tt][s]);
           xf[tt][s] = *reinterpret_cast<half8*>(&cv);
         }
-      }
       // n'(token) = |M' x|^2: x~^T[r][tok] by MFMA, squares summed over the register rows and the halves
       float nrm[2] = {0.f, 0.f};
 #pragma unroll
