@@ -94,6 +94,32 @@ def test_forward_small(shape, bf16, causal, path):
     U.assert_close(_np(out), want, U.TOL["bf16" if bf16 else "f32"], f"out {shape} causal={causal}")
 
 
+# Shapes chosen for the fp32 GEMMs: every tile shape (64, 96 and 128 columns), operands that 16-byte
+# loads can fetch and operands they cannot (odd r, m or d), matrix edges inside a group of four
+# (dv + 1 = 5, 32, 65, 97 padded to a multiple of four), single rows, and a tile boundary at L.
+F32_SWEEP = [
+    # B, H, L,   d,  r,  m,   dv
+    (1, 1, 1, 4, 4, 4, 4),
+    (1, 2, 5, 12, 8, 32, 31),
+    (1, 1, 127, 8, 6, 100, 4),
+    (1, 1, 128, 64, 64, 256, 64),
+    (2, 1, 129, 20, 20, 132, 96),
+    (1, 1, 259, 16, 16, 97, 65),
+]
+
+
+@pytest.mark.parametrize("shape", F32_SWEEP)
+@pytest.mark.parametrize("causal", [False, True])
+def test_f32_path_shape_sweep(shape, causal):
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(21, B, H, L, d, r, m, dv, amp=1.5)
+    dev = U.to_device(inp, False)
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    out = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32)
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, causal), U.TOL["f32"], f"fp32 path {shape} causal={causal}")
+
+
 @pytest.mark.parametrize("chunk", [16, 100, 128, 512])
 def test_causal_chunk_is_only_a_schedule(chunk):
     inp = U.random_problem(3, 1, 2, 300, 16, 16, 48, 20)
