@@ -52,6 +52,8 @@ __device__ inline void store_from_f32(__hip_bfloat16* p, long long i, float v) {
 // transposes are free.  The innermost batch index (b2) may shorten M, N and K
 // ("ragged" chunks): effective size = clamp(lim - b2 * step, 0, size) if lim > 0.
 // mask == 1 writes zeros where column > row (lower-triangular result).
+// A second product with its own operands, strides and K may be added into the same C before it is
+// stored (see the x* fields): two GEMMs that would otherwise write C and then read and rewrite it.
 // ---------------------------------------------------------------------------
 struct Gemm {
   const float* A;
@@ -65,6 +67,15 @@ struct Gemm {
   int mask;
   int mlim, mstep, nlim, nstep, klim, kstep;
   int modeA, modeB;  // GL_* fetch modes, set by run_gemm
+  // Optional second product accumulated into the same tile (register-blocked kernel only):
+  // C = alpha (A B + xA xB) + beta C, same M, N, batch counts and limits on M and N; xA == nullptr: none.
+  const float* xA;
+  const float* xB;
+  int xK;
+  long long xsAm, xsAk, xsBk, xsBn;
+  long long xsA0, xsA1, xsA2, xsB0, xsB1, xsB2;
+  int xklim, xkstep;
+  int xmodeA, xmodeB;
 };
 
 constexpr int GT = 64;  // C tile edge
@@ -145,6 +156,9 @@ struct GemmTile {
   const float* B;
   float* C;
   int m0, n0, Me, Ne, Ke;
+  const float* xA;  // second product (null if none)
+  const float* xB;
+  int xKe;
 };
 
 // Field by field, so that both tiles stay in scalar registers.
@@ -158,6 +172,9 @@ __device__ __forceinline__ GemmTile pick_tile(bool second, const GemmTile& a, co
   o.Me = second ? b.Me : a.Me;
   o.Ne = second ? b.Ne : a.Ne;
   o.Ke = second ? b.Ke : a.Ke;
+  o.xA = second ? b.xA : a.xA;
+  o.xB = second ? b.xB : a.xB;
+  o.xKe = second ? b.xKe : a.xKe;
   return o;
 }
 
@@ -182,6 +199,15 @@ __device__ __forceinline__ bool gemm_tile(const Gemm& g, int t, int tilesM, int 
   o.A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
   o.B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
   o.C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
+  o.xA = nullptr;
+  o.xB = nullptr;
+  o.xKe = 0;
+  if (g.xA != nullptr) {
+    o.xA = g.xA + b0 * g.xsA0 + b1 * g.xsA1 + b2 * g.xsA2;
+    o.xB = g.xB + b0 * g.xsB0 + b1 * g.xsB1 + b2 * g.xsB2;
+    o.xKe = g.xK;
+    if (g.xklim > 0) o.xKe = max(0, min(g.xK, g.xklim - b2 * g.xkstep));
+  }
   return o.m0 < o.Me && o.n0 < o.Ne;
 }
 
@@ -439,7 +465,6 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
   const int lane = tid % 64, wv = __builtin_amdgcn_readfirstlane(tid / 64), l32 = lane % 32, hf = lane / 32;
   const int rbase = 32 * BM * (wv / WN), cbase = 32 * BN * (wv % WN);  // the wave's corner inside the tile
   const int row32 = rb_row(l32);
-  const RbLane la = rb_lane<TM>(ax, g.sAm, g.sAk, tid), lb = rb_lane<TN>(bx, g.sBn, g.sBk, tid);
 
   // which of the wave's blocks do any work: inside the matrix and, for a triangular result, not
   // wholly above the diagonal
@@ -459,37 +484,50 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  Fetch ra, rb;
-  bool edge_a = rb_fetch<TM>(ra, la, ax, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, 0, cur.Ke, true);
-  bool edge_b = rb_fetch<TN>(rb, lb, bx, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, 0, cur.Ke, true);
-  int buf = 0;
-  // at least one step, so that an empty contraction still stores beta * C
-  for (int k0 = 0; k0 == 0 || k0 < cur.Ke; k0 += RK) {
-    if (edge_a) trim_fetch(ra);
-    if (edge_b) trim_fetch(rb);
-    rb_park<TM>(As[buf], ra, ax, tid);
-    rb_park<TN>(Bs[buf], rb, bx, tid);
-    const bool more = k0 + RK < cur.Ke;
-    edge_a = rb_fetch<TM>(ra, la, ax, cur.A, g.sAm, g.sAk, cur.m0, cur.Me, k0 + RK, cur.Ke, more);
-    edge_b = rb_fetch<TN>(rb, lb, bx, cur.B, g.sBn, g.sBk, cur.n0, cur.Ne, k0 + RK, cur.Ke, more);
-    __syncthreads();
-    const int ng = min(RK / 8, (cur.Ke - k0 + 7) / 8);  // groups of eight k that hold data
-    for (int gq = 0; gq < ng; ++gq) {
-      f32x4 a[BM], b[BN];
+  // one product A B over its K steps, added into acc
+  auto product = [&](const float* Ap, const float* Bp, long long sAm, long long sAk, long long sBn, long long sBk, int Ke,
+                     bool a_x, bool b_x) {
+    const RbLane la = rb_lane<TM>(a_x, sAm, sAk, tid), lb = rb_lane<TN>(b_x, sBn, sBk, tid);
+    Fetch ra, rb;
+    bool edge_a = rb_fetch<TM>(ra, la, a_x, Ap, sAm, sAk, cur.m0, cur.Me, 0, Ke, true);
+    bool edge_b = rb_fetch<TN>(rb, lb, b_x, Bp, sBn, sBk, cur.n0, cur.Ne, 0, Ke, true);
+    int buf = 0;
+    // at least one step, so that an empty contraction still stores beta * C
+    for (int k0 = 0; k0 == 0 || k0 < Ke; k0 += RK) {
+      if (edge_a) trim_fetch(ra);
+      if (edge_b) trim_fetch(rb);
+      rb_park<TM>(As[buf], ra, a_x, tid);
+      rb_park<TN>(Bs[buf], rb, b_x, tid);
+      const bool more = k0 + RK < Ke;
+      edge_a = rb_fetch<TM>(ra, la, a_x, Ap, sAm, sAk, cur.m0, cur.Me, k0 + RK, Ke, more);
+      edge_b = rb_fetch<TN>(rb, lb, b_x, Bp, sBn, sBk, cur.n0, cur.Ne, k0 + RK, Ke, more);
+      __syncthreads();
+      const int ng = min(RK / 8, (Ke - k0 + 7) / 8);  // groups of eight k that hold data
+      for (int gq = 0; gq < ng; ++gq) {
+        f32x4 a[BM], b[BN];
 #pragma unroll
-      for (int i = 0; i < BM; ++i) a[i] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&As[buf].v[gq][hf][rbase + 32 * i + row32][0], 16));
-#pragma unroll
-      for (int j = 0; j < BN; ++j) b[j] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&Bs[buf].v[gq][hf][cbase + 32 * j + row32][0], 16));
-#pragma unroll
-      for (int i = 0; i < BM; ++i)
+        for (int i = 0; i < BM; ++i)
+          a[i] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&As[buf].v[gq][hf][rbase + 32 * i + row32][0], 16));
 #pragma unroll
         for (int j = 0; j < BN; ++j)
-          if (work[i][j]) {
+          b[j] = *reinterpret_cast<const f32x4*>(__builtin_assume_aligned(&Bs[buf].v[gq][hf][cbase + 32 * j + row32][0], 16));
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
-          }
+        for (int i = 0; i < BM; ++i)
+#pragma unroll
+          for (int j = 0; j < BN; ++j)
+            if (work[i][j]) {
+#pragma unroll
+              for (int s = 0; s < 4; ++s)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][s], b[j][s], acc[i][j], 0, 0, 0);
+            }
+      }
+      buf ^= 1;
     }
-    buf ^= 1;
+  };
+  product(cur.A, cur.B, g.sAm, g.sAk, g.sBn, g.sBk, cur.Ke, ax, bx);
+  if (cur.xA != nullptr) {
+    __syncthreads();  // the slower waves may still be reading the last step's buffer
+    product(cur.xA, cur.xB, g.xsAm, g.xsAk, g.xsBn, g.xsBk, cur.xKe, g.xmodeA == GL_VEC_X, g.xmodeB == GL_VEC_X);
   }
 #pragma unroll
   for (int i = 0; i < BM; ++i)
@@ -739,6 +777,15 @@ Gemm gemm_base(const float* A, const float* B, float* C, int M, int N, int K) {
   return g;
 }
 
+// g += second product taken from the operand side of `x` (same M, N, batches and C as g).
+void add_product(Gemm& g, const Gemm& x) {
+  g.xA = x.A; g.xB = x.B; g.xK = x.K;
+  g.xsAm = x.sAm; g.xsAk = x.sAk; g.xsBk = x.sBk; g.xsBn = x.sBn;
+  g.xsA0 = x.sA0; g.xsA1 = x.sA1; g.xsA2 = x.sA2;
+  g.xsB0 = x.sB0; g.xsB1 = x.sB1; g.xsB2 = x.sB2;
+  g.xklim = x.klim; g.xkstep = x.kstep;
+}
+
 template <int WM, int WN, int BM, int BN>
 dark_status launch_gemm_rb(const Gemm& g, hipStream_t st) {
   typedef RbShape<WM, WN, BM, BN> S;
@@ -760,6 +807,24 @@ dark_status run_gemm(const Gemm& g_in, hipStream_t st) {
   Gemm g = g_in;
   g.modeA = gemm_load_mode(g.A, g.sAm, g.sAk, g.M, g.K, g.sA0, g.sA1, g.sA2);
   g.modeB = gemm_load_mode(g.B, g.sBn, g.sBk, g.N, g.K, g.sB0, g.sB1, g.sB2);
+  if (g.xA != nullptr) {
+    g.xmodeA = gemm_load_mode(g.xA, g.xsAm, g.xsAk, g.M, g.xK, g.xsA0, g.xsA1, g.xsA2);
+    g.xmodeB = gemm_load_mode(g.xB, g.xsBn, g.xsBk, g.N, g.xK, g.xsB0, g.xsB1, g.xsB2);
+    if (g.modeA == GL_SCALAR || g.modeB == GL_SCALAR || g.xmodeA == GL_SCALAR || g.xmodeB == GL_SCALAR) {
+      // only the register-blocked kernel adds a second product: run it as a GEMM of its own
+      Gemm first = g, second = g;
+      first.xA = nullptr;
+      second.xA = nullptr;
+      second.A = g.xA; second.B = g.xB; second.K = g.xK;
+      second.sAm = g.xsAm; second.sAk = g.xsAk; second.sBk = g.xsBk; second.sBn = g.xsBn;
+      second.sA0 = g.xsA0; second.sA1 = g.xsA1; second.sA2 = g.xsA2;
+      second.sB0 = g.xsB0; second.sB1 = g.xsB1; second.sB2 = g.xsB2;
+      second.klim = g.xklim; second.kstep = g.xkstep;
+      second.beta = 1.f;  // alpha (A B + xA xB) + beta C  =  alpha xA xB + (alpha A B + beta C)
+      DARK_TRY(run_gemm(first, st));
+      return run_gemm(second, st);
+    }
+  }
   const bool vec = g.modeA != GL_SCALAR && g.modeB != GL_SCALAR;
   if (vec) {
     // The largest tile that still gives about as many tiles as the chip holds workgroups.
@@ -997,9 +1062,9 @@ dark_status piece_states(const Problem& pb, const float* Phi, int mm, const floa
 // Rows times a per-(b,h[,chunk]) matrix:  dst[rows_piece][nn] (+)= X_piece[rows][kk] * St(^T).
 // st_t == false: St is [kk][nn] (row-major, leading dimension ld_st);  true: St is [nn][kk].
 // batch_shared: St is indexed by the head only ([H, ...], e.g. A_s) instead of by (b, h).
-dark_status rows_times_state(const Problem& pb, const float* X, int kk, int ldx, const float* St, int ld_st, bool st_t,
-                             bool per_chunk, long long st_elems, float* dst, int nn, int ldd, int piece, int npiece,
-                             float alpha, float beta, bool batch_shared = false) {
+Gemm make_rows_times_state(const Problem& pb, const float* X, int kk, int ldx, const float* St, int ld_st, bool st_t,
+                           bool per_chunk, long long st_elems, float* dst, int nn, int ldd, int piece, int npiece,
+                           float alpha, float beta, bool batch_shared = false) {
   const dark_params& p = pb.p;
   Gemm g = gemm_base(X, St, dst, piece, nn, kk);
   g.sAm = ldx; g.sAk = 1;
@@ -1013,7 +1078,15 @@ dark_status rows_times_state(const Problem& pb, const float* X, int kk, int ldx,
   g.sB0 = batch_shared ? 0 : g.sB1 * p.H;
   g.mlim = p.L; g.mstep = piece;
   g.alpha = alpha; g.beta = beta;
-  return run_gemm(g, pb.st);
+  return g;
+}
+
+dark_status rows_times_state(const Problem& pb, const float* X, int kk, int ldx, const float* St, int ld_st, bool st_t,
+                             bool per_chunk, long long st_elems, float* dst, int nn, int ldd, int piece, int npiece,
+                             float alpha, float beta, bool batch_shared = false) {
+  return run_gemm(make_rows_times_state(pb, X, kk, ldx, St, ld_st, st_t, per_chunk, st_elems, dst, nn, ldd, piece, npiece,
+                                        alpha, beta, batch_shared),
+                  pb.st);
 }
 
 // Score-like tiles per chunk:  T[bh][c][i][l] = sum_k X[cC+i][k] Y[cC+l][k], lower-triangular.
@@ -1033,8 +1106,8 @@ dark_status chunk_tiles(const Problem& pb, const float* X, int ldx, const float*
 }
 
 // dst_chunk[rows][nn] += T_chunk(^T) [rows][C] * X_chunk[C][nn].
-dark_status tile_times_rows(const Problem& pb, const float* T, bool transpose, const float* X, int ldx, float* dst,
-                            int nn, int ldd) {
+Gemm make_tile_times_rows(const Problem& pb, const float* T, bool transpose, const float* X, int ldx, float* dst,
+                          int nn, int ldd) {
   const dark_params& p = pb.p;
   const int C = pb.chunk;
   const int nchunk = (p.L + C - 1) / C;
@@ -1047,7 +1120,14 @@ dark_status tile_times_rows(const Problem& pb, const float* T, bool transpose, c
   bhl(g.sC0, g.sC1, g.sC2, p, ldd, C);
   g.mlim = p.L; g.mstep = C; g.klim = p.L; g.kstep = C;
   g.beta = 1.f;
-  return run_gemm(g, pb.st);
+  return g;
+}
+
+// dst_chunk = rows-times-state product + tile-times-rows product, one pass over dst: `first` as built
+// by make_rows_times_state (per chunk, beta = 0), `second` by make_tile_times_rows for the same dst.
+dark_status run_chunk_pair(const Problem& pb, Gemm first, const Gemm& second) {
+  add_product(first, second);
+  return run_gemm(first, pb.st);
 }
 
 // Everything the forward pass computes up to ND = [numerator | denominator].
@@ -1086,10 +1166,11 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.SZ, pb.BH(), b.nchunk,
                 st_elems, 0);
     // inter-chunk: Phi_Q,c [S|z]_{<c};  intra-chunk: tril(Phi_Q,c Phi_K,c^T) [V_c|1]
-    DARK_TRY(rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, ldv, false, true, st_elems, b.ND, dv1, ldv, C, b.nchunk,
-                              1.f, 0.f));
     DARK_TRY(chunk_tiles(pb, b.q.Phi, p.m, b.k.Phi, p.m, p.m, b.Pm));
-    DARK_TRY(tile_times_rows(pb, b.Pm, false, b.Vx, ldv, b.ND, dv1, ldv));
+    DARK_TRY(run_chunk_pair(pb,
+                            make_rows_times_state(pb, b.q.Phi, p.m, p.m, b.SZ, ldv, false, true, st_elems, b.ND, dv1, ldv,
+                                                  C, b.nchunk, 1.f, 0.f),
+                            make_tile_times_rows(pb, b.Pm, false, b.Vx, ldv, b.ND, dv1, ldv)));
   }
   return DARK_OK;
 }
@@ -1171,16 +1252,19 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
                 st_elems, 1);
     DARK_TRY(chunk_tiles(pb, dND, ldv, b.Vx, ldv, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
     // b.Pm = tril(Phi_Q Phi_K^T) is left over from forward_core.
-    DARK_TRY(rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,
-                              0.f));
-    DARK_TRY(tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m));
-    DARK_TRY(rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, true, st_elems, dPk, p.m, p.m, C, b.nchunk, 1.f, 0.f));
-    DARK_TRY(tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m));
-    if (dV) {
-      DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, true, st_elems, dVo, p.dv, p.dv, C, b.nchunk,
-                                1.f, 0.f));
-      DARK_TRY(tile_times_rows(pb, b.Pm, true, dND, ldv, dVo, p.dv, p.dv));
-    }
+    DARK_TRY(run_chunk_pair(pb,
+                            make_rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C,
+                                                  b.nchunk, 1.f, 0.f),
+                            make_tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m)));
+    DARK_TRY(run_chunk_pair(pb,
+                            make_rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, true, st_elems, dPk, p.m, p.m, C,
+                                                  b.nchunk, 1.f, 0.f),
+                            make_tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m)));
+    if (dV)
+      DARK_TRY(run_chunk_pair(pb,
+                              make_rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, true, st_elems, dVo, p.dv, p.dv,
+                                                    C, b.nchunk, 1.f, 0.f),
+                              make_tile_times_rows(pb, b.Pm, true, dND, ldv, dVo, p.dv, p.dv)));
   }
   // dlogit (in dPq / dPk), dXt (in Xt buffers)
   DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dlogit, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, dPq, b.q.Phi, b.q.Xt, rows,
