@@ -52,6 +52,8 @@ __device__ inline void store_from_f32(__hip_bfloat16* p, long long i, float v) {
 // transposes are free.  The innermost batch index (b2) may shorten M, N and K
 // ("ragged" chunks): effective size = clamp(lim - b2 * step, 0, size) if lim > 0.
 // mask == 1 writes zeros where column > row (lower-triangular result).
+// E != nullptr: C = (alpha * A B + beta * C) .* E, E laid out like C (the gradient of a logit is the
+// gradient of its feature times the feature, Section 4.1's exponential).
 // A second product with its own operands, strides and K may be added into the same C before it is
 // stored (see the x* fields): two GEMMs that would otherwise write C and then read and rewrite it.
 // ---------------------------------------------------------------------------
@@ -65,6 +67,7 @@ struct Gemm {
   long long sA0, sA1, sA2, sB0, sB1, sB2, sC0, sC1, sC2;
   float alpha, beta;
   int mask;
+  const float* E;  // optional: the stored value is multiplied element-wise by E (indexed like C)
   int mlim, mstep, nlim, nstep, klim, kstep;
   int modeA, modeB;  // GL_* fetch modes, set by run_gemm
   // Optional second product accumulated into the same tile (register-blocked kernel only):
@@ -155,6 +158,7 @@ struct GemmTile {
   const float* A;
   const float* B;
   float* C;
+  const float* E;  // null if none
   int m0, n0, Me, Ne, Ke;
   const float* xA;  // second product (null if none)
   const float* xB;
@@ -167,6 +171,7 @@ __device__ __forceinline__ GemmTile pick_tile(bool second, const GemmTile& a, co
   o.A = second ? b.A : a.A;
   o.B = second ? b.B : a.B;
   o.C = second ? b.C : a.C;
+  o.E = second ? b.E : a.E;
   o.m0 = second ? b.m0 : a.m0;
   o.n0 = second ? b.n0 : a.n0;
   o.Me = second ? b.Me : a.Me;
@@ -199,6 +204,7 @@ __device__ __forceinline__ bool gemm_tile(const Gemm& g, int t, int tilesM, int 
   o.A = g.A + b0 * g.sA0 + b1 * g.sA1 + b2 * g.sA2;
   o.B = g.B + b0 * g.sB0 + b1 * g.sB1 + b2 * g.sB2;
   o.C = g.C + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2;
+  o.E = g.E != nullptr ? g.E + b0 * g.sC0 + b1 * g.sC1 + b2 * g.sC2 : nullptr;
   o.xA = nullptr;
   o.xB = nullptr;
   o.xKe = 0;
@@ -218,17 +224,20 @@ __device__ __forceinline__ bool gemm_tile(const Gemm& g, int t, int tilesM, int 
 // the matrix takes a path without per-element branches: behind a branch the compiler can no longer
 // count the stores in flight and would wait for each one to finish.  Clears the accumulator.
 typedef float gemm_acc_t __attribute__((ext_vector_type(16)));
-template <bool kFull, bool kBeta>
-__device__ __forceinline__ void gemm_store_block_as(const Gemm& g, float* C, int m_first, int Me, int gn, int Ne,
-                                                    gemm_acc_t& acc) {
+template <bool kFull, bool kBeta, bool kMul>
+__device__ __forceinline__ void gemm_store_block_as(const Gemm& g, float* C, const float* E, int m_first, int Me, int gn,
+                                                    int Ne, gemm_acc_t& acc) {
   long long off = m_first * g.sCm + gn * g.sCn;
   const float* cb = C + off;
+  const float* eb = E + off;
   const bool col = gn < Ne;
-  float cv[16];
+  float cv[16], ev[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int r = 8 * (v / 4) + (v % 4);
-    cv[v] = kBeta ? ((kFull || (col && m_first + r < Me)) ? cb[r * g.sCm] : 0.f) : 0.f;
+    const bool in = kFull || (col && m_first + r < Me);
+    cv[v] = kBeta ? (in ? cb[r * g.sCm] : 0.f) : 0.f;
+    ev[v] = kMul ? (in ? eb[r * g.sCm] : 0.f) : 1.f;
   }
   asm volatile("" : "+v"(off));
   float* cs = C + off;
@@ -238,6 +247,7 @@ __device__ __forceinline__ void gemm_store_block_as(const Gemm& g, float* C, int
     if (kFull || (col && m_first + r < Me)) {
       float x = g.alpha * acc[v];
       if (kBeta) x += g.beta * cv[v];
+      if (kMul) x *= ev[v];
       if (g.mask == 1 && gn > m_first + r) x = 0.f;
       cs[r * g.sCm] = x;
     }
@@ -245,16 +255,22 @@ __device__ __forceinline__ void gemm_store_block_as(const Gemm& g, float* C, int
   }
 }
 
-__device__ __forceinline__ void gemm_store_block(const Gemm& g, float* C, int bm0, int hf, int Me, int bn0, int l32,
-                                                 int Ne, gemm_acc_t& acc) {
+__device__ __forceinline__ void gemm_store_block(const Gemm& g, float* C, const float* E, int bm0, int hf, int Me, int bn0,
+                                                 int l32, int Ne, gemm_acc_t& acc) {
   const bool full = bm0 + 32 <= Me && bn0 + 32 <= Ne;
   const int m_first = bm0 + 4 * hf, gn = bn0 + l32;
-  if (g.beta != 0.f) {
-    if (full) gemm_store_block_as<true, true>(g, C, m_first, Me, gn, Ne, acc);
-    else gemm_store_block_as<false, true>(g, C, m_first, Me, gn, Ne, acc);
+  if (E != nullptr && g.beta != 0.f) {
+    if (full) gemm_store_block_as<true, true, true>(g, C, E, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, true, true>(g, C, E, m_first, Me, gn, Ne, acc);
+  } else if (E != nullptr) {
+    if (full) gemm_store_block_as<true, false, true>(g, C, E, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, false, true>(g, C, E, m_first, Me, gn, Ne, acc);
+  } else if (g.beta != 0.f) {
+    if (full) gemm_store_block_as<true, true, false>(g, C, E, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, true, false>(g, C, E, m_first, Me, gn, Ne, acc);
   } else {
-    if (full) gemm_store_block_as<true, false>(g, C, m_first, Me, gn, Ne, acc);
-    else gemm_store_block_as<false, false>(g, C, m_first, Me, gn, Ne, acc);
+    if (full) gemm_store_block_as<true, false, false>(g, C, E, m_first, Me, gn, Ne, acc);
+    else gemm_store_block_as<false, false, false>(g, C, E, m_first, Me, gn, Ne, acc);
   }
 }
 
@@ -321,7 +337,7 @@ __global__ __launch_bounds__(256, 3) void k_gemm(Gemm g, int total_tiles) {
       k0 += GK;
       continue;
     }
-    gemm_store_block(g, cur.C, cur.m0 + 32 * wm, hf, cur.Me, cur.n0 + 32 * wn, l32, cur.Ne, acc);
+    gemm_store_block(g, cur.C, cur.E, cur.m0 + 32 * wm, hf, cur.Me, cur.n0 + 32 * wn, l32, cur.Ne, acc);
     if (!more) break;
     cur = nxt;
     t = tn;
@@ -533,7 +549,7 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
   for (int i = 0; i < BM; ++i)
 #pragma unroll
     for (int j = 0; j < BN; ++j)
-      gemm_store_block(g, cur.C, cur.m0 + rbase + 32 * i, hf, cur.Me, cur.n0 + cbase + 32 * j, l32, cur.Ne, acc[i][j]);
+      gemm_store_block(g, cur.C, cur.E, cur.m0 + rbase + 32 * i, hf, cur.Me, cur.n0 + cbase + 32 * j, l32, cur.Ne, acc[i][j]);
 }
 
 // dst[row][0..cols) = (float)src[row][0..cols);  dst[row][cols] = 1 if ones.
@@ -735,22 +751,29 @@ __global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const
   if (lane == 0) o[dv] = -dot * invD;
 }
 
-// Backward, per row (one wave): dlogit = dPhi * Phi (in place in dPhi),
-// dn = -sum_j dlogit_j,  dXt = dn * Xt (in place in Xt).
-__global__ __launch_bounds__(256) void k_dlogit(float* __restrict__ dPhi, const float* __restrict__ Phi,
-                                                float* __restrict__ Xt, long long rows, int m, int r) {
+// Backward, per key row (one wave).  The logit gradients come out of the GEMMs already multiplied by the
+// features.  What is left is the path through the norm term n = 1/2 |x~|^2, which enters every logit of
+// the row with coefficient -1:  dn = -sum_j dlogit_j.  For a key row that sum is
+// sum_j phi_K,lj (R_lj . [v_l | 1]) = [v_l | 1] . dVx_l, with dVx = Phi_K R over all dv + 1 columns (the
+// first dv of them are dV), so it needs no pass over the m features.  For a query row the sum is
+// N_i . dN_i + D_i dD_i = 0 identically (the output does not change when a query's features are all
+// scaled alike), so the query side has no such term.
+//   dXt = dn * Xt (in place), and dV = the first dv columns of dVx if asked for.
+__global__ __launch_bounds__(256) void k_key_dn(const float* __restrict__ Vx, const float* __restrict__ dVx,
+                                                float* __restrict__ Xt, float* __restrict__ dV, long long rows, int dv,
+                                                int ld, int r) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
-  float* dp = dPhi + row * m;
-  const float* ph = Phi + row * m;
+  const float* vx = Vx + row * ld;
+  const float* dx = dVx + row * ld;
   float s = 0.f;
-  for (int j = lane; j < m; j += kWave) {
-    float v = dp[j] * ph[j];
-    dp[j] = v;
-    s += v;
+  for (int c = lane; c <= dv; c += kWave) {
+    const float g = dx[c];
+    s = fmaf(vx[c], g, s);
+    if (dV != nullptr && c < dv) dV[row * dv + c] = g;
   }
-  float dn = -wave_sum(s);
+  const float dn = -wave_sum(s);
   float* xt = Xt + row * r;
   for (int t = lane; t < r; t += kWave) xt[t] *= dn;
 }
@@ -814,6 +837,7 @@ dark_status run_gemm(const Gemm& g_in, hipStream_t st) {
       // only the register-blocked kernel adds a second product: run it as a GEMM of its own
       Gemm first = g, second = g;
       first.xA = nullptr;
+      first.E = nullptr;  // the element-wise factor multiplies the whole sum
       second.xA = nullptr;
       second.A = g.xA; second.B = g.xB; second.K = g.xK;
       second.sAm = g.xsAm; second.sAk = g.xsAk; second.sBk = g.xsBk; second.sBn = g.xsBn;
@@ -1200,9 +1224,10 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
 //   R_l  = sum_{i >= l} Phi_Q,i [dN_i | dD_i]^T            (all i if bidirectional)
 //   dV_l = R_l[:, :dv]^T Phi_K,l
 //   dPhi_Q,i = [S_i | z_i] [dN_i | dD_i]^T,   dPhi_K,l = R_l [v_l | 1]^T
-//   dlogit = dPhi * Phi,  dn = -sum_j dlogit_j,  dXt = dn Xt
-//   dX = dlogit A_s + sqrt(scale) dXt M
-//   dM_h = sum_b sqrt(scale) ( W^T (dlogit_Q^T Q + dlogit_K^T K) + dXt_Q^T Q + dXt_K^T K )
+//   dlogit = dPhi * Phi (applied in the epilogue of the GEMM that forms dPhi)
+//   dn_l = -sum_j dlogit_K,lj = -[v_l | 1] . (R_l^T Phi_K,l),  dXt_K = dn Xt_K;  the query rows have dn = 0
+//   dQ = dlogit_Q A_s,   dK = dlogit_K A_s + sqrt(scale) dXt_K M
+//   dM_h = sum_b sqrt(scale) ( W^T (dlogit_Q^T Q + dlogit_K^T K) + dXt_K^T K )
 // Stabilising shifts cancel between dPhi and Phi, so the stabilised features are used
 // throughout.  Causal: states are exclusive prefix (S) / suffix (R) sums over chunks plus
 // masked within-chunk tiles  P = tril(Phi_Q Phi_K^T),  E = tril([dN|dD] [V|1]^T).
@@ -1220,6 +1245,7 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   float* dND = ar.take<float>((size_t)rows * ldv);
   float* dPq = ar.take<float>((size_t)rows * p.m);
   float* dPk = ar.take<float>((size_t)rows * p.m);
+  float* dVx = ar.take<float>((size_t)rows * ldv);  // Phi_K R over all dv + 1 columns
   float* R = ar.take<float>((size_t)pb.BH() * (causal ? b.nchunk : 1) * st_elems);
   float* Rpart = causal ? nullptr : ar.take<float>((size_t)pb.BH() * b.P * st_elems);
   float* Em = causal ? ar.take<float>((size_t)pb.BH() * b.nchunk * C * C) : nullptr;
@@ -1236,52 +1262,56 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   else
     Gf = const_cast<float*>(static_cast<const float*>(dOut));
   DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND, Gf, dND, rows, p.dv, ldv);
-  float* dVo = dV;
+  // dVx feeds dV and, through the key norms, dK and dM
+  const bool need_dvx = dV != nullptr || dK != nullptr || dM != nullptr;
 
   if (!causal) {
     DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, ldv, Rpart, ldv, slice_len(pb), b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, Rpart, R,
                 pb.BH(), b.P, st_elems, st_elems * b.P, st_elems);
-    DARK_TRY(rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, false, st_elems, dPq, p.m, p.m, p.L, 1, 1.f, 0.f));
-    DARK_TRY(rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, false, st_elems, dPk, p.m, p.m, p.L, 1, 1.f, 0.f));
-    if (dV) DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, false, st_elems, dVo, p.dv, p.dv, p.L, 1,
-                                      1.f, 0.f));
+    Gemm gq = make_rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, false, st_elems, dPq, p.m, p.m, p.L, 1, 1.f, 0.f);
+    gq.E = b.q.Phi;
+    DARK_TRY(run_gemm(gq, pb.st));
+    Gemm gk = make_rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, false, st_elems, dPk, p.m, p.m, p.L, 1, 1.f, 0.f);
+    gk.E = b.k.Phi;
+    DARK_TRY(run_gemm(gk, pb.st));
+    if (need_dvx)
+      DARK_TRY(rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, false, st_elems, dVx, dv1, ldv, p.L, 1, 1.f, 0.f));
   } else {
     DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, ldv, R, ldv, C, b.nchunk, 0.f));
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, R, pb.BH(), b.nchunk,
                 st_elems, 1);
     DARK_TRY(chunk_tiles(pb, dND, ldv, b.Vx, ldv, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
     // b.Pm = tril(Phi_Q Phi_K^T) is left over from forward_core.
-    DARK_TRY(run_chunk_pair(pb,
-                            make_rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C,
-                                                  b.nchunk, 1.f, 0.f),
-                            make_tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m)));
-    DARK_TRY(run_chunk_pair(pb,
-                            make_rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, true, st_elems, dPk, p.m, p.m, C,
-                                                  b.nchunk, 1.f, 0.f),
-                            make_tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m)));
-    if (dV)
+    Gemm gq = make_rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,
+                                    0.f);
+    gq.E = b.q.Phi;
+    DARK_TRY(run_chunk_pair(pb, gq, make_tile_times_rows(pb, Em, false, b.k.Phi, p.m, dPq, p.m, p.m)));
+    Gemm gk = make_rows_times_state(pb, b.Vx, dv1, ldv, R, ldv, true, true, st_elems, dPk, p.m, p.m, C, b.nchunk, 1.f,
+                                    0.f);
+    gk.E = b.k.Phi;
+    DARK_TRY(run_chunk_pair(pb, gk, make_tile_times_rows(pb, Em, true, b.q.Phi, p.m, dPk, p.m, p.m)));
+    if (need_dvx)
       DARK_TRY(run_chunk_pair(pb,
-                              make_rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, true, st_elems, dVo, p.dv, p.dv,
+                              make_rows_times_state(pb, b.k.Phi, p.m, p.m, R, ldv, false, true, st_elems, dVx, dv1, ldv,
                                                     C, b.nchunk, 1.f, 0.f),
-                              make_tile_times_rows(pb, b.Pm, true, dND, ldv, dVo, p.dv, p.dv)));
+                              make_tile_times_rows(pb, b.Pm, true, dND, ldv, dVx, dv1, ldv)));
   }
-  // dlogit (in dPq / dPk), dXt (in Xt buffers)
-  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dlogit, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, dPq, b.q.Phi, b.q.Xt, rows,
-              p.m, p.r);
-  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dlogit, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, dPk, b.k.Phi, b.k.Xt, rows,
-              p.m, p.r);
+  // dPq / dPk hold the logit gradients; dXt_K (in the key Xt buffer) and dV
+  if (need_dvx)
+    DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_key_dn, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.Vx, dVx, b.k.Xt, dV, rows,
+                p.dv, ldv, p.r);
   const float alpha = std::sqrt(pb.scale);
   const long long as_elems = (long long)p.m * p.d, m_elems = (long long)p.r * p.d;
   for (int side = 0; side < 2; ++side) {
     float* dX = side == 0 ? dQ : dK;
     if (!dX) continue;
     float* dl = side == 0 ? dPq : dPk;
-    float* dxt = side == 0 ? b.q.Xt : b.k.Xt;
     DARK_TRY(rows_times_state(pb, dl, p.m, p.m, b.As, p.d, false, false, as_elems, dX, p.d, p.d, p.L, 1, 1.f, 0.f,
                               true));
+    if (side == 0) continue;  // no norm term on the query side
     // M is [H, r, d] shared over the batch: per-head stride only.
-    Gemm g = gemm_base(dxt, M, dX, p.L, p.d, p.r);
+    Gemm g = gemm_base(b.k.Xt, M, dX, p.L, p.d, p.r);
     g.sAm = p.r; g.sAk = 1; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
     g.nb0 = p.B; g.nb1 = p.H;
     g.sA0 = (long long)p.H * p.L * p.r; g.sA1 = (long long)p.L * p.r;
@@ -1296,8 +1326,7 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
     DARK_TRY(piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 1.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * as_elems)), dim3(256), 0, Tpart, T,
                 pb.BH(), b.P, as_elems, as_elems * b.P, as_elems);
-    DARK_TRY(piece_states(pb, b.q.Xt, p.r, b.q.Xf, p.d, p.d, T2part, p.d, SL, b.P, 0.f));
-    DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, p.d, SL, b.P, 1.f));
+    DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, p.d, SL, b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * m_elems)), dim3(256), 0, T2part, T2,
                 pb.BH(), b.P, m_elems, m_elems * b.P, m_elems);
     // T2_bh = alpha * W_h^T T_bh + alpha * T2_bh
