@@ -732,18 +732,18 @@ __global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long lo
 
 // Backward, per row (one wave): from ND = [N | D] and G = dOut,
 //   dN = G / D,  dD = -(G . out) / D  with out = N / D;  written as dND = [dN | dD].
-__global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const float* __restrict__ G,
+template <typename T>
+__global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const T* __restrict__ G,
                                              float* __restrict__ dND, long long rows, int dv, int ld) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
   const float* nd = ND + row * ld;
-  const float* gp = G + row * dv;
   float* o = dND + row * ld;
   float invD = 1.f / nd[dv];
   float dot = 0.f;
   for (int c = lane; c < dv; c += kWave) {
-    float gv = gp[c];
+    float gv = load_as_f32(G, row * dv + c);
     o[c] = gv * invD;
     dot = fmaf(gv, nd[c] * invD, dot);
   }
@@ -1241,7 +1241,6 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   AttnBufs b{};
   plan_attn(pb, ar, causal, true, b);
   const long long st_elems = (long long)p.m * ldv;
-  float* Gf = p.io_dtype == DARK_BF16 ? ar.take<float>((size_t)rows * p.dv) : nullptr;
   float* dND = ar.take<float>((size_t)rows * ldv);
   float* dPq = ar.take<float>((size_t)rows * p.m);
   float* dPk = ar.take<float>((size_t)rows * p.m);
@@ -1258,10 +1257,11 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
 
   DARK_TRY(forward_core(pb, b, causal, Q, K, V, M, W));
   if (p.io_dtype == DARK_BF16)
-    DARK_TRY(to_f32(pb, dOut, Gf, rows, p.dv, p.dv, 0));
+    DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd<__hip_bfloat16>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND,
+                (const __hip_bfloat16*)dOut, dND, rows, p.dv, ldv);
   else
-    Gf = const_cast<float*>(static_cast<const float*>(dOut));
-  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND, Gf, dND, rows, p.dv, ldv);
+    DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dnd<float>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.ND,
+                (const float*)dOut, dND, rows, p.dv, ldv);
   // dVx feeds dV and, through the key norms, dK and dM
   const bool need_dvx = dV != nullptr || dK != nullptr || dM != nullptr;
 
