@@ -635,8 +635,10 @@ __global__ __launch_bounds__(256) void k_headmax(const float* __restrict__ rowma
 // Per-feature maximum over the L rows of each (b,h): colmax[bh][j] = max_l logit[bh][l][j].
 // One block per (bh, 64-column group); threads = 64 columns x 16 row phases, eight loads in flight.
 constexpr int kColmaxPhases = 16;
+// rown (optional): a per-row term subtracted from every entry first (the norm term n_l).
 __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __restrict__ logit,
-                                                               float* __restrict__ colmax, int L, int m) {
+                                                               float* __restrict__ colmax, int L, int m,
+                                                               const float* __restrict__ rown) {
   __shared__ float sm[kColmaxPhases][64];
   const int groups = (m + 63) / 64;
   const long long bh = blockIdx.x / groups;
@@ -645,15 +647,20 @@ __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __re
   float mx = -INFINITY;
   if (j < m) {
     const float* p = logit + bh * L * (long long)m + j;
+    const float* rn = rown ? rown + bh * L : nullptr;
     int l = ph;
     for (; l + 7 * kColmaxPhases < L; l += 8 * kColmaxPhases) {
       float v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = p[(long long)(l + u * kColmaxPhases) * m];
+      if (rn) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] -= rn[l + u * kColmaxPhases];
+      }
 #pragma unroll
       for (int u = 0; u < 8; ++u) mx = fmaxf(mx, v[u]);
     }
-    for (; l < L; l += kColmaxPhases) mx = fmaxf(mx, p[(long long)l * m]);
+    for (; l < L; l += kColmaxPhases) mx = fmaxf(mx, p[(long long)l * m] - (rn ? rn[l] : 0.f));
   }
   sm[ph][threadIdx.x % 64] = mx;
   __syncthreads();
@@ -666,16 +673,30 @@ __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __re
 
 // Phi = exp(logit - c) * mult.  mode 0: c = cvec[row];  1: c = cvec[row / L] (per head);
 // 2: c = cvec[(row / L) * m + j] (per head and feature).
+// rown (optional): a per-row term added to c (the norm term n_l, when the logits do not hold it yet).
 template <typename T>
 __global__ void k_exp(const float* __restrict__ logit, T* __restrict__ out, const float* __restrict__ cvec,
-                      long long rows, int m, int L, int mode, float mult) {
+                      long long rows, int m, int L, int mode, float mult, const float* __restrict__ rown) {
   long long total = rows * m;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
     long long row = i / m;
     float c = mode == 0 ? cvec[row] : (mode == 1 ? cvec[row / L] : cvec[(row / L) * m + (i % m)]);
+    if (rown) c += rown[row];
     store_from_f32(out, i, expf(logit[i] - c) * mult);
   }
+}
+
+// n[row] = 1/2 |x~_row|^2, one wave per row.
+__global__ __launch_bounds__(256) void k_rownorm(const float* __restrict__ Xt, float* __restrict__ n, long long rows, int r) {
+  long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
+  if (row >= rows) return;
+  int lane = threadIdx.x % kWave;
+  const float* xt = Xt + row * r;
+  float s = 0.f;
+  for (int t = lane; t < r; t += kWave) s = fmaf(xt[t], xt[t], s);
+  s = 0.5f * wave_sum(s);
+  if (lane == 0) n[row] = s;
 }
 
 // out[o*so_out + e] = sum_{p<P} in[o*so + p*sp + e], p ascending (fixed order).
@@ -936,13 +957,18 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
     g.sC0 = (long long)p.H * p.L * p.m; g.sC1 = (long long)p.L * p.m;
     DARK_TRY(run_gemm(g, pb.st));
   }
+  if (mode == STAB_KEY_FEATURE) {
+    // The logits stay U: the norm term (kept in fb.rowmax, which this mode does not otherwise use) is
+    // applied where they are read, by the per-feature maximum here and by exp_inplace.
+    DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rownorm, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Xt, fb.rowmax, rows, p.r);
+    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(64 * kColmaxPhases), 0, fb.Phi,
+                fb.colmax, p.L, p.m, fb.rowmax);
+    return DARK_OK;
+  }
   DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
               fb.rowmax, mode == STAB_QUERY_ROW ? qbias : nullptr, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
   if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
-  if (mode == STAB_KEY_FEATURE)
-    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(64 * kColmaxPhases), 0, fb.Phi,
-                fb.colmax, p.L, p.m);
   return DARK_OK;
 }
 
@@ -950,7 +976,7 @@ dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
   const long long rows = pb.rows();
   const float* c = mode == STAB_QUERY_ROW ? fb.rowmax : (mode == STAB_KEY_HEAD ? fb.headmax : fb.colmax);
   DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * pb.p.m)), dim3(256), 0, fb.Phi, fb.Phi, c, rows,
-              pb.p.m, pb.p.L, (int)mode, 1.0f);
+              pb.p.m, pb.p.L, (int)mode, 1.0f, mode == STAB_KEY_FEATURE ? fb.rowmax : nullptr);
   return DARK_OK;
 }
 
@@ -996,10 +1022,10 @@ dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const flo
   const float* cvec = is_query ? fb.rowmax : fb.headmax;
   if (p.io_dtype == DARK_BF16)
     DARK_LAUNCH(KID_EXP, pb.st, k_exp<__hip_bfloat16>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi,
-                (__hip_bfloat16*)phi, cvec, rows, p.m, p.L, is_query ? 0 : 1, mult);
+                (__hip_bfloat16*)phi, cvec, rows, p.m, p.L, is_query ? 0 : 1, mult, (const float*)nullptr);
   else
     DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi, (float*)phi, cvec,
-                rows, p.m, p.L, is_query ? 0 : 1, mult);
+                rows, p.m, p.L, is_query ? 0 : 1, mult, (const float*)nullptr);
   if (stab != nullptr) {
     long long n = is_query ? rows : pb.BH();
     // plain copy through the sum kernel (P = 1)
