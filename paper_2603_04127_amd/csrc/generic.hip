@@ -575,10 +575,33 @@ __global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, 
 // which the query side adds back so that every product phi_Q,j * phi_K,j is unchanged).
 // exp_rows != 0: the row is left as exp(logit - rowmax) instead (the query features), the logits of up
 // to 512 features staying in registers in between, so the row is read and written once.
+// (V = 4: the row is walked in 16-byte groups; needs m % 4 == 0 and 16-byte aligned rows.)
+template <int V>
+__device__ __forceinline__ void load_v(const float* p, float (&o)[V]) {
+  if (V == 4) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 x = *reinterpret_cast<const f32x4*>(p);
+#pragma unroll
+    for (int e = 0; e < V; ++e) o[e] = x[e];
+  } else {
+    o[0] = p[0];
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_v(float* p, const float (&o)[V]) {
+  if (V == 4) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    *reinterpret_cast<f32x4*>(p) = f32x4{o[0], o[V > 1 ? 1 : 0], o[V > 2 ? 2 : 0], o[V > 3 ? 3 : 0]};
+  } else {
+    p[0] = o[0];
+  }
+}
+
+template <int V>
 __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const float* __restrict__ Xt,
                                                  float* __restrict__ rowmax, const float* __restrict__ bias,
                                                  long long rows, int m, int r, int L, int exp_rows) {
-  constexpr int kKeep = 8;
+  constexpr int kKeep = 8 / (V == 4 ? 4 : 1);  // groups kept in registers: up to 512 features
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
@@ -588,25 +611,39 @@ __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const fl
   for (int t = lane; t < r; t += kWave) s = fmaf(xt[t], xt[t], s);
   s = 0.5f * wave_sum(s);
   float* u = U + row * m;
+  const int ng = m / V;  // groups in the row
   float mx = -INFINITY;
-  float keep[kKeep];
+  float keep[kKeep][V];
 #pragma unroll
   for (int t = 0; t < kKeep; ++t) {
     const int j = lane + kWave * t;
-    float v = -INFINITY;
-    if (j < m) {
-      v = u[j] - s;
-      if (bs) v += bs[j];
-      if (!exp_rows) u[j] = v;
+#pragma unroll
+    for (int e = 0; e < V; ++e) keep[t][e] = -INFINITY;
+    if (j < ng) {
+      float b4[V];
+      load_v<V>(u + V * j, keep[t]);
+#pragma unroll
+      for (int e = 0; e < V; ++e) b4[e] = 0.f;
+      if (bs) load_v<V>(bs + V * j, b4);
+#pragma unroll
+      for (int e = 0; e < V; ++e) keep[t][e] = keep[t][e] - s + b4[e];
+      if (!exp_rows) store_v<V>(u + V * j, keep[t]);
     }
-    keep[t] = v;
-    mx = fmaxf(mx, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) mx = fmaxf(mx, keep[t][e]);
   }
-  for (int j = lane + kWave * kKeep; j < m; j += kWave) {
-    float v = u[j] - s;
-    if (bs) v += bs[j];
-    u[j] = v;
-    mx = fmaxf(mx, v);
+  for (int j = lane + kWave * kKeep; j < ng; j += kWave) {
+    float v[V], b4[V];
+    load_v<V>(u + V * j, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) b4[e] = 0.f;
+    if (bs) load_v<V>(bs + V * j, b4);
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      v[e] = v[e] - s + b4[e];
+      mx = fmaxf(mx, v[e]);
+    }
+    store_v<V>(u + V * j, v);
   }
   mx = wave_max(mx);
   if (lane == 0) rowmax[row] = mx;
@@ -614,9 +651,20 @@ __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const fl
 #pragma unroll
     for (int t = 0; t < kKeep; ++t) {
       const int j = lane + kWave * t;
-      if (j < m) u[j] = expf(keep[t] - mx);
+      if (j < ng) {
+        float o[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] = expf(keep[t][e] - mx);
+        store_v<V>(u + V * j, o);
+      }
     }
-    for (int j = lane + kWave * kKeep; j < m; j += kWave) u[j] = expf(u[j] - mx);
+    for (int j = lane + kWave * kKeep; j < ng; j += kWave) {
+      float v[V];
+      load_v<V>(u + V * j, v);
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] = expf(v[e] - mx);
+      store_v<V>(u + V * j, v);
+    }
   }
 }
 
@@ -674,16 +722,32 @@ __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __re
 // Phi = exp(logit - c) * mult.  mode 0: c = cvec[row];  1: c = cvec[row / L] (per head);
 // 2: c = cvec[(row / L) * m + j] (per head and feature).
 // rown (optional): a per-row term added to c (the norm term n_l, when the logits do not hold it yet).
-template <typename T>
-__global__ void k_exp(const float* __restrict__ logit, T* __restrict__ out, const float* __restrict__ cvec,
-                      long long rows, int m, int L, int mode, float mult, const float* __restrict__ rown) {
-  long long total = rows * m;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    long long row = i / m;
-    float c = mode == 0 ? cvec[row] : (mode == 1 ? cvec[row / L] : cvec[(row / L) * m + (i % m)]);
-    if (rown) c += rown[row];
-    store_from_f32(out, i, expf(logit[i] - c) * mult);
+// One wave per row, V features per lane and step (V = 4 needs m % 4 == 0 and 16-byte aligned rows).
+template <typename T, int V>
+__global__ __launch_bounds__(256) void k_exp(const float* __restrict__ logit, T* __restrict__ out,
+                                             const float* __restrict__ cvec, long long rows, int m, int L, int mode,
+                                             float mult, const float* __restrict__ rown) {
+  long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
+  if (row >= rows) return;
+  const int lane = threadIdx.x % kWave;
+  const float rn = rown ? rown[row] : 0.f;
+  const float crow = (mode == 0 ? cvec[row] : (mode == 1 ? cvec[row / L] : 0.f)) + rn;
+  const float* cj = mode == 2 ? cvec + (row / L) * m : nullptr;
+  const float* src = logit + row * m;
+  for (int j = lane; j < m / V; j += kWave) {
+    float v[V], c[V];
+    load_v<V>(src + V * j, v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) c[e] = 0.f;
+    if (cj) load_v<V>(cj + V * j, c);
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = expf(v[e] - (c[e] + crow)) * mult;
+    if (sizeof(T) == 4) {
+      store_v<V>(reinterpret_cast<float*>(out) + row * m + V * j, v);
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) store_from_f32(out, row * m + V * j + e, v[e]);
+    }
   }
 }
 
@@ -965,8 +1029,13 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
                 fb.colmax, p.L, p.m, fb.rowmax);
     return DARK_OK;
   }
-  DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
-              fb.rowmax, mode == STAB_QUERY_ROW ? qbias : nullptr, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
+  const float* bias = mode == STAB_QUERY_ROW ? qbias : nullptr;
+  if (p.m % 4 == 0 && ((reinterpret_cast<uintptr_t>(fb.Phi) | reinterpret_cast<uintptr_t>(bias)) & 15) == 0)
+    DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat<4>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
+                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
+  else
+    DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
+                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
   if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
   return DARK_OK;
@@ -975,8 +1044,14 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
 dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
   const long long rows = pb.rows();
   const float* c = mode == STAB_QUERY_ROW ? fb.rowmax : (mode == STAB_KEY_HEAD ? fb.headmax : fb.colmax);
-  DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * pb.p.m)), dim3(256), 0, fb.Phi, fb.Phi, c, rows,
-              pb.p.m, pb.p.L, (int)mode, 1.0f, mode == STAB_KEY_FEATURE ? fb.rowmax : nullptr);
+  const float* rown = mode == STAB_KEY_FEATURE ? fb.rowmax : nullptr;
+  const unsigned grid = (unsigned)((rows + 3) / 4);
+  if (pb.p.m % 4 == 0 && ((reinterpret_cast<uintptr_t>(fb.Phi) | reinterpret_cast<uintptr_t>(c)) & 15) == 0)
+    DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 4>), dim3(grid), dim3(256), 0, fb.Phi, fb.Phi, c, rows, pb.p.m, pb.p.L,
+                (int)mode, 1.0f, rown);
+  else
+    DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 1>), dim3(grid), dim3(256), 0, fb.Phi, fb.Phi, c, rows, pb.p.m, pb.p.L,
+                (int)mode, 1.0f, rown);
   return DARK_OK;
 }
 
@@ -1020,12 +1095,27 @@ dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const flo
   DARK_TRY(features(pb, fb, M, As, is_query ? STAB_QUERY_ROW : STAB_KEY_HEAD));
   const float mult = 1.0f / std::sqrt((float)p.m);
   const float* cvec = is_query ? fb.rowmax : fb.headmax;
-  if (p.io_dtype == DARK_BF16)
-    DARK_LAUNCH(KID_EXP, pb.st, k_exp<__hip_bfloat16>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi,
-                (__hip_bfloat16*)phi, cvec, rows, p.m, p.L, is_query ? 0 : 1, mult, (const float*)nullptr);
-  else
-    DARK_LAUNCH(KID_EXP, pb.st, k_exp<float>, dim3(grid_for(rows * p.m)), dim3(256), 0, fb.Phi, (float*)phi, cvec,
-                rows, p.m, p.L, is_query ? 0 : 1, mult, (const float*)nullptr);
+  {
+    // phi is the caller's buffer: 16-byte aligned by contract, rows of m elements
+    const unsigned grid = (unsigned)((rows + 3) / 4);
+    const bool vec = p.m % 4 == 0 && (reinterpret_cast<uintptr_t>(fb.Phi) & 15) == 0;
+    const int kmode = is_query ? 0 : 1;
+    if (p.io_dtype == DARK_BF16) {
+      if (vec)
+        DARK_LAUNCH(KID_EXP, pb.st, (k_exp<__hip_bfloat16, 4>), dim3(grid), dim3(256), 0, fb.Phi, (__hip_bfloat16*)phi, cvec,
+                    rows, p.m, p.L, kmode, mult, (const float*)nullptr);
+      else
+        DARK_LAUNCH(KID_EXP, pb.st, (k_exp<__hip_bfloat16, 1>), dim3(grid), dim3(256), 0, fb.Phi, (__hip_bfloat16*)phi, cvec,
+                    rows, p.m, p.L, kmode, mult, (const float*)nullptr);
+    } else {
+      if (vec && (reinterpret_cast<uintptr_t>(phi) & 15) == 0)
+        DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 4>), dim3(grid), dim3(256), 0, fb.Phi, (float*)phi, cvec, rows, p.m, p.L,
+                    kmode, mult, (const float*)nullptr);
+      else
+        DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 1>), dim3(grid), dim3(256), 0, fb.Phi, (float*)phi, cvec, rows, p.m, p.L,
+                    kmode, mult, (const float*)nullptr);
+    }
+  }
   if (stab != nullptr) {
     long long n = is_query ? rows : pb.BH();
     // plain copy through the sum kernel (P = 1)
