@@ -556,18 +556,11 @@ __global__ __launch_bounds__(256, (RbShape<WM, WN, BM, BN>::per_cu)) void k_gemm
 template <typename T>
 __global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, long long rows, int cols, int ld,
                             int ones) {
-  long long total = rows * ld;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    long long row = i / ld;
-    int c = (int)(i % ld);
-    float v;
-    if (c < cols)
-      v = load_as_f32(src, row * cols + c);
-    else
-      v = ones ? 1.f : 0.f;
-    dst[i] = v;
-  }
+  // threadIdx.x walks the columns, threadIdx.y the rows of the block: no index division
+  const long long row = blockIdx.x * (long long)blockDim.y + threadIdx.y;
+  if (row >= rows) return;
+  for (int c = threadIdx.x; c < ld; c += blockDim.x)
+    dst[row * ld + c] = c < cols ? load_as_f32(src, row * cols + c) : (ones ? 1.f : 0.f);
 }
 
 // One wave per row: n = 1/2 |x~|^2, logits = U - n (+ bias_j) in place, rowmax.
@@ -799,17 +792,23 @@ __global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long lo
     long long bh = i / E, e = i % E;
     float* p = st + bh * nchunk * E + e;
     float run = 0.f;
-    if (!reverse) {
-      for (int c = 0; c < nchunk; ++c) {
-        float t = p[c * E];
-        p[c * E] = run;
-        run += t;
+    // eight chunks' entries are loaded before the first is overwritten: the loads do not depend on the
+    // running sum, but the compiler may not move them across the stores by itself
+    constexpr int kBatch = 8;
+    for (int c0 = 0; c0 < nchunk; c0 += kBatch) {
+      float t[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int c = reverse ? nchunk - 1 - (c0 + u) : c0 + u;
+        t[u] = c0 + u < nchunk ? p[c * E] : 0.f;
       }
-    } else {
-      for (int c = nchunk - 1; c >= 0; --c) {
-        float t = p[c * E];
-        p[c * E] = run;
-        run += t;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int c = reverse ? nchunk - 1 - (c0 + u) : c0 + u;
+        if (c0 + u < nchunk) {
+          p[c * E] = run;
+          run += t[u];
+        }
       }
     }
   }
@@ -959,12 +958,18 @@ dark_status run_gemm(const Gemm& g_in, hipStream_t st) {
 
 // Convert (or alias) an io tensor to fp32 rows with leading dimension ld.
 dark_status to_f32(const Problem& pb, const void* src, float* dst, long long rows, int cols, int ld, int ones) {
+  int tpr = 8;  // threads per row: the largest power of two not above ld, between 8 and 256
+  while (tpr * 2 <= ld && tpr < 256) tpr *= 2;
+  const dim3 block(tpr, 256 / tpr);
+  const long long blocks = (rows + block.y - 1) / block.y;
+  if (blocks > 0x7fffffffLL) return DARK_EUNSUPPORTED;
+  if (blocks <= 0) return DARK_OK;
   if (pb.p.io_dtype == DARK_BF16)
-    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<__hip_bfloat16>, dim3(grid_for(rows * ld)), dim3(256), 0,
+    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<__hip_bfloat16>, dim3((unsigned)blocks), block, 0,
                 (const __hip_bfloat16*)src, dst, rows, cols, ld, ones);
   else
-    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<float>, dim3(grid_for(rows * ld)), dim3(256), 0, (const float*)src, dst,
-                rows, cols, ld, ones);
+    DARK_LAUNCH(KID_LOAD, pb.st, k_load_rows<float>, dim3((unsigned)blocks), block, 0, (const float*)src, dst, rows, cols,
+                ld, ones);
   return DARK_OK;
 }
 
