@@ -211,7 +211,8 @@ def test_bitwise_deterministic():
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("shape", [(2, 2, 200, 24, 16, 48, 20), (1, 1, 130, 16, 16, 64, 16),
-                                   (1, 2, 300, 64, 64, 256, 64)])  # the last: every GEMM tile shape, ragged
+                                   (1, 2, 300, 64, 64, 256, 64),   # every GEMM tile shape, ragged
+                                   (1, 1, 70, 7, 5, 33, 3)])       # odd sizes: the general GEMM kernel throughout
 def test_backward_small(shape, causal, bf16):
     B, H, L, d, r, m, dv = shape
     inp = U.random_problem(9, B, H, L, d, r, m, dv, bf16=bf16, backward=True)
