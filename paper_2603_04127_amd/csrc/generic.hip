@@ -1061,10 +1061,11 @@ dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
 }
 
 // Length of the L-slices whose partial states are summed in a fixed order: short enough that a
-// states GEMM (four 64-row tiles per (b,h, slice)) has about a thousand workgroups, whole 64-token
-// multiples, at most 4096.  A function of the shape only, so results stay reproducible.
+// states GEMM (two 128-row tiles per (b,h, slice) at m = 256) has about a thousand workgroups, whole
+// 64-token multiples, at least 256 and at most 4096.  A function of the shape only, so results stay
+// reproducible.
 int slice_len(const Problem& pb) {
-  long long want = 1024 / (pb.BH() * 4 > 0 ? pb.BH() * 4 : 1);
+  long long want = 1024 / (pb.BH() * 2 > 0 ? pb.BH() * 2 : 1);
   if (want < 1) want = 1;
   long long sl = (pb.p.L + want - 1) / want;
   sl = ((sl + 63) / 64) * 64;
