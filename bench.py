@@ -49,6 +49,8 @@ def algorithmic_work(cfg):
         "fused_causal_state": ("hbm", th * (d + dv) * s_in),
         "fused_key_norms": ("hbm", th * d * s_in),
         "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
+        # dark_featurize, per launch (one tensor): rows read once, features written once
+        "fused_featurize": ("hbm", th * (d + m) * s_in),
     }
     return th * f_tok, th * b_tok, per_kernel
 
@@ -74,6 +76,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2, the headline)")
     ap.add_argument("--path", choices=["auto", "f32", "fused"], default="auto")
+    ap.add_argument("--op", choices=["attn", "featurize"], default="attn",
+                    help="attn (default): the attention step the metric is quoted on; featurize: dark_featurize of "
+                         "the configuration's Q (query contract) and K (key contract), a side measurement of that "
+                         "entry point (value = rows/s)")
     ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -115,6 +121,10 @@ def main():
     gen_s = time.time() - t0
 
     def step(c):
+        if args.op == "featurize":
+            dk.dark_featurize(c["Q"], c["M"], c["W"], True, path=path)
+            dk.dark_featurize(c["K"], c["M"], c["W"], False, path=path)
+            return
         if cfg.causal:
             dk.dark_attn_causal_fwd(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"], chunk=cfg.chunk, path=path)
         else:
@@ -140,6 +150,11 @@ def main():
     ms = dt / args.steps * 1e3
     tokens = cfg.B * cfg.L
     flops, nbytes, per_kernel = algorithmic_work(cfg)
+    if args.op == "featurize":
+        # two tensors of B*H*L rows each: projections (2dm + 2dr flops per row), rows in, features out
+        th = cfg.B * cfg.H * cfg.L
+        flops = 2 * th * (2 * cfg.d * cfg.m + 2 * cfg.d * cfg.r)
+        nbytes = 2 * per_kernel["fused_featurize"][1]
 
     # Per-kernel device time: a second loop in which the library attaches start/stop events to every
     # launch (stamped with the kernel's own begin and end on the launch stream; the stream is drained
@@ -162,14 +177,16 @@ def main():
                 "avg_kernel_us": kernels[dom]["avg_us"], "launches_per_step": kernels[dom]["launches"] / args.steps}
 
     line = {
-        "metric": "DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)",
-        "value": tokens / (ms * 1e-3),
-        "unit": "tokens/s",
+        "metric": ("DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)" if args.op == "attn"
+                   else "dark_featurize rows/sec (query rows + key rows); % of MFMA/HBM roofline (1 GPU)"),
+        "value": (tokens if args.op == "attn" else 2 * cfg.B * cfg.H * cfg.L) / (ms * 1e-3),
+        "unit": "tokens/s" if args.op == "attn" else "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "H": cfg.H, "L": cfg.L, "d": cfg.d, "m": cfg.m, "dv": cfg.dv,
-                   "causal": cfg.causal, "backward": cfg.backward, "path": args.path, "input_copies": len(copies)},
+                   "causal": cfg.causal, "backward": cfg.backward, "path": args.path, "input_copies": len(copies),
+                   "op": args.op},
         "tflops": flops / (ms * 1e-3) / 1e12,
         "algorithmic_gbps": nbytes / (ms * 1e-3) / 1e9,
         "step_frac_of_binding_roofline": max(flops / 2.5e15, nbytes / 8e12) / (ms * 1e-3),
@@ -178,7 +195,7 @@ def main():
         "input_generation_s": gen_s,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.op == "attn":
         # The oracle as it stands, on a bounded sample of the same workload: whole heads of batch 0
         # until about --cpu-seconds of CPU time have been spent.
         from oracle import dark_oracle as O
