@@ -842,10 +842,12 @@ __global__ __launch_bounds__(256) void k_dnd(const float* __restrict__ ND, const
 // first dv of them are dV), so it needs no pass over the m features.  For a query row the sum is
 // N_i . dN_i + D_i dD_i = 0 identically (the output does not change when a query's features are all
 // scaled alike), so the query side has no such term.
-//   dXt = dn * Xt (in place), and dV = the first dv columns of dVx if asked for.
+//   dXt = alpha dn * Xt (in place; alpha = sqrt(scale), the factor x~ carries from x' = sqrt(scale) x is
+//   applied here so that the products that use dXt need no scale of their own), and dV = the first dv
+//   columns of dVx if asked for.
 __global__ __launch_bounds__(256) void k_key_dn(const float* __restrict__ Vx, const float* __restrict__ dVx,
                                                 float* __restrict__ Xt, float* __restrict__ dV, long long rows, int dv,
-                                                int ld, int r) {
+                                                int ld, int r, float alpha) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
@@ -857,7 +859,7 @@ __global__ __launch_bounds__(256) void k_key_dn(const float* __restrict__ Vx, co
     s = fmaf(vx[c], g, s);
     if (dV != nullptr && c < dv) dV[row * dv + c] = g;
   }
-  const float dn = -wave_sum(s);
+  const float dn = -alpha * wave_sum(s);
   float* xt = Xt + row * r;
   for (int t = lane; t < r; t += kWave) xt[t] *= dn;
 }
@@ -1189,8 +1191,8 @@ inline void bhl(long long& s0, long long& s1, long long& s2, const dark_params& 
 }
 
 // States: per piece (slice or chunk) of the sequence, Phi_piece^T X_piece  ->  dst[bh][piece][mm][ldd] (nn columns used).
-dark_status piece_states(const Problem& pb, const float* Phi, int mm, const float* X, int nn, int ldx, float* dst,
-                         int ldd, int piece, int npiece, float beta) {
+Gemm make_piece_states(const Problem& pb, const float* Phi, int mm, const float* X, int nn, int ldx, float* dst, int ldd,
+                       int piece, int npiece, float beta) {
   const dark_params& p = pb.p;
   Gemm g = gemm_base(Phi, X, dst, mm, nn, piece);
   g.sAm = 1; g.sAk = mm; g.sBk = ldx; g.sBn = 1; g.sCm = ldd; g.sCn = 1;
@@ -1202,7 +1204,12 @@ dark_status piece_states(const Problem& pb, const float* Phi, int mm, const floa
   g.sC0 = g.sC1 * p.H;
   g.klim = p.L; g.kstep = piece;
   g.beta = beta;
-  return run_gemm(g, pb.st);
+  return g;
+}
+
+dark_status piece_states(const Problem& pb, const float* Phi, int mm, const float* X, int nn, int ldx, float* dst,
+                         int ldd, int piece, int npiece, float beta) {
+  return run_gemm(make_piece_states(pb, Phi, mm, X, nn, ldx, dst, ldd, piece, npiece, beta), pb.st);
 }
 
 // Rows times a per-(b,h[,chunk]) matrix:  dst[rows_piece][nn] (+)= X_piece[rows][kk] * St(^T).
@@ -1347,9 +1354,9 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
 //   dV_l = R_l[:, :dv]^T Phi_K,l
 //   dPhi_Q,i = [S_i | z_i] [dN_i | dD_i]^T,   dPhi_K,l = R_l [v_l | 1]^T
 //   dlogit = dPhi * Phi (applied in the epilogue of the GEMM that forms dPhi)
-//   dn_l = -sum_j dlogit_K,lj = -[v_l | 1] . (R_l^T Phi_K,l),  dXt_K = dn Xt_K;  the query rows have dn = 0
-//   dQ = dlogit_Q A_s,   dK = dlogit_K A_s + sqrt(scale) dXt_K M
-//   dM_h = sum_b sqrt(scale) ( W^T (dlogit_Q^T Q + dlogit_K^T K) + dXt_K^T K )
+//   dn_l = -sum_j dlogit_K,lj = -[v_l | 1] . (R_l^T Phi_K,l),  dXt_K = sqrt(scale) dn Xt_K;  the query rows have dn = 0
+//   dQ = dlogit_Q A_s,   dK = dlogit_K A_s + dXt_K M
+//   dM_h = sum_b ( sqrt(scale) W^T (dlogit_Q^T Q + dlogit_K^T K) + dXt_K^T K )
 // Stabilising shifts cancel between dPhi and Phi, so the stabilised features are used
 // throughout.  Causal: states are exclusive prefix (S) / suffix (R) sums over chunks plus
 // masked within-chunk tiles  P = tril(Phi_Q Phi_K^T),  E = tril([dN|dD] [V|1]^T).
@@ -1422,43 +1429,45 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   // dPq / dPk hold the logit gradients; dXt_K (in the key Xt buffer) and dV
   if (need_dvx)
     DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_key_dn, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, b.Vx, dVx, b.k.Xt, dV, rows,
-                p.dv, ldv, p.r);
+                p.dv, ldv, p.r, std::sqrt(pb.scale));
   const float alpha = std::sqrt(pb.scale);
   const long long as_elems = (long long)p.m * p.d, m_elems = (long long)p.r * p.d;
   for (int side = 0; side < 2; ++side) {
     float* dX = side == 0 ? dQ : dK;
     if (!dX) continue;
     float* dl = side == 0 ? dPq : dPk;
-    DARK_TRY(rows_times_state(pb, dl, p.m, p.m, b.As, p.d, false, false, as_elems, dX, p.d, p.d, p.L, 1, 1.f, 0.f,
-                              true));
-    if (side == 0) continue;  // no norm term on the query side
-    // M is [H, r, d] shared over the batch: per-head stride only.
-    Gemm g = gemm_base(b.k.Xt, M, dX, p.L, p.d, p.r);
-    g.sAm = p.r; g.sAk = 1; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
-    g.nb0 = p.B; g.nb1 = p.H;
-    g.sA0 = (long long)p.H * p.L * p.r; g.sA1 = (long long)p.L * p.r;
-    g.sB0 = 0; g.sB1 = m_elems;
-    g.sC0 = (long long)p.H * p.L * p.d; g.sC1 = (long long)p.L * p.d;
-    g.alpha = alpha; g.beta = 1.f;
+    Gemm g = make_rows_times_state(pb, dl, p.m, p.m, b.As, p.d, false, false, as_elems, dX, p.d, p.d, p.L, 1, 1.f, 0.f,
+                                   true);
+    if (side == 1) {
+      // the norm term (keys only): + dXt_K M, with M [H, r, d] shared over the batch
+      Gemm x = gemm_base(b.k.Xt, M, dX, p.L, p.d, p.r);
+      x.sAm = p.r; x.sAk = 1; x.sBk = p.d; x.sBn = 1;
+      x.sA0 = (long long)p.H * p.L * p.r; x.sA1 = (long long)p.L * p.r;
+      x.sB0 = 0; x.sB1 = m_elems;
+      add_product(g, x);
+    }
     DARK_TRY(run_gemm(g, pb.st));
   }
   if (dM) {
     const int SL = slice_len(pb);
-    DARK_TRY(piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 0.f));
-    DARK_TRY(piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 1.f));
+    {  // Tpart = dlogit_Q^T Q + dlogit_K^T K per slice, one pass
+      Gemm g = make_piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 0.f);
+      add_product(g, make_piece_states(pb, dPk, p.m, b.k.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 0.f));
+      DARK_TRY(run_gemm(g, pb.st));
+    }
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * as_elems)), dim3(256), 0, Tpart, T,
                 pb.BH(), b.P, as_elems, as_elems * b.P, as_elems);
     DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, p.d, SL, b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * m_elems)), dim3(256), 0, T2part, T2,
                 pb.BH(), b.P, m_elems, m_elems * b.P, m_elems);
-    // T2_bh = alpha * W_h^T T_bh + alpha * T2_bh
+    // T2_bh = alpha * W_h^T T_bh + T2_bh
     Gemm g = gemm_base(W, T, T2, p.r, p.d, p.m);
     g.sAm = 1; g.sAk = p.r; g.sBk = p.d; g.sBn = 1; g.sCm = p.d; g.sCn = 1;
     g.nb0 = p.B; g.nb1 = p.H;
     g.sA0 = 0; g.sA1 = p.w_shared ? 0 : (long long)p.m * p.r;
     g.sB0 = as_elems * p.H; g.sB1 = as_elems;
     g.sC0 = m_elems * p.H; g.sC1 = m_elems;
-    g.alpha = alpha; g.beta = alpha;
+    g.alpha = alpha; g.beta = 1.f;  // dXt carries its factor already
     DARK_TRY(run_gemm(g, pb.st));
     // dM_h = sum_b T2_bh, b ascending
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for((long long)p.H * m_elems)), dim3(256), 0, T2, dM,
