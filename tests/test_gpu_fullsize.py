@@ -26,7 +26,7 @@ def test_bidirectional_configs(n, heads):
     for b, h in heads:
         want = O.attn_bidir(*U.head(inp, b, h))
         e = U.assert_close(_np(out[b, h]), want, U.TOL["bf16"], f"config {n} head {(b, h)}")
-        print(f"config {n} head {(b, h)}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+        print(f"config {n} head {(b, h)}: {U.fmt(e)}")
 
 
 def test_causal_config3():
@@ -39,7 +39,7 @@ def test_causal_config3():
     for b, h in [(0, 0), (3, 15)]:
         want = O.attn_causal(*U.head(inp, b, h), rows=rows)
         e = U.assert_close(_np(out[b, h])[rows], want, U.TOL["bf16"], f"config 3 head {(b, h)}")
-        print(f"config 3 head {(b, h)}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+        print(f"config 3 head {(b, h)}: {U.fmt(e)}")
 
 
 def test_finetune_config5():
@@ -59,6 +59,6 @@ def test_finetune_config5():
             U.assert_close(_np(out[b, h]), O.attn_brute(Q, K, V, M, W, True), U.TOL["bf16"], "config 5 out")
         for name, want in (("dQ", dQ), ("dK", dK), ("dV", dV)):
             e = U.assert_close(_np(g[name][b, h]), want, U.TOL["bf16"], f"config 5 {name}[{b},{h}]")
-            print(f"config 5 {name}[{b},{h}]: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+            print(f"config 5 {name}[{b},{h}]: {U.fmt(e)}")
     e = U.assert_close(_np(g["dM"][h]), dM, U.TOL["bf16"], "config 5 dM")
-    print(f"config 5 dM[{h}]: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+    print(f"config 5 dM[{h}]: {U.fmt(e)}")

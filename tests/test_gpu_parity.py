@@ -259,7 +259,7 @@ def test_fused_forward(shape, out_f32):
     torch.cuda.synchronize()
     assert out.dtype == (torch.float32 if out_f32 else torch.bfloat16)
     e = U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], f"fused {shape}")
-    print(f"fused {shape} out_f32={out_f32}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+    print(f"fused {shape} out_f32={out_f32}: {U.fmt(e)}")
 
 
 def test_fused_large_logit_range():
@@ -294,7 +294,7 @@ def test_fused_long_slices(L, wgs, monkeypatch):
     out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
     torch.cuda.synchronize()
     e = U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], f"fused long slices L={L} wgs={wgs}")
-    print(f"fused long slices L={L} wgs={wgs}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+    print(f"fused long slices L={L} wgs={wgs}: {U.fmt(e)}")
 
 
 def test_fused_shift_raised_mid_slice(monkeypatch):
@@ -345,7 +345,7 @@ def test_fused_causal_forward(shape, out_f32):
     torch.cuda.synchronize()
     assert out.dtype == (torch.float32 if out_f32 else torch.bfloat16)
     e = U.assert_close(_np(out), U.oracle_attn(inp, True), U.TOL["bf16"], f"fused causal {shape}")
-    print(f"fused causal {shape} out_f32={out_f32}: normalised max err {e[0]:.3e}, row-wise {e[1]:.3e}")
+    print(f"fused causal {shape} out_f32={out_f32}: {U.fmt(e)}")
 
 
 def test_fused_causal_first_row_and_last_row():
