@@ -46,7 +46,8 @@ typedef enum {
   DARK_EUNSUPPORTED = 2, /* shape / dtype not supported by the requested path */
   DARK_EWORKSPACE = 3,   /* ws == NULL or ws_bytes too small */
   DARK_EALIGN = 4,       /* a pointer is not 16-byte aligned (ws: 256) */
-  DARK_EHIP = 5          /* a HIP runtime call failed (launch error) */
+  DARK_EHIP = 5,         /* a HIP runtime call failed (launch error) */
+  DARK_ESCRATCH = 6      /* dark_attn_fwd_static: the problem needs more than the static scratch */
 } dark_status;
 
 typedef enum { DARK_F32 = 0, DARK_BF16 = 1 } dark_dtype;
@@ -114,6 +115,24 @@ dark_status dark_featurize(const dark_params* p, const void* X, const float* M, 
 dark_status dark_attn_fwd(const dark_params* p, const void* Q, const void* K, const void* V,
                           const float* M, const float* W, void* out,
                           void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * dark_attn_fwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bitwise the same result as
+ * dark_attn_fwd, minus `ws`: the scratch is a fixed array of
+ * DARK_STATIC_SCRATCH_BYTES in device memory that every GPU the library runs on
+ * holds until the process ends.  The call allocates and frees nothing.  A problem
+ * whose dark_workspace_bytes(p, DARK_OP_ATTN_FWD, 0) exceeds
+ * dark_static_scratch_bytes() is rejected with DARK_ESCRATCH before any HIP call.
+ * All calls on one GPU share that GPU's array, which keeps the last call's
+ * contents (every part that is read is written first by the same call): calls
+ * that overlap on one GPU (two streams, two threads) race; order them.
+ */
+#define DARK_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+size_t dark_static_scratch_bytes(void);
+dark_status dark_attn_fwd_static(const dark_params* p, const void* Q, const void* K, const void* V,
+                                 const float* M, const float* W, void* out, void* hip_stream);
 
 /*
  * Causal form: out_i uses only keys l <= i (prefix sums of S and z).  The

@@ -15,7 +15,7 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdark.so")
 
-DARK_OK, DARK_EINVAL, DARK_EUNSUPPORTED, DARK_EWORKSPACE, DARK_EALIGN, DARK_EHIP = range(6)
+DARK_OK, DARK_EINVAL, DARK_EUNSUPPORTED, DARK_EWORKSPACE, DARK_EALIGN, DARK_EHIP, DARK_ESCRATCH = range(7)
 DARK_F32, DARK_BF16 = 0, 1
 OP_FEATURIZE, OP_ATTN_FWD, OP_ATTN_CAUSAL_FWD, OP_ATTN_BWD = range(4)
 PATH_AUTO, PATH_F32, PATH_FUSED = range(3)
@@ -60,6 +60,9 @@ def lib() -> ctypes.CDLL:
     for f in (L.dark_attn_fwd, L.dark_attn_causal_fwd):
         f.restype = i32
         f.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_attn_fwd_static.restype = i32
+    L.dark_attn_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
+    L.dark_static_scratch_bytes.restype = sz
     L.dark_attn_bwd.restype = i32
     L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_timing_enable.argtypes = [i32]
@@ -187,6 +190,22 @@ def _attn(fn_name, op, Q, K, V, M, W, out, chunk, scale, path, out_dtype):
 def dark_attn_fwd(Q, K, V, M, W, *, out=None, scale=0.0, path=PATH_AUTO, out_dtype=None):
     """Bidirectional random-feature attention, out [B,H,L,dv]."""
     return _attn("dark_attn_fwd", OP_ATTN_FWD, Q, K, V, M, W, out, 0, scale, path, out_dtype)
+
+
+def dark_attn_fwd_static(Q, K, V, M, W, out, *, scale=0.0, path=PATH_AUTO):
+    """dark_attn_fwd on the library's static scratch: no workspace, no allocation (``out`` is the caller's)."""
+    p = _params_from(Q, V, M, W, out_dtype=out.dtype, scale=scale, path=path)
+    if K.shape != Q.shape or V.shape[:3] != Q.shape[:3] or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V shapes/dtypes disagree")
+    if tuple(out.shape) != tuple(V.shape):
+        raise ValueError("out must have the shape of V")
+    _check(lib().dark_attn_fwd_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(out),
+                                      _stream()), "dark_attn_fwd_static")
+    return out
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().dark_static_scratch_bytes())
 
 
 def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None):

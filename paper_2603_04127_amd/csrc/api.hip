@@ -120,6 +120,28 @@ static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const 
   return DARK_EINVAL;
 }
 
+// ---------------------------------------------------------------------------
+// Scratch of the entry point that allocates nothing (dark_attn_fwd_static): a fixed
+// array in device memory, one copy per GPU.  In host code the array's name is only a
+// stand-in: its device address is asked for once per device and kept.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = DARK_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+
+static dark_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DARK_EHIP;
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return DARK_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DARK_OK;
+}
+
 static size_t measure(const Problem& pb, int op, bool causal) {
   Arena ar(nullptr, 0);
   // In measuring mode the paths only walk their allocation plan; pointers are unused.
@@ -145,6 +167,7 @@ const char* dark_status_string(dark_status s) {
     case DARK_EWORKSPACE: return "workspace missing or too small";
     case DARK_EALIGN: return "misaligned pointer";
     case DARK_EHIP: return "HIP runtime error";
+    case DARK_ESCRATCH: return "problem needs more scratch than the static buffer of dark_attn_fwd_static holds";
   }
   return "unknown status";
 }
@@ -200,6 +223,29 @@ static dark_status attn_common(const dark_params* p, int op, const void* Q, cons
 dark_status dark_attn_fwd(const dark_params* p, const void* Q, const void* K, const void* V, const float* M,
                           const float* W, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
   return attn_common(p, DARK_OP_ATTN_FWD, Q, K, V, M, W, out, ws, ws_bytes, hip_stream);
+}
+
+size_t dark_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+dark_status dark_attn_fwd_static(const dark_params* p, const void* Q, const void* K, const void* V, const float* M,
+                                 const float* W, void* out, void* hip_stream) {
+  Problem pb;
+  DARK_TRY(check_params(p, &pb));
+  if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;
+  if (!Q || !K || !V || !M || !W || !out) return DARK_EINVAL;
+  if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
+      !aligned(out, 16))
+    return DARK_EALIGN;
+  dark_status err;
+  (void)use_fused(pb, DARK_OP_ATTN_FWD, false, &err);
+  if (err != DARK_OK) return err;
+  if (measure(pb, DARK_OP_ATTN_FWD, false) > kStaticScratchBytes) return DARK_ESCRATCH;  // before any HIP call
+  void* ws = nullptr;
+  DARK_TRY(static_scratch(&ws));
+  pb.st = static_cast<hipStream_t>(hip_stream);
+  Arena ar(ws, kStaticScratchBytes);
+  return run(pb, ar, DARK_OP_ATTN_FWD, false, Q, K, V, M, W, nullptr, out, nullptr, 0, nullptr, nullptr, nullptr,
+             nullptr);
 }
 
 dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void* K, const void* V,
