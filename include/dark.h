@@ -77,6 +77,13 @@ typedef struct {
   float scale;       /* 0 = 1/sqrt(d) */
   int32_t w_shared;  /* W is [m, r] for all heads */
   int32_t path;      /* dark_path */
+  /* Schedule overrides of the fused MFMA kernels, for tests and tuning; 0 = the library's choice.
+   * They change how many slices a sequence is cut into, hence dark_workspace_bytes(), the order of
+   * summation and with it the low bits of the result (never the mathematics).  Negative: DARK_EINVAL. */
+  int32_t sched_kv_wgs;   /* bidirectional key/value pass: workgroups to aim for (default 512; 256 at d = 128) */
+  int32_t sched_ro_wgs;   /* bidirectional readout: workgroups to aim for (default 256) */
+  int32_t sched_cs_wgs;   /* causal pass: workgroups (slices over all (b,h)) to aim for (default 256) */
+  int32_t sched_cs_state; /* causal pass at d = 64: 1 = slice states by the 8-wave state kernel, else the key/value pass */
 } dark_params;
 
 /* Library version (major*10000 + minor*100 + patch). */

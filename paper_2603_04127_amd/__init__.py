@@ -27,6 +27,8 @@ class DarkParams(ctypes.Structure):
         ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("m", ctypes.c_int32), ("dv", ctypes.c_int32),
         ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("scale", ctypes.c_float), ("w_shared", ctypes.c_int32), ("path", ctypes.c_int32),
+        ("sched_kv_wgs", ctypes.c_int32), ("sched_ro_wgs", ctypes.c_int32), ("sched_cs_wgs", ctypes.c_int32),
+        ("sched_cs_state", ctypes.c_int32),
     ]
 
 
@@ -81,9 +83,15 @@ def status_string(status: int) -> str:
 
 
 def make_params(B, H, L, d, r, m, dv, *, io_dtype=DARK_F32, out_dtype=None, chunk=0, scale=0.0, w_shared=False,
-                path=PATH_AUTO) -> DarkParams:
+                path=PATH_AUTO, sched=None) -> DarkParams:
+    """`sched`: optional dict of the schedule overrides of dark_params (kv_wgs, ro_wgs, cs_wgs, cs_state)."""
+    sched = sched or {}
+    unknown = set(sched) - {"kv_wgs", "ro_wgs", "cs_wgs", "cs_state"}
+    if unknown:
+        raise ValueError(f"unknown schedule override(s) {sorted(unknown)}")
     return DarkParams(B, H, L, d, r, m, dv, chunk, io_dtype, io_dtype if out_dtype is None else out_dtype,
-                      float(scale), int(bool(w_shared)), path)
+                      float(scale), int(bool(w_shared)), path, int(sched.get("kv_wgs", 0)), int(sched.get("ro_wgs", 0)),
+                      int(sched.get("cs_wgs", 0)), int(sched.get("cs_state", 0)))
 
 
 def workspace_bytes(p: DarkParams, op: int, causal: bool = False) -> int:
@@ -135,7 +143,7 @@ def _workspace(nbytes: int, device):
     return buf
 
 
-def _params_from(Q, V, M, W, *, out_dtype=None, chunk=0, scale=0.0, path=PATH_AUTO) -> DarkParams:
+def _params_from(Q, V, M, W, *, out_dtype=None, chunk=0, scale=0.0, path=PATH_AUTO, sched=None) -> DarkParams:
     B, H, L, d = Q.shape
     dv = V.shape[-1] if V is not None else 1
     r = M.shape[-2]
@@ -149,7 +157,7 @@ def _params_from(Q, V, M, W, *, out_dtype=None, chunk=0, scale=0.0, path=PATH_AU
     io = _dtype_code(Q)
     od = io if out_dtype is None else (DARK_BF16 if out_dtype == torch.bfloat16 else DARK_F32)
     return make_params(B, H, L, d, r, m, dv, io_dtype=io, out_dtype=od, chunk=chunk, scale=scale, w_shared=w_shared,
-                       path=path)
+                       path=path, sched=sched)
 
 
 def _check(status: int, where: str):
@@ -171,9 +179,9 @@ def dark_featurize(X, M, W, is_query: bool, *, scale=0.0, path=PATH_AUTO):
     return phi, stab
 
 
-def _attn(fn_name, op, Q, K, V, M, W, out, chunk, scale, path, out_dtype):
+def _attn(fn_name, op, Q, K, V, M, W, out, chunk, scale, path, out_dtype, sched=None):
     torch = _torch()
-    p = _params_from(Q, V, M, W, out_dtype=out_dtype, chunk=chunk, scale=scale, path=path)
+    p = _params_from(Q, V, M, W, out_dtype=out_dtype, chunk=chunk, scale=scale, path=path, sched=sched)
     if K.shape != Q.shape or V.shape[:3] != Q.shape[:3] or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise ValueError("Q, K, V shapes/dtypes disagree")
     if out is None:
@@ -187,9 +195,9 @@ def _attn(fn_name, op, Q, K, V, M, W, out, chunk, scale, path, out_dtype):
     return out
 
 
-def dark_attn_fwd(Q, K, V, M, W, *, out=None, scale=0.0, path=PATH_AUTO, out_dtype=None):
+def dark_attn_fwd(Q, K, V, M, W, *, out=None, scale=0.0, path=PATH_AUTO, out_dtype=None, sched=None):
     """Bidirectional random-feature attention, out [B,H,L,dv]."""
-    return _attn("dark_attn_fwd", OP_ATTN_FWD, Q, K, V, M, W, out, 0, scale, path, out_dtype)
+    return _attn("dark_attn_fwd", OP_ATTN_FWD, Q, K, V, M, W, out, 0, scale, path, out_dtype, sched)
 
 
 def dark_attn_fwd_static(Q, K, V, M, W, out, *, scale=0.0, path=PATH_AUTO):
@@ -208,9 +216,9 @@ def static_scratch_bytes() -> int:
     return int(lib().dark_static_scratch_bytes())
 
 
-def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None):
+def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None, sched=None):
     """Causal random-feature attention (keys l <= i), out [B,H,L,dv]."""
-    return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype)
+    return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype, sched)
 
 
 def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path=PATH_AUTO, need=("dQ", "dK", "dV", "dM")):

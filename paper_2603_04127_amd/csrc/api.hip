@@ -73,6 +73,7 @@ dark_status check_params(const dark_params* p, Problem* out) {
   if (p->out_dtype != DARK_F32 && p->out_dtype != DARK_BF16) return DARK_EINVAL;
   if (p->path != DARK_PATH_AUTO && p->path != DARK_PATH_F32 && p->path != DARK_PATH_FUSED) return DARK_EINVAL;
   if (!(p->scale >= 0.f) || std::isinf(p->scale)) return DARK_EINVAL;
+  if (p->sched_kv_wgs < 0 || p->sched_ro_wgs < 0 || p->sched_cs_wgs < 0 || p->sched_cs_state < 0) return DARK_EINVAL;
   // Index arithmetic is 64-bit, but single dimensions must stay well inside int32.
   if ((long long)p->L * p->m > (1LL << 40) || p->d > 65536 || p->m > (1 << 20) || p->dv > 65536 || p->r > 65536)
     return DARK_EUNSUPPORTED;

@@ -18,7 +18,6 @@
 //   k_kv_merge   fixed-order merge of the slice states (deterministic), bf16 S^T for the readout
 //   k_readout    per (b,h, token range): out = phi_Q S / phi_Q z
 #include <cmath>
-#include <cstdlib>
 
 #include "fused_common.h"
 
@@ -1046,13 +1045,6 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 
 constexpr size_t kLdsMax = 160 * 1024;
 
-int env_int(const char* name, int dflt) {
-  const char* s = std::getenv(name);
-  if (!s || !*s) return dflt;
-  int v = std::atoi(s);
-  return v > 0 ? v : dflt;
-}
-
 struct Plan {
   int P, slice_len, nfb, n_work, kv_grid;
   int ro_nw, chunks_per_bh, n_items, items_per_wg, ro_grid;
@@ -1065,7 +1057,7 @@ Plan make_plan(const Problem& pb) {
   const long long BH = pb.BH();
   // K pass: about two workgroups per CU (256 CUs); slices are whole tiles.
   // (d = 128: the 8-wave slice-state kernel, one workgroup per CU)
-  int target = env_int("DARK_KV_WGS", p.d == 128 ? 256 : 512);
+  int target = p.sched_kv_wgs > 0 ? p.sched_kv_wgs : (p.d == 128 ? 256 : 512);
   long long want = target / (BH * pl.nfb);  // rounding down keeps all workgroups co-resident
   if (want < 1) want = 1;
   int sl = (int)((p.L + want - 1) / want);
@@ -1081,7 +1073,7 @@ Plan make_plan(const Problem& pb) {
   const int ro_tok = 64 * pl.ro_nw;
   pl.chunks_per_bh = (p.L + ro_tok - 1) / ro_tok;
   pl.n_items = (int)(BH * pl.chunks_per_bh);
-  const int ro_wgs = env_int("DARK_RO_WGS", 256);
+  const int ro_wgs = p.sched_ro_wgs > 0 ? p.sched_ro_wgs : 256;
   pl.items_per_wg = (pl.n_items + ro_wgs - 1) / ro_wgs;
   pl.ro_grid = (pl.n_items + pl.items_per_wg - 1) / pl.items_per_wg;
   return pl;

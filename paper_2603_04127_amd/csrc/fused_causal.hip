@@ -750,13 +750,6 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
   }
 }
 
-int env_int(const char* name, int dflt) {
-  const char* s = std::getenv(name);
-  if (s == nullptr || *s == 0) return dflt;
-  const int v = std::atoi(s);
-  return v > 0 ? v : dflt;
-}
-
 template <int D>
 dark_status launch_key_norms(const Problem& pb, const void* K, const _Float16* Mh, float* nrm) {
   const dark_params& p = pb.p;
@@ -792,7 +785,7 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
                           float* cpre, float* nrm, void* out, int P, int slice_len) {
   const dark_params& p = pb.p;
   const unsigned BH = (unsigned)pb.BH();
-  if (D == 128 || env_int("DARK_CS_STATE", 2) == 1) {
+  if (D == 128 || p.sched_cs_state == 1) {
     DARK_TRY((launch_slice_state<D>(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, P, slice_len)));
   } else {
     DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
@@ -831,7 +824,7 @@ dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, c
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
   // Slices: one workgroup per CU (one fits), whole 64-token tiles of the key pass.
-  long long want = env_int("DARK_CS_WGS", 256) / BH;
+  long long want = (p.sched_cs_wgs > 0 ? p.sched_cs_wgs : 256) / BH;
   want = want < 1 ? 1 : (want > kMaxP ? kMaxP : want);
   int sl = (int)((p.L + want - 1) / want);
   sl = ((sl + kTile - 1) / kTile) * kTile;

@@ -60,7 +60,8 @@ def test_argument_errors_before_any_device_work():
     assert f(ctypes.byref(p), A, A, A, A, A, A, None, 0, None) == dk.DARK_EWORKSPACE
     assert f(ctypes.byref(p), A, A, A, A, A, A, ws, 16, None) == dk.DARK_EWORKSPACE
     assert f(ctypes.byref(p), A, A, A, A, A, A, ws + 16, big, None) == dk.DARK_EALIGN
-    for bad in (dict(m=0), dict(H=0), dict(L=-1), dict(io_dtype=7), dict(path=9), dict(scale=-1.0), dict(chunk=-2)):
+    for bad in (dict(m=0), dict(H=0), dict(L=-1), dict(io_dtype=7), dict(path=9), dict(scale=-1.0), dict(chunk=-2),
+                dict(sched={"kv_wgs": -1})):
         q = _p(**bad)
         assert f(ctypes.byref(q), A, A, A, A, A, A, ws, big, None) == dk.DARK_EINVAL, bad
     assert f(ctypes.byref(_p(chunk=4096)), A, A, A, A, A, A, ws, big, None) == dk.DARK_EUNSUPPORTED

@@ -284,24 +284,22 @@ def test_fused_matches_f32_path_and_is_deterministic():
 
 
 @pytest.mark.parametrize("L,wgs", [(1000, 2), (1000, 6), (4096 + 37, 2), (200, 2)])
-def test_fused_long_slices(L, wgs, monkeypatch):
+def test_fused_long_slices(L, wgs):
     """Few workgroups in the key/value pass, so that one slice runs over many tiles (the small shapes
     above give every workgroup one or two): the pass's buffers rotate several times, with a ragged last
     tile."""
-    monkeypatch.setenv("DARK_KV_WGS", str(wgs))
     inp = U.random_problem(21, 1, 2, L, 64, 64, 256, 64, bf16=True, amp=2.0)
     dev = U.to_device(inp, True)
-    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED, sched={"kv_wgs": wgs})
     torch.cuda.synchronize()
     e = U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], f"fused long slices L={L} wgs={wgs}")
     print(f"fused long slices L={L} wgs={wgs}: {U.fmt(e)}")
 
 
-def test_fused_shift_raised_mid_slice(monkeypatch):
+def test_fused_shift_raised_mid_slice():
     """Keys ordered by growing norm inside one long slice: the per-feature shifts chosen from the first
     block are far too low for the later ones, so the rare path (raise the shift, rescale the state) runs
     in the middle of the slice."""
-    monkeypatch.setenv("DARK_KV_WGS", "1")
     inp = U.random_problem(22, 1, 1, 900, 64, 64, 256, 64, bf16=True, amp=1.0)
     ramp = np.linspace(0.02, 8.0, 900, dtype=np.float32)[None, None, :, None]
     from paper_2603_04127_amd import synth
@@ -313,7 +311,7 @@ def test_fused_shift_raised_mid_slice(monkeypatch):
     # 2^40 = 27.7 nats above the first block's shift is where the kernel raises a feature's shift
     assert np.sum(later - first > 30.0) > 50
     dev = U.to_device(inp, True)
-    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED, sched={"kv_wgs": 1})
     torch.cuda.synchronize()
     U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], "fused, shift raised mid-slice")
 
