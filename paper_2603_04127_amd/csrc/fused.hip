@@ -635,39 +635,52 @@ template <int D, int DV>
 struct RoSmem {
   static constexpr int AS = D + 8;
   static constexpr int stage_row = 128 + 8;                   // bytes: 64 bf16 or 32 fp32, plus pad
-  static constexpr size_t stage_bytes = 32 * stage_row;       // per wave: 32 tokens
-  __host__ __device__ static size_t a_bytes(int m) { return (size_t)m * AS * 2; }
-  __host__ __device__ static size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
-  __host__ __device__ static size_t misc_bytes(int m) { return (size_t)m * 4 + 16 * (size_t)((m / 64 + 3) / 4); }  // z, shifts
-  __host__ __device__ static size_t total(int m, int nw) { return a_bytes(m) + s_bytes(m) + misc_bytes(m) + nw * stage_bytes; }
+  __host__ __device__ static constexpr int stage_rows(int nbuf) { return nbuf == 2 ? 16 : 32; }  // tokens per pass
+  __host__ __device__ static constexpr size_t stage_bytes(int nbuf) { return (size_t)stage_rows(nbuf) * stage_row; }
+  __host__ __device__ static constexpr size_t a_bytes(int m) { return (size_t)m * AS * 2; }
+  __host__ __device__ static constexpr size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
+  __host__ __device__ static constexpr size_t misc_bytes(int m) { return (size_t)m * 4 + 16 * (size_t)((m / 64 + 3) / 4); }  // z, shifts
+  // nbuf copies of A', S^T, z and the shifts (two where the LDS allows: the next head and (b,h) are then
+  // resident before the workgroup's run of items reaches them; the output stage is halved to make room)
+  __host__ __device__ static size_t total(int m, int nw, int nbuf) {
+    return nbuf * (a_bytes(m) + s_bytes(m) + misc_bytes(m)) + nw * stage_bytes(nbuf);
+  }
 };
+template <int D, int NFB, int NW>
+constexpr int ro_nbuf() { return (D == 64 && NFB == 1 && NW == 8) ? 2 : 1; }
 
 template <int D, int DV, int NFB, bool OUT_BF16, int NW>
 __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __restrict__ Qg,
                                                        const _Float16* __restrict__ Ah,
                                                        const unsigned short* __restrict__ St,
                                                        const float* __restrict__ zt, const float* __restrict__ cf,
-                                                       void* __restrict__ outp, int H, int L,
+                                                       void* __restrict__ outp, int Bsz, int H, int L,
                                                        int chunks_per_bh, int n_items, int items_per_wg) {
   using SM = RoSmem<D, DV>;
   constexpr int m = 256 * NFB;
+  constexpr int NBUF = ro_nbuf<D, NFB, NW>();
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Asl = reinterpret_cast<_Float16*>(smem);
-  unsigned short* Stl = reinterpret_cast<unsigned short*>(smem + SM::a_bytes(m));
-  float* zl = reinterpret_cast<float*>(smem + SM::a_bytes(m) + SM::s_bytes(m));  // z, 16-byte aligned
-  float* cl = zl + m;
+  // LDS: NBUF copies of A', then NBUF copies of (S^T, z, shifts), then the per-wave output stages
+  constexpr size_t kABytes = SM::a_bytes(m);
+  constexpr size_t kSBase = NBUF * kABytes;
+  constexpr size_t kBufBytes = SM::s_bytes(m) + SM::misc_bytes(m);
+  constexpr int SR = SM::stage_rows(NBUF);
   const int SS = m + 4;
   constexpr int NT = 64 * NW;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
-  unsigned char* stage = smem + SM::a_bytes(m) + SM::s_bytes(m) + SM::misc_bytes(m) + wv * SM::stage_bytes;
+  unsigned char* stage = smem + kSBase + NBUF * kBufBytes + wv * SM::stage_bytes(NBUF);
   const int l32 = lane % 32, hf = lane / 32;
 
-  // Work items are (b,h, 64 NW-token chunk) pairs; a workgroup takes a contiguous run of them, so it
-  // refills its LDS copy of A', S^T, z only when the run crosses into the next (b,h).
+  // Work items are (head, batch entry, 64 NW-token chunk) triples, head slowest, so that neighbouring
+  // items share first the (b,h) and then at least the head.  A workgroup takes a contiguous run of
+  // them: A' is refilled only when the run crosses into the next head, and S^T, z of the next (b,h) are
+  // already resident when a second buffer exists (the run of a workgroup rarely spans more than two).
   const int item_begin = blockIdx.x * items_per_wg;
   const int item_end = min(n_items, item_begin + items_per_wg);
-  int cur_bh = -1;
+  auto bh_of = [&](int vb) { return (vb % Bsz) * H + vb / Bsz; };
+  const int vb0 = item_begin / chunks_per_bh;
+  int cur_vb = -1, cur_h = -1;
   // X fragments (B operand of the projection): token = t0 + 32 tt + l32, k = 16 s + 8 hf + [0,8).
   // The raw bf16 rows of the next tile are fetched into these registers during the last slot of
   // the current one (their last use is the projection of the last unit), so the fetch latency
@@ -686,21 +699,18 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       }
     }
   };
-  // The first tile's rows are requested before the first LDS fill, so that the two cold fetches overlap.
-  if (item_begin < item_end) {
-    const int t00 = (item_begin % chunks_per_bh) * NT + 64 * wv;
-    if (t00 < L) {
-      fetch_x(item_begin / chunks_per_bh, t00);
-      have_x = true;
-    }
-  }
-  for (int item = item_begin; item < item_end; ++item) {
-    const int bh = item / chunks_per_bh, chunk = item % chunks_per_bh;
-    if (bh != cur_bh) {
-      const int h = bh % H;
-      if (cur_bh >= 0) __syncthreads();  // everyone is done reading the previous head's operands
-      if (cur_bh < 0 || (cur_bh % H) != h) {
-        for (int c0 = tid; c0 < m * D / 8; c0 += NT * 4) {  // m * D / 8 is a multiple of 2048
+  // LDS fill: A' of head h (h >= 0), S^T, z, shifts of (b,h) bhA into buffer bufA and, with two buffers, of
+  // bhB into bufB (each when >= 0).  Every load is issued before the first store, so a fill costs one
+  // memory round trip.
+  auto fill = [&](int h, int abuf, int h2, int bhA, int bufA, int bhB, int bufB) {
+    constexpr int NA = m * D / 8 / NT;   // 16-byte pieces of A' per thread
+    constexpr int NS = DV * m / 4 / NT;  // 8-byte pieces of S^T per thread
+    constexpr int NZ = (m + NT - 1) / NT;
+    static_assert(m * D / 8 % NT == 0 && DV * m / 4 % NT == 0, "fill assumes whole pieces per thread");
+    if constexpr (NA > 4 || NS > 8) {
+      // large operands: in passes of a few pieces per thread (all of them in flight at once would spill)
+      if (h >= 0) {
+        for (int c0 = tid; c0 < m * D / 8; c0 += NT * 4) {
           u32x4 v[4];
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
@@ -710,27 +720,135 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int ci = c0 + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
-            *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) = v[u];
+            *reinterpret_cast<u32x4*>(reinterpret_cast<_Float16*>(smem) + row * SM::AS + 8 * kc) = v[u];
           }
         }
       }
-      for (int c0 = tid; c0 < DV * m / 4; c0 += NT * 8) {  // DV * m / 4 is a multiple of 4096
-        u32x2 v[8];
+      if (bhA >= 0) {
+        unsigned char* base = smem + kSBase + bufA * kBufBytes;
+        unsigned short* sl = reinterpret_cast<unsigned short*>(base);
+        float* zq = reinterpret_cast<float*>(base + SM::s_bytes(m));
+        for (int c0 = tid; c0 < DV * m / 4; c0 += NT * 8) {
+          u32x2 v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
-          v[u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bh * DV + row) * m + 4 * fc);
+          for (int u = 0; u < 8; ++u) {
+            const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+            v[u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bhA * DV + row) * m + 4 * fc);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+            *reinterpret_cast<u32x2*>(sl + row * SS + 4 * fc) = v[u];
+          }
         }
+        for (int i = tid; i < m; i += NT) zq[i] = zt[(size_t)bhA * m + i];
+        for (int i = tid; i < m / 64; i += NT) zq[m + i] = cf[(size_t)bhA * (m / 64) + i];
+      }
+      return;
+    }
+    // (two buffers) h: A' of that head into buffer abuf; h2: A' of that head into the other one
+    u32x4 av[NBUF][NA];
+    u32x2 sv[NBUF][NS];
+    float zv[NBUF][NZ], cv[NBUF];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int ci = c0 + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
-          *reinterpret_cast<u32x2*>(Stl + row * SS + 4 * fc) = v[u];
+    for (int q = 0; q < NBUF; ++q) {
+      const int hq = q ? h2 : h;
+      if (hq >= 0) {
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+          const int ci = tid + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
+          av[q][u] = *reinterpret_cast<const u32x4*>(Ah + ((size_t)hq * m + row) * D + 8 * kc);
         }
       }
-      for (int i = tid; i < m; i += NT) zl[i] = zt[(size_t)bh * m + i];
-      for (int i = tid; i < m / 64; i += NT) cl[i] = cf[(size_t)bh * (m / 64) + i];
-      __syncthreads();
-      cur_bh = bh;
+    }
+#pragma unroll
+    for (int q = 0; q < NBUF; ++q) {
+      const int bhq = q ? bhB : bhA;
+      if (bhq >= 0) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+          const int ci = tid + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+          sv[q][u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bhq * DV + row) * m + 4 * fc);
+        }
+#pragma unroll
+        for (int u = 0; u < NZ; ++u) zv[q][u] = (tid + NT * u < m) ? zt[(size_t)bhq * m + tid + NT * u] : 0.f;
+        cv[q] = tid < m / 64 ? cf[(size_t)bhq * (m / 64) + tid] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NBUF; ++q) {
+      const int hq = q ? h2 : h;
+      if (hq >= 0) {
+        _Float16* al = reinterpret_cast<_Float16*>(smem + (q ? abuf ^ 1 : abuf) * kABytes);
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+          const int ci = tid + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
+          *reinterpret_cast<u32x4*>(al + row * SM::AS + 8 * kc) = av[q][u];
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NBUF; ++q) {
+      const int bhq = q ? bhB : bhA;
+      if (bhq >= 0) {
+        unsigned char* base = smem + kSBase + (q ? bufB : bufA) * kBufBytes;
+        unsigned short* sl = reinterpret_cast<unsigned short*>(base);
+        float* zq = reinterpret_cast<float*>(base + SM::s_bytes(m));
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+          const int ci = tid + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+          *reinterpret_cast<u32x2*>(sl + row * SS + 4 * fc) = sv[q][u];
+        }
+#pragma unroll
+        for (int u = 0; u < NZ; ++u)
+          if (tid + NT * u < m) zq[tid + NT * u] = zv[q][u];
+        if (tid < m / 64) zq[m + tid] = cv[q];
+      }
+    }
+  };
+  // The first tile's rows are requested before the first LDS fill, so that the two cold fetches overlap.
+  if (item_begin < item_end) {
+    const int t00 = (item_begin % chunks_per_bh) * NT + 64 * wv;
+    if (t00 < L) {
+      fetch_x(bh_of(vb0), t00);
+      have_x = true;
+    }
+  }
+  const _Float16* Asl = reinterpret_cast<const _Float16*>(smem);
+  const unsigned short* Stl = reinterpret_cast<const unsigned short*>(smem + kSBase);
+  const float* zl = reinterpret_cast<const float*>(smem + kSBase + SM::s_bytes(m));
+  const float* cl = zl + m;
+  const int h0 = vb0 / Bsz;
+  for (int item = item_begin; item < item_end; ++item) {
+    const int vb = item / chunks_per_bh, chunk = item % chunks_per_bh;
+    const int bh = bh_of(vb);
+    if (vb != cur_vb) {
+      const int h = vb / Bsz, k = vb - vb0, ha = h - h0;
+      if (cur_vb < 0) {
+        // first fill: with two buffers, also what the next (b,h) of the run needs
+        const bool two = NBUF == 2 && (item_end - 1) / chunks_per_bh > vb;
+        const int hn = (vb + 1) / Bsz;
+        fill(h, 0, (two && hn != h) ? hn : -1, bh, 0, two ? bh_of(vb + 1) : -1, 1);
+        __syncthreads();
+      } else {
+        const bool came_with_first = NBUF == 2 && k == 1;
+        const bool need_a = h != cur_h && !came_with_first;
+        const bool need_s = !came_with_first;
+        if (need_a || need_s) {
+          __syncthreads();  // everyone is done reading what is overwritten (the buffers of two steps back)
+          fill(need_a ? h : -1, ha % NBUF, -1, need_s ? bh : -1, k % NBUF, -1, 0);
+          __syncthreads();
+        }
+      }
+      cur_vb = vb;
+      cur_h = h;
+      if constexpr (NBUF == 2) {
+        Asl = reinterpret_cast<const _Float16*>(smem + (ha % NBUF) * kABytes);
+        const unsigned char* base = smem + kSBase + (k % NBUF) * kBufBytes;
+        Stl = reinterpret_cast<const unsigned short*>(base);
+        zl = reinterpret_cast<const float*>(base + SM::s_bytes(m));
+        cl = zl + m;
+      }
     }
     const int t0 = chunk * NT + 64 * wv;
     const int wg_end = L;
@@ -741,7 +859,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     // the tile fetched ahead: the next one, or this one again when there is none (never used then)
     const bool more = item + 1 < item_end;
     const int nitem = more ? item + 1 : item;
-    const int nbh = nitem / chunks_per_bh, nt0 = (nitem % chunks_per_bh) * NT + 64 * wv;
+    const int nbh = bh_of(nitem / chunks_per_bh), nt0 = (nitem % chunks_per_bh) * NT + 64 * wv;
     if (!have_x) fetch_x(bh, t0);
     have_x = false;
 #pragma unroll
@@ -992,51 +1110,64 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     for (int tt = 0; tt < 2; ++tt) {
       const float inv = 1.f / (den[tt] + __shfl_xor(den[tt], 32, 64));
       const int row = lane / 8, ch = lane % 8;  // read side: 8 lanes per token row, 16 bytes each
-      if (OUT_BF16) {
+      constexpr int NHP = 32 / SR;              // passes of SR tokens through the stage
 #pragma unroll
-        for (int c64 = 0; c64 < DV / 64; ++c64) {  // 64 output columns (one 128-byte row piece) at a time
+      for (int hp = 0; hp < NHP; ++hp) {
+        const bool mine = NHP == 1 || l32 / SR == hp;
+        const int srow = l32 % SR;
+        if (OUT_BF16) {
 #pragma unroll
-          for (int cl2 = 0; cl2 < 2; ++cl2)
+          for (int c64 = 0; c64 < DV / 64; ++c64) {  // 64 output columns (one 128-byte row piece) at a time
+            if (mine) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const int ct = 2 * c64 + cl2;
-              u32x2 w = {pack_bf16(O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv),
-                         pack_bf16(O[ct][tt][4 * g + 2] * inv, O[ct][tt][4 * g + 3] * inv)};
-              *reinterpret_cast<u32x2*>(stage + l32 * SM::stage_row + (32 * cl2 + 8 * g + 4 * hf) * 2) = w;
+              for (int cl2 = 0; cl2 < 2; ++cl2)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                  const int ct = 2 * c64 + cl2;
+                  u32x2 w = {pack_bf16(O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv),
+                             pack_bf16(O[ct][tt][4 * g + 2] * inv, O[ct][tt][4 * g + 3] * inv)};
+                  *reinterpret_cast<u32x2*>(stage + srow * SM::stage_row + (32 * cl2 + 8 * g + 4 * hf) * 2) = w;
+                }
             }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-          for (int ps = 0; ps < 4; ++ps) {
-            const int tok = t0 + 32 * tt + 8 * ps + row;
-            u32x4 w = *reinterpret_cast<const u32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
-            if (tok < wg_end)
-              *reinterpret_cast<u32x4*>(reinterpret_cast<unsigned short*>(outp) + ((size_t)bh * L + tok) * DV + 64 * c64 +
-                                        8 * ch) = w;
+            for (int ps = 0; ps < SR / 8; ++ps) {
+              const int tok = t0 + 32 * tt + SR * hp + 8 * ps + row;
+              u32x4 w = *reinterpret_cast<const u32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
+              // streaming store: the output is not read again by this launch, and lines left dirty in the
+              // L2 would all be written back at the end of the kernel, on the critical path of the step
+              if (tok < wg_end)
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(reinterpret_cast<unsigned short*>(outp) +
+                                                                        ((size_t)bh * L + tok) * DV + 64 * c64 + 8 * ch));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
           }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-        }
-      } else {
+        } else {
 #pragma unroll
-        for (int ct = 0; ct < DV / 32; ++ct) {
+          for (int ct = 0; ct < DV / 32; ++ct) {
+            if (mine) {
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            f32x4 w = {O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv, O[ct][tt][4 * g + 2] * inv,
-                       O[ct][tt][4 * g + 3] * inv};
-            *reinterpret_cast<f32x4*>(stage + l32 * SM::stage_row + (8 * g + 4 * hf) * 4) = w;
+              for (int g = 0; g < 4; ++g) {
+                f32x4 w = {O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv, O[ct][tt][4 * g + 2] * inv,
+                           O[ct][tt][4 * g + 3] * inv};
+                *reinterpret_cast<f32x4*>(stage + srow * SM::stage_row + (8 * g + 4 * hf) * 4) = w;
+              }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ps = 0; ps < SR / 8; ++ps) {
+              const int tok = t0 + 32 * tt + SR * hp + 8 * ps + row;
+              f32x4 w = *reinterpret_cast<const f32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
+              if (tok < wg_end)
+                __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) +
+                                                                        ((size_t)bh * L + tok) * DV + 32 * ct + 4 * ch));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
           }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-#pragma unroll
-          for (int ps = 0; ps < 4; ++ps) {
-            const int tok = t0 + 32 * tt + 8 * ps + row;
-            f32x4 w = *reinterpret_cast<const f32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
-            if (tok < wg_end)
-              *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + ((size_t)bh * L + tok) * DV + 32 * ct + 4 * ch) = w;
-          }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
         }
       }
     }
@@ -1117,18 +1248,18 @@ dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, con
 template <int D, int DV, int NFB, int NW>
 dark_status launch_ro(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* Q, void* out) {
   const dark_params& p = pb.p;
-  const size_t lds = RoSmem<D, DV>::total(p.m, NW);
+  const size_t lds = RoSmem<D, DV>::total(p.m, NW, ro_nbuf<D, NFB, NW>());
   const unsigned grid = (unsigned)pl.ro_grid;
   if (p.out_dtype == DARK_BF16) {
     auto kern = k_readout<D, DV, NFB, true, NW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
+                b.cf, out, p.B, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   } else {
     auto kern = k_readout<D, DV, NFB, false, NW>;
     DARK_TRY(allow_lds(kern, lds));
     DARK_LAUNCH(KID_READOUT, pb.st, kern, dim3(grid), dim3(64 * NW), lds, (const unsigned short*)Q, b.Ah, b.St, b.zt,
-                b.cf, out, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
+                b.cf, out, p.B, p.H, p.L, pl.chunks_per_bh, pl.n_items, pl.items_per_wg);
   }
   return DARK_OK;
 }
