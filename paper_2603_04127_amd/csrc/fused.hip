@@ -878,10 +878,11 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     // Units of 32 features.  For unit g:  P(g) projection MFMAs -> U,  E(g) exp2/pack/denominator
     // (vector ALU) -> pk,  S(g) second MFMAs -> O.  Slot g of the schedule issues S(g-1), then
     // P(g+1), with the 16 pieces of E(g) spread between the MFMAs, so the matrix pipe and the
-    // vector ALU work on different units at the same time.  The per-token shift mu is taken from
-    // unit 0 only and never raised; a token whose later features exceed it by more than the fp32
-    // range shows up as a non-finite or out-of-range denominator, and then the whole tile is
-    // redone by the careful path below.
+    // vector ALU work on different units at the same time.  The fast path applies no shift at all: the
+    // features are 2^u with u the projection itself (the key shift c* and any per-token shift are per-row
+    // factors of numerator and denominator alike), which is exact in bf16/fp32 as long as nothing leaves the
+    // exponent range.  A token whose logits do is seen afterwards as a non-finite or out-of-range
+    // denominator, and then the whole tile is redone by the careful path below with a running row shift.
     {
       constexpr int NS = 4 * CT;        // S MFMAs per unit
       constexpr int NP = 2 * (D / 16);  // P MFMAs per unit
@@ -892,7 +893,6 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) O[ct][tt] = zero16;
       den[0] = den[1] = 0.f;
-      float sh[2] = {0.f, 0.f};
 #pragma unroll
       for (int fb = 0; fb < NFB; ++fb) {
         const _Float16* Ab = Asl + (size_t)(256 * fb + l32) * SM::AS + 8 * hf;
@@ -912,16 +912,6 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt)
             U[0][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s2], xf[tt][s2], s2 == 0 ? zero16 : U[0][tt], 0, 0, 0);
-        if (fb == 0) {
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            float m0 = U[0][tt][0];
-#pragma unroll
-            for (int v = 1; v < 16; v += 2) m0 = max3(m0, U[0][tt][v], U[0][tt][(v + 1) % 16]);
-            m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
-            sh[tt] = -m0;  // the key shift c* is one scalar per (b,h): it cancels against the row maximum
-          }
-        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
@@ -966,8 +956,8 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
                 const int kn = (k + 1) % 4, gn = g + (k + 1) / 4;
                 zf[(k + 1) % 2] = *reinterpret_cast<const f32x4*>(zb + 32 * (gn % 8) + 8 * kn);
               }
-              const float a = fast_exp2(U[cur][tt][8 * hh + 2 * q] + sh[tt]);
-              const float b = fast_exp2(U[cur][tt][8 * hh + 2 * q + 1] + sh[tt]);
+              const float a = fast_exp2(U[cur][tt][8 * hh + 2 * q]);
+              const float b = fast_exp2(U[cur][tt][8 * hh + 2 * q + 1]);
               pk[cur][tt][hh][q] = pack_bf16(a, b);
               // plain fmas: a dot2 instruction stalls behind the MFMAs in flight (measured: one
               // v_dot2c per MFMA costs as much as six ordinary vector instructions)
