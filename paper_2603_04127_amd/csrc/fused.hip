@@ -134,6 +134,9 @@ struct KvSmem {
 };
 constexpr float kF16Max = 65504.f;
 
+// TP: the partial state is written feature-contiguous ([bh][p][dv][m], the layout of the merged S^T) for
+// k_kv_merge_t; otherwise [bh][p][m][dv], which the causal prefix kernel reads.
+template <bool TP>
 __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __restrict__ Kg,
                                                     const unsigned short* __restrict__ Vg,
                                                     const _Float16* __restrict__ Ah, const _Float16* __restrict__ Mh,
@@ -500,7 +503,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
   const size_t pbase = (size_t)bh * P + p;
   wait_vmcnt0();   // the key loads issued for tiles past the end
   __syncthreads();  // every wave is done with the tile buffers
-  {
+  if (!TP) {
     constexpr int ROWB = DV * 2 + 16;
     static_assert(4 * 64 * ROWB <= SM::x_bytes + SM::v_bytes, "stage does not fit the tile buffers");
     unsigned char* stg = smem + wv * 64 * ROWB;
@@ -522,6 +525,30 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       const int i = lane + 64 * k, row = i / CPR, ch = i % CPR;
       const u32x4 w = *reinterpret_cast<const u32x4*>(stg + row * ROWB + 16 * ch);
       *reinterpret_cast<u32x4*>(Spart + (pbase * m + f0 + row) * DV + 8 * ch) = w;
+    }
+  } else {
+    // transposed: row = value column, the 64 features of this wave along the row (the accumulators hold four
+    // consecutive features of one value column per register group: the stage is written 8 bytes at a time)
+    constexpr int ROWB = 64 * 2 + 16;
+    static_assert(4 * DV * ROWB <= SM::x_bytes + SM::v_bytes, "stage does not fit the tile buffers");
+    unsigned char* stg = smem + wv * DV * ROWB;
+#pragma unroll
+    for (int ft = 0; ft < 2; ++ft)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const u32x2 w = {pack_bf16(S[ft][ct][4 * g], S[ft][ct][4 * g + 1]),
+                           pack_bf16(S[ft][ct][4 * g + 2], S[ft][ct][4 * g + 3])};
+          *reinterpret_cast<u32x2*>(stg + (32 * ct + l32) * ROWB + (32 * ft + 8 * g + 4 * hf) * 2) = w;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < DV * 8 / 64; ++k) {
+      const int i = lane + 64 * k, row = i / 8, ch = i % 8;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(stg + row * ROWB + 16 * ch);
+      *reinterpret_cast<u32x4*>(Spart + (pbase * DV + row) * m + f0 + 8 * ch) = w;
     }
   }
 #pragma unroll
@@ -617,6 +644,78 @@ __global__ __launch_bounds__(256) void k_kv_merge(const unsigned short* __restri
     int idx = tid + 256 * i;
     int cc = idx / 64, f = idx % 64;
     St[((size_t)bh * DV + cc) * m + 64 * blk + f] = (unsigned short)(pack_bf16(tile[f][cc], 0.f) & 0xffffu);
+  }
+  if (tid < 64) zt[(size_t)bh * m + 64 * blk + tid] = zacc;
+  if (tid == 0) cf[(size_t)bh * nblk + blk] = cs;
+}
+
+// ---------------------------------------------------------------------------
+// k_kv_merge_t: the same merge for feature-contiguous partial states [bh][p][dv][m] (dv = 64), which are
+// already laid out like S^T: no transpose, and every load of the block is in flight before the first
+// wait (one memory round trip; the kernel is pure latency).  One block per (b,h, 64-feature block),
+// P <= kMergeTMaxP slices.
+// ---------------------------------------------------------------------------
+constexpr int kMergeTMaxP = 8;
+__global__ __launch_bounds__(256) void k_kv_merge_t(const unsigned short* __restrict__ Spart,
+                                                    const float* __restrict__ zpart, const float* __restrict__ cpart,
+                                                    unsigned short* __restrict__ St, float* __restrict__ zt,
+                                                    float* __restrict__ cf, int m, int P) {
+  constexpr int DV = 64, PP = kMergeTMaxP;
+  __shared__ float fac[PP][64];
+  __shared__ float red[4];
+  const int nblk = m / 64;
+  const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
+  const int tid = threadIdx.x;
+  const size_t sbase = (size_t)bh * P;
+  // thread t: 16-byte pieces (value column t / 8 and 32 + t / 8, features 8 (t % 8) .. + 7 of the block)
+  const int row = tid / 8, fch = tid % 8;
+  u32x4 v[PP][2];
+  float cmine[PP], zmine[PP];
+#pragma unroll
+  for (int u = 0; u < PP; ++u) {
+    const int pu = min(u, P - 1);
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+      v[u][k] = *reinterpret_cast<const u32x4*>(Spart + ((sbase + pu) * DV + row + 32 * k) * m + 64 * blk + 8 * fch);
+    cmine[u] = cpart[(sbase + pu) * m + 64 * blk + (tid % 64)];
+    zmine[u] = zpart[(sbase + pu) * m + 64 * blk + (tid % 64)];
+  }
+  // c* over every slice and feature of the (b,h)
+  float cs = -INFINITY;
+  for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[sbase * m + i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
+  if (tid % 64 == 0) red[tid / 64] = cs;
+  __syncthreads();
+  cs = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float zacc = 0.f;
+#pragma unroll
+  for (int u = 0; u < PP; ++u) {
+    const float f = fast_exp2(cmine[u] - cs);
+    if (tid < 64) fac[u][tid] = f;
+    if (u < P) zacc = fmaf(f, zmine[u], zacc);   // p ascending
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < PP; ++u) {  // p ascending: the order of summation is fixed
+      if (u < P) {
+        const f32x4 f0 = *reinterpret_cast<const f32x4*>(&fac[u][8 * fch]);
+        const f32x4 f1 = *reinterpret_cast<const f32x4*>(&fac[u][8 * fch + 4]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const unsigned w = v[u][k][j];
+          const float fa = j < 2 ? f0[2 * j] : f1[2 * j - 4], fb = j < 2 ? f0[2 * j + 1] : f1[2 * j - 3];
+          acc[2 * j] = fmaf(fa, __uint_as_float(w << 16), acc[2 * j]);
+          acc[2 * j + 1] = fmaf(fb, __uint_as_float(w & 0xffff0000u), acc[2 * j + 1]);
+        }
+      }
+    }
+    const u32x4 o = {pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3]), pack_bf16(acc[4], acc[5]),
+                     pack_bf16(acc[6], acc[7])};
+    *reinterpret_cast<u32x4*>(St + ((size_t)bh * DV + row + 32 * k) * m + 64 * blk + 8 * fch) = o;
   }
   if (tid < 64) zt[(size_t)bh * m + 64 * blk + tid] = zacc;
   if (tid == 0) cf[(size_t)bh * nblk + blk] = cs;
@@ -1168,6 +1267,7 @@ constexpr size_t kLdsMax = 160 * 1024;
 
 struct Plan {
   int P, slice_len, nfb, n_work, kv_grid;
+  bool tp;  // partial states feature-contiguous, merged by k_kv_merge_t
   int ro_nw, chunks_per_bh, n_items, items_per_wg, ro_grid;
 };
 
@@ -1187,6 +1287,7 @@ Plan make_plan(const Problem& pb) {
   pl.P = (p.L + sl - 1) / sl;
   pl.n_work = (int)(BH * pl.P);
   pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
+  pl.tp = p.d == 64 && pl.P <= kMergeTMaxP;
   // readout: (b,h, 256-token chunk) items dealt out in contiguous runs to about as many
   // workgroups as fit on the chip at once
   // one workgroup per CU: eight waves when the registers (d = 64) and the LDS allow, else four
@@ -1228,10 +1329,17 @@ void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
 
 dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, const void* K, const void* V) {
   const dark_params& p = pb.p;
-  DARK_TRY(allow_lds(k_kv_reduce, KvSmem::total));
-  DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce, dim3(pl.kv_grid), dim3(256), KvSmem::total, (const unsigned short*)K,
-              (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m, pl.P, pl.slice_len,
-              pl.n_work);
+  if (pl.tp) {
+    DARK_TRY(allow_lds(k_kv_reduce<true>, KvSmem::total));
+    DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<true>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
+                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m,
+                pl.P, pl.slice_len, pl.n_work);
+  } else {
+    DARK_TRY(allow_lds(k_kv_reduce<false>, KvSmem::total));
+    DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<false>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
+                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m,
+                pl.P, pl.slice_len, pl.n_work);
+  }
   return DARK_OK;
 }
 
@@ -1296,7 +1404,10 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
     DARK_TRY(fused_launch_slice_state128(pb, K, V, b.Ah, b.Mh, b.nrm, b.Spart, b.zpart, b.cpart, pl.P, pl.slice_len));
   }
   const unsigned mgrid = (unsigned)(pb.BH() * (p.m / 64));
-  if (p.dv == 64)
+  if (pl.tp)
+    DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge_t, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St, b.zt,
+                b.cf, p.m, pl.P);
+  else if (p.dv == 64)
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<64>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
                 b.zt, b.cf, p.m, pl.P);
   else
@@ -1322,6 +1433,7 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
   pl.slice_len = slice_len;
   pl.n_work = (int)(pb.BH() * P);
   pl.kv_grid = ((pl.n_work + 7) / 8) * 8 * pl.nfb;
+  pl.tp = false;
   FusedBufs b{};
   b.Ah = const_cast<_Float16*>(Ah);
   b.Mh = const_cast<_Float16*>(Mh);
