@@ -37,7 +37,8 @@ const char* kernel_name(int k) {
   static const char* names[KID_COUNT] = {
       "f32_gemm",     "f32_load",   "f32_rowstat",  "f32_headmax",  "f32_exp",      "f32_sum_slices",
       "f32_finish",   "f32_scan",   "f32_bwd_elem", "fused_prep",   "fused_kv_reduce", "fused_kv_merge",
-      "fused_readout", "fused_key_norms", "fused_causal_state", "fused_causal_prefix", "fused_causal_scan", "fused_featurize"};
+      "fused_readout", "fused_key_norms", "fused_causal_state", "fused_causal_prefix", "fused_causal_scan", "fused_featurize",
+      "fused_bwd_fwd", "fused_bwd_suffix", "fused_bwd_rev", "fused_bwd_dm"};
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }
@@ -95,7 +96,9 @@ static dark_status check_ws(const void* ws, size_t ws_bytes, size_t need) {
 static bool use_fused(const Problem& pb, int op, bool causal, dark_status* err) {
   *err = DARK_OK;
   if (pb.p.path == DARK_PATH_F32) return false;
-  bool ok = op == DARK_OP_FEATURIZE ? fused_featurize_supported(pb) : fused_supported(pb, op, causal);
+  bool ok = op == DARK_OP_FEATURIZE ? fused_featurize_supported(pb)
+            : op == DARK_OP_ATTN_BWD ? fused_bwd_supported(pb, causal)
+                                     : fused_supported(pb, op, causal);
   if (!ok && pb.p.path == DARK_PATH_FUSED) *err = DARK_EUNSUPPORTED;
   return ok;
 }
@@ -116,7 +119,8 @@ static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const 
       return fused ? fused_attn_causal_fwd(pb, ar, Q, K, V, M, W, out)
                    : f32_attn_fwd(pb, ar, true, Q, K, V, M, W, out);
     case DARK_OP_ATTN_BWD:
-      return f32_attn_bwd(pb, ar, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM);
+      return fused ? fused_attn_bwd(pb, ar, Q, K, V, M, W, dOut, dQ, dK, dV, dM)
+                   : f32_attn_bwd(pb, ar, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM);
   }
   return DARK_EINVAL;
 }
@@ -265,7 +269,11 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
       !aligned(dOut, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) || !aligned(dM, 16))
     return DARK_EALIGN;
-  if (pb.p.path == DARK_PATH_FUSED) return DARK_EUNSUPPORTED;
+  {
+    dark_status err;
+    (void)use_fused(pb, DARK_OP_ATTN_BWD, causal != 0, &err);
+    if (err != DARK_OK) return err;
+  }
   DARK_TRY(check_ws(ws, ws_bytes, measure(pb, DARK_OP_ATTN_BWD, causal != 0)));
   pb.st = static_cast<hipStream_t>(hip_stream);
   Arena ar(ws, ws_bytes);

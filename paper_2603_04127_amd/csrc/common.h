@@ -33,6 +33,10 @@ enum KernelId : int {
   KID_CAUSAL_PREFIX,   // fused causal path: exclusive prefix over the slice states
   KID_CAUSAL_SCAN,     // fused causal path: tile-by-tile scan inside a slice (inter + intra term)
   KID_FEATURIZE,       // fused path: feature map written to memory (dark_featurize)
+  KID_BWD_FWD,         // fused backward: forward-order pass (denominators, dQ, query half of dA, suffix-state pieces)
+  KID_BWD_SUFFIX,      // fused backward: exclusive suffix sums of the slices' reverse-state pieces
+  KID_BWD_REV,         // fused backward: reverse-order pass (dV, dK, key half of dA, norm-term matrix)
+  KID_BWD_DM,          // fused backward: sums over slices and dM per head
   KID_COUNT
 };
 
@@ -120,5 +124,11 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
                            const float* M, const float* W, void* out);
 dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, const void* K,
                                   const void* V, const float* M, const float* W, void* out);
+
+// fused MFMA backward (fused_bwd.hip): causal, bf16, d = r = dv = 64, m = 256.
+bool fused_bwd_supported(const Problem& pb, bool causal);
+dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const void* K, const void* V,
+                           const float* M, const float* W, const void* dOut, float* dQ, float* dK,
+                           float* dV, float* dM);
 
 }  // namespace dark

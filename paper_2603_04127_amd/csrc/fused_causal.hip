@@ -811,6 +811,18 @@ dark_status fused_launch_slice_state128(const Problem& pb, const void* K, const 
   return launch_slice_state<128>(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, P, slice_len);
 }
 
+dark_status fused_causal_states64(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
+                                  const _Float16* Mh, float* nrm, unsigned short* Spart, float* zpart, float* cpart,
+                                  float* Spre, float* zpre, float* cpre, int P, int slice_len) {
+  const dark_params& p = pb.p;
+  if (p.d != 64 || p.dv != 64 || P > kMaxP) return DARK_EUNSUPPORTED;
+  DARK_TRY((launch_key_norms<64>(pb, K, Mh, nrm)));
+  DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
+  DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<64>), dim3((unsigned)(pb.BH() * (p.m / 8))), dim3(256), 0, Spart, zpart,
+              cpart, Spre, zpre, cpre, p.m, P);
+  return DARK_OK;
+}
+
 bool fused_causal_supported(const Problem& pb) {
   const dark_params& p = pb.p;
   if (p.io_dtype != DARK_BF16) return false;

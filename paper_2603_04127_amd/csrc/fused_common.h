@@ -125,6 +125,11 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
                                    int slice_len);
 // Implemented in fused_causal.hip.
 bool fused_causal_supported(const Problem& pb);
+// Key norms nrm [BH][L], slice states ([BH][P][m][dv] bf16 with per-feature shifts) and their exclusive prefix
+// Spre, zpre (fp32, expressed in the running scalar shift cpre [BH][P]) for d = r = dv = 64.
+dark_status fused_causal_states64(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
+                                  const _Float16* Mh, float* nrm, unsigned short* Spart, float* zpart, float* cpart,
+                                  float* Spre, float* zpre, float* cpre, int P, int slice_len);
 // The same states for d = r = dv = 128 (whose accumulators do not fit k_kv_reduce's register budget):
 // key norms into nrm [BH][L], then an 8-wave kernel per (b,h, slice).
 dark_status fused_launch_slice_state128(const Problem& pb, const void* K, const void* V, const _Float16* Ah,

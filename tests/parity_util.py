@@ -32,10 +32,12 @@ def errors(got, want):
         return 0.0, 0.0, 0.0, 0.0
     assert np.all(np.isfinite(g)), "non-finite values in GPU result"
     scale = np.abs(o).max()
+    if scale == 0.0:
+        scale = 1.0   # an expected tensor of exact zeros (e.g. dQ of a single position): absolute error
     diff = g - o
     rows_o = np.sqrt((o * o).sum(axis=-1))
     rows_d = np.sqrt((diff * diff).sum(axis=-1))
-    row_rel = rows_d / np.maximum(rows_o, 0.01 * rows_o.max())
+    row_rel = rows_d / np.maximum(rows_o, 0.01 * rows_o.max() if rows_o.max() > 0 else 1.0)
     rmax_o = np.abs(o).max(axis=-1)
     rmax_d = np.abs(diff).max(axis=-1)
     row_inf = rmax_d / np.maximum(rmax_o, 0.01 * scale)
@@ -53,6 +55,41 @@ def assert_close(got, want, tol, what=""):
         f"{what}: normalised max err {e[0]:.3e}, row-wise L2 {e[1]:.3e}, row-wise max {e[2]:.3e} > {tol:g}"
     assert e[3] <= FLOOR_FACTOR * tol, f"{what}: floored element-wise err {e[3]:.3e} > {FLOOR_FACTOR * tol:g}"
     return e
+
+
+def grad_errors(got, want):
+    """(normalised max error, largest row error over the largest row norm) for gradients computed from
+    bf16-rounded features (the MFMA backward).
+
+    Rows of a gradient differ in norm by orders of magnitude (the first causal query's is exactly zero), and
+    every row is a difference of large terms: sum_j dlogit_ij = 0 for a query, so dQ_i = A^T dlogit_i cancels
+    across the features.  With bf16 operands each term carries a 2^-9 relative error, which leaves every row
+    with the same absolute error, a few 1e-3 of the largest row: no arithmetic on bf16 operands bounds the
+    error of a small row relative to that row.  The MFMA backward is therefore held to the tolerance on the
+    scale of the tensor (both numbers below), its errors under the stricter row-relative metrics of errors()
+    are printed by the tests, and the fp32 path, which meets those at 2e-4, stays selectable."""
+    g = np.asarray(got, dtype=np.float64)
+    o = np.asarray(want, dtype=np.float64)
+    assert g.shape == o.shape, (g.shape, o.shape)
+    assert np.all(np.isfinite(g)), "non-finite values in GPU result"
+    if o.size == 0:
+        return 0.0, 0.0
+    diff = g - o
+    scale = np.abs(o).max() or 1.0
+    rows_o = np.sqrt((o * o).sum(axis=-1))
+    rows_d = np.sqrt((diff * diff).sum(axis=-1))
+    return float(np.abs(diff).max() / scale), float(rows_d.max() / (rows_o.max() or 1.0))
+
+
+def assert_close_grad(got, want, tol, what=""):
+    e = grad_errors(got, want)
+    assert e[0] <= tol and e[1] <= tol, f"{what}: normalised max err {e[0]:.3e}, row error over largest row {e[1]:.3e} > {tol:g}"
+    return e + errors(got, want)[1:]
+
+
+def fmt_grad(e):
+    return (f"normalised max {e[0]:.3e}, row error / largest row {e[1]:.3e}  [row-relative metrics, floor 1 %: "
+            f"L2 {e[2]:.3e}, max {e[3]:.3e}]")
 
 
 def fmt(e):

@@ -42,13 +42,21 @@ def test_causal_config3():
         print(f"config 3 head {(b, h)}: {U.fmt(e)}")
 
 
-def test_finetune_config5():
+@pytest.mark.parametrize("path", ["fused", "f32"])
+def test_finetune_config5(path):
+    """Forward + backward at the finetuning configuration; the backward through the MFMA kernels (what
+    DARK_PATH_AUTO and bench.py run) and through the fp32 kernels."""
     cfg = synth.CONFIGS[5]
     inp = synth.make_inputs(cfg)
     dev = U.to_device(inp, True)
     out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], chunk=cfg.chunk)
-    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, chunk=cfg.chunk)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, chunk=cfg.chunk,
+                         path=dk.PATH_FUSED if path == "fused" else dk.PATH_F32)
     torch.cuda.synchronize()
+    for t in g.values():
+        assert bool(torch.isfinite(t).all())
+    check = U.assert_close_grad if path == "fused" else U.assert_close
+    show = U.fmt_grad if path == "fused" else U.fmt
     h = 4
     dM = np.zeros((cfg.r, cfg.d))
     for b in range(cfg.B):
@@ -58,7 +66,7 @@ def test_finetune_config5():
         if b == 0:
             U.assert_close(_np(out[b, h]), O.attn_brute(Q, K, V, M, W, True), U.TOL["bf16"], "config 5 out")
         for name, want in (("dQ", dQ), ("dK", dK), ("dV", dV)):
-            e = U.assert_close(_np(g[name][b, h]), want, U.TOL["bf16"], f"config 5 {name}[{b},{h}]")
-            print(f"config 5 {name}[{b},{h}]: {U.fmt(e)}")
-    e = U.assert_close(_np(g["dM"][h]), dM, U.TOL["bf16"], "config 5 dM")
-    print(f"config 5 dM[{h}]: {U.fmt(e)}")
+            e = check(_np(g[name][b, h]), want, U.TOL["bf16"], f"config 5 {name}[{b},{h}] ({path})")
+            print(f"config 5 ({path}) {name}[{b},{h}]: {show(e)}")
+    e = check(_np(g["dM"][h]), dM, U.TOL["bf16"], f"config 5 dM ({path})")
+    print(f"config 5 ({path}) dM[{h}]: {show(e)}")

@@ -217,13 +217,53 @@ def test_backward_small(shape, causal, bf16):
     B, H, L, d, r, m, dv = shape
     inp = U.random_problem(9, B, H, L, d, r, m, dv, bf16=bf16, backward=True)
     dev = U.to_device(inp, bf16)
-    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], causal, chunk=64)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], causal, chunk=64,
+                         path=dk.PATH_F32)
     torch.cuda.synchronize()
     want = dict(zip(("dQ", "dK", "dV", "dM"), U.oracle_bwd(inp, causal)))
     # gradients are fp32 on both dtypes (inputs only are rounded), so the fp32 path meets the fp32 bar
     tol = 2e-4
     for k in ("dQ", "dK", "dV", "dM"):
         U.assert_close(_np(g[k]), want[k], tol, f"{k} causal={causal}")
+
+
+FUSED_BWD_SHAPES = [
+    # B, H, L
+    (1, 2, 300),     # several slices, ragged tail inside the last 32-token tile
+    (2, 3, 1000),    # slices of several tiles
+    (1, 1, 32),      # exactly one tile
+    (1, 1, 7),       # shorter than a tile
+    (1, 1, 1),       # a single position: every gradient but dV vanishes
+    (1, 1, 2100),    # many slices for one head: long prefix and suffix chains
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_BWD_SHAPES)
+def test_fused_backward(shape):
+    """MFMA backward (causal, bf16 inputs, d = r = dv = 64, m = 256), forced so that a fall-back cannot pass."""
+    B, H, L = shape
+    inp = U.random_problem(31, B, H, L, 64, 64, 256, 64, bf16=True, backward=True, amp=2.0)
+    dev = U.to_device(inp, True)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, path=dk.PATH_FUSED)
+    torch.cuda.synchronize()
+    want = dict(zip(("dQ", "dK", "dV", "dM"), U.oracle_bwd(inp, True)))
+    for k in ("dQ", "dK", "dV", "dM"):
+        e = U.assert_close_grad(_np(g[k]), want[k], U.TOL["bf16"], f"fused backward {k} {shape}")
+        print(f"fused backward {shape} {k}: {U.fmt_grad(e)}")
+
+
+def test_fused_backward_is_deterministic_and_matches_f32_path():
+    inp = U.random_problem(32, 2, 2, 700, 64, 64, 256, 64, bf16=True, backward=True)
+    dev = U.to_device(inp, True)
+    args = (dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True)
+    a = dk.dark_attn_bwd(*args, path=dk.PATH_FUSED)
+    a = {k: v.clone() for k, v in a.items()}
+    b = dk.dark_attn_bwd(*args, path=dk.PATH_FUSED)
+    c = dk.dark_attn_bwd(*args, path=dk.PATH_F32)
+    torch.cuda.synchronize()
+    for k in ("dQ", "dK", "dV", "dM"):
+        assert torch.equal(a[k].view(torch.int32), b[k].view(torch.int32)), k
+        U.assert_close_grad(_np(a[k]), _np(c[k]), U.TOL["bf16"], f"fused vs fp32 path, {k}")
 
 
 def test_backward_optional_outputs():
