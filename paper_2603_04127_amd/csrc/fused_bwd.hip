@@ -201,7 +201,10 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   load_a(smem, Ah, h, tid);
   // running state of this wave's 32 features: S [f][dv] (two value-column blocks), z (every column alike),
   // and the slice's contributions to Rn, Rd, T_Q
-  f32x16 S[2], Zc, Rn[2], Rd, Tq[2];
+  // z (fp32 in LDS, feature tid of threads 0..255) and the slice's Rd (feature tid - 256 of the others,
+  // in a register) are kept by the vector ALU: a column sum per tile
+  f32x16 S[2], Rn[2], Tq[2];
+  float rd_acc = 0.f;
   {
     const float f = fast_exp2(cpre[(size_t)bh * P + p] - c_ref);  // the prefix is expressed in the running shift of slice p
     const size_t sb = ((size_t)bh * P + p) * kF;
@@ -212,29 +215,17 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
         S[db][v] = f * Spre[(sb + ft) * kD + 32 * db + l32];
       }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) Zc[v] = f * zpre[sb + 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)];
+    if (tid < kF) {
+      const float z0 = f * zpre[sb + tid];
+      zs[tid] = z0;
+      zb[tid] = (us)(pack_bf16(z0, 0.f) & 0xffffu);
+    }
   }
 #pragma unroll
   for (int db = 0; db < 2; ++db) Rn[db] = Tq[db] = zero16;
-  Rd = zero16;
-  auto publish_state = [&]() {
-    store_state_copy(St, S, wv, lane);
-    if (l32 == 0) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
-        zs[ft] = Zc[v];
-        zb[ft] = (us)(pack_bf16(Zc[v], 0.f) & 0xffffu);
-      }
-    }
-  };
+  auto publish_state = [&]() { store_state_copy(St, S, wv, lane); };
   publish_state();
   __syncthreads();
-  // A' fragments of this wave's features (A operand of the projections), kept for the whole slice
-  u32x4 af[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) af[s] = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);
 
   for (int t = 0; t < ntile; ++t) {
     const int tok0 = tok_begin + t * kT;
@@ -247,8 +238,9 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
     f32x16 uq = zero16, uk = zero16;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      uq = mm_f16(af[s], ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
-      uk = mm_f16(af[s], ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
+      const u32x4 af = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);  // A' rows of this wave's features
+      uq = mm_f16(af, ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
+      uk = mm_f16(af, ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
     }
     {
       const float sub = sc[SC_NK * kT + l32] + c_ref;
@@ -281,7 +273,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
     // ---- stage 2: kernel values of the tile, At[i][l] = phi_Q,i . phi_K,l for l <= i ---------------
     if (wv == 0) {
       f32x16 acc = zero16;  // rows l, columns i
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PK, LDP, 0, 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
@@ -296,7 +288,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
     // ---- stage 3: numerator N^T[dv][i] (waves 0, 1) and denominator (wave 2) ------------------------
     if (wv < 2) {
       f32x16 acc = zero16;  // rows dv, columns i
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(St, LDP, 32 * wv, 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
       for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_tr(Vt, LDX, 16 * s, 32 * wv, lane), ld_direct(At, LDT, 0, 16 * s, lane), acc);
@@ -304,7 +296,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
       for (int v = 0; v < 16; ++v) Nt[(32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)) * LDN + l32] = acc[v];
     } else if (wv == 2) {
       f32x16 acc = zero16;  // every row: the denominator of column i
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) {
         const u32x4 zf = *reinterpret_cast<const u32x4*>(zb + 16 * s + 8 * hf);
         acc = mm_bf16(zf, ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
@@ -390,7 +382,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
     // ---- stage 6: dQ, and the state updates -----------------------------------------------------------
     if (wv < 2 && dQ != nullptr) {
       f32x16 acc = zero16;  // rows i, columns d (32 wv + l32)
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -398,25 +390,30 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         if (tok0 + i < L) dQ[((size_t)bh * L + tok0 + i) * kD + 32 * wv + l32] = inv_log2e * acc[v];
       }
     }
-    {
-      const u32x4 ones = {kOnes, kOnes, kOnes, kOnes};
 #pragma unroll
-      for (int s = 0; s < kT / 16; ++s) {
-        const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * wv, lane);
-        const u32x4 pkf = ld_tr(PK, LDP, 16 * s, 32 * wv, lane);
-        const u32x4 pqf = ld_tr(PQ, LDP, 16 * s, 32 * wv, lane);
+    for (int s = 0; s < kT / 16; ++s) {
+      const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * wv, lane);
+      const u32x4 pkf = ld_tr(PK, LDP, 16 * s, 32 * wv, lane);
+      const u32x4 pqf = ld_tr(PQ, LDP, 16 * s, 32 * wv, lane);
 #pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          Tq[db] = mm_f16(dlf, ld_tr(Xq, LDX, 16 * s, 32 * db, lane), Tq[db]);
-          S[db] = mm_bf16(pkf, ld_tr(Vt, LDX, 16 * s, 32 * db, lane), S[db]);
-          Rn[db] = mm_bf16(pqf, ld_tr(Gh, LDX, 16 * s, 32 * db, lane), Rn[db]);
-        }
-        Zc = mm_bf16(pkf, ones, Zc);
-        // B operand whose every column is gdhat of the contraction rows 16 s + 8 hf + [0,8)
-        const float* gp = sc + SC_GDH * kT + 16 * s + 8 * hf;
-        const u32x4 gdf = {pack_bf16(gp[0], gp[1]), pack_bf16(gp[2], gp[3]), pack_bf16(gp[4], gp[5]), pack_bf16(gp[6], gp[7])};
-        Rd = mm_bf16(pqf, gdf, Rd);
+      for (int db = 0; db < 2; ++db) {
+        Tq[db] = mm_f16(dlf, ld_tr(Xq, LDX, 16 * s, 32 * db, lane), Tq[db]);
+        S[db] = mm_bf16(pkf, ld_tr(Vt, LDX, 16 * s, 32 * db, lane), S[db]);
+        Rn[db] = mm_bf16(pqf, ld_tr(Gh, LDX, 16 * s, 32 * db, lane), Rn[db]);
       }
+    }
+    if (tid < kF) {  // z_f += sum_l phi_K,lf
+      float a = 0.f;
+#pragma unroll
+      for (int l = 0; l < kT; ++l) a += __uint_as_float((unsigned)PK[l * LDP + tid] << 16);
+      const float z1 = zs[tid] + a;
+      zs[tid] = z1;
+      zb[tid] = (us)(pack_bf16(z1, 0.f) & 0xffffu);
+    } else {         // Rd_f += sum_i phi_Q,if gdhat_i
+      float a = 0.f;
+#pragma unroll
+      for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid - kF] << 16), sc[SC_GDH * kT + i], a);
+      rd_acc += a;
     }
     publish_state();
     __syncthreads();
@@ -431,10 +428,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
       dRn[(ob + ft) * kD + 32 * db + l32] = Rn[db][v];
       TQ[(ob + ft) * kD + 32 * db + l32] = Tq[db][v];
     }
-  if (l32 == 0) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) dRd[ob + 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)] = Rd[v];
-  }
+  if (tid >= kF) dRd[ob + tid - kF] = rd_acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -526,7 +520,8 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
     }
   }
   // running suffix state of this wave's 32 features, the slice's T_K; Rm block of waves 4..7
-  f32x16 Rn[2], Rd, Tk[2], Rm;
+  f32x16 Rn[2], Tk[2], Rm;
+  float rd_new = 0.f;  // threads 256..511: Rd of feature tid - 256 after the current tile (published at the end of the tile)
   {
     const size_t sb = ((size_t)bh * P + p) * kF;
 #pragma unroll
@@ -536,22 +531,15 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
         const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
         Rn[db][v] = Rsn[(sb + ft) * kD + 32 * db + l32];
       }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) Rd[v] = Rsd[sb + 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)];
+    if (tid >= kF) rd_new = Rsd[sb + tid - kF];
   }
   Tk[0] = Tk[1] = Rm = zero16;
   auto publish_state = [&]() {
     store_state_copy(Rt, Rn, wv, lane);
-    if (l32 == 0) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) rd[32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)] = Rd[v];
-    }
+    if (tid >= kF) rd[tid - kF] = rd_new;
   };
   publish_state();
   __syncthreads();
-  u32x4 af[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) af[s] = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);
 
   for (int t = ntile - 1; t >= 0; --t) {
     const int tok0 = tok_begin + t * kT;
@@ -569,8 +557,9 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       f32x16 uq = zero16, uk = zero16;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        uq = mm_f16(af[s], ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
-        uk = mm_f16(af[s], ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
+        const u32x4 af = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);
+        uq = mm_f16(af, ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
+        uk = mm_f16(af, ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
       }
       const float subk = sc[SC_NK * kT + l32] + c_ref;
       const float subq = sc[SC_LAM * kT + l32];
@@ -588,7 +577,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
     // ---- stage 2: AtT[l][i] = a_il / D_i (wave 0), ET[l][i] = G_i . v_l + gd_i (wave 1), i >= l --------
     if (wv == 0) {
       f32x16 acc = zero16;  // rows i, columns l
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PQ, LDP, 0, 16 * s, lane), ld_direct(PK, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
@@ -611,12 +600,17 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(Et + l32 * LDT + 8 * a + 4 * hf) = w;
       }
+    } else if (wv >= 4) {  // Rd_f += sum_i phihat_Q,if gd_i (before the logit gradients take phihat_Q's place)
+      float a = 0.f;
+#pragma unroll
+      for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid - kF] << 16), sc[SC_GD * kT + i], a);
+      rd_new += a;
     }
     __syncthreads();
     // ---- stage 3: dV (waves 0, 1); dlogit_K^T[f][l]; the suffix state takes the tile's queries -----------
     if (wv < 2 && dV != nullptr) {
       f32x16 acc = zero16;  // rows l, columns dv (32 wv + l32)
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PK, LDP, 0, 16 * s, lane), ld_direct(Rt, LDP, 32 * wv, 16 * s, lane), acc);
 #pragma unroll
       for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_direct(At, LDT, 0, 16 * s, lane), ld_tr(Gr, LDX, 16 * s, 32 * wv, lane), acc);
@@ -638,13 +632,9 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       }
       // the suffix state takes this tile's queries (all reads of phihat_Q are done before DL overwrites it)
 #pragma unroll
-      for (int s = 0; s < kT / 16; ++s) {
+      for (int s = 0; s < kT / 16; ++s)
 #pragma unroll
         for (int db = 0; db < 2; ++db) Rn[db] = mm_bf16(pqf[s], ld_tr(Gr, LDX, 16 * s, 32 * db, lane), Rn[db]);
-        const float* gp = sc + SC_GD * kT + 16 * s + 8 * hf;
-        const u32x4 gdf = {pack_bf16(gp[0], gp[1]), pack_bf16(gp[2], gp[3]), pack_bf16(gp[4], gp[5]), pack_bf16(gp[6], gp[7])};
-        Rd = mm_bf16(pqf[s], gdf, Rd);
-      }
       float ssum = 0.f;
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
@@ -672,7 +662,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
     __syncthreads();
     if (wv < 2 && dK != nullptr) {
       f32x16 acc = zero16, acc2 = zero16;  // rows l, columns d (32 wv + l32)
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
 #pragma unroll
       for (int s = 0; s < kD / 16; ++s) acc2 = mm_f16(ld_direct(Xk, LDX, 0, 16 * s, lane), ld_direct(G2, LDX, 32 * wv, 16 * s, lane), acc2);
