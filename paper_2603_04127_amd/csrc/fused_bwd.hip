@@ -107,25 +107,35 @@ static_assert((size_t)kD * LDX * 2 <= (size_t)kT * LDP * 2, "G2 must fit the reg
 // Per-token scalar slots in BwdSmem::sc
 enum { SC_NK = 0, SC_MU = 1, SC_DSUM = 2, SC_RHO = 3, SC_GDH = 4, SC_LAM = 5, SC_GD = 6, SC_S = 7 };
 
-// Loads the 32-token tiles of Q, K (converted to fp16), V and dOut (bf16; zero past the end) into LDS.
-__device__ __forceinline__ void load_tiles(unsigned char* smem, const us* Qb, const us* Kb, const us* Vb, const us* Gb,
-                                           int tok0, int L, int tid) {
+// The 32-token tiles of Q, K (converted to fp16), V and dOut (bf16; zero past the end): fetched into
+// registers a tile ahead (tile_fetch), written to LDS when the previous tile is done with the buffers
+// (tile_commit).  Threads 0..255 carry Q and V pieces, the others K and dOut pieces.
+struct TileRegs {
+  u32x4 x, y;
+};
+__device__ __forceinline__ TileRegs tile_fetch(const us* Qb, const us* Kb, const us* Vb, const us* Gb, int tok0, int L,
+                                               int tid) {
   const int c = tid % 256, row = c / 8, ch = c % 8;
   const int tok = tok0 + row;
   const bool in = tok < L;
-  const size_t off = (size_t)min(tok, L - 1) * kD + 8 * ch;
+  const size_t off = (size_t)max(min(tok, L - 1), 0) * kD + 8 * ch;
   const u32x4 zero = {0u, 0u, 0u, 0u};
+  TileRegs r;
   if (tid < 256) {
-    const u32x4 q = *reinterpret_cast<const u32x4*>(Qb + off);
-    const u32x4 v = in ? *reinterpret_cast<const u32x4*>(Vb + off) : zero;
-    *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::xq) + row * LDX + 8 * ch) = bf16x8_to_f16x8(q);
-    *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::vt) + row * LDX + 8 * ch) = v;
+    r.x = *reinterpret_cast<const u32x4*>(Qb + off);
+    r.y = in ? *reinterpret_cast<const u32x4*>(Vb + off) : zero;
   } else {
-    const u32x4 k = *reinterpret_cast<const u32x4*>(Kb + off);
-    const u32x4 g = in ? *reinterpret_cast<const u32x4*>(Gb + off) : zero;
-    *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::xk) + row * LDX + 8 * ch) = bf16x8_to_f16x8(k);
-    *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::gr) + row * LDX + 8 * ch) = g;
+    r.x = *reinterpret_cast<const u32x4*>(Kb + off);
+    r.y = in ? *reinterpret_cast<const u32x4*>(Gb + off) : zero;
   }
+  return r;
+}
+__device__ __forceinline__ void tile_commit(unsigned char* smem, const TileRegs& r, int tid) {
+  const int c = tid % 256, row = c / 8, ch = c % 8;
+  us* xdst = reinterpret_cast<us*>(smem + (tid < 256 ? BwdSmem::xq : BwdSmem::xk));
+  us* ydst = reinterpret_cast<us*>(smem + (tid < 256 ? BwdSmem::vt : BwdSmem::gr));
+  *reinterpret_cast<u32x4*>(xdst + row * LDX + 8 * ch) = bf16x8_to_f16x8(r.x);
+  *reinterpret_cast<u32x4*>(ydst + row * LDX + 8 * ch) = r.y;
 }
 
 // A' of head h into LDS.
@@ -227,11 +237,17 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   publish_state();
   __syncthreads();
 
+  TileRegs nxt = tile_fetch(Qb, Kb, Vb, Gb, tok_begin, L, tid);
+  float nk_nxt = (tid < kT && tok_begin + tid < L) ? nrm[(size_t)bh * L + tok_begin + tid] : kBigShift;
   for (int t = 0; t < ntile; ++t) {
     const int tok0 = tok_begin + t * kT;
-    // ---- stage 0: tiles -----------------------------------------------------------------------
-    load_tiles(smem, Qb, Kb, Vb, Gb, tok0, L, tid);
-    if (tid < kT) sc[SC_NK * kT + tid] = tok0 + tid < L ? nrm[(size_t)bh * L + tok0 + tid] : kBigShift;
+    // ---- stage 0: this tile into LDS, the next one on its way -------------------------------------
+    tile_commit(smem, nxt, tid);
+    if (tid < kT) sc[SC_NK * kT + tid] = nk_nxt;
+    if (t + 1 < ntile) {
+      nxt = tile_fetch(Qb, Kb, Vb, Gb, tok0 + kT, L, tid);
+      nk_nxt = (tid < kT && tok0 + kT + tid < L) ? nrm[(size_t)bh * L + tok0 + kT + tid] : kBigShift;
+    }
     __syncthreads();
     // ---- stage 1: projections, features ---------------------------------------------------------
     const us* Xk = reinterpret_cast<const us*>(smem + SM::xk);
@@ -541,15 +557,27 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
   publish_state();
   __syncthreads();
 
+  auto fetch_scalars = [&](int tk0, float& a, float& b, float& c) {
+    const bool valid = tid < kT && tk0 + tid < L;
+    a = valid ? nrm[(size_t)bh * L + tk0 + tid] : kBigShift;
+    b = valid ? lam[(size_t)bh * L + tk0 + tid] : kBigShift;
+    c = valid ? gdv[(size_t)bh * L + tk0 + tid] : 0.f;
+  };
+  TileRegs nxt = tile_fetch(Qb, Kb, Vb, Gb, tok_begin + (ntile - 1) * kT, L, tid);
+  float s_nk, s_lam, s_gd;
+  fetch_scalars(tok_begin + (ntile - 1) * kT, s_nk, s_lam, s_gd);
   for (int t = ntile - 1; t >= 0; --t) {
     const int tok0 = tok_begin + t * kT;
-    // ---- stage 0 ----------------------------------------------------------------------------------
-    load_tiles(smem, Qb, Kb, Vb, Gb, tok0, L, tid);
+    // ---- stage 0: this tile into LDS, the next one (towards the start of the slice) on its way --------
+    tile_commit(smem, nxt, tid);
     if (tid < kT) {
-      const bool valid = tok0 + tid < L;
-      sc[SC_NK * kT + tid] = valid ? nrm[(size_t)bh * L + tok0 + tid] : kBigShift;
-      sc[SC_LAM * kT + tid] = valid ? lam[(size_t)bh * L + tok0 + tid] : kBigShift;
-      sc[SC_GD * kT + tid] = valid ? gdv[(size_t)bh * L + tok0 + tid] : 0.f;
+      sc[SC_NK * kT + tid] = s_nk;
+      sc[SC_LAM * kT + tid] = s_lam;
+      sc[SC_GD * kT + tid] = s_gd;
+    }
+    if (t > 0) {
+      nxt = tile_fetch(Qb, Kb, Vb, Gb, tok0 - kT, L, tid);
+      fetch_scalars(tok0 - kT, s_nk, s_lam, s_gd);
     }
     __syncthreads();
     // ---- stage 1: phihat_Q = exp2(u - lambda), phi_K ------------------------------------------------
