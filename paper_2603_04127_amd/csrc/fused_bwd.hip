@@ -80,6 +80,23 @@ __device__ __forceinline__ float bf_lo(unsigned w) { return __uint_as_float(w <<
 __device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 constexpr unsigned kOnes = 0x3f803f80u;
 
+// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global load and
+// store in flight, which would expose the latency of the next tile's prefetch and of the gradient stores at
+// each of the tile's barriers.  Registers filled by global loads are private to the lane; the compiler
+// still waits for them where they are used.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Scheduling hint: the next NR LDS reads are issued together, then NM MFMAs.  Without it the compiler, short
+// of registers next to ~100 accumulators of running state, issues each operand read right before its MFMA
+// into the same registers and waits for it: every step then pays the full LDS latency.
+#define SCHED_READS_MFMAS(NR, NM)                          \
+  do {                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x100, (NR), 0);   \
+    __builtin_amdgcn_sched_group_barrier(0x008, (NM), 0);   \
+  } while (0)
+
 struct BwdSmem {
   // byte offsets; F = forward-order kernel, R = reverse-order kernel (same map, a few regions differ in use)
   static constexpr size_t al = 0;                                  // A' fp16 [256][LDX]
@@ -248,7 +265,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
       nxt = tile_fetch(Qb, Kb, Vb, Gb, tok0 + kT, L, tid);
       nk_nxt = (tid < kT && tok0 + kT + tid < L) ? nrm[(size_t)bh * L + tok0 + kT + tid] : kBigShift;
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 1: projections, features ---------------------------------------------------------
     const us* Xk = reinterpret_cast<const us*>(smem + SM::xk);
     f32x16 uq = zero16, uk = zero16;
@@ -272,7 +289,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         *reinterpret_cast<u32x2*>(PK + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
     }
-    __syncthreads();
+    lds_barrier();
     {
       float mu = mx[l32];
 #pragma unroll
@@ -285,8 +302,10 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
     }
-    __syncthreads();
-    // ---- stage 2: kernel values of the tile, At[i][l] = phi_Q,i . phi_K,l for l <= i ---------------
+    lds_barrier();
+    // ---- stage 2: wave 0: kernel values of the tile, At[i][l] = phi_Q,i . phi_K,l for l <= i; meanwhile
+    // waves 1, 2: the state part of the numerator N^T[dv][i], wave 3: of the denominator, wave 4: G_i . v_l ----
+    f32x16 held = zero16;
     if (wv == 0) {
       f32x16 acc = zero16;  // rows l, columns i
 #pragma unroll 4
@@ -299,30 +318,33 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(At + l32 * LDT + 8 * a + 4 * hf) = w;
       }
-    }
-    __syncthreads();
-    // ---- stage 3: numerator N^T[dv][i] (waves 0, 1) and denominator (wave 2) ------------------------
-    if (wv < 2) {
-      f32x16 acc = zero16;  // rows dv, columns i
+    } else if (wv < 3) {    // rows dv (block wv - 1), columns i
 #pragma unroll 4
-      for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(St, LDP, 32 * wv, 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
-#pragma unroll
-      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_tr(Vt, LDX, 16 * s, 32 * wv, lane), ld_direct(At, LDT, 0, 16 * s, lane), acc);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) Nt[(32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)) * LDN + l32] = acc[v];
-    } else if (wv == 2) {
-      f32x16 acc = zero16;  // every row: the denominator of column i
+      for (int s = 0; s < kF / 16; ++s) held = mm_bf16(ld_direct(St, LDP, 32 * (wv - 1), 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), held);
+    } else if (wv == 3) {   // every row: the denominator of column i
 #pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) {
         const u32x4 zf = *reinterpret_cast<const u32x4*>(zb + 16 * s + 8 * hf);
-        acc = mm_bf16(zf, ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
+        held = mm_bf16(zf, ld_direct(PQ, LDP, 0, 16 * s, lane), held);
       }
+    } else if (wv == 4) {   // rows l, columns i: G_i . v_l from the unscaled dOut (exact products of bf16 values)
+#pragma unroll
+      for (int s = 0; s < kD / 16; ++s) held = mm_bf16(ld_direct(Vt, LDX, 0, 16 * s, lane), ld_direct(Gr, LDX, 0, 16 * s, lane), held);
+    }
+    lds_barrier();
+    // ---- stage 3: the tile's own keys enter numerator and denominator -------------------------------
+    if (wv == 1 || wv == 2) {
+#pragma unroll
+      for (int s = 0; s < kT / 16; ++s) held = mm_bf16(ld_tr(Vt, LDX, 16 * s, 32 * (wv - 1), lane), ld_direct(At, LDT, 0, 16 * s, lane), held);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) Nt[(32 * (wv - 1) + 8 * (v / 4) + 4 * hf + (v % 4)) * LDN + l32] = held[v];
+    } else if (wv == 3) {
       const u32x4 ones = {kOnes, kOnes, kOnes, kOnes};
 #pragma unroll
-      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ones, ld_direct(At, LDT, 0, 16 * s, lane), acc);
-      if (hf == 0) sc[SC_DSUM * kT + l32] = acc[0];
+      for (int s = 0; s < kT / 16; ++s) held = mm_bf16(ones, ld_direct(At, LDT, 0, 16 * s, lane), held);
+      if (hf == 0) sc[SC_DSUM * kT + l32] = held[0];
     }
-    __syncthreads();
+    lds_barrier();
     // ---- per-token scalars: rho = 1 / D, gd, lambda; the scaled dOut tile ----------------------------
     {
       const int i = tid / 16, q = tid % 16;
@@ -355,23 +377,29 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         }
       }
     }
-    __syncthreads();
-    // ---- stage 4: Et[i][l] = (G_i . v_l + gd_i) / D_i for l <= i --------------------------------------
-    if (wv == 0) {
-      f32x16 acc = zero16;  // rows l, columns i
-#pragma unroll
-      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_direct(Vt, LDX, 0, 16 * s, lane), ld_direct(Gh, LDX, 0, 16 * s, lane), acc);
-      const float gd = sc[SC_GDH * kT + l32];
+    if (wv == 4) {
+      // Et[i][l] = (G_i . v_l - G_i . out_i) / D_i for l <= i, from the products held since stage 2; this wave
+      // forms rho_i and G_i . N_i of its column i itself (the others' results are not visible yet)
+      const float dsum = sc[SC_DSUM * kT + l32];
+      const float rho = tok0 + l32 < L ? 1.f / dsum : 0.f;
+      float dr = 0.f;
+#pragma unroll 8
+      for (int dd = 0; dd < 32; ++dd) {
+        const int d = 32 * hf + dd;
+        dr = fmaf(__uint_as_float((unsigned)Gr[l32 * LDX + d] << 16), Nt[d * LDN + l32], dr);
+      }
+      dr += __shfl_xor(dr, 32, 64);
+      const float gd = -rho * rho * dr;
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         float e[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) e[j] = (8 * a + 4 * hf + j <= l32) ? acc[4 * a + j] + gd : 0.f;
+        for (int j = 0; j < 4; ++j) e[j] = (8 * a + 4 * hf + j <= l32) ? fmaf(rho, held[4 * a + j], gd) : 0.f;
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(Et + l32 * LDT + 8 * a + 4 * hf) = w;
       }
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 5: dlogit_Q^T[f][i] = phi_Q ( S Ghat_i + z gdhat_i + sum_{l<=i} E_il phi_K,l ) ----------
     {
       f32x16 acc = zero16;  // rows f (this wave's 32), columns i
@@ -394,12 +422,15 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         *reinterpret_cast<u32x2*>(DL + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 6: dQ, and the state updates -----------------------------------------------------------
     if (wv < 2 && dQ != nullptr) {
       f32x16 acc = zero16;  // rows i, columns d (32 wv + l32)
 #pragma unroll 4
-      for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+      for (int s = 0; s < kF / 16; ++s) {
+        acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+        if (s % 4 == 3) SCHED_READS_MFMAS(12, 4);
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = 8 * (v / 4) + 4 * hf + (v % 4);
@@ -417,6 +448,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         S[db] = mm_bf16(pkf, ld_tr(Vt, LDX, 16 * s, 32 * db, lane), S[db]);
         Rn[db] = mm_bf16(pqf, ld_tr(Gh, LDX, 16 * s, 32 * db, lane), Rn[db]);
       }
+      SCHED_READS_MFMAS(18, 6);
     }
     if (tid < kF) {  // z_f += sum_l phi_K,lf
       float a = 0.f;
@@ -432,7 +464,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
       rd_acc += a;
     }
     publish_state();
-    __syncthreads();
+    lds_barrier();
   }
   // ---- the slice's contributions ---------------------------------------------------------------------
   const size_t ob = ((size_t)bh * P + p) * kF;
@@ -480,8 +512,9 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
                                                    const float* __restrict__ lam, const float* __restrict__ gdv,
                                                    const float* __restrict__ Rsn, const float* __restrict__ Rsd,
                                                    float* __restrict__ dK, float* __restrict__ dV,
-                                                   float* __restrict__ TK, float* __restrict__ RM, int H, int L, int P,
-                                                   int slice_len, float inv_log2e) {
+                                                   const float* __restrict__ TQ, float* __restrict__ TK,
+                                                   float* __restrict__ RM, int H, int L, int P, int slice_len,
+                                                   float inv_log2e) {
   using SM = BwdSmem;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   us* Al = reinterpret_cast<us*>(smem + SM::al);
@@ -549,7 +582,14 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       }
     if (tid >= kF) rd_new = Rsd[sb + tid - kF];
   }
-  Tk[0] = Tk[1] = Rm = zero16;
+  {  // T of the slice: the query half comes from the forward-order pass, the key half is added here
+    const size_t sb = ((size_t)bh * P + p) * kF;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) Tk[db][v] = TQ[(sb + 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)) * kD + 32 * db + l32];
+  }
+  Rm = zero16;
   auto publish_state = [&]() {
     store_state_copy(Rt, Rn, wv, lane);
     if (tid >= kF) rd[tid - kF] = rd_new;
@@ -579,7 +619,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       nxt = tile_fetch(Qb, Kb, Vb, Gb, tok0 - kT, L, tid);
       fetch_scalars(tok0 - kT, s_nk, s_lam, s_gd);
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 1: phihat_Q = exp2(u - lambda), phi_K ------------------------------------------------
     {
       f32x16 uq = zero16, uk = zero16;
@@ -601,7 +641,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
         *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = wq;
       }
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 2: AtT[l][i] = a_il / D_i (wave 0), ET[l][i] = G_i . v_l + gd_i (wave 1), i >= l --------
     if (wv == 0) {
       f32x16 acc = zero16;  // rows i, columns l
@@ -634,7 +674,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid - kF] << 16), sc[SC_GD * kT + i], a);
       rd_new += a;
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 3: dV (waves 0, 1); dlogit_K^T[f][l]; the suffix state takes the tile's queries -----------
     if (wv < 2 && dV != nullptr) {
       f32x16 acc = zero16;  // rows l, columns dv (32 wv + l32)
@@ -679,7 +719,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       ssum += __shfl_xor(ssum, 32, 64);
       if (hf == 0) sp[wv * kT + l32] = ssum;
     }
-    __syncthreads();
+    lds_barrier();
     // ---- stage 4: s_l; dK; T_K; Rm; publish the new suffix state -----------------------------------------
     if (tid < kT) {
       float s = 0.f;
@@ -687,11 +727,14 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       for (int w = 0; w < 8; ++w) s += sp[w * kT + tid];
       sc[SC_S * kT + tid] = s;
     }
-    __syncthreads();
+    lds_barrier();
     if (wv < 2 && dK != nullptr) {
       f32x16 acc = zero16, acc2 = zero16;  // rows l, columns d (32 wv + l32)
 #pragma unroll 4
-      for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+      for (int s = 0; s < kF / 16; ++s) {
+        acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+        if (s % 4 == 3) SCHED_READS_MFMAS(12, 4);
+      }
 #pragma unroll
       for (int s = 0; s < kD / 16; ++s) acc2 = mm_f16(ld_direct(Xk, LDX, 0, 16 * s, lane), ld_direct(G2, LDX, 32 * wv, 16 * s, lane), acc2);
 #pragma unroll
@@ -723,7 +766,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       }
     }
     publish_state();
-    __syncthreads();
+    lds_barrier();
   }
   const size_t ob = ((size_t)bh * P + p) * kF;
 #pragma unroll
@@ -742,45 +785,51 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
 }
 
 // ---------------------------------------------------------------------------
-// k_bwd_sum: Tsum[bh] = sum_p (TQ_p + TK_p), Rmsum[bh] = sum_p RM_p (p ascending: fixed order).
+// k_bwd_sum: per head, Tsum[h] = sum over batch entries and slices of the slice matrices T (queries and keys
+// together), Rmsum[h] likewise; (b, p) ascending: fixed order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_bwd_sum(const float* __restrict__ TQ, const float* __restrict__ TK,
-                                                 const float* __restrict__ RM, float* __restrict__ Tsum,
-                                                 float* __restrict__ Rmsum, int P, long long BH) {
+__global__ __launch_bounds__(256) void k_bwd_sum(const float* __restrict__ T, const float* __restrict__ RM,
+                                                 float* __restrict__ Tsum, float* __restrict__ Rmsum, int B, int H, int P) {
   const long long per = (long long)kF * kD + kD * kD;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= BH * per) return;
-  const long long bh = idx / per, e = idx % per;
+  if (idx >= (long long)H * per) return;
+  const int h = (int)(idx / per);
+  const long long e = idx % per;
   float run = 0.f;
   if (e < (long long)kF * kD) {
-    for (int p = 0; p < P; ++p) run += TQ[((size_t)bh * P + p) * kF * kD + e] + TK[((size_t)bh * P + p) * kF * kD + e];
-    Tsum[(size_t)bh * kF * kD + e] = run;
+    for (int b = 0; b < B; ++b)
+      for (int p = 0; p < P; ++p) run += T[(((size_t)b * H + h) * P + p) * kF * kD + e];
+    Tsum[(size_t)h * kF * kD + e] = run;
   } else {
     const long long e2 = e - (long long)kF * kD;
-    for (int p = 0; p < P; ++p) run += RM[((size_t)bh * P + p) * kD * kD + e2];
-    Rmsum[(size_t)bh * kD * kD + e2] = run;
+    for (int b = 0; b < B; ++b)
+      for (int p = 0; p < P; ++p) run += RM[(((size_t)b * H + h) * P + p) * kD * kD + e2];
+    Rmsum[(size_t)h * kD * kD + e2] = run;
   }
 }
 
 // ---------------------------------------------------------------------------
-// k_bwd_dm: dM[h][r][d] = sum_b ( alpha sum_j W[h][j][r] T[b,h][j][d] - alpha^2 sum_e M[h][r][e] Rm[b,h][e][d] ),
-// b ascending.  One block of 64 threads (d) per (h, r).
+// k_bwd_dm: dM[h][r][d] = alpha sum_j W[h][j][r] Tsum[h][j][d] - alpha^2 sum_e M[h][r][e] Rmsum[h][e][d].
+// One block per (h, four rows r): thread (r, d), the contraction split over nothing (320 terms).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_bwd_dm(const float* __restrict__ Tsum, const float* __restrict__ Rmsum,
-                                               const float* __restrict__ M, const float* __restrict__ W,
-                                               float* __restrict__ dM, int B, int H, int w_shared, float alpha) {
-  const int h = blockIdx.x / kD, r = blockIdx.x % kD, d = threadIdx.x;
+__global__ __launch_bounds__(256) void k_bwd_dm(const float* __restrict__ Tsum, const float* __restrict__ Rmsum,
+                                                const float* __restrict__ M, const float* __restrict__ W,
+                                                float* __restrict__ dM, int H, int w_shared, float alpha) {
+  const int h = blockIdx.x / (kD / 4), r = 4 * (blockIdx.x % (kD / 4)) + threadIdx.x / kD, d = threadIdx.x % kD;
   const float* Wh = W + (w_shared ? 0 : (size_t)h * kF * kD);
   const float* Mr = M + ((size_t)h * kD + r) * kD;
-  float total = 0.f;
-  for (int b = 0; b < B; ++b) {
-    const size_t bh = (size_t)b * H + h;
-    float a1 = 0.f, a2 = 0.f;
-    for (int j = 0; j < kF; ++j) a1 = fmaf(Wh[(size_t)j * kD + r], Tsum[(bh * kF + j) * kD + d], a1);
-    for (int e = 0; e < kD; ++e) a2 = fmaf(Mr[e], Rmsum[(bh * kD + e) * kD + d], a2);
-    total += alpha * a1 - alpha * alpha * a2;
+  float a1 = 0.f, a2 = 0.f, b1 = 0.f, b2 = 0.f;
+#pragma unroll 4
+  for (int j = 0; j < kF; j += 2) {
+    a1 = fmaf(Wh[(size_t)j * kD + r], Tsum[((size_t)h * kF + j) * kD + d], a1);
+    b1 = fmaf(Wh[(size_t)(j + 1) * kD + r], Tsum[((size_t)h * kF + j + 1) * kD + d], b1);
   }
-  dM[((size_t)h * kD + r) * kD + d] = total;
+#pragma unroll 4
+  for (int e = 0; e < kD; e += 2) {
+    a2 = fmaf(Mr[e], Rmsum[((size_t)h * kD + e) * kD + d], a2);
+    b2 = fmaf(Mr[e + 1], Rmsum[((size_t)h * kD + e + 1) * kD + d], b2);
+  }
+  dM[((size_t)h * kD + r) * kD + d] = alpha * (a1 + b1) - alpha * alpha * (a2 + b2);
 }
 
 }  // namespace
@@ -821,8 +870,8 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   float* TQ = ar.take<float>(nstate * kD);
   float* TK = ar.take<float>(nstate * kD);
   float* RM = ar.take<float>((size_t)BH * P * kD * kD);
-  float* Tsum = ar.take<float>((size_t)BH * kF * kD);
-  float* Rmsum = ar.take<float>((size_t)BH * kD * kD);
+  float* Tsum = ar.take<float>((size_t)p.H * kF * kD);
+  float* Rmsum = ar.take<float>((size_t)p.H * kD * kD);
   if (ar.base == nullptr) return DARK_OK;
   if (ar.overflow) return DARK_EWORKSPACE;
 
@@ -841,11 +890,12 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   }
   DARK_TRY(allow_lds(k_bwd_rev, BwdSmem::total));
   DARK_LAUNCH(KID_BWD_REV, pb.st, k_bwd_rev, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah, Mh,
-              nrm, cpre, lam, gdv, Rsn, Rsd, dK, dV, TK, RM, p.H, p.L, P, sl, inv_log2e);
+              nrm, cpre, lam, gdv, Rsn, Rsd, dK, dV, TQ, TK, RM, p.H, p.L, P, sl, inv_log2e);
   if (dM != nullptr) {
-    const long long n = BH * ((long long)kF * kD + kD * kD);
-    DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_sum, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, TQ, TK, RM, Tsum, Rmsum, P, BH);
-    DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_dm, dim3((unsigned)(p.H * kD)), dim3(64), 0, Tsum, Rmsum, M, W, dM, p.B, p.H,
+    const long long n = (long long)p.H * ((long long)kF * kD + kD * kD);
+    DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_sum, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, TK, RM, Tsum, Rmsum, p.B, p.H,
+                P);
+    DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_dm, dim3((unsigned)(p.H * (kD / 4))), dim3(256), 0, Tsum, Rmsum, M, W, dM, p.H,
                 p.w_shared, std::sqrt(pb.scale));
   }
   return DARK_OK;
