@@ -88,15 +88,6 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Scheduling hint: the next NR LDS reads are issued together, then NM MFMAs.  Without it the compiler, short
-// of registers next to ~100 accumulators of running state, issues each operand read right before its MFMA
-// into the same registers and waits for it: every step then pays the full LDS latency.
-#define SCHED_READS_MFMAS(NR, NM)                          \
-  do {                                                      \
-    __builtin_amdgcn_sched_group_barrier(0x100, (NR), 0);   \
-    __builtin_amdgcn_sched_group_barrier(0x008, (NM), 0);   \
-  } while (0)
-
 struct BwdSmem {
   // byte offsets; F = forward-order kernel, R = reverse-order kernel (same map, a few regions differ in use)
   static constexpr size_t al = 0;                                  // A' fp16 [256][LDX]
@@ -111,7 +102,7 @@ struct BwdSmem {
   static constexpr size_t gh = gr + (size_t)kT * LDX * 2;          // F: dOut / D (bf16)
   static constexpr size_t at = gh + (size_t)kT * LDX * 2;          // kernel-value tile bf16 [32][LDT]
   static constexpr size_t et = at + (size_t)kT * LDT * 2;          // E tile bf16 [32][LDT]
-  static constexpr size_t nt = et + (size_t)kT * LDT * 2;          // F: N^T fp32 [64][LDN]
+  static constexpr size_t nt = et + (size_t)kT * LDT * 2;          // F: N^T fp32 [64][LDN]; then the staging tile fp32 [32][64] of dQ (F), dV and dK (R)
   static constexpr size_t zs = nt + (size_t)kD * LDN * 4;          // F: z fp32 [256];  R: Rd fp32 [256]
   static constexpr size_t zb = zs + (size_t)kF * 4;                // F: z bf16 [256]
   static constexpr size_t mx = zb + (size_t)kF * 2;                // fp32 [8][32]: row maxima (F) / partial row sums (R)
@@ -124,37 +115,35 @@ static_assert((size_t)kD * LDX * 2 <= (size_t)kT * LDP * 2, "G2 must fit the reg
 // Per-token scalar slots in BwdSmem::sc
 enum { SC_NK = 0, SC_MU = 1, SC_DSUM = 2, SC_RHO = 3, SC_GDH = 4, SC_LAM = 5, SC_GD = 6, SC_S = 7 };
 
-// Workgroups of the two tile kernels: four waves, one per SIMD, so that a wave may use the whole register file
-// (the ~190 accumulators of running state of a wave sit in the accumulation registers, the rest is free for
-// operand fragments in flight); wave w owns the feature blocks 2 w and 2 w + 1 (32 features each).
-constexpr int kNT = 256;
-
 // The 32-token tiles of Q, K (converted to fp16), V and dOut (bf16; zero past the end): fetched into
 // registers a tile ahead (tile_fetch), written to LDS when the previous tile is done with the buffers
-// (tile_commit).  Thread t carries the 16-byte piece t % 8 of row t / 8 of all four tiles.
+// (tile_commit).  Threads 0..255 carry Q and V pieces, the others K and dOut pieces.
 struct TileRegs {
-  u32x4 q, k, v, g;
+  u32x4 x, y;
 };
 __device__ __forceinline__ TileRegs tile_fetch(const us* Qb, const us* Kb, const us* Vb, const us* Gb, int tok0, int L,
                                                int tid) {
-  const int row = tid / 8, ch = tid % 8;
+  const int c = tid % 256, row = c / 8, ch = c % 8;
   const int tok = tok0 + row;
   const bool in = tok < L;
   const size_t off = (size_t)max(min(tok, L - 1), 0) * kD + 8 * ch;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   TileRegs r;
-  r.q = *reinterpret_cast<const u32x4*>(Qb + off);
-  r.k = *reinterpret_cast<const u32x4*>(Kb + off);
-  r.v = in ? *reinterpret_cast<const u32x4*>(Vb + off) : zero;
-  r.g = in ? *reinterpret_cast<const u32x4*>(Gb + off) : zero;
+  if (tid < 256) {
+    r.x = *reinterpret_cast<const u32x4*>(Qb + off);
+    r.y = in ? *reinterpret_cast<const u32x4*>(Vb + off) : zero;
+  } else {
+    r.x = *reinterpret_cast<const u32x4*>(Kb + off);
+    r.y = in ? *reinterpret_cast<const u32x4*>(Gb + off) : zero;
+  }
   return r;
 }
 __device__ __forceinline__ void tile_commit(unsigned char* smem, const TileRegs& r, int tid) {
-  const int row = tid / 8, ch = tid % 8, at = row * LDX + 8 * ch;
-  *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::xq) + at) = bf16x8_to_f16x8(r.q);
-  *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::xk) + at) = bf16x8_to_f16x8(r.k);
-  *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::vt) + at) = r.v;
-  *reinterpret_cast<u32x4*>(reinterpret_cast<us*>(smem + BwdSmem::gr) + at) = r.g;
+  const int c = tid % 256, row = c / 8, ch = c % 8;
+  us* xdst = reinterpret_cast<us*>(smem + (tid < 256 ? BwdSmem::xq : BwdSmem::xk));
+  us* ydst = reinterpret_cast<us*>(smem + (tid < 256 ? BwdSmem::vt : BwdSmem::gr));
+  *reinterpret_cast<u32x4*>(xdst + row * LDX + 8 * ch) = bf16x8_to_f16x8(r.x);
+  *reinterpret_cast<u32x4*>(ydst + row * LDX + 8 * ch) = r.y;
 }
 
 // A' of head h into LDS.
@@ -162,29 +151,42 @@ __device__ __forceinline__ void load_a(unsigned char* smem, const _Float16* Ah, 
   us* Al = reinterpret_cast<us*>(smem + BwdSmem::al);
   const us* src = reinterpret_cast<const us*>(Ah) + (size_t)h * kF * kD;
 #pragma unroll
-  for (int u = 0; u < kF * kD / 8 / kNT; ++u) {
-    const int ci = tid + kNT * u, row = ci / 8, ch = ci % 8;
+  for (int u = 0; u < kF * kD / 8 / 512; ++u) {
+    const int ci = tid + 512 * u, row = ci / 8, ch = ci % 8;
     *reinterpret_cast<u32x4*>(Al + row * LDX + 8 * ch) = *reinterpret_cast<const u32x4*>(src + (size_t)row * kD + 8 * ch);
   }
 }
 
-// Writes the 32-feature block fb of a [feature][dv] fp32 state (two 32 x 32 accumulators: lane = value
+// Writes a wave's 32-feature block of a [feature][dv] fp32 state (two 32 x 32 accumulators: lane = value
 // column, registers = features 8 a + 4 hf + j) as bf16 into the [dv][F] copy.
-__device__ __forceinline__ void store_state_copy(us* St, const f32x16 (&S)[2], int fb, int lane) {
+__device__ __forceinline__ void store_state_copy(us* St, const f32x16 (&S)[2], int wv, int lane) {
   const int l32 = lane % 32, hf = lane / 32;
 #pragma unroll
   for (int db = 0; db < 2; ++db)
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       const u32x2 w = {pack_bf16(S[db][4 * a], S[db][4 * a + 1]), pack_bf16(S[db][4 * a + 2], S[db][4 * a + 3])};
-      *reinterpret_cast<u32x2*>(St + (32 * db + l32) * LDP + 32 * fb + 8 * a + 4 * hf) = w;
+      *reinterpret_cast<u32x2*>(St + (32 * db + l32) * LDP + 32 * wv + 8 * a + 4 * hf) = w;
     }
+}
+
+// Gradient tiles (32 tokens x 64, fp32) leave through LDS: the waves that hold the accumulators write them
+// to a staging tile, and after the next barrier all threads store full rows (16 bytes per lane, a row per
+// 16 lanes), the rows past the end of the sequence left out.  (Stores straight from the accumulator layout
+// need an address per row, which cost registers or spills.)
+__device__ __forceinline__ void stage_tile(float* Ns, const f32x16& acc, float f, int cb, int lane) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) Ns[(8 * (v / 4) + 4 * (lane / 32) + (v % 4)) * kD + 32 * cb + lane % 32] = f * acc[v];
+}
+__device__ __forceinline__ void flush_tile(const float* Ns, float* dst, size_t row0, int nvalid, int tid) {
+  const int row = tid / 16, ch = tid % 16;
+  if (row < nvalid) *reinterpret_cast<f32x4*>(dst + (row0 + row) * kD + 4 * ch) = *reinterpret_cast<const f32x4*>(Ns + row * kD + 4 * ch);
 }
 
 // ---------------------------------------------------------------------------
 // k_bwd_fwd
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kNT, 1) void k_bwd_fwd(const us* __restrict__ Qg, const us* __restrict__ Kg,
+__global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, const us* __restrict__ Kg,
                                                    const us* __restrict__ Vg, const us* __restrict__ Gg,
                                                    const _Float16* __restrict__ Ah, const float* __restrict__ nrm,
                                                    const float* __restrict__ Spre, const float* __restrict__ zpre,
@@ -201,7 +203,6 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   us* PK = reinterpret_cast<us*>(smem + SM::pk);
   us* DL = reinterpret_cast<us*>(smem + SM::dl);
   us* Xq = reinterpret_cast<us*>(smem + SM::xq);
-  us* Xk = reinterpret_cast<us*>(smem + SM::xk);
   us* Vt = reinterpret_cast<us*>(smem + SM::vt);
   us* Gr = reinterpret_cast<us*>(smem + SM::gr);
   us* Gh = reinterpret_cast<us*>(smem + SM::gh);
@@ -229,33 +230,32 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   load_a(smem, Ah, h, tid);
-  // running state of this wave's two feature blocks: S [f][dv] (two value-column blocks each), the slice's
-  // contributions to Rn and T_Q.  z (fp32 in LDS) and the slice's Rd (a register) of feature tid are kept by
-  // the vector ALU: a column sum per tile.
-  f32x16 S[2][2], Rn[2][2], Tq[2][2];
+  // running state of this wave's 32 features: S [f][dv] (two value-column blocks), z (every column alike),
+  // and the slice's contributions to Rn, Rd, T_Q
+  // z (fp32 in LDS, feature tid of threads 0..255) and the slice's Rd (feature tid - 256 of the others,
+  // in a register) are kept by the vector ALU: a column sum per tile
+  f32x16 S[2], Rn[2], Tq[2];
   float rd_acc = 0.f;
   {
     const float f = fast_exp2(cpre[(size_t)bh * P + p] - c_ref);  // the prefix is expressed in the running shift of slice p
     const size_t sb = ((size_t)bh * P + p) * kF;
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int ft = 32 * (2 * wv + u) + 8 * (v / 4) + 4 * hf + (v % 4);
-          S[u][db][v] = f * Spre[(sb + ft) * kD + 32 * db + l32];
-        }
-    const float z0 = f * zpre[sb + tid];
-    zs[tid] = z0;
-    zb[tid] = (us)(pack_bf16(z0, 0.f) & 0xffffu);
+      for (int v = 0; v < 16; ++v) {
+        const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
+        S[db][v] = f * Spre[(sb + ft) * kD + 32 * db + l32];
+      }
+    if (tid < kF) {
+      const float z0 = f * zpre[sb + tid];
+      zs[tid] = z0;
+      zb[tid] = (us)(pack_bf16(z0, 0.f) & 0xffffu);
+    }
   }
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int db = 0; db < 2; ++db) Rn[u][db] = Tq[u][db] = zero16;
-  store_state_copy(St, S[0], 2 * wv, lane);
-  store_state_copy(St, S[1], 2 * wv + 1, lane);
+  for (int db = 0; db < 2; ++db) Rn[db] = Tq[db] = zero16;
+  auto publish_state = [&]() { store_state_copy(St, S, wv, lane); };
+  publish_state();
   __syncthreads();
 
   TileRegs nxt = tile_fetch(Qb, Kb, Vb, Gb, tok_begin, L, tid);
@@ -264,60 +264,54 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
     const int tok0 = tok_begin + t * kT;
     // ---- stage 0: this tile into LDS, the next one on its way -------------------------------------
     tile_commit(smem, nxt, tid);
+    if (dQ != nullptr && t > 0) flush_tile(Nt, dQ, (size_t)bh * L + tok0 - kT, kT, tid);  // the previous tile's dQ
     if (tid < kT) sc[SC_NK * kT + tid] = nk_nxt;
     if (t + 1 < ntile) {
       nxt = tile_fetch(Qb, Kb, Vb, Gb, tok0 + kT, L, tid);
       nk_nxt = (tid < kT && tok0 + kT + tid < L) ? nrm[(size_t)bh * L + tok0 + kT + tid] : kBigShift;
     }
-    lds_barrier();
+    __syncthreads();
     // ---- stage 1: projections, features ---------------------------------------------------------
-    f32x16 uq[2];
+    const us* Xk = reinterpret_cast<const us*>(smem + SM::xk);
+    f32x16 uq = zero16, uk = zero16;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int fb = 2 * wv + u;
-      f32x16 uk = zero16;
-      uq[u] = zero16;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const u32x4 af = ld_direct(Al, LDX, 32 * fb, 16 * s, lane);  // A' rows of the block's features
-        uq[u] = mm_f16(af, ld_direct(Xq, LDX, 0, 16 * s, lane), uq[u]);
-        uk = mm_f16(af, ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
-      }
+    for (int s = 0; s < 4; ++s) {
+      const u32x4 af = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);  // A' rows of this wave's features
+      uq = mm_f16(af, ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
+      uk = mm_f16(af, ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
+    }
+    {
       const float sub = sc[SC_NK * kT + l32] + c_ref;
-      float m0 = uq[u][0];
+      float m0 = uq[0];
 #pragma unroll
-      for (int v = 1; v < 16; ++v) m0 = fmaxf(m0, uq[u][v]);
+      for (int v = 1; v < 16; ++v) m0 = fmaxf(m0, uq[v]);
       m0 = fmaxf(m0, __shfl_xor(m0, 32, 64));
-      if (hf == 0) mx[fb * kT + l32] = m0;
+      if (hf == 0) mx[wv * kT + l32] = m0;
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         const u32x2 w = {pack_bf16(fast_exp2(uk[4 * a] - sub), fast_exp2(uk[4 * a + 1] - sub)),
                          pack_bf16(fast_exp2(uk[4 * a + 2] - sub), fast_exp2(uk[4 * a + 3] - sub))};
-        *reinterpret_cast<u32x2*>(PK + l32 * LDP + 32 * fb + 8 * a + 4 * hf) = w;
+        *reinterpret_cast<u32x2*>(PK + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
     }
-    lds_barrier();
+    __syncthreads();
     {
       float mu = mx[l32];
 #pragma unroll
       for (int w = 1; w < 8; ++w) mu = fmaxf(mu, mx[w * kT + l32]);
       if (wv == 0 && hf == 0) sc[SC_MU * kT + l32] = mu;
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          const u32x2 w = {pack_bf16(fast_exp2(uq[u][4 * a] - mu), fast_exp2(uq[u][4 * a + 1] - mu)),
-                           pack_bf16(fast_exp2(uq[u][4 * a + 2] - mu), fast_exp2(uq[u][4 * a + 3] - mu))};
-          *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * (2 * wv + u) + 8 * a + 4 * hf) = w;
-        }
+      for (int a = 0; a < 4; ++a) {
+        const u32x2 w = {pack_bf16(fast_exp2(uq[4 * a] - mu), fast_exp2(uq[4 * a + 1] - mu)),
+                         pack_bf16(fast_exp2(uq[4 * a + 2] - mu), fast_exp2(uq[4 * a + 3] - mu))};
+        *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
+      }
     }
-    lds_barrier();
-    // ---- stage 2: wave 0: kernel values of the tile, At[i][l] = phi_Q,i . phi_K,l for l <= i; meanwhile
-    // waves 1, 2: the state part of the numerator N^T[dv][i]; wave 3: of the denominator, and G_i . v_l -------
-    f32x16 held = zero16, heldE = zero16;
+    __syncthreads();
+    // ---- stage 2: kernel values of the tile, At[i][l] = phi_Q,i . phi_K,l for l <= i ---------------
     if (wv == 0) {
       f32x16 acc = zero16;  // rows l, columns i
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PK, LDP, 0, 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
@@ -327,176 +321,149 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(At + l32 * LDT + 8 * a + 4 * hf) = w;
       }
-    } else if (wv < 3) {    // rows dv (block wv - 1), columns i
+    }
+    __syncthreads();
+    // ---- stage 3: numerator N^T[dv][i] (waves 0, 1) and denominator (wave 2) ------------------------
+    if (wv < 2) {
+      f32x16 acc = zero16;  // rows dv, columns i
+#pragma unroll 4
+      for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(St, LDP, 32 * wv, 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
-      for (int s = 0; s < kF / 16; ++s) held = mm_bf16(ld_direct(St, LDP, 32 * (wv - 1), 16 * s, lane), ld_direct(PQ, LDP, 0, 16 * s, lane), held);
-    } else {                // every row: the denominator of column i
+      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_tr(Vt, LDX, 16 * s, 32 * wv, lane), ld_direct(At, LDT, 0, 16 * s, lane), acc);
 #pragma unroll
+      for (int v = 0; v < 16; ++v) Nt[(32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)) * LDN + l32] = acc[v];
+    } else if (wv == 2) {
+      f32x16 acc = zero16;  // every row: the denominator of column i
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) {
         const u32x4 zf = *reinterpret_cast<const u32x4*>(zb + 16 * s + 8 * hf);
-        held = mm_bf16(zf, ld_direct(PQ, LDP, 0, 16 * s, lane), held);
+        acc = mm_bf16(zf, ld_direct(PQ, LDP, 0, 16 * s, lane), acc);
       }
-      // rows l, columns i: G_i . v_l from the unscaled dOut (exact products of bf16 values)
-#pragma unroll
-      for (int s = 0; s < kD / 16; ++s) heldE = mm_bf16(ld_direct(Vt, LDX, 0, 16 * s, lane), ld_direct(Gr, LDX, 0, 16 * s, lane), heldE);
-    }
-    lds_barrier();
-    // ---- stage 3: the tile's own keys enter numerator and denominator -------------------------------
-    if (wv == 1 || wv == 2) {
-#pragma unroll
-      for (int s = 0; s < kT / 16; ++s) held = mm_bf16(ld_tr(Vt, LDX, 16 * s, 32 * (wv - 1), lane), ld_direct(At, LDT, 0, 16 * s, lane), held);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) Nt[(32 * (wv - 1) + 8 * (v / 4) + 4 * hf + (v % 4)) * LDN + l32] = held[v];
-    } else if (wv == 3) {
       const u32x4 ones = {kOnes, kOnes, kOnes, kOnes};
 #pragma unroll
-      for (int s = 0; s < kT / 16; ++s) held = mm_bf16(ones, ld_direct(At, LDT, 0, 16 * s, lane), held);
-      if (hf == 0) sc[SC_DSUM * kT + l32] = held[0];
+      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ones, ld_direct(At, LDT, 0, 16 * s, lane), acc);
+      if (hf == 0) sc[SC_DSUM * kT + l32] = acc[0];
     }
-    lds_barrier();
+    __syncthreads();
     // ---- per-token scalars: rho = 1 / D, gd, lambda; the scaled dOut tile ----------------------------
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int item = tid + kNT * it, i = item / 16, q = item % 16;
+    {
+      const int i = tid / 16, q = tid % 16;
       const bool valid = tok0 + i < L;
       const float dsum = sc[SC_DSUM * kT + i];
       const float rho = valid ? 1.f / dsum : 0.f;
       const u32x2 gw = *reinterpret_cast<const u32x2*>(Gr + i * LDX + 4 * q);
       // dOut / D is rounded to bf16 for the MFMAs; gd is formed from the rounded values, so that
-      // Ghat_i . S + gdhat_i z is exactly Ghat_i . (S - out_i z) and cancels where it should
+      // E_il = Ghat_i . v_l + gdhat_i is exactly Ghat_i . (v_l - out_i) and cancels where it should
       const u32x2 w = {pack_bf16(rho * bf_lo(gw[0]), rho * bf_hi(gw[0])), pack_bf16(rho * bf_lo(gw[1]), rho * bf_hi(gw[1]))};
       *reinterpret_cast<u32x2*>(Gh + i * LDX + 4 * q) = w;
-      const float n0 = Nt[(4 * q) * LDN + i], n1 = Nt[(4 * q + 1) * LDN + i], n2 = Nt[(4 * q + 2) * LDN + i],
-                  n3 = Nt[(4 * q + 3) * LDN + i];
-      float dot = bf_lo(w[0]) * n0 + bf_hi(w[0]) * n1 + bf_lo(w[1]) * n2 + bf_hi(w[1]) * n3;       // Ghat_i . N_i
-      float draw = bf_lo(gw[0]) * n0 + bf_hi(gw[0]) * n1 + bf_lo(gw[1]) * n2 + bf_hi(gw[1]) * n3;  // G_i . N_i
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) {
-        dot += __shfl_xor(dot, o, 64);
-        draw += __shfl_xor(draw, o, 64);
-      }
+      float dot = bf_lo(w[0]) * Nt[(4 * q) * LDN + i] + bf_hi(w[0]) * Nt[(4 * q + 1) * LDN + i] +
+                  bf_lo(w[1]) * Nt[(4 * q + 2) * LDN + i] + bf_hi(w[1]) * Nt[(4 * q + 3) * LDN + i];
+      dot += __shfl_xor(dot, 8, 64);
+      dot += __shfl_xor(dot, 4, 64);
+      dot += __shfl_xor(dot, 2, 64);
+      dot += __shfl_xor(dot, 1, 64);   // = Ghat_i . N_i
+      float draw = bf_lo(gw[0]) * Nt[(4 * q) * LDN + i] + bf_hi(gw[0]) * Nt[(4 * q + 1) * LDN + i] +
+                   bf_lo(gw[1]) * Nt[(4 * q + 2) * LDN + i] + bf_hi(gw[1]) * Nt[(4 * q + 3) * LDN + i];
+      draw += __shfl_xor(draw, 8, 64);
+      draw += __shfl_xor(draw, 4, 64);
+      draw += __shfl_xor(draw, 2, 64);
+      draw += __shfl_xor(draw, 1, 64);  // = G_i . N_i (the reverse pass works with the unscaled dOut)
       if (q == 0) {
         sc[SC_RHO * kT + i] = rho;
         sc[SC_GDH * kT + i] = -rho * dot;
-        sc[SC_GD * kT + i] = -rho * rho * draw;   // for the tile's own E below (the unscaled dOut times rho)
         if (valid) {
           lam[(size_t)bh * L + tok0 + i] = sc[SC_MU * kT + i] + __builtin_log2f(dsum);
           gdv[(size_t)bh * L + tok0 + i] = -rho * draw;
         }
       }
     }
-    if (wv == 3) {
-      // Et[i][l] = (G_i . v_l - G_i . out_i) / D_i for l <= i, from the products held since stage 2.  The
-      // scalars of column i were written by this wave itself (items 16 i of threads 192..255 are tokens
-      // 12..15 and 28..31 only), so they are recomputed here from what the last barrier made visible.
-      const float dsum = sc[SC_DSUM * kT + l32];
-      const float rho = tok0 + l32 < L ? 1.f / dsum : 0.f;
-      float dr = 0.f;
+    __syncthreads();
+    // ---- stage 4: Et[i][l] = (G_i . v_l + gd_i) / D_i for l <= i --------------------------------------
+    if (wv == 0) {
+      f32x16 acc = zero16;  // rows l, columns i
 #pragma unroll
-      for (int dd = 0; dd < 32; ++dd) {
-        const int dcol = 32 * hf + dd;
-        dr = fmaf(__uint_as_float((unsigned)Gr[l32 * LDX + dcol] << 16), Nt[dcol * LDN + l32], dr);
-      }
-      dr += __shfl_xor(dr, 32, 64);
-      const float gd = -rho * rho * dr;
+      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_direct(Vt, LDX, 0, 16 * s, lane), ld_direct(Gh, LDX, 0, 16 * s, lane), acc);
+      const float gd = sc[SC_GDH * kT + l32];
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         float e[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) e[j] = (8 * a + 4 * hf + j <= l32) ? fmaf(rho, heldE[4 * a + j], gd) : 0.f;
+        for (int j = 0; j < 4; ++j) e[j] = (8 * a + 4 * hf + j <= l32) ? acc[4 * a + j] + gd : 0.f;
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(Et + l32 * LDT + 8 * a + 4 * hf) = w;
       }
     }
-    lds_barrier();
+    __syncthreads();
     // ---- stage 5: dlogit_Q^T[f][i] = phi_Q ( S Ghat_i + z gdhat_i + sum_{l<=i} E_il phi_K,l ) ----------
+    {
+      f32x16 acc = zero16;  // rows f (this wave's 32), columns i
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int fb = 2 * wv + u;
-      f32x16 acc = zero16;  // rows f (the block's 32), columns i
+      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_tr(St, LDP, 16 * s, 32 * wv, lane), ld_direct(Gh, LDX, 0, 16 * s, lane), acc);
 #pragma unroll
-      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_tr(St, LDP, 16 * s, 32 * fb, lane), ld_direct(Gh, LDX, 0, 16 * s, lane), acc);
-#pragma unroll
-      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_tr(PK, LDP, 16 * s, 32 * fb, lane), ld_direct(Et, LDT, 0, 16 * s, lane), acc);
+      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_tr(PK, LDP, 16 * s, 32 * wv, lane), ld_direct(Et, LDT, 0, 16 * s, lane), acc);
       const float gd = sc[SC_GDH * kT + l32];
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         // z as the denominator saw it (rounded to bf16): with the same S, z and features in out_i and here,
         // the terms G_i . (v_l - out_i) cancel as they do in exact arithmetic
-        const u32x2 zw = *reinterpret_cast<const u32x2*>(zb + 32 * fb + 8 * a + 4 * hf);
-        const u32x2 pw = *reinterpret_cast<const u32x2*>(PQ + l32 * LDP + 32 * fb + 8 * a + 4 * hf);
+        const u32x2 zw = *reinterpret_cast<const u32x2*>(zb + 32 * wv + 8 * a + 4 * hf);
+        const u32x2 pw = *reinterpret_cast<const u32x2*>(PQ + l32 * LDP + 32 * wv + 8 * a + 4 * hf);
         const float d0 = bf_lo(pw[0]) * fmaf(bf_lo(zw[0]), gd, acc[4 * a]);
         const float d1 = bf_hi(pw[0]) * fmaf(bf_hi(zw[0]), gd, acc[4 * a + 1]);
         const float d2 = bf_lo(pw[1]) * fmaf(bf_lo(zw[1]), gd, acc[4 * a + 2]);
         const float d3 = bf_hi(pw[1]) * fmaf(bf_hi(zw[1]), gd, acc[4 * a + 3]);
         const u32x2 w = {pack_f16(d0, d1), pack_f16(d2, d3)};
-        *reinterpret_cast<u32x2*>(DL + l32 * LDP + 32 * fb + 8 * a + 4 * hf) = w;
+        *reinterpret_cast<u32x2*>(DL + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
     }
-    lds_barrier();
+    __syncthreads();
     // ---- stage 6: dQ, and the state updates -----------------------------------------------------------
     if (wv < 2 && dQ != nullptr) {
       f32x16 acc = zero16;  // rows i, columns d (32 wv + l32)
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = 8 * (v / 4) + 4 * hf + (v % 4);
-        if (tok0 + i < L) dQ[((size_t)bh * L + tok0 + i) * kD + 32 * wv + l32] = inv_log2e * acc[v];
-      }
+      stage_tile(Nt, acc, inv_log2e, wv, lane);
     }
 #pragma unroll
     for (int s = 0; s < kT / 16; ++s) {
-      u32x4 xqf[2], vtf[2], ghf[2];
+      const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * wv, lane);
+      const u32x4 pkf = ld_tr(PK, LDP, 16 * s, 32 * wv, lane);
+      const u32x4 pqf = ld_tr(PQ, LDP, 16 * s, 32 * wv, lane);
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
-        xqf[db] = ld_tr(Xq, LDX, 16 * s, 32 * db, lane);
-        vtf[db] = ld_tr(Vt, LDX, 16 * s, 32 * db, lane);
-        ghf[db] = ld_tr(Gh, LDX, 16 * s, 32 * db, lane);
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int fb = 2 * wv + u;
-        const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * fb, lane);
-        const u32x4 pkf = ld_tr(PK, LDP, 16 * s, 32 * fb, lane);
-        const u32x4 pqf = ld_tr(PQ, LDP, 16 * s, 32 * fb, lane);
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          Tq[u][db] = mm_f16(dlf, xqf[db], Tq[u][db]);
-          S[u][db] = mm_bf16(pkf, vtf[db], S[u][db]);
-          Rn[u][db] = mm_bf16(pqf, ghf[db], Rn[u][db]);
-        }
+        Tq[db] = mm_f16(dlf, ld_tr(Xq, LDX, 16 * s, 32 * db, lane), Tq[db]);
+        S[db] = mm_bf16(pkf, ld_tr(Vt, LDX, 16 * s, 32 * db, lane), S[db]);
+        Rn[db] = mm_bf16(pqf, ld_tr(Gh, LDX, 16 * s, 32 * db, lane), Rn[db]);
       }
     }
-    {  // z_f += sum_l phi_K,lf;  Rd_f += sum_i phi_Q,if gdhat_i  (feature f = tid)
-      float a = 0.f, b2 = 0.f;
+    if (tid < kF) {  // z_f += sum_l phi_K,lf
+      float a = 0.f;
 #pragma unroll
-      for (int l = 0; l < kT; ++l) {
-        a += __uint_as_float((unsigned)PK[l * LDP + tid] << 16);
-        b2 = fmaf(__uint_as_float((unsigned)PQ[l * LDP + tid] << 16), sc[SC_GDH * kT + l], b2);
-      }
+      for (int l = 0; l < kT; ++l) a += __uint_as_float((unsigned)PK[l * LDP + tid] << 16);
       const float z1 = zs[tid] + a;
       zs[tid] = z1;
       zb[tid] = (us)(pack_bf16(z1, 0.f) & 0xffffu);
-      rd_acc += b2;
+    } else {         // Rd_f += sum_i phi_Q,if gdhat_i
+      float a = 0.f;
+#pragma unroll
+      for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid - kF] << 16), sc[SC_GDH * kT + i], a);
+      rd_acc += a;
     }
-    store_state_copy(St, S[0], 2 * wv, lane);
-    store_state_copy(St, S[1], 2 * wv + 1, lane);
-    lds_barrier();
+    publish_state();
+    __syncthreads();
   }
+  if (dQ != nullptr) flush_tile(Nt, dQ, (size_t)bh * L + tok_begin + (ntile - 1) * kT, min(kT, L - (tok_begin + (ntile - 1) * kT)), tid);
   // ---- the slice's contributions ---------------------------------------------------------------------
   const size_t ob = ((size_t)bh * P + p) * kF;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int db = 0; db < 2; ++db)
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ft = 32 * (2 * wv + u) + 8 * (v / 4) + 4 * hf + (v % 4);
-        dRn[(ob + ft) * kD + 32 * db + l32] = Rn[u][db][v];
-        TQ[(ob + ft) * kD + 32 * db + l32] = Tq[u][db][v];
-      }
-  dRd[ob + tid] = rd_acc;
+    for (int v = 0; v < 16; ++v) {
+      const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
+      dRn[(ob + ft) * kD + 32 * db + l32] = Rn[db][v];
+      TQ[(ob + ft) * kD + 32 * db + l32] = Tq[db][v];
+    }
+  if (tid >= kF) dRd[ob + tid - kF] = rd_acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -525,7 +492,7 @@ __global__ __launch_bounds__(256) void k_bwd_suffix(const float* __restrict__ dR
 // ---------------------------------------------------------------------------
 // k_bwd_rev
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, const us* __restrict__ Kg,
+__global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, const us* __restrict__ Kg,
                                                    const us* __restrict__ Vg, const us* __restrict__ Gg,
                                                    const _Float16* __restrict__ Ah, const _Float16* __restrict__ Mh,
                                                    const float* __restrict__ nrm, const float* __restrict__ cpre,
@@ -540,7 +507,7 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
   us* Al = reinterpret_cast<us*>(smem + SM::al);
   us* Rt = reinterpret_cast<us*>(smem + SM::st);
   us* PQ = reinterpret_cast<us*>(smem + SM::pq);
-  us* DL = PQ;  // the logit gradients take the place of phihat_Q (a wave owns the same feature columns of both)
+  us* DL = PQ;  // the logit gradients take the place of phihat_Q (each wave owns its 32 feature columns of both)
   us* PK = reinterpret_cast<us*>(smem + SM::pk);
   us* G2 = reinterpret_cast<us*>(smem + SM::dl);
   us* Xq = reinterpret_cast<us*>(smem + SM::xq);
@@ -549,6 +516,7 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
   us* Gr = reinterpret_cast<us*>(smem + SM::gr);
   us* At = reinterpret_cast<us*>(smem + SM::at);   // AtT[l][i]
   us* Et = reinterpret_cast<us*>(smem + SM::et);   // ET[l][i]
+  float* Ns = reinterpret_cast<float*>(smem + SM::nt);  // staging tile of dV, then of dK
   float* rd = reinterpret_cast<float*>(smem + SM::zs);
   float* sp = reinterpret_cast<float*>(smem + SM::mx);
   float* sc = reinterpret_cast<float*>(smem + SM::sc);
@@ -571,49 +539,48 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
   load_a(smem, Ah, h, tid);
   {  // M' of the head into the phi_K region for a moment: G2 = M'^T M' (= alpha^2 log2e/2 M^T M)
     const us* src = reinterpret_cast<const us*>(Mh) + (size_t)h * kD * kD;
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int ci = tid + kNT * it, row = ci / 8, ch = ci % 8;
-      *reinterpret_cast<u32x4*>(PK + row * LDX + 8 * ch) = *reinterpret_cast<const u32x4*>(src + (size_t)row * kD + 8 * ch);
-    }
+    const int row = tid / 8, ch = tid % 8;
+    *reinterpret_cast<u32x4*>(PK + row * LDX + 8 * ch) = *reinterpret_cast<const u32x4*>(src + (size_t)row * kD + 8 * ch);
   }
   __syncthreads();
-  const int eb = wv / 2, dbw = wv % 2;  // this wave's 32 x 32 block of the d x d matrices G2 and Rm
-  {
+  if (wv < 4) {
+    const int eb = wv / 2, db = wv % 2;
     f32x16 acc = zero16;  // rows e, columns d
 #pragma unroll
-    for (int s = 0; s < kD / 16; ++s) acc = mm_f16(ld_tr(PK, LDX, 16 * s, 32 * eb, lane), ld_tr(PK, LDX, 16 * s, 32 * dbw, lane), acc);
+    for (int s = 0; s < kD / 16; ++s) acc = mm_f16(ld_tr(PK, LDX, 16 * s, 32 * eb, lane), ld_tr(PK, LDX, 16 * s, 32 * db, lane), acc);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       fp16x2 hv2;
       hv2[0] = (__fp16)acc[v];
       hv2[1] = (__fp16)0.f;
-      G2[(32 * eb + 8 * (v / 4) + 4 * hf + (v % 4)) * LDX + 32 * dbw + l32] = (us)(*reinterpret_cast<unsigned*>(&hv2) & 0xffffu);
+      G2[(32 * eb + 8 * (v / 4) + 4 * hf + (v % 4)) * LDX + 32 * db + l32] = (us)(*reinterpret_cast<unsigned*>(&hv2) & 0xffffu);
     }
   }
-  // running suffix state of this wave's two feature blocks, the slice's T (starting from the query half that
-  // the forward-order pass left), this wave's block of Rm; Rd of feature tid in a register (published to LDS
-  // at the end of each tile)
-  f32x16 Rn[2][2], Tk[2][2], Rm = zero16;
-  float rd_new;
+  // running suffix state of this wave's 32 features, the slice's T_K; Rm block of waves 4..7
+  f32x16 Rn[2], Tk[2], Rm;
+  float rd_new = 0.f;  // threads 256..511: Rd of feature tid - 256 after the current tile (published at the end of the tile)
   {
     const size_t sb = ((size_t)bh * P + p) * kF;
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int ft = 32 * (2 * wv + u) + 8 * (v / 4) + 4 * hf + (v % 4);
-          Rn[u][db][v] = Rsn[(sb + ft) * kD + 32 * db + l32];
-          Tk[u][db][v] = TQ[(sb + ft) * kD + 32 * db + l32];
-        }
-    rd_new = Rsd[sb + tid];
+      for (int v = 0; v < 16; ++v) {
+        const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
+        Rn[db][v] = Rsn[(sb + ft) * kD + 32 * db + l32];
+      }
+    if (tid >= kF) rd_new = Rsd[sb + tid - kF];
   }
+  {  // T of the slice: the query half comes from the forward-order pass, the key half is added here
+    const size_t sb = ((size_t)bh * P + p) * kF;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) Tk[db][v] = TQ[(sb + 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4)) * kD + 32 * db + l32];
+  }
+  Rm = zero16;
   auto publish_state = [&]() {
-    store_state_copy(Rt, Rn[0], 2 * wv, lane);
-    store_state_copy(Rt, Rn[1], 2 * wv + 1, lane);
-    rd[tid] = rd_new;
+    store_state_copy(Rt, Rn, wv, lane);
+    if (tid >= kF) rd[tid - kF] = rd_new;
   };
   publish_state();
   __syncthreads();
@@ -631,6 +598,7 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
     const int tok0 = tok_begin + t * kT;
     // ---- stage 0: this tile into LDS, the next one (towards the start of the slice) on its way --------
     tile_commit(smem, nxt, tid);
+    if (dK != nullptr && t < ntile - 1) flush_tile(Ns, dK, (size_t)bh * L + tok0 + kT, min(kT, L - (tok0 + kT)), tid);  // the previous tile's dK
     if (tid < kT) {
       sc[SC_NK * kT + tid] = s_nk;
       sc[SC_LAM * kT + tid] = s_lam;
@@ -642,13 +610,11 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
     }
     lds_barrier();
     // ---- stage 1: phihat_Q = exp2(u - lambda), phi_K ------------------------------------------------
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int fb = 2 * wv + u;
+    {
       f32x16 uq = zero16, uk = zero16;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const u32x4 af = ld_direct(Al, LDX, 32 * fb, 16 * s, lane);
+        const u32x4 af = ld_direct(Al, LDX, 32 * wv, 16 * s, lane);
         uq = mm_f16(af, ld_direct(Xq, LDX, 0, 16 * s, lane), uq);
         uk = mm_f16(af, ld_direct(Xk, LDX, 0, 16 * s, lane), uk);
       }
@@ -658,19 +624,17 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       for (int a = 0; a < 4; ++a) {
         const u32x2 wk = {pack_bf16(fast_exp2(uk[4 * a] - subk), fast_exp2(uk[4 * a + 1] - subk)),
                           pack_bf16(fast_exp2(uk[4 * a + 2] - subk), fast_exp2(uk[4 * a + 3] - subk))};
-        *reinterpret_cast<u32x2*>(PK + l32 * LDP + 32 * fb + 8 * a + 4 * hf) = wk;
+        *reinterpret_cast<u32x2*>(PK + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = wk;
         const u32x2 wq = {pack_bf16(fast_exp2(uq[4 * a] - subq), fast_exp2(uq[4 * a + 1] - subq)),
                           pack_bf16(fast_exp2(uq[4 * a + 2] - subq), fast_exp2(uq[4 * a + 3] - subq))};
-        *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * fb + 8 * a + 4 * hf) = wq;
+        *reinterpret_cast<u32x2*>(PQ + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = wq;
       }
     }
     lds_barrier();
-    // ---- stage 2: wave 0: AtT[l][i] = a_il / D_i; wave 1: ET[l][i] = G_i . v_l + gd_i (i >= l); waves 2, 3:
-    // the state part of dV; everyone: Rd takes the tile's queries (before the logit gradients take phihat_Q's place)
-    f32x16 held = zero16;
+    // ---- stage 2: AtT[l][i] = a_il / D_i (wave 0), ET[l][i] = G_i . v_l + gd_i (wave 1), i >= l --------
     if (wv == 0) {
       f32x16 acc = zero16;  // rows i, columns l
-#pragma unroll
+#pragma unroll 4
       for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PQ, LDP, 0, 16 * s, lane), ld_direct(PK, LDP, 0, 16 * s, lane), acc);
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
@@ -693,59 +657,52 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
         const u32x2 w = {pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3])};
         *reinterpret_cast<u32x2*>(Et + l32 * LDT + 8 * a + 4 * hf) = w;
       }
-    } else if (dV != nullptr) {  // rows l, columns dv (block wv - 2)
-#pragma unroll
-      for (int s = 0; s < kF / 16; ++s) held = mm_bf16(ld_direct(PK, LDP, 0, 16 * s, lane), ld_direct(Rt, LDP, 32 * (wv - 2), 16 * s, lane), held);
-    }
-    {
+    } else if (wv >= 4) {  // Rd_f += sum_i phihat_Q,if gd_i (before the logit gradients take phihat_Q's place)
       float a = 0.f;
 #pragma unroll
-      for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid] << 16), sc[SC_GD * kT + i], a);
+      for (int i = 0; i < kT; ++i) a = fmaf(__uint_as_float((unsigned)PQ[i * LDP + tid - kF] << 16), sc[SC_GD * kT + i], a);
       rd_new += a;
     }
     lds_barrier();
-    // ---- stage 3: dV (waves 2, 3); dlogit_K^T[f][l]; the suffix state takes the tile's queries -----------
-    if (wv >= 2 && dV != nullptr) {
+    // ---- stage 3: dV (waves 0, 1); dlogit_K^T[f][l]; the suffix state takes the tile's queries -----------
+    if (wv < 2 && dV != nullptr) {
+      f32x16 acc = zero16;  // rows l, columns dv (32 wv + l32)
+#pragma unroll 4
+      for (int s = 0; s < kF / 16; ++s) acc = mm_bf16(ld_direct(PK, LDP, 0, 16 * s, lane), ld_direct(Rt, LDP, 32 * wv, 16 * s, lane), acc);
 #pragma unroll
-      for (int s = 0; s < kT / 16; ++s) held = mm_bf16(ld_direct(At, LDT, 0, 16 * s, lane), ld_tr(Gr, LDX, 16 * s, 32 * (wv - 2), lane), held);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int l = 8 * (v / 4) + 4 * hf + (v % 4);
-        if (tok0 + l < L) dV[((size_t)bh * L + tok0 + l) * kD + 32 * (wv - 2) + l32] = held[v];
-      }
+      for (int s = 0; s < kT / 16; ++s) acc = mm_bf16(ld_direct(At, LDT, 0, 16 * s, lane), ld_tr(Gr, LDX, 16 * s, 32 * wv, lane), acc);
+      stage_tile(Ns, acc, 1.f, wv, lane);
     }
+    {
+      f32x16 acc = zero16;  // rows f (this wave's 32), columns l
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int fb = 2 * wv + u;
-      f32x16 acc = zero16;  // rows f (the block's 32), columns l
-#pragma unroll
-      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_tr(Rt, LDP, 16 * s, 32 * fb, lane), ld_direct(Vt, LDX, 0, 16 * s, lane), acc);
+      for (int s = 0; s < kD / 16; ++s) acc = mm_bf16(ld_tr(Rt, LDP, 16 * s, 32 * wv, lane), ld_direct(Vt, LDX, 0, 16 * s, lane), acc);
       u32x4 pqf[kT / 16];
 #pragma unroll
       for (int s = 0; s < kT / 16; ++s) {
-        pqf[s] = ld_tr(PQ, LDP, 16 * s, 32 * fb, lane);
+        pqf[s] = ld_tr(PQ, LDP, 16 * s, 32 * wv, lane);
         acc = mm_bf16(pqf[s], ld_direct(Et, LDT, 0, 16 * s, lane), acc);
       }
       // the suffix state takes this tile's queries (all reads of phihat_Q are done before DL overwrites it)
 #pragma unroll
       for (int s = 0; s < kT / 16; ++s)
 #pragma unroll
-        for (int db = 0; db < 2; ++db) Rn[u][db] = mm_bf16(pqf[s], ld_tr(Gr, LDX, 16 * s, 32 * db, lane), Rn[u][db]);
+        for (int db = 0; db < 2; ++db) Rn[db] = mm_bf16(pqf[s], ld_tr(Gr, LDX, 16 * s, 32 * db, lane), Rn[db]);
       float ssum = 0.f;
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rd + 32 * fb + 8 * a + 4 * hf);
-        const u32x2 pw = *reinterpret_cast<const u32x2*>(PK + l32 * LDP + 32 * fb + 8 * a + 4 * hf);
+        const f32x4 r4 = *reinterpret_cast<const f32x4*>(rd + 32 * wv + 8 * a + 4 * hf);
+        const u32x2 pw = *reinterpret_cast<const u32x2*>(PK + l32 * LDP + 32 * wv + 8 * a + 4 * hf);
         const float d0 = bf_lo(pw[0]) * (acc[4 * a] + r4[0]);
         const float d1 = bf_hi(pw[0]) * (acc[4 * a + 1] + r4[1]);
         const float d2 = bf_lo(pw[1]) * (acc[4 * a + 2] + r4[2]);
         const float d3 = bf_hi(pw[1]) * (acc[4 * a + 3] + r4[3]);
         ssum += (d0 + d1) + (d2 + d3);
         const u32x2 w = {pack_f16(d0, d1), pack_f16(d2, d3)};
-        *reinterpret_cast<u32x2*>(DL + l32 * LDP + 32 * fb + 8 * a + 4 * hf) = w;
+        *reinterpret_cast<u32x2*>(DL + l32 * LDP + 32 * wv + 8 * a + 4 * hf) = w;
       }
       ssum += __shfl_xor(ssum, 32, 64);
-      if (hf == 0) sp[fb * kT + l32] = ssum;
+      if (hf == 0) sp[wv * kT + l32] = ssum;
     }
     lds_barrier();
     // ---- stage 4: s_l; dK; T_K; Rm; publish the new suffix state -----------------------------------------
@@ -755,58 +712,58 @@ __global__ __launch_bounds__(kNT, 1) void k_bwd_rev(const us* __restrict__ Qg, c
       for (int w = 0; w < 8; ++w) s += sp[w * kT + tid];
       sc[SC_S * kT + tid] = s;
     }
+    if (dV != nullptr) flush_tile(Ns, dV, (size_t)bh * L + tok0, min(kT, L - tok0), tid);
     lds_barrier();
     if (wv < 2 && dK != nullptr) {
       f32x16 acc = zero16, acc2 = zero16;  // rows l, columns d (32 wv + l32)
-#pragma unroll
-      for (int s = 0; s < kF / 16; ++s) acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+#pragma unroll 4
+      for (int s = 0; s < kF / 16; ++s) {
+        acc = mm_f16(ld_direct(DL, LDP, 0, 16 * s, lane), ld_tr(Al, LDX, 16 * s, 32 * wv, lane), acc);
+      }
 #pragma unroll
       for (int s = 0; s < kD / 16; ++s) acc2 = mm_f16(ld_direct(Xk, LDX, 0, 16 * s, lane), ld_direct(G2, LDX, 32 * wv, 16 * s, lane), acc2);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int l = 8 * (v / 4) + 4 * hf + (v % 4);
-        if (tok0 + l < L)
-          dK[((size_t)bh * L + tok0 + l) * kD + 32 * wv + l32] = inv_log2e * (acc[v] - 2.f * sc[SC_S * kT + l] * acc2[v]);
-      }
+      for (int v = 0; v < 16; ++v) acc[v] -= 2.f * sc[SC_S * kT + 8 * (v / 4) + 4 * hf + (v % 4)] * acc2[v];
+      stage_tile(Ns, acc, inv_log2e, wv, lane);
     }
 #pragma unroll
     for (int s = 0; s < kT / 16; ++s) {
-      u32x4 xkf[2];
+      const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * wv, lane);
 #pragma unroll
-      for (int db = 0; db < 2; ++db) xkf[db] = ld_tr(Xk, LDX, 16 * s, 32 * db, lane);
+      for (int db = 0; db < 2; ++db) Tk[db] = mm_f16(dlf, ld_tr(Xk, LDX, 16 * s, 32 * db, lane), Tk[db]);
+    }
+    if (wv >= 4) {
+      const int eb = (wv - 4) / 2, db = (wv - 4) % 2;
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const u32x4 dlf = ld_tr(DL, LDP, 16 * s, 32 * (2 * wv + u), lane);
+      for (int s = 0; s < kT / 16; ++s) {
+        u32x4 xa = ld_tr(Xk, LDX, 16 * s, 32 * eb, lane);  // k_l[e] for l = 16 s + 8 hf + [0,8): scale by s_l
+        const float* sl = sc + SC_S * kT + 16 * s + 8 * hf;
 #pragma unroll
-        for (int db = 0; db < 2; ++db) Tk[u][db] = mm_f16(dlf, xkf[db], Tk[u][db]);
+        for (int q = 0; q < 4; ++q) {
+          unsigned wq = xa[q];
+          fp16x2 hv2 = *reinterpret_cast<fp16x2*>(&wq);
+          xa[q] = pack_f16((float)hv2[0] * sl[2 * q], (float)hv2[1] * sl[2 * q + 1]);
+        }
+        Rm = mm_f16(xa, ld_tr(Xk, LDX, 16 * s, 32 * db, lane), Rm);
       }
-      u32x4 xa = eb == dbw ? xkf[dbw] : ld_tr(Xk, LDX, 16 * s, 32 * eb, lane);  // k_l[e] for l = 16 s + 8 hf + [0,8): scale by s_l
-      const float* sl = sc + SC_S * kT + 16 * s + 8 * hf;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        unsigned wq = xa[q];
-        fp16x2 hv2 = *reinterpret_cast<fp16x2*>(&wq);
-        xa[q] = pack_f16((float)hv2[0] * sl[2 * q], (float)hv2[1] * sl[2 * q + 1]);
-      }
-      Rm = mm_f16(xa, xkf[dbw], Rm);
     }
     publish_state();
     lds_barrier();
   }
+  if (dK != nullptr) flush_tile(Ns, dK, (size_t)bh * L + tok_begin, min(kT, L - tok_begin), tid);
   const size_t ob = ((size_t)bh * P + p) * kF;
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int db = 0; db < 2; ++db)
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int ft = 32 * (2 * wv + u) + 8 * (v / 4) + 4 * hf + (v % 4);
-        TK[(ob + ft) * kD + 32 * db + l32] = Tk[u][db][v];
-      }
-  {
+    for (int v = 0; v < 16; ++v) {
+      const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
+      TK[(ob + ft) * kD + 32 * db + l32] = Tk[db][v];
+    }
+  if (wv >= 4) {
+    const int eb = (wv - 4) / 2, db = (wv - 4) % 2;
     const size_t rb = ((size_t)bh * P + p) * kD;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) RM[(rb + 32 * eb + 8 * (v / 4) + 4 * hf + (v % 4)) * kD + 32 * dbw + l32] = Rm[v];
+    for (int v = 0; v < 16; ++v) RM[(rb + 32 * eb + 8 * (v / 4) + 4 * hf + (v % 4)) * kD + 32 * db + l32] = Rm[v];
   }
 }
 
@@ -907,7 +864,7 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   const unsigned grid = (unsigned)(BH * P);
   typedef const unsigned short* cus;
   DARK_TRY(allow_lds(k_bwd_fwd, BwdSmem::total));
-  DARK_LAUNCH(KID_BWD_FWD, pb.st, k_bwd_fwd, dim3(grid), dim3(kNT), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah,
+  DARK_LAUNCH(KID_BWD_FWD, pb.st, k_bwd_fwd, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah,
               nrm, Spre, zpre, cpre, dQ, lam, gdv, dRn, dRd, TQ, p.H, p.L, P, sl, inv_log2e);
   {
     const long long n = BH * ((long long)kF * kD + kF);
@@ -915,7 +872,7 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
                 BH);
   }
   DARK_TRY(allow_lds(k_bwd_rev, BwdSmem::total));
-  DARK_LAUNCH(KID_BWD_REV, pb.st, k_bwd_rev, dim3(grid), dim3(kNT), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah, Mh,
+  DARK_LAUNCH(KID_BWD_REV, pb.st, k_bwd_rev, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah, Mh,
               nrm, cpre, lam, gdv, Rsn, Rsd, dK, dV, TQ, TK, RM, p.H, p.L, P, sl, inv_log2e);
   if (dM != nullptr) {
     const long long n = (long long)p.H * ((long long)kF * kD + kD * kD);
