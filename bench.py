@@ -51,6 +51,12 @@ def algorithmic_work(cfg):
         "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
         # dark_featurize, per launch (one tensor): rows read once, features written once
         "fused_featurize": ("hbm", th * (d + m) * s_in),
+        # backward, forward-order pass (tiles of T = 32 tokens): both projections, numerator and denominator
+        # again, the logit gradients of the queries (state part and tile triangle), dQ, and the updates of
+        # S, Rn and T_Q; reverse-order pass: projections, dV, the logit gradients of the keys, dK (with the
+        # norm term through M'^T M'), and the updates of Rn, T_K and Rm
+        "fused_bwd_fwd": ("mfma", th * (4 * d * m + 4 * m * (dv + 1) + 4 * m * d + 4 * m * dv + 33 * (2 * m + dv + 1))),
+        "fused_bwd_rev": ("mfma", th * (4 * d * m + 6 * m * dv + 4 * m * d + 4 * d * r + 33 * (2 * m + dv))),
     }
     return th * f_tok, th * b_tok, per_kernel
 
@@ -59,7 +65,7 @@ def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` on `workload`, from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known
     size), or None when no such measurement is on file."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    path = os.path.join(ROOT, traffic_file(workload))
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -67,6 +73,45 @@ def measured_traffic(workload, kernel):
         if len(parts) >= 2 and parts[0] == kernel and parts[1].startswith("hbm_bytes_per_launch="):
             return float(parts[1].split("=", 1)[1])
     return None
+
+
+def traffic_file(workload):
+    return os.path.join("profiles", f"hbm_traffic_{workload}.txt")
+
+
+def measure_ceilings(dk, torch):
+    """What this chip sustains right now with plain kernels: copy and read rates over 256 MiB buffers
+    (rotated, so that the memory-side cache serves none of it) and a dense fp16 MFMA loop.  Timed with
+    events on the stream the kernels run on, after the attention loops (clocks already settled)."""
+    n = 64 * 1024 * 1024
+    bufs = [torch.full((n,), float(k + 1), dtype=torch.float32, device="cuda") for k in range(3)]
+    dsts = [torch.empty_like(bufs[0]) for _ in range(2)]
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+    def timed(fn, reps, warm):
+        for i in range(warm):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    nb = n * 4
+    t_copy = timed(lambda i: dk.ceiling_copy(dsts[i % 2], bufs[i % 3]), 24, 6)
+    t_read = timed(lambda i: dk.ceiling_read(bufs[i % 3], sink), 24, 6)
+    flops = dk.ceiling_mfma(1, sink)
+    iters = 20000
+    t_mfma = timed(lambda i: dk.ceiling_mfma(iters, sink), 6, 2)
+    del bufs, dsts
+    return {
+        "copy_GBps": 2 * nb / t_copy / 1e9, "read_GBps": nb / t_read / 1e9,
+        "mfma_f16_TFLOPs": flops * iters / t_mfma / 1e12,
+        "how": "plain kernels of the library (dark_ceiling_*): 256 MiB copy (bytes read + written) and read, "
+               "rotated buffers; 2048 waves x 4 independent chains of 32x32x16 fp16 MFMAs",
+    }
 
 
 def to_device(inp, bf16):
@@ -108,10 +153,6 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy (read 256 MiB, write 256 MiB) three times before the "
-                         "timed region: under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its counter value gives the "
-                         "scale factor between the counters and real HBM bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every GPU box has one GPU); use --gpus 1", file=sys.stderr)
@@ -156,13 +197,6 @@ def main():
         if cfg.backward:
             dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], cfg.causal, chunk=cfg.chunk)
 
-    if args.calibrate_copy:
-        src = torch.full((64 * 1024 * 1024,), 1.0, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
     if args.steps is None or args.warmup is None:
         # size the run from a short probe: about 0.3 s timed, a quarter of that as warm-up
         for i in range(3):
@@ -211,9 +245,19 @@ def main():
     us_step = kernels[dom]["us_per_step"]
     peak, unit = PEAK[bound]
     achieved = units / (us_step * 1e-6) / (1e9 if bound == "hbm" else 1e12)
+    traffic = measured_traffic(cfg.name, dom)
     roofline = {"bound": bound, "kernel": dom, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": measured_traffic(cfg.name, dom),
+                "frac": achieved / peak, "traffic": traffic,
+                "traffic_source": traffic_file(cfg.name) if traffic is not None else None,
                 "avg_kernel_us": kernels[dom]["avg_us"], "launches_per_step": kernels[dom]["launches"] / ksteps}
+    for k in kernels:
+        tb = measured_traffic(cfg.name, k)
+        if tb is not None:
+            kernels[k]["hbm_bytes_per_launch"] = tb
+    ceilings = measure_ceilings(dk, torch)
+    measured_peak = {"hbm": ceilings["read_GBps"], "mfma": ceilings["mfma_f16_TFLOPs"]}.get(bound)
+    if measured_peak:
+        roofline["frac_of_measured_ceiling"] = achieved / measured_peak
 
     line = {
         "metric": ("DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)" if args.op == "attn"
@@ -229,11 +273,15 @@ def main():
         "tflops": flops / (ms * 1e-3) / 1e12,
         "algorithmic_gbps": nbytes / (ms * 1e-3) / 1e9,
         "step_frac_of_binding_roofline": max(flops / 2.5e15, nbytes / 8e12) / (ms * 1e-3),
+        "step_frac_of_measured_ceilings": None,
         "roofline": roofline,
+        "ceilings": ceilings,
         "kernels": kernels,
         "input_generation_s": gen_s,
     }
 
+    line["step_frac_of_measured_ceilings"] = max(flops / (ceilings["mfma_f16_TFLOPs"] * 1e12),
+                                                 nbytes / (ceilings["copy_GBps"] * 1e9)) / (ms * 1e-3)
     if not args.no_cpu_baseline and args.op == "attn":
         # The oracle as it stands, on a bounded sample of the same workload: whole heads of batch 0
         # until about --cpu-seconds of CPU time have been spent.

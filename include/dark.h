@@ -185,6 +185,25 @@ void dark_timing_reset(void);
 int dark_timing_slots(void);
 dark_status dark_timing_read(int k, const char** name, int64_t* launches, double* total_ms);
 
+/*
+ * Measured ceilings of the device, for benchmarks that report the attention
+ * kernels against what the chip sustains rather than against its data-sheet
+ * peaks.  Plain kernels, no part of the attention path; each call enqueues one
+ * launch on `hip_stream` and returns (time it with events on that stream).
+ * Device pointers; nbytes a multiple of 16; `sink` is a device buffer of at
+ * least 4 bytes that is (practically) never written.
+ *   dark_ceiling_copy  reads nbytes from src and writes them to dst.
+ *   dark_ceiling_read  reads nbytes from src.
+ *   dark_ceiling_mfma  runs `iters` rounds of four independent 32x32x16 fp16
+ *                      MFMAs in each of 2048 waves (eight per compute unit)
+ *                      and stores the floating-point operations of the launch
+ *                      in *flops (host pointer).
+ * DARK_EINVAL for null pointers, nbytes not a multiple of 16 or iters < 0.
+ */
+dark_status dark_ceiling_copy(void* dst, const void* src, size_t nbytes, void* hip_stream);
+dark_status dark_ceiling_read(const void* src, size_t nbytes, void* sink, void* hip_stream);
+dark_status dark_ceiling_mfma(int iters, void* sink, double* flops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

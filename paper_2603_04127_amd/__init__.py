@@ -74,6 +74,12 @@ def lib() -> ctypes.CDLL:
     L.dark_timing_read.restype = i32
     L.dark_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int64),
                                    ctypes.POINTER(ctypes.c_double)]
+    L.dark_ceiling_copy.restype = i32
+    L.dark_ceiling_copy.argtypes = [vp, vp, sz, vp]
+    L.dark_ceiling_read.restype = i32
+    L.dark_ceiling_read.argtypes = [vp, sz, vp, vp]
+    L.dark_ceiling_mfma.restype = i32
+    L.dark_ceiling_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = L
     return L
 
@@ -263,3 +269,27 @@ def timing_read() -> dict:
         if n.value:
             out[name.value.decode()] = (n.value, ms.value)
     return out
+
+
+# ----------------------------------------------------------------------------
+# measured ceilings of the device (benchmarks)
+# ----------------------------------------------------------------------------
+def ceiling_copy(dst, src):
+    """One launch of the plain copy kernel: src -> dst (same byte size, a multiple of 16)."""
+    nb = src.numel() * src.element_size()
+    _check(lib().dark_ceiling_copy(_ptr(dst), _ptr(src), nb, _stream()), "dark_ceiling_copy")
+    return nb
+
+
+def ceiling_read(src, sink):
+    """One launch of the plain read kernel over src."""
+    nb = src.numel() * src.element_size()
+    _check(lib().dark_ceiling_read(_ptr(src), nb, _ptr(sink), _stream()), "dark_ceiling_read")
+    return nb
+
+
+def ceiling_mfma(iters, sink) -> float:
+    """One launch of the MFMA loop kernel; returns the floating-point operations it performs."""
+    fl = ctypes.c_double()
+    _check(lib().dark_ceiling_mfma(int(iters), _ptr(sink), ctypes.byref(fl), _stream()), "dark_ceiling_mfma")
+    return fl.value
