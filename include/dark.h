@@ -59,6 +59,29 @@ typedef enum {
   DARK_OP_ATTN_BWD = 3
 } dark_op;
 
+/*
+ * Numerical range of the two families of kernels.
+ *
+ * Fused MFMA kernels (bf16 io, d = r = dv in {64, 128}, m a multiple of 256 ...; what DARK_PATH_AUTO
+ * takes for such shapes): rows of Q, K (and X of dark_featurize) are converted bf16 -> fp16 and projected
+ * by fp16 MFMAs with fp32 accumulation.
+ *   - Elements of magnitude in [2^-14, 65504] convert exactly; smaller ones lose bits (absolute error at
+ *     most 2^-25 per element); larger ones have no fp16 value and become +-infinity: every output row that
+ *     depends on such an element is then non-finite (NaN), never the result of a clamped input.
+ *   - A key whose norm term (log2(e)/2) |sqrt(scale) M k|^2 exceeds 65504 contributes features that are
+ *     zero to within fp32; it is treated as exactly that (no clamped norm enters).
+ *   - The projection operands are rounded to fp16, so a logit w.x~ carries an error of about 2^-11 |w.x~|:
+ *     the tolerance quoted for the bf16 path holds for |w.x~| up to a few hundred.
+ *   - Stabilisers: one shift per (b, h) and block of 64 features (bidirectional; the readout adds a running
+ *     shift per row when a row's logits leave the fp32 exponent range), one scalar shift per (b, h) along the
+ *     running prefix (causal forward, backward).  Keys more than about 80 nats (2^115) below the shift they
+ *     are stored under vanish; a row all of whose keys have vanished comes out non-finite (0/0).
+ * fp32 kernels (DARK_PATH_F32; any shape and dtype): inputs of any finite magnitude; bidirectional attention
+ * keeps a shift per feature and per row and has no range limit; the causal and backward passes keep one
+ * shift per (b, h) and feature for the whole sequence and are specified for key logits that spread over
+ * less than about 80 nats along a sequence.
+ * None of these conditions is checked on the host: the entry points only enqueue work.
+ */
 typedef enum {
   DARK_PATH_AUTO = 0,   /* fused MFMA kernels when the shape allows, else the fp32 kernels */
   DARK_PATH_F32 = 1,    /* fp32 arithmetic throughout (any shape, any io_dtype) */

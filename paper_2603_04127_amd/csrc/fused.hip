@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) void k_prep(const float* __restrict__ M, const
 // still reads V(t-1) after the barrier).
 // ---------------------------------------------------------------------------
 struct KvSmem {
-  static constexpr int XS = 88;  // fp16 per staged key row: 64 coordinates, 8 extra slots, pad (conflict-free 16-byte reads)
+  static constexpr int XS = 88;  // fp16 per staged key row: 64 coordinates, 8 extra slots, 8 zeros, pad (conflict-free 16-byte reads)
   static constexpr int MS = 72;
   static constexpr size_t x_buf = (size_t)kTile * XS * 2;
   static constexpr size_t v_buf = (size_t)kTile * 64 * 2;
@@ -257,9 +257,11 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
     for (int tl2 = 0; tl2 < 2; ++tl2) {
       // rows past the end get the largest norm fp16 holds: their features are exp2(-65504 ...) = 0;
       // all four lane groups hold the same n' and write the same 16 bytes
-      const float n = (tok_begin + tl2 * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(tot[tl2][0], kF16Max);
+      // A norm beyond the fp16 range turns into +inf: the token's features are exp2(-inf) = 0, which is their
+      // value to within fp32 next to any key of ordinary norm (and 0/0 = NaN in the output if every key is so).
+      const float n = (tok_begin + tl2 * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : tot[tl2][0];
       const _Float16 hi = (_Float16)n;
-      const _Float16 lo = (_Float16)(n - (float)hi);
+      const _Float16 lo = (float)hi > kF16Max ? (_Float16)0.f : (_Float16)(n - (float)hi);
       fp16x2 hl;
       hl[0] = hi;
       hl[1] = lo;
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
 
   // per-lane byte offsets of the operand fetches
   const unsigned xoff = l32 * XROW + 16 * hf;   // + 32 s: fragment s < 4 of a key row
-  const unsigned xoff4 = l32 * XROW + 128;      // the extra slots (both half-waves read the same eight)
+  const unsigned xoff4 = l32 * XROW + 128 + 16 * hf;  // the extra slots (lower half-wave) / the zeros behind them (upper)
   const int jj = l32 % 16, tl = 4 * hf + jj / 4, kq = 2 * (l32 / 16) + (jj % 4) / 2;
   unsigned voff[2];
   voff[0] = tl * 128 + 16 * (kq ^ (tl & 7)) + 8 * (jj % 2);
@@ -319,6 +321,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       const int ci = tid + 256 * u, row = ci / (D / 8), kc = ci % (D / 8);
       *reinterpret_cast<u32x4*>(Ms + row * SM::MS + 8 * kc) = mreg[u];
     }
+    // 16 zero bytes behind each row's extra slots (never written again): the upper half-wave, whose feature-side
+    // extra slots are zero, reads these instead of the row's norm, which may be infinite (inf x 0 = NaN)
+    *reinterpret_cast<u32x4*>(Xs + (tid / kTile) * SM::x_buf + (tid % kTile) * XROW + 144) = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();  // M' is read by every wave's norm MFMAs
     stage01(kreg, k1);
 #pragma unroll
@@ -376,9 +381,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       sq0 = sq1 = 0.f;
     }
     if (slot == 22) {  // all four lane groups hold the same n' and write the same 16 bytes: no branch
-      const float n = (tok_begin + (t + 2) * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : fminf(ntot[0], kF16Max);
-      const _Float16 hi = (_Float16)n;
-      const _Float16 lo = (_Float16)(n - (float)hi);
+      const float n = (tok_begin + (t + 2) * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : ntot[0];
+      const _Float16 hi = (_Float16)n;   // +inf beyond the fp16 range (see the first tiles above)
+      const _Float16 lo = (float)hi > kF16Max ? (_Float16)0.f : (_Float16)(n - (float)hi);
       fp16x2 hl;
       hl[0] = hi;
       hl[1] = lo;
@@ -1081,17 +1086,18 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 
     // ---- careful path: running per-token shift, raised whenever a block exceeds it by 2^kTau ---
     if (redo) {
-    if (have_x) {  // the fragments already hold the next tile: fetch this one again
-      fetch_x(bh, t0);
-      have_x = false;
+    // The fragments hold raw rows fetched during the last unit: those of the next tile (fetch this one
+    // again), or, when this is the workgroup's last tile, this tile's own once more.  Either way they are
+    // bf16 and have to be converted.
+    if (have_x) fetch_x(bh, t0);
+    have_x = false;
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+    for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-          u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<u32x4*>(&xf[tt][s]));
-          xf[tt][s] = *reinterpret_cast<half8*>(&cv);
-        }
-    }
+      for (int s = 0; s < D / 16; ++s) {
+        u32x4 cv = bf16x8_to_f16x8(*reinterpret_cast<u32x4*>(&xf[tt][s]));
+        xf[tt][s] = *reinterpret_cast<half8*>(&cv);
+      }
 #pragma unroll
     for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll

@@ -35,10 +35,13 @@ __device__ static inline unsigned pack_bf16(float a, float b) {
   return *reinterpret_cast<unsigned*>(&p);
 }
 __device__ static inline unsigned pack_f16_from_bf16pair(unsigned w) {
-  // w holds two bf16; both are exactly representable in fp16 unless out of its range
-  float lo = __uint_as_float(w << 16);
-  float hi = __uint_as_float(w & 0xffff0000u);
-  fp16x2 h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
+  // w holds two bf16.  Magnitudes in [2^-14, 65504] convert exactly (8 significand bits fit in 11); smaller
+  // ones lose bits to fp16's subnormals and vanish below 2^-25 (absolute error at most 2^-25 per element);
+  // larger ones become +-inf (round to nearest), so that the result is visibly non-finite instead of
+  // silently that of a clamped input.
+  fp16x2 h;
+  h[0] = (__fp16)__uint_as_float(w << 16);
+  h[1] = (__fp16)__uint_as_float(w & 0xffff0000u);
   return *reinterpret_cast<unsigned*>(&h);
 }
 __device__ static inline u32x4 bf16x8_to_f16x8(u32x4 r) {

@@ -312,6 +312,167 @@ def test_fused_large_logit_range():
     U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], "fused, wide logit range")
 
 
+def _reround(inp, name):
+    from paper_2603_04127_amd import synth
+    bits = synth.to_bf16_bits(inp[name])
+    inp[name + "_bits"] = bits
+    inp[name] = synth.bf16_bits_to_f32(bits)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_keys_with_norms_beyond_fp16_range(causal):
+    """A few keys so long that their norm term (log2 domain) exceeds what fp16 holds: their features are zero
+    to within fp32 next to the ordinary keys, and the result is the oracle's (no clamped norm enters)."""
+    inp = U.random_problem(31, 1, 2, 600, 64, 64, 256, 64, bf16=True, amp=1.5)
+    rows = [5, 100, 333, 599]
+    for h in range(2):
+        x = inp["K"][0, h, rows] @ inp["M"][h].T.astype(np.float64)
+        inp["K"][0, h, rows] *= (900.0 / np.linalg.norm(x, axis=1))[:, None].astype(np.float32)
+    _reround(inp, "K")
+    for h in range(2):
+        xt = (inp["K"][0, h, rows].astype(np.float64) @ inp["M"][h].T.astype(np.float64)) * 64 ** -0.25
+        assert (0.5 * np.log2(np.e) * (xt ** 2).sum(axis=1)).min() > 65504.0
+    assert np.abs(inp["K"]).max() < 65504.0
+    dev = U.to_device(inp, True)
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    out = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])      # DARK_PATH_AUTO: the MFMA kernels
+    ref = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32)
+    torch.cuda.synchronize()
+    want = U.oracle_attn(inp, causal)
+    e = U.assert_close(_np(out), want, U.TOL["bf16"], "long keys, auto path")
+    U.assert_close(_np(ref), want, U.TOL["bf16"], "long keys, fp32 path")
+    print(f"keys beyond the fp16 norm range, causal={causal}: {U.fmt(e)}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_inputs_beyond_fp16_range_are_not_silently_clamped(causal):
+    """bf16 elements above 65504 have no fp16 value: through DARK_PATH_AUTO the affected rows come out
+    non-finite (the conversion saturates to infinity), everything else is unaffected; the fp32 kernels
+    take such inputs."""
+    inp = U.random_problem(32, 1, 3, 300, 64, 64, 256, 64, bf16=True, amp=1.5)
+    inp["K"][0, 1, 70, 3] = 1.0e5      # a key of head 1: every later (causal) or every (bidirectional) row of head 1
+    inp["Q"][0, 0, 90, 2] = -2.0e5     # a query of head 0: that row only
+    _reround(inp, "K")
+    _reround(inp, "Q")
+    dev = U.to_device(inp, True)
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    out = _np(fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"]))
+    torch.cuda.synchronize()
+    want = U.oracle_attn(inp, causal)
+    bad_q = ~np.isfinite(out[0, 0]).all(axis=1)
+    assert bad_q[90] and bad_q.sum() == 1
+    good = np.ones(300, bool)
+    good[90] = False
+    U.assert_close(out[0, 0][good], want[0, 0][good], U.TOL["bf16"], "head 0, other rows")
+    bad_k = ~np.isfinite(out[0, 1]).all(axis=1)
+    first = 70 if causal else 0
+    assert bad_k[first:].all() and not bad_k[:first].any()
+    if causal:
+        U.assert_close(out[0, 1][:70], want[0, 1][:70], U.TOL["bf16"], "head 1, rows before the key")
+    U.assert_close(out[0, 2], want[0, 2], U.TOL["bf16"], "head 2")
+    f32 = _np(fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32))
+    assert np.isfinite(f32).all()
+
+
+@pytest.mark.parametrize("L", [64, 300, 1100])
+def test_fused_rows_with_extreme_logits(L):
+    """Queries whose logits spread over hundreds of powers of two (an in-range element of -1000): the readout
+    has to take its path with a running row shift, also on the last tile a workgroup handles and on tiles in
+    the middle of its run; the row then follows a single feature."""
+    inp = U.random_problem(34, 1, 3, L, 64, 64, 256, 64, bf16=True, amp=1.5)
+    rows = sorted({0, 17, L // 2, L - 2, L - 1})
+    for i, r in enumerate(rows):
+        h = i % 3
+        for j in range(3 * i, 3 * i + 64):
+            # the fp16 operands of the MFMA path carry a logit error of about 2^-11 |w.x~| (a few tenths of
+            # a nat here): take a coordinate for which the winning feature leads by a clear margin
+            q = inp["Q"][0, h, r].copy()
+            q[j % 64] = -1000.0 if i % 2 == 0 else 700.0
+            top = np.sort(O.logits(q[None, :], inp["M"][h], inp["W"][h])[0])[-2:]
+            if top[1] - top[0] > 12.0:
+                inp["Q"][0, h, r] = q
+                break
+        else:
+            raise AssertionError("no coordinate with a clear winner")
+    _reround(inp, "Q")
+    dev = U.to_device(inp, True)
+    for causal in (False, True):
+        fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+        a = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+        torch.cuda.synchronize()
+        e = U.assert_close(_np(a), U.oracle_attn(inp, causal), U.TOL["bf16"], f"extreme rows, L={L} causal={causal}")
+        print(f"rows with extreme logits L={L} causal={causal}: {U.fmt(e)}")
+
+
+@pytest.mark.parametrize("scale", [1e-6, 1e-3, 4.0])
+def test_fused_matches_f32_path_at_extreme_amplitudes(scale):
+    """Tiny inputs (fp16 subnormals and below: the logits are ~0 either way) and large ones (logits spread
+    over about 180 nats)."""
+    inp = U.random_problem(33, 1, 2, 400, 64, 64, 256, 64, bf16=True, amp=1.0)
+    for n in ("Q", "K"):
+        inp[n] *= np.float32(scale)
+        _reround(inp, n)
+    dev = U.to_device(inp, True)
+    for causal in (False, True):
+        fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+        a = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED)
+        c = fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_F32)
+        torch.cuda.synchronize()
+        want = U.oracle_attn(inp, causal)
+        e = U.assert_close(_np(a), want, U.TOL["bf16"], f"fused, inputs x{scale}")
+        U.assert_close(_np(c), want, U.TOL["bf16"], f"fp32 path, inputs x{scale}")
+        print(f"inputs x{scale} causal={causal}: fused {U.fmt(e)}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_logit_spread_beyond_the_supported_range(causal):
+    """Inputs 15 times the usual size: key logits spread over ~1900 nats along the sequence, far beyond the
+    ~80 nats the kernels with one shift per (b, h) (MFMA paths: one scalar per running prefix or feature
+    block) are specified for.  The MFMA paths then return non-finite rows (0/0) where every key a row depends
+    on has vanished below the shift, and since all features share that shift, whatever survives dominates
+    what vanished: the finite rows are still the oracle's.  The bidirectional fp32 kernels have no such
+    limit.  (The fp32 causal kernels keep one shift per feature for the whole sequence and are specified for
+    the same ~80 nats; beyond it they are not checked.)"""
+    inp = U.random_problem(33, 1, 2, 400, 64, 64, 256, 64, bf16=True, amp=1.0)
+    for n in ("Q", "K"):
+        inp[n] *= np.float32(15.0)
+        _reround(inp, n)
+    dev = U.to_device(inp, True)
+    fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+    want = U.oracle_attn(inp, causal)
+    for path, name in ((dk.PATH_FUSED, "fused"), (dk.PATH_F32, "f32")):
+        if causal and name == "f32":
+            continue
+        got = _np(fn(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=path))
+        torch.cuda.synchronize()
+        finite = np.isfinite(got).all(axis=-1)
+        if name == "f32":
+            assert finite.all()
+        assert finite.mean() > 0.5
+        # the MFMA path's fp16 operands carry a logit error that grows with the logits (2^-11 |w.x~|)
+        tol = 1.5 * U.TOL["bf16"] if name == "fused" else U.TOL["bf16"]
+        e = U.assert_close(got[finite], want[finite], tol, f"x15 inputs, {name}, causal={causal}")
+        print(f"x15 inputs {name} causal={causal}: {int((~finite).sum())} of {finite.size} rows non-finite; finite rows: {U.fmt(e)}")
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_causal_key_logits_growing_along_the_sequence(path):
+    """Keys whose norm shrinks along the sequence, so that the key logits rise by about 60 nats from the
+    first token to the last (inside the ~80 nats the causal kernels are specified for): early rows see only
+    keys far below the shift that later keys set."""
+    inp = U.random_problem(35, 1, 2, 700, 64, 64, 256, 64, bf16=True, amp=1.0)
+    ramp = np.linspace(5.0, 1.0, 700, dtype=np.float32)[None, None, :, None]
+    inp["K"] = inp["K"] * ramp
+    _reround(inp, "K")
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0]).max(axis=1)
+    assert 40.0 < lg[-50:].mean() - lg[:50].mean() < 80.0
+    dev = U.to_device(inp, True)
+    got = _np(dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=path))
+    torch.cuda.synchronize()
+    e = U.assert_close(got, U.oracle_attn(inp, True), U.TOL["bf16"], f"rising key logits, {path}")
+    print(f"causal, key logits rising ~60 nats along the sequence ({path}): {U.fmt(e)}")
+
+
 def test_fused_matches_f32_path_and_is_deterministic():
     inp = U.random_problem(13, 2, 3, 900, 64, 64, 256, 64, bf16=True)
     dev = U.to_device(inp, True)
