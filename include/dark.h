@@ -62,9 +62,10 @@ typedef enum {
 /*
  * Numerical range of the two families of kernels.
  *
- * Fused MFMA kernels (bf16 io, d = r = dv in {64, 128}, m a multiple of 256 ...; what DARK_PATH_AUTO
- * takes for such shapes): rows of Q, K (and X of dark_featurize) are converted bf16 -> fp16 and projected
- * by fp16 MFMAs with fp32 accumulation.
+ * Fused MFMA kernels, what DARK_PATH_AUTO takes for bf16 io with d = r = dv in {64, 128} and m = 256
+ * (bidirectional forward also m = 512 at d = 64; dark_featurize any m that is a multiple of 64 and fits the
+ * LDS; backward only causal, d = 64, m = 256): rows of Q, K (and X of dark_featurize) are converted
+ * bf16 -> fp16 and projected by fp16 MFMAs with fp32 accumulation.
  *   - Elements of magnitude in [2^-14, 65504] convert exactly; smaller ones lose bits (absolute error at
  *     most 2^-25 per element); larger ones have no fp16 value and become +-infinity: every output row that
  *     depends on such an element is then non-finite (NaN), never the result of a clamped input.
