@@ -152,14 +152,14 @@ def _workspace(nbytes: int, device):
 def _params_from(Q, V, M, W, *, out_dtype=None, chunk=0, scale=0.0, path=PATH_AUTO, sched=None) -> DarkParams:
     B, H, L, d = Q.shape
     dv = V.shape[-1] if V is not None else 1
-    r = M.shape[-2]
+    r = M.shape[-2] if M is not None else d      # M = None: the identity (isotropic features), r = d
     w_shared = W.dim() == 2
     m = W.shape[-2]
     torch = _torch()
-    if M.dtype != torch.float32 or W.dtype != torch.float32:
+    if (M is not None and M.dtype != torch.float32) or W.dtype != torch.float32:
         raise TypeError("M and W must be float32")
-    if tuple(M.shape) != (H, r, d) or W.shape[-1] != r or (not w_shared and W.shape[0] != H):
-        raise ValueError("M must be [H, r, d] and W [H, m, r] or [m, r]")
+    if (M is not None and tuple(M.shape) != (H, r, d)) or W.shape[-1] != r or (not w_shared and W.shape[0] != H):
+        raise ValueError("M must be [H, r, d] (or None) and W [H, m, r] or [m, r]")
     io = _dtype_code(Q)
     od = io if out_dtype is None else (DARK_BF16 if out_dtype == torch.bfloat16 else DARK_F32)
     return make_params(B, H, L, d, r, m, dv, io_dtype=io, out_dtype=od, chunk=chunk, scale=scale, w_shared=w_shared,
@@ -236,7 +236,7 @@ def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path
         "dQ": torch.empty(Q.shape, **f32) if "dQ" in need else None,
         "dK": torch.empty(K.shape, **f32) if "dK" in need else None,
         "dV": torch.empty(V.shape, **f32) if "dV" in need else None,
-        "dM": torch.empty(M.shape, **f32) if "dM" in need else None,
+        "dM": torch.empty(M.shape if M is not None else (Q.shape[1], Q.shape[3], Q.shape[3]), **f32) if "dM" in need else None,
     }
     nb = workspace_bytes(p, OP_ATTN_BWD, causal)
     ws = _workspace(nb, Q.device)

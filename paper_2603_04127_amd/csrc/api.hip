@@ -109,6 +109,15 @@ static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const 
   dark_status err;
   bool fused = use_fused(pb, op, causal, &err);
   if (err != DARK_OK) return err;
+  // M == NULL stands for the identity (isotropic positive random features): it is written out here, so that
+  // every kernel downstream sees an ordinary M.  The buffer is part of every plan with r == d.
+  if (pb.p.r == pb.p.d) {
+    float* Mid = ar.take<float>((size_t)pb.p.H * pb.p.d * pb.p.d);
+    if (pb.m_identity && ar.base != nullptr && !ar.overflow) {
+      DARK_TRY(fill_identity(pb, Mid));
+      M = Mid;
+    }
+  }
   switch (op) {
     case DARK_OP_FEATURIZE:
       return fused ? fused_featurize(pb, ar, Q, M, W, is_query, out, stab)
@@ -190,7 +199,9 @@ dark_status dark_featurize(const dark_params* p, const void* X, const float* M, 
   Problem pb;
   DARK_TRY(check_params(p, &pb));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;
-  if (X == nullptr || M == nullptr || W == nullptr || phi == nullptr) return DARK_EINVAL;
+  if (X == nullptr || W == nullptr || phi == nullptr) return DARK_EINVAL;
+  if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
+  pb.m_identity = M == nullptr;
   if (!aligned(X, 16) || !aligned(M, 16) || !aligned(W, 16) || !aligned(phi, 16) || !aligned(stab, 4))
     return DARK_EALIGN;
   {
@@ -211,7 +222,9 @@ static dark_status attn_common(const dark_params* p, int op, const void* Q, cons
   Problem pb;
   DARK_TRY(check_params(p, &pb));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;
-  if (!Q || !K || !V || !M || !W || !out) return DARK_EINVAL;
+  if (!Q || !K || !V || !W || !out) return DARK_EINVAL;
+  if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
+  pb.m_identity = M == nullptr;
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
       !aligned(out, 16))
     return DARK_EALIGN;
@@ -237,7 +250,9 @@ dark_status dark_attn_fwd_static(const dark_params* p, const void* Q, const void
   Problem pb;
   DARK_TRY(check_params(p, &pb));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;
-  if (!Q || !K || !V || !M || !W || !out) return DARK_EINVAL;
+  if (!Q || !K || !V || !W || !out) return DARK_EINVAL;
+  if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
+  pb.m_identity = M == nullptr;
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
       !aligned(out, 16))
     return DARK_EALIGN;
@@ -265,7 +280,9 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
   Problem pb;
   DARK_TRY(check_params(p, &pb));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;  // nothing to enqueue; gradients are left untouched
-  if (!Q || !K || !V || !M || !W || !dOut) return DARK_EINVAL;
+  if (!Q || !K || !V || !W || !dOut) return DARK_EINVAL;
+  if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
+  pb.m_identity = M == nullptr;
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
       !aligned(dOut, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) || !aligned(dM, 16))
     return DARK_EALIGN;

@@ -95,6 +95,7 @@ struct Problem {
   dark_params p;
   float scale;     // resolved (never 0)
   int chunk;       // resolved
+  bool m_identity = false;  // the caller passed M == NULL: Sigma = I (needs r == d)
   hipStream_t st;
   long long BH() const { return (long long)p.B * p.H; }
   long long rows() const { return (long long)p.B * p.H * p.L; }
@@ -104,6 +105,8 @@ struct Problem {
 dark_status check_params(const dark_params* p, Problem* out);
 inline bool aligned(const void* q, size_t a) { return (reinterpret_cast<uintptr_t>(q) & (a - 1)) == 0; }
 
+// M[h] = I for every head, into a [H, d, d] fp32 buffer (generic.hip).
+dark_status fill_identity(const Problem& pb, float* Mid);
 // fp32 path (generic.hip).  With arena.base == nullptr these only measure.
 dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,
                           int is_query, void* phi, float* stab);

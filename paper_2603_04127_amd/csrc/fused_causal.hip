@@ -750,10 +750,38 @@ __global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __
   }
 }
 
+// The same norms for M = I: nrm[row] = (scale log2(e) / 2) |k_row|^2, with no projection: D / 8 lanes per
+// key row, 16 bytes each, squares summed in fp32, the partial sums added across the row's lanes.
+template <int D>
+__global__ __launch_bounds__(256) void k_key_norms_identity(const unsigned short* __restrict__ Kg,
+                                                            float* __restrict__ nrm, long long rows, float f) {
+  constexpr int LPR = D / 8;  // lanes per row
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long row = i / LPR;
+  float s = 0.f;
+  if (row < rows) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(Kg + row * D + 8 * (i % LPR));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xffff0000u);
+      s = fmaf(lo, lo, fmaf(hi, hi, s));
+    }
+  }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (row < rows && i % LPR == 0) nrm[row] = f * s;
+}
+
 template <int D>
 dark_status launch_key_norms(const Problem& pb, const void* K, const _Float16* Mh, float* nrm) {
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
+  if (pb.m_identity) {
+    const long long rows = BH * p.L, threads = rows * (D / 8);
+    DARK_LAUNCH(KID_KEY_NORMS, pb.st, (k_key_norms_identity<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                (const unsigned short*)K, nrm, rows, 0.5f * kLog2e * pb.scale);
+    return DARK_OK;
+  }
   // about 1024 workgroups (four fit a CU), each over a run of 256-token chunks of one (b,h): M' is copied
   // to LDS once per workgroup
   const int chunks_per_bh = (p.L + 255) / 256;

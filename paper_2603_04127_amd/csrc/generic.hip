@@ -1076,7 +1076,18 @@ int slice_len(const Problem& pb) {
   return (int)sl;
 }
 
+__global__ __launch_bounds__(256) void k_fill_identity(float* __restrict__ Mid, long long n, int d) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) Mid[i] = ((i / d) % d == i % d) ? 1.f : 0.f;
+}
+
 }  // namespace
+
+dark_status fill_identity(const Problem& pb, float* Mid) {
+  const long long n = (long long)pb.p.H * pb.p.d * pb.p.d;
+  DARK_LAUNCH(KID_LOAD, pb.st, k_fill_identity, dim3(grid_for(n)), dim3(256), 0, Mid, n, pb.p.d);
+  return DARK_OK;
+}
 
 // ===========================================================================
 // dark_featurize

@@ -20,13 +20,17 @@ Recipe
   V_M^T with sigma log-spaced from 1 down to 1/kappa and Haar U_M, V_M.
 * bf16 configurations round Q, K, V, dOut to bfloat16 once (round to nearest
   even) and hand out both the 16-bit patterns and their exact fp32 values.
+* ``orthogonal_features``: the other way of drawing W that the paper names
+  (Section 2, orthogonal random features): directions orthogonal within blocks
+  of r rows, lengths distributed as those of Gaussian vectors.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass, field
 import numpy as np
 
-__all__ = ["Config", "CONFIGS", "make_inputs", "to_bf16_bits", "bf16_bits_to_f32", "scaled_config"]
+__all__ = ["Config", "CONFIGS", "make_inputs", "to_bf16_bits", "bf16_bits_to_f32", "scaled_config",
+           "orthogonal_features"]
 
 
 @dataclass(frozen=True)
@@ -160,3 +164,36 @@ def make_inputs(cfg: Config) -> dict:
             out[nme + "_bits"] = bits
             out[nme] = bf16_bits_to_f32(bits)
     return out
+
+
+def _gram_schmidt_rows(G: np.ndarray) -> np.ndarray:
+    """Orthonormal rows spanning the same nested subspaces as the rows of G (modified Gram-Schmidt,
+    each row cleaned twice against the rows before it)."""
+    Qm = np.array(G, dtype=np.float64)
+    for i in range(Qm.shape[0]):
+        for _ in range(2):
+            for j in range(i):
+                Qm[i] -= (Qm[i] @ Qm[j]) * Qm[j]
+        Qm[i] /= np.linalg.norm(Qm[i])
+    return Qm
+
+
+def orthogonal_features(seed: int, H: int, m: int, r: int) -> np.ndarray:
+    """W [H, m, r] (fp32) with orthogonal random features (Section 2 of the paper: the directions are
+    orthogonalised by Gram-Schmidt; Section 6: the isotropic baseline uses them).
+
+    Per head the m rows come in blocks of r: a block is a Gaussian r x r matrix whose rows are
+    orthonormalised, each then given the length of an independent Gaussian vector of r coordinates (a chi
+    variable with r degrees of freedom), so that every single row is distributed as N(0, I_r) exactly while
+    the rows of a block are mutually orthogonal.  Different blocks, and different heads, are independent.
+    """
+    root = np.random.SeedSequence(seed)
+    W = np.empty((H, m, r), dtype=np.float64)
+    for h, child in enumerate(root.spawn(H)):
+        rng = np.random.Generator(np.random.PCG64(child))
+        for j0 in range(0, m, r):
+            Qm = _gram_schmidt_rows(rng.standard_normal((r, r)))
+            lengths = np.linalg.norm(rng.standard_normal((r, r)), axis=1)
+            n = min(r, m - j0)
+            W[h, j0:j0 + n] = (lengths[:, None] * Qm)[:n]
+    return W.astype(np.float32)

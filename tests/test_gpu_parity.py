@@ -1,5 +1,7 @@
 """GPU parity: the HIP library (through the C-ABI binding) against the fp64 oracle,
 element by element on the same seeded inputs."""
+import ctypes
+
 import numpy as np
 import pytest
 
@@ -66,6 +68,51 @@ def test_featurize_fused(shape, is_query):
             # phi * exp(shift) is the unstabilised feature vector: compare that, shift-independently
             adj = phi[b, h] * np.exp((got_c - c)[:, None] if is_query else (got_c - c))
             U.assert_close(adj, want, U.TOL["bf16"], f"fused phi[{b},{h}]")
+
+
+# ---------------------------------------------------------------------------
+# M = None: the identity geometry (isotropic positive random features)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_identity_geometry(bf16, path):
+    """Every entry point with M = None against the oracle with M = I (r = d = 64)."""
+    inp = U.random_problem(41, 2, 2, 330, 64, 64, 256, 64, bf16=bf16, amp=1.0, backward=True)
+    inp["M"] = np.broadcast_to(np.eye(64, dtype=np.float32), (2, 64, 64)).copy()
+    dev = U.to_device(inp, bf16)
+    tol = U.TOL["bf16" if bf16 else "f32"]
+    for causal in (False, True):
+        fn = dk.dark_attn_causal_fwd if causal else dk.dark_attn_fwd
+        out = fn(dev["Q"], dev["K"], dev["V"], None, dev["W"], path=path)
+        torch.cuda.synchronize()
+        e = U.assert_close(_np(out), U.oracle_attn(inp, causal), tol, f"M = None, causal={causal}")
+        print(f"M = None forward bf16={bf16} path={path} causal={causal}: {U.fmt(e)}")
+        g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], None, dev["W"], dev["dOut"], causal, path=path)
+        torch.cuda.synchronize()
+        fused_bwd = bf16 and causal and path == dk.PATH_AUTO
+        check = U.assert_close_grad if fused_bwd else U.assert_close
+        dM = np.zeros((2, 64, 64))
+        for b in range(2):
+            for h in range(2):
+                Q, K, V, M, W = U.head(inp, b, h)
+                dQ, dK, dV, dMb = O.attn_bwd_brute(Q, K, V, M, W, inp["dOut"][b, h], causal)
+                dM[h] += dMb
+                for name, want in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+                    check(_np(g[name][b, h]), want, tol, f"M = None, {name}[{b},{h}] causal={causal}")
+        check(_np(g["dM"]), dM, tol, f"M = None, dM causal={causal}")
+    for is_query in (True, False):
+        phi, stab = dk.dark_featurize(dev["Q"], None, dev["W"], is_query, path=path)
+        phi2, stab2 = dk.dark_featurize(dev["Q"], dev["M"], dev["W"], is_query, path=path)
+        torch.cuda.synchronize()
+        assert torch.equal(phi, phi2) and torch.equal(stab, stab2)
+    with pytest.raises(dk.DarkError):      # r != d has no identity
+        Wr = torch.randn(2, 256, 32, device="cuda")
+        p = dk.make_params(2, 2, 330, 64, 32, 256, 64, io_dtype=dk.DARK_BF16 if bf16 else dk.DARK_F32,
+                           out_dtype=dk.DARK_BF16 if bf16 else dk.DARK_F32)
+        out = torch.empty_like(dev["V"])
+        ws = torch.empty(max(dk.workspace_bytes(p, dk.OP_ATTN_FWD), 256), dtype=torch.uint8, device="cuda")
+        dk._check(dk.lib().dark_attn_fwd(ctypes.byref(p), dev["Q"].data_ptr(), dev["K"].data_ptr(), dev["V"].data_ptr(),
+                                         None, Wr.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(), None), "dark_attn_fwd")
 
 
 # ---------------------------------------------------------------------------

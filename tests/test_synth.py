@@ -50,3 +50,28 @@ def test_top_k_spectrum():
     ev = np.sort(np.linalg.eigvalsh(q.T @ q / q.shape[0]))[::-1]
     assert abs(ev[:8].sum() / ev.sum() - 0.9) < 0.01
     assert abs(ev.sum() / cfg.d - 1) < 0.05
+
+
+# --- orthogonal random features (Section 2 of the paper: Gram-Schmidt orthogonalised directions) -------------
+def test_orthogonal_features_blocks_are_orthogonal_with_gaussian_lengths():
+    import scipy.stats
+    H, m, r = 5, 200, 32
+    W32 = synth.orthogonal_features(3, H, m, r)
+    assert W32.shape == (H, m, r) and W32.dtype == np.float32
+    W = W32.astype(np.float64)
+    assert np.array_equal(synth.orthogonal_features(3, H, m, r), synth.orthogonal_features(3, H, m, r))
+    assert not np.array_equal(synth.orthogonal_features(3, H, m, r), synth.orthogonal_features(4, H, m, r))
+    for h in range(H):
+        for j0 in range(0, m, r):
+            blk = W[h, j0:j0 + r]                      # the last block is ragged (200 = 6 * 32 + 8)
+            n = np.linalg.norm(blk, axis=1)
+            G = (blk / n[:, None]) @ (blk / n[:, None]).T
+            assert np.abs(G - np.eye(len(blk))).max() < 1e-6      # fp32 storage of the rows
+        # rows of different blocks are independent draws: not orthogonal
+        assert np.abs(W[h, :r] @ W[h, r:2 * r].T).max() > 1.0
+    # every single row is N(0, I_r): its length is chi(r), its coordinates standard normal
+    lengths = np.linalg.norm(W.reshape(-1, r), axis=1)
+    assert scipy.stats.kstest(lengths, "chi", args=(r,)).pvalue > 1e-3
+    assert scipy.stats.kstest(W.ravel(), "norm").pvalue > 1e-3
+    # fewer rows than one block, and a head count of one
+    assert synth.orthogonal_features(0, 1, 5, 16).shape == (1, 5, 16)
