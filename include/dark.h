@@ -199,6 +199,21 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
                           void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * dark_attn_bwd with one more output: the gradient with respect to the draws W, which turns
+ * the kernel into the learned feature kernel the paper compares against (Section 6: the
+ * projections omega of Eq. (1) replaced by trainable vectors; with M == NULL, dW is exactly
+ * that gradient).  The logits depend on W through w_j^T (M x') only, so
+ *   dW[h][j][:] = sum over the batch and over all query and key rows of dlogit_j (M x')^T.
+ *   dW: [H, m, r], or [m, r] (summed over the heads as well) when w_shared != 0; float32,
+ *       overwritten; may be NULL, as may every other gradient pointer.
+ * Everything else as dark_attn_bwd, including the workspace size.
+ */
+dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, const void* K,
+                             const void* V, const float* M, const float* W, const void* dOut,
+                             float* dQ, float* dK, float* dV, float* dM, float* dW,
+                             void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel
  * launch of the library carries a start and a stop event that the launch itself
  * stamps with the kernel's begin and end on the device, and the launch stream is

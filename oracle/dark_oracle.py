@@ -32,7 +32,8 @@ Pins (tests/test_oracle_pins.py): Performer special case M = I (Eq. (1)),
 Monte-Carlo unbiasedness and closed-form variance (Eq. (3), Lemma 2.1),
 causal == bidirectional at the last position, O(L^2) brute force == linear
 time, polarisation identity (Section 4.1), convex-hull and gauge invariances,
-softmax limit for large m, finite differences for every gradient.
+softmax limit for large m, finite differences for every gradient (Q, K, V, M
+and the draws W).
 """
 from __future__ import annotations
 
@@ -191,8 +192,10 @@ def attn_row(Q, K, V, M, W, i: int, causal: bool, scale=None):
     return (a @ V[:hi]) / a.sum()
 
 
-def attn_bwd_brute(Q, K, V, M, W, G, causal: bool, scale=None):
-    """Gradients of sum(out * G) w.r.t. Q, K, V, M for one head, O(L^2).
+def attn_bwd_brute(Q, K, V, M, W, G, causal: bool, scale=None, with_dW=False):
+    """Gradients of sum(out * G) w.r.t. Q, K, V, M for one head, O(L^2); with_dW adds the gradient
+    w.r.t. the draws W [m, r] as a fifth result (Section 6: the learned feature kernel trains the
+    projections of Eq. (1) themselves).
 
     The paper only says M is learnable (Section 4.1); these are the chain-rule
     derivatives of the definition above, written through the literal forward
@@ -234,4 +237,7 @@ def attn_bwd_brute(Q, K, V, M, W, G, causal: bool, scale=None):
     dM = dQt.T @ Qp + dKt.T @ Kp
     dQ = al * (dQt @ M)
     dK = al * (dKt @ M)
+    if with_dW:
+        # logit_j = w_j^T x~ - ... depends on w_j through the first term only
+        return dQ, dK, dV, dM, dlq.T @ Qt + dlk.T @ Kt
     return dQ, dK, dV, dM

@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.dark_static_scratch_bytes.restype = sz
     L.dark_attn_bwd.restype = i32
     L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_attn_bwd_dw.restype = i32
+    L.dark_attn_bwd_dw.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_timing_enable.argtypes = [i32]
     L.dark_timing_enable.restype = None
     L.dark_timing_reset.restype = None
@@ -228,18 +230,26 @@ def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PA
 
 
 def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path=PATH_AUTO, need=("dQ", "dK", "dV", "dM")):
-    """Gradients of sum(out*dOut): returns dict with float32 dQ, dK, dV, dM."""
+    """Gradients of sum(out*dOut): returns dict with the float32 gradients named in `need`
+    ("dQ", "dK", "dV", "dM", and "dW", the gradient with respect to the draws)."""
     torch = _torch()
     p = _params_from(Q, V, M, W, chunk=chunk, scale=scale, path=path)
     f32 = dict(dtype=torch.float32, device=Q.device)
+    H, d = Q.shape[1], Q.shape[3]
     g = {
         "dQ": torch.empty(Q.shape, **f32) if "dQ" in need else None,
         "dK": torch.empty(K.shape, **f32) if "dK" in need else None,
         "dV": torch.empty(V.shape, **f32) if "dV" in need else None,
-        "dM": torch.empty(M.shape if M is not None else (Q.shape[1], Q.shape[3], Q.shape[3]), **f32) if "dM" in need else None,
+        "dM": torch.empty(M.shape if M is not None else (H, d, d), **f32) if "dM" in need else None,
     }
     nb = workspace_bytes(p, OP_ATTN_BWD, causal)
     ws = _workspace(nb, Q.device)
+    if "dW" in need:
+        g["dW"] = torch.empty(W.shape, **f32)
+        _check(lib().dark_attn_bwd_dw(ctypes.byref(p), int(causal), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W),
+                                      _ptr(dOut), _ptr(g["dQ"]), _ptr(g["dK"]), _ptr(g["dV"]), _ptr(g["dM"]),
+                                      _ptr(g["dW"]), ws.data_ptr(), ws.numel(), _stream()), "dark_attn_bwd_dw")
+        return g
     _check(lib().dark_attn_bwd(ctypes.byref(p), int(causal), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(dOut),
                                _ptr(g["dQ"]), _ptr(g["dK"]), _ptr(g["dV"]), _ptr(g["dM"]), ws.data_ptr(), ws.numel(),
                                _stream()), "dark_attn_bwd")

@@ -105,7 +105,8 @@ static bool use_fused(const Problem& pb, int op, bool causal, dark_status* err) 
 
 static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const void* Q, const void* K,
                        const void* V, const float* M, const float* W, const void* dOut, void* out,
-                       float* stab, int is_query, float* dQ, float* dK, float* dV, float* dM) {
+                       float* stab, int is_query, float* dQ, float* dK, float* dV, float* dM,
+                       float* dW = nullptr) {
   dark_status err;
   bool fused = use_fused(pb, op, causal, &err);
   if (err != DARK_OK) return err;
@@ -128,8 +129,8 @@ static dark_status run(const Problem& pb, Arena& ar, int op, bool causal, const 
       return fused ? fused_attn_causal_fwd(pb, ar, Q, K, V, M, W, out)
                    : f32_attn_fwd(pb, ar, true, Q, K, V, M, W, out);
     case DARK_OP_ATTN_BWD:
-      return fused ? fused_attn_bwd(pb, ar, Q, K, V, M, W, dOut, dQ, dK, dV, dM)
-                   : f32_attn_bwd(pb, ar, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM);
+      return fused ? fused_attn_bwd(pb, ar, Q, K, V, M, W, dOut, dQ, dK, dV, dM, dW)
+                   : f32_attn_bwd(pb, ar, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM, dW);
   }
   return DARK_EINVAL;
 }
@@ -274,9 +275,9 @@ dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void
   return attn_common(p, DARK_OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, ws, ws_bytes, hip_stream);
 }
 
-dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
-                          const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
-                          float* dM, void* ws, size_t ws_bytes, void* hip_stream) {
+dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
+                             const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
+                             float* dM, float* dW, void* ws, size_t ws_bytes, void* hip_stream) {
   Problem pb;
   DARK_TRY(check_params(p, &pb));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;  // nothing to enqueue; gradients are left untouched
@@ -284,7 +285,7 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
   if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
   pb.m_identity = M == nullptr;
   if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(M, 16) || !aligned(W, 16) ||
-      !aligned(dOut, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) || !aligned(dM, 16))
+      !aligned(dOut, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) || !aligned(dM, 16) || !aligned(dW, 16))
     return DARK_EALIGN;
   {
     dark_status err;
@@ -294,7 +295,13 @@ dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const
   DARK_TRY(check_ws(ws, ws_bytes, measure(pb, DARK_OP_ATTN_BWD, causal != 0)));
   pb.st = static_cast<hipStream_t>(hip_stream);
   Arena ar(ws, ws_bytes);
-  return run(pb, ar, DARK_OP_ATTN_BWD, causal != 0, Q, K, V, M, W, dOut, nullptr, nullptr, 0, dQ, dK, dV, dM);
+  return run(pb, ar, DARK_OP_ATTN_BWD, causal != 0, Q, K, V, M, W, dOut, nullptr, nullptr, 0, dQ, dK, dV, dM, dW);
+}
+
+dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
+                          const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
+                          float* dM, void* ws, size_t ws_bytes, void* hip_stream) {
+  return dark_attn_bwd_dw(p, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM, nullptr, ws, ws_bytes, hip_stream);
 }
 
 void dark_timing_enable(int on) { g_timing = on != 0; }

@@ -114,7 +114,10 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
                          const void* V, const float* M, const float* W, void* out);
 dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K,
                          const void* V, const float* M, const float* W, const void* dOut, float* dQ,
-                         float* dK, float* dV, float* dM);
+                         float* dK, float* dV, float* dM, float* dW);
+// dW[h][j][t] = alpha sum over the nb batch entries b and over c of T[b][h][j][c] M[h][t][c]  (T: [nb, H, m, d]);
+// with a shared W the heads are summed as well (generic.hip).
+dark_status launch_dw(const Problem& pb, const float* T, int nb, const float* M, float* dW);
 
 // fused MFMA feature map (fused_feat.hip).
 bool fused_featurize_supported(const Problem& pb);
@@ -132,6 +135,6 @@ dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, c
 bool fused_bwd_supported(const Problem& pb, bool causal);
 dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const void* K, const void* V,
                            const float* M, const float* W, const void* dOut, float* dQ, float* dK,
-                           float* dV, float* dM);
+                           float* dV, float* dM, float* dW);
 
 }  // namespace dark

@@ -823,7 +823,7 @@ bool fused_bwd_supported(const Problem& pb, bool causal) {
 }
 
 dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const void* K, const void* V, const float* M,
-                           const float* W, const void* dOut, float* dQ, float* dK, float* dV, float* dM) {
+                           const float* W, const void* dOut, float* dQ, float* dK, float* dV, float* dM, float* dW) {
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
   // slices: one workgroup per CU, whole 64-token tiles of the key/value pass that provides the slice states
@@ -874,12 +874,14 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   DARK_TRY(allow_lds(k_bwd_rev, BwdSmem::total));
   DARK_LAUNCH(KID_BWD_REV, pb.st, k_bwd_rev, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah, Mh,
               nrm, cpre, lam, gdv, Rsn, Rsd, dK, dV, TQ, TK, RM, p.H, p.L, P, sl, inv_log2e);
-  if (dM != nullptr) {
+  if (dM != nullptr || dW != nullptr) {
     const long long n = (long long)p.H * ((long long)kF * kD + kD * kD);
     DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_sum, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, TK, RM, Tsum, Rmsum, p.B, p.H,
                 P);
-    DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_dm, dim3((unsigned)(p.H * (kD / 4))), dim3(256), 0, Tsum, Rmsum, M, W, dM, p.H,
-                p.w_shared, std::sqrt(pb.scale));
+    if (dM != nullptr)
+      DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_dm, dim3((unsigned)(p.H * (kD / 4))), dim3(256), 0, Tsum, Rmsum, M, W, dM, p.H,
+                  p.w_shared, std::sqrt(pb.scale));
+    if (dW != nullptr) DARK_TRY(launch_dw(pb, Tsum, 1, M, dW));  // Tsum is already summed over the batch
   }
   return DARK_OK;
 }

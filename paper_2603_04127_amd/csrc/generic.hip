@@ -1076,12 +1076,43 @@ int slice_len(const Problem& pb) {
   return (int)sl;
 }
 
+// Gradient with respect to the draws W (the parameters of a learned feature kernel): the logits depend on W
+// through w_j^T x~ only, so dW[h][j][:] = sum over tokens of dlogit_j x~^T = alpha (dlogit^T X)[j][:] M_h^T
+// = alpha T[j][:] M_h^T, summed over the batch in ascending order (and over heads when W is shared).
+__global__ __launch_bounds__(256) void k_dw(const float* __restrict__ T, const float* __restrict__ M,
+                                            float* __restrict__ dW, int nb, int H, int m, int r, int d, int w_shared,
+                                            float alpha) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long per = (long long)m * r;
+  if (i >= (w_shared ? 1 : H) * per) return;
+  const int t = (int)(i % r), j = (int)((i / r) % m);
+  const int h0 = w_shared ? 0 : (int)(i / per), h1 = w_shared ? H : h0 + 1;
+  float acc = 0.f;
+  for (int h = h0; h < h1; ++h)
+    for (int b = 0; b < nb; ++b) {
+      const float* Tr = T + (((size_t)b * H + h) * m + j) * d;
+      const float* Mr = M + ((size_t)h * r + t) * d;
+      float s0 = 0.f;
+      for (int c = 0; c < d; ++c) s0 = fmaf(Tr[c], Mr[c], s0);
+      acc += s0;
+    }
+  dW[i] = alpha * acc;
+}
+
 __global__ __launch_bounds__(256) void k_fill_identity(float* __restrict__ Mid, long long n, int d) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) Mid[i] = ((i / d) % d == i % d) ? 1.f : 0.f;
 }
 
 }  // namespace
+
+dark_status launch_dw(const Problem& pb, const float* T, int nb, const float* M, float* dW) {
+  const dark_params& p = pb.p;
+  const long long n = (long long)(p.w_shared ? 1 : p.H) * p.m * p.r;
+  DARK_LAUNCH(KID_BWD_ELEM, pb.st, k_dw, dim3(grid_for(n)), dim3(256), 0, T, M, dW, nb, p.H, p.m, p.r, p.d, p.w_shared,
+              std::sqrt(pb.scale));
+  return DARK_OK;
+}
 
 dark_status fill_identity(const Problem& pb, float* Mid) {
   const long long n = (long long)pb.p.H * pb.p.d * pb.p.d;
@@ -1373,7 +1404,7 @@ dark_status f32_attn_fwd(const Problem& pb, Arena& ar, bool causal, const void* 
 // masked within-chunk tiles  P = tril(Phi_Q Phi_K^T),  E = tril([dN|dD] [V|1]^T).
 dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* Q, const void* K, const void* V,
                          const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
-                         float* dM) {
+                         float* dM, float* dW) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
   const int dv1 = p.dv + 1, ldv = padded_ld(dv1);
@@ -1459,7 +1490,7 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
     }
     DARK_TRY(run_gemm(g, pb.st));
   }
-  if (dM) {
+  if (dM || dW) {
     const int SL = slice_len(pb);
     {  // Tpart = dlogit_Q^T Q + dlogit_K^T K per slice, one pass
       Gemm g = make_piece_states(pb, dPq, p.m, b.q.Xf, p.d, p.d, Tpart, p.d, SL, b.P, 0.f);
@@ -1468,6 +1499,10 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
     }
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * as_elems)), dim3(256), 0, Tpart, T,
                 pb.BH(), b.P, as_elems, as_elems * b.P, as_elems);
+    if (dW) DARK_TRY(launch_dw(pb, T, p.B, M, dW));
+  }
+  if (dM) {
+    const int SL = slice_len(pb);
     DARK_TRY(piece_states(pb, b.k.Xt, p.r, b.k.Xf, p.d, p.d, T2part, p.d, SL, b.P, 0.f));
     DARK_LAUNCH(KID_SUM_SLICES, pb.st, k_sum_slices, dim3(grid_for(pb.BH() * m_elems)), dim3(256), 0, T2part, T2,
                 pb.BH(), b.P, m_elems, m_elems * b.P, m_elems);

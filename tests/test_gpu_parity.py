@@ -116,6 +116,49 @@ def test_identity_geometry(bf16, path):
 
 
 # ---------------------------------------------------------------------------
+# dW: the gradient with respect to the draws (learned feature kernel)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("case", ["f32", "bf16_f32path", "bf16_auto", "shared_w", "identity"])
+def test_gradient_of_the_draws(case, causal):
+    bf16 = case.startswith("bf16") or case == "identity"
+    shared = case == "shared_w"
+    if case in ("f32", "shared_w"):
+        inp = U.random_problem(51, 2, 3, 150, 24, 16, 80, 40, bf16=False, w_shared=shared, amp=2.0, backward=True)
+    else:
+        inp = U.random_problem(52, 2, 2, 330, 64, 64, 256, 64, bf16=True, amp=1.0, backward=True)
+    if case == "identity":
+        inp["M"] = np.broadcast_to(np.eye(64, dtype=np.float32), (2, 64, 64)).copy()
+    dev = U.to_device(inp, bf16)
+    path = dk.PATH_AUTO if case in ("bf16_auto", "identity") else dk.PATH_F32
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], None if case == "identity" else dev["M"], dev["W"], dev["dOut"],
+                         causal, path=path, need=("dQ", "dK", "dV", "dM", "dW"))
+    g0 = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], None if case == "identity" else dev["M"], dev["W"], dev["dOut"],
+                          causal, path=path)
+    only = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], None if case == "identity" else dev["M"], dev["W"], dev["dOut"],
+                            causal, path=path, need=("dW",))
+    torch.cuda.synchronize()
+    for k in g0:
+        assert torch.equal(g[k], g0[k]), k
+    assert torch.equal(only["dW"], g["dW"]) and tuple(g["dW"].shape) == tuple(dev["W"].shape)
+    B, H = inp["Q"].shape[:2]
+    want = np.zeros(inp["W"].shape)
+    for b in range(B):
+        for h in range(H):
+            Q, K, V, M, W = U.head(inp, b, h)
+            dW = O.attn_bwd_brute(Q, K, V, M, W, inp["dOut"][b, h], causal, with_dW=True)[4]
+            if shared:
+                want += dW
+            else:
+                want[h] += dW
+    fused_bwd = bf16 and causal and path == dk.PATH_AUTO
+    check = U.assert_close_grad if fused_bwd else U.assert_close
+    tol = U.TOL["bf16"] if bf16 else 2e-4
+    e = check(_np(g["dW"]).reshape(-1, want.shape[-1]), want.reshape(-1, want.shape[-1]), tol, f"dW {case} causal={causal}")
+    print(f"dW {case} causal={causal}: {(U.fmt_grad if fused_bwd else U.fmt)(e)}")
+
+
+# ---------------------------------------------------------------------------
 # forward, small shapes spanning several tiles with ragged tails
 # ---------------------------------------------------------------------------
 SMALL = [

@@ -198,3 +198,23 @@ def test_backward_finite_differences(causal):
         np.testing.assert_allclose(grad, num, rtol=2e-6, atol=2e-8, err_msg=name)
     # shifting all values by a constant shifts every output by it
     np.testing.assert_allclose(dV.sum(0), G.sum(0), rtol=1e-10)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_gradient_of_the_draws_finite_differences(causal):
+    """dW (Section 6: the learned feature kernel trains the projections) against central differences."""
+    Q, K, V, M, W = _small(15, L=6, d=5, r=4, m=7, dv=3)
+    G = _rng(16).standard_normal(V.shape)
+    *_, dW = O.attn_bwd_brute(Q, K, V, M, W, G, causal, with_dW=True)
+    assert dW.shape == W.shape
+    h = 1e-6
+    num = np.zeros_like(W)
+    for idx in np.ndindex(W.shape):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += h
+        Wm[idx] -= h
+        num[idx] = (np.sum(O.attn_brute(Q, K, V, M, Wp, causal) * G) - np.sum(O.attn_brute(Q, K, V, M, Wm, causal) * G)) / (2 * h)
+    np.testing.assert_allclose(dW, num, rtol=2e-6, atol=2e-8)
+    # the four other gradients do not change when dW is asked for
+    for a, b in zip(O.attn_bwd_brute(Q, K, V, M, W, G, causal), O.attn_bwd_brute(Q, K, V, M, W, G, causal, with_dW=True)):
+        np.testing.assert_array_equal(a, b)
