@@ -4,7 +4,9 @@
 One "step" is one pass of the whole hot path over one batch of synthetic input:
 a forward call of the configuration's entry point (dark_attn_fwd for the
 bidirectional configurations, dark_attn_causal_fwd for the causal ones; the
-finetuning configuration adds dark_attn_bwd).  Inputs are resident in HBM before
+finetuning configuration runs the training pair dark_attn_causal_fwd_save +
+dark_attn_bwd_saved, in which the backward takes over the forward's key norms and
+prefix states instead of recomputing them).  Inputs are resident in HBM before
 the timed region; several distinct input copies are rotated so that the 256 MB
 memory-side cache cannot serve a step's reads from the previous step.
 
@@ -182,6 +184,10 @@ def main():
                     # same distribution, different memory: rotate batch and sequence
                     c[n] = torch.roll(dev0[n], shifts=(k % max(cfg.B, 1), 17 * k), dims=(0, 2)).contiguous()
         c["out"] = torch.empty_like(c["V"])
+        if cfg.backward:
+            f32 = dict(dtype=torch.float32, device="cuda")
+            c["grads"] = {"dQ": torch.empty(c["Q"].shape, **f32), "dK": torch.empty(c["K"].shape, **f32),
+                          "dV": torch.empty(c["V"].shape, **f32), "dM": torch.empty(c["M"].shape, **f32)}
         copies.append(c)
     gen_s = time.time() - t0
 
@@ -190,12 +196,21 @@ def main():
             dk.dark_featurize(c["Q"], c["M"], c["W"], True, path=path)
             dk.dark_featurize(c["K"], c["M"], c["W"], False, path=path)
             return
+        if cfg.causal and cfg.backward:
+            # training step: the forward leaves its operand copies, key norms and prefix states to the backward
+            _, saved = dk.dark_attn_causal_fwd_save(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"],
+                                                    saved=c.get("saved"), chunk=cfg.chunk, path=path)
+            c["saved"] = saved
+            dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], True, chunk=cfg.chunk, path=path,
+                             saved=saved, grads=c["grads"])
+            return
         if cfg.causal:
             dk.dark_attn_causal_fwd(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"], chunk=cfg.chunk, path=path)
         else:
             dk.dark_attn_fwd(c["Q"], c["K"], c["V"], c["M"], c["W"], out=c["out"], path=path)
         if cfg.backward:
-            dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], cfg.causal, chunk=cfg.chunk)
+            dk.dark_attn_bwd(c["Q"], c["K"], c["V"], c["M"], c["W"], c["dOut"], cfg.causal, chunk=cfg.chunk, path=path,
+                             grads=c["grads"])
 
     if args.steps is None or args.warmup is None:
         # size the run from a short probe: about 0.3 s timed, a quarter of that as warm-up

@@ -214,6 +214,33 @@ dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, co
                              void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Causal forward and backward as a pair (training): the backward needs the fp16 operand
+ * copies of (M, W), the key norms and the exclusive prefix states of the key/value pass,
+ * all of which the causal forward has just computed.  dark_attn_causal_fwd_save() is
+ * dark_attn_causal_fwd() that leaves them in `saved` (device memory, 256-byte aligned, at
+ * least dark_saved_bytes(p) bytes, owned by the caller); dark_attn_bwd_saved() is the causal
+ * dark_attn_bwd_dw() that reads them from there instead of recomputing them.  The caller
+ * guarantees that `saved` was written by dark_attn_causal_fwd_save() with the same
+ * parameters and the same K, V, M, W and has not been modified since; results are then bit
+ * for bit those of dark_attn_bwd_dw().
+ * dark_saved_bytes() is 0 for parameters without such a hand-over (anything the fused
+ * MFMA backward does not take: the two calls then behave exactly like
+ * dark_attn_causal_fwd() and dark_attn_bwd_dw(causal = 1) and ignore `saved`, which may be
+ * NULL).  Otherwise: DARK_EWORKSPACE if saved is NULL or too small, DARK_EALIGN if it is
+ * misaligned.  The workspace sizes are those of the plain calls.
+ */
+size_t dark_saved_bytes(const dark_params* p);
+dark_status dark_attn_causal_fwd_save(const dark_params* p, const void* Q, const void* K, const void* V,
+                                      const float* M, const float* W, void* out,
+                                      void* saved, size_t saved_bytes,
+                                      void* ws, size_t ws_bytes, void* hip_stream);
+dark_status dark_attn_bwd_saved(const dark_params* p, const void* Q, const void* K, const void* V,
+                                const float* M, const float* W, const void* dOut,
+                                const void* saved, size_t saved_bytes,
+                                float* dQ, float* dK, float* dV, float* dM, float* dW,
+                                void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel
  * launch of the library carries a start and a stop event that the launch itself
  * stamps with the kernel's begin and end on the device, and the launch stream is

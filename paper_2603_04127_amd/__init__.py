@@ -69,6 +69,12 @@ def lib() -> ctypes.CDLL:
     L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_attn_bwd_dw.restype = i32
     L.dark_attn_bwd_dw.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_saved_bytes.restype = sz
+    L.dark_saved_bytes.argtypes = [pp]
+    L.dark_attn_causal_fwd_save.restype = i32
+    L.dark_attn_causal_fwd_save.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+    L.dark_attn_bwd_saved.restype = i32
+    L.dark_attn_bwd_saved.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_timing_enable.argtypes = [i32]
     L.dark_timing_enable.restype = None
     L.dark_timing_reset.restype = None
@@ -229,23 +235,60 @@ def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PA
     return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype, sched)
 
 
-def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path=PATH_AUTO, need=("dQ", "dK", "dV", "dM")):
+def saved_bytes(p: DarkParams) -> int:
+    return int(lib().dark_saved_bytes(ctypes.byref(p)))
+
+
+def dark_attn_causal_fwd_save(Q, K, V, M, W, *, out=None, saved=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None):
+    """Causal forward that leaves what the backward can take over in `saved` (a uint8 device tensor of at
+    least saved_bytes(p) bytes; allocated here when not given).  Returns (out, saved); `saved` is None for
+    parameters that have no hand-over."""
+    torch = _torch()
+    p = _params_from(Q, V, M, W, out_dtype=out_dtype, chunk=chunk, scale=scale, path=path)
+    if out is None:
+        out = torch.empty(V.shape, dtype=Q.dtype if out_dtype is None else out_dtype, device=Q.device)
+    ns = saved_bytes(p)
+    if ns and saved is None:
+        saved = torch.empty(ns, dtype=torch.uint8, device=Q.device)
+    ws = _workspace(workspace_bytes(p, OP_ATTN_CAUSAL_FWD), Q.device)
+    _check(lib().dark_attn_causal_fwd_save(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(out),
+                                           _ptr(saved) if ns else None, saved.numel() if ns else 0,
+                                           ws.data_ptr(), ws.numel(), _stream()), "dark_attn_causal_fwd_save")
+    return out, (saved if ns else None)
+
+
+def dark_attn_bwd(Q, K, V, M, W, dOut, causal: bool, *, chunk=0, scale=0.0, path=PATH_AUTO, need=("dQ", "dK", "dV", "dM"),
+                  saved=None, grads=None):
     """Gradients of sum(out*dOut): returns dict with the float32 gradients named in `need`
-    ("dQ", "dK", "dV", "dM", and "dW", the gradient with respect to the draws)."""
+    ("dQ", "dK", "dV", "dM", and "dW", the gradient with respect to the draws).  `saved`: the hand-over
+    buffer of dark_attn_causal_fwd_save for the same inputs (causal only).  `grads`: a dict of preallocated
+    output tensors to write into instead of allocating."""
     torch = _torch()
     p = _params_from(Q, V, M, W, chunk=chunk, scale=scale, path=path)
     f32 = dict(dtype=torch.float32, device=Q.device)
     H, d = Q.shape[1], Q.shape[3]
-    g = {
-        "dQ": torch.empty(Q.shape, **f32) if "dQ" in need else None,
-        "dK": torch.empty(K.shape, **f32) if "dK" in need else None,
-        "dV": torch.empty(V.shape, **f32) if "dV" in need else None,
-        "dM": torch.empty(M.shape if M is not None else (H, d, d), **f32) if "dM" in need else None,
-    }
+    if grads is not None:
+        g = {k: grads.get(k) for k in ("dQ", "dK", "dV", "dM", "dW")}
+    else:
+        g = {
+            "dQ": torch.empty(Q.shape, **f32) if "dQ" in need else None,
+            "dK": torch.empty(K.shape, **f32) if "dK" in need else None,
+            "dV": torch.empty(V.shape, **f32) if "dV" in need else None,
+            "dM": torch.empty(M.shape if M is not None else (H, d, d), **f32) if "dM" in need else None,
+        }
+        if "dW" in need:
+            g["dW"] = torch.empty(W.shape, **f32)
     nb = workspace_bytes(p, OP_ATTN_BWD, causal)
     ws = _workspace(nb, Q.device)
-    if "dW" in need:
-        g["dW"] = torch.empty(W.shape, **f32)
+    if saved is not None:
+        if not causal:
+            raise ValueError("saved state exists for the causal form only")
+        _check(lib().dark_attn_bwd_saved(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W), _ptr(dOut),
+                                         _ptr(saved), saved.numel(), _ptr(g.get("dQ")), _ptr(g.get("dK")),
+                                         _ptr(g.get("dV")), _ptr(g.get("dM")), _ptr(g.get("dW")), ws.data_ptr(),
+                                         ws.numel(), _stream()), "dark_attn_bwd_saved")
+        return g
+    if g.get("dW") is not None:
         _check(lib().dark_attn_bwd_dw(ctypes.byref(p), int(causal), _ptr(Q), _ptr(K), _ptr(V), _ptr(M), _ptr(W),
                                       _ptr(dOut), _ptr(g["dQ"]), _ptr(g["dK"]), _ptr(g["dV"]), _ptr(g["dM"]),
                                       _ptr(g["dW"]), ws.data_ptr(), ws.numel(), _stream()), "dark_attn_bwd_dw")

@@ -217,11 +217,25 @@ dark_status dark_featurize(const dark_params* p, const void* X, const float* M, 
              nullptr, nullptr, nullptr);
 }
 
+// Validates a hand-over buffer and arms the problem with it (mode 1: the forward writes, 2: the backward reads).
+// Parameters without a hand-over (dark_saved_bytes() == 0) ignore the buffer.
+static dark_status arm_saved(Problem& pb, int mode, void* saved, size_t saved_bytes) {
+  const size_t need = fused_saved_causal_bytes(pb);
+  if (need == 0) return DARK_OK;
+  if (saved == nullptr || saved_bytes < need) return DARK_EWORKSPACE;
+  if (!aligned(saved, 256)) return DARK_EALIGN;
+  pb.saved_mode = mode;
+  pb.saved = saved;
+  pb.saved_bytes = saved_bytes;
+  return DARK_OK;
+}
+
 static dark_status attn_common(const dark_params* p, int op, const void* Q, const void* K, const void* V,
                                const float* M, const float* W, void* out, void* ws, size_t ws_bytes,
-                               void* hip_stream) {
+                               void* hip_stream, void* saved = nullptr, size_t saved_bytes = 0, bool save = false) {
   Problem pb;
   DARK_TRY(check_params(p, &pb));
+  if (save) DARK_TRY(arm_saved(pb, 1, saved, saved_bytes));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;
   if (!Q || !K || !V || !W || !out) return DARK_EINVAL;
   if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
@@ -275,11 +289,28 @@ dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void
   return attn_common(p, DARK_OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, ws, ws_bytes, hip_stream);
 }
 
-dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
-                             const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
-                             float* dM, float* dW, void* ws, size_t ws_bytes, void* hip_stream) {
+size_t dark_saved_bytes(const dark_params* p) {
+  Problem pb;
+  if (check_params(p, &pb) != DARK_OK) return 0;
+  if (pb.p.B == 0 || pb.p.L == 0) return 0;
+  return fused_saved_causal_bytes(pb);
+}
+
+dark_status dark_attn_causal_fwd_save(const dark_params* p, const void* Q, const void* K, const void* V,
+                                      const float* M, const float* W, void* out, void* saved, size_t saved_bytes,
+                                      void* ws, size_t ws_bytes, void* hip_stream) {
+  return attn_common(p, DARK_OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, ws, ws_bytes, hip_stream, saved, saved_bytes, true);
+}
+
+}  // extern "C"
+
+static dark_status bwd_common(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
+                              const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
+                              float* dM, float* dW, void* ws, size_t ws_bytes, void* hip_stream, const void* saved,
+                              size_t saved_bytes, bool use_saved) {
   Problem pb;
   DARK_TRY(check_params(p, &pb));
+  if (use_saved) DARK_TRY(arm_saved(pb, 2, const_cast<void*>(saved), saved_bytes));
   if (pb.p.B == 0 || pb.p.L == 0) return DARK_OK;  // nothing to enqueue; gradients are left untouched
   if (!Q || !K || !V || !W || !dOut) return DARK_EINVAL;
   if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
@@ -296,6 +327,21 @@ dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, co
   pb.st = static_cast<hipStream_t>(hip_stream);
   Arena ar(ws, ws_bytes);
   return run(pb, ar, DARK_OP_ATTN_BWD, causal != 0, Q, K, V, M, W, dOut, nullptr, nullptr, 0, dQ, dK, dV, dM, dW);
+}
+
+extern "C" {
+
+dark_status dark_attn_bwd_dw(const dark_params* p, int causal, const void* Q, const void* K, const void* V,
+                             const float* M, const float* W, const void* dOut, float* dQ, float* dK, float* dV,
+                             float* dM, float* dW, void* ws, size_t ws_bytes, void* hip_stream) {
+  return bwd_common(p, causal, Q, K, V, M, W, dOut, dQ, dK, dV, dM, dW, ws, ws_bytes, hip_stream, nullptr, 0, false);
+}
+
+dark_status dark_attn_bwd_saved(const dark_params* p, const void* Q, const void* K, const void* V, const float* M,
+                                const float* W, const void* dOut, const void* saved, size_t saved_bytes, float* dQ,
+                                float* dK, float* dV, float* dM, float* dW, void* ws, size_t ws_bytes,
+                                void* hip_stream) {
+  return bwd_common(p, 1, Q, K, V, M, W, dOut, dQ, dK, dV, dM, dW, ws, ws_bytes, hip_stream, saved, saved_bytes, true);
 }
 
 dark_status dark_attn_bwd(const dark_params* p, int causal, const void* Q, const void* K, const void* V,

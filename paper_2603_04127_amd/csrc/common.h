@@ -96,6 +96,11 @@ struct Problem {
   float scale;     // resolved (never 0)
   int chunk;       // resolved
   bool m_identity = false;  // the caller passed M == NULL: Sigma = I (needs r == d)
+  // Hand-over of the causal forward's operand copies, key norms and prefix states to the backward:
+  // 0 = none, 1 = the forward writes them into `saved`, 2 = the backward reads them from `saved`.
+  int saved_mode = 0;
+  void* saved = nullptr;
+  size_t saved_bytes = 0;
   hipStream_t st;
   long long BH() const { return (long long)p.B * p.H; }
   long long rows() const { return (long long)p.B * p.H * p.L; }
@@ -119,6 +124,9 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
 // with a shared W the heads are summed as well (generic.hip).
 dark_status launch_dw(const Problem& pb, const float* T, int nb, const float* M, float* dW);
 
+// Bytes of the hand-over buffer of the causal forward/backward pair on the MFMA path (0: no hand-over for
+// these parameters).  fused_causal.hip.
+size_t fused_saved_causal_bytes(const Problem& pb);
 // fused MFMA feature map (fused_feat.hip).
 bool fused_featurize_supported(const Problem& pb);
 dark_status fused_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,

@@ -826,24 +826,19 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
                            const float* W, const void* dOut, float* dQ, float* dK, float* dV, float* dM, float* dW) {
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
-  // slices: one workgroup per CU, whole 64-token tiles of the key/value pass that provides the slice states
-  long long want = (p.sched_cs_wgs > 0 ? p.sched_cs_wgs : 256) / BH;
-  want = want < 1 ? 1 : (want > 64 ? 64 : want);
-  int sl = (int)((p.L + want - 1) / want);
-  sl = ((sl + kTile - 1) / kTile) * kTile;
-  if (sl < kTile) sl = kTile;
-  const int P = (p.L + sl - 1) / sl;
+  int P, sl;
+  causal_slices(pb, &P, &sl);
 
   const size_t nstate = (size_t)BH * P * kF;
-  _Float16* Ah = ar.take<_Float16>((size_t)p.H * kF * kD);
-  _Float16* Mh = ar.take<_Float16>((size_t)p.H * kD * kD);
+  // operand copies, key norms and prefix states: from the forward's hand-over buffer when the caller has one
+  Arena sv(pb.saved, pb.saved_bytes);
+  const bool handover = pb.saved_mode == 2 && ar.base != nullptr;
+  const CausalKeep kp = take_causal_keep(handover ? sv : ar, pb, P);
+  _Float16 *Ah = kp.Ah, *Mh = kp.Mh;
+  float *Spre = kp.Spre, *zpre = kp.zpre, *cpre = kp.cpre, *nrm = kp.nrm;
   unsigned short* Spart = ar.take<unsigned short>(nstate * kD);
   float* zpart = ar.take<float>(nstate);
   float* cpart = ar.take<float>(nstate);
-  float* Spre = ar.take<float>(nstate * kD);
-  float* zpre = ar.take<float>(nstate);
-  float* cpre = ar.take<float>((size_t)BH * P);
-  float* nrm = ar.take<float>((size_t)BH * p.L);
   float* lam = ar.take<float>((size_t)BH * p.L);
   float* gdv = ar.take<float>((size_t)BH * p.L);
   float* dRn = ar.take<float>(nstate * kD);
@@ -856,10 +851,12 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   float* Tsum = ar.take<float>((size_t)p.H * kF * kD);
   float* Rmsum = ar.take<float>((size_t)p.H * kD * kD);
   if (ar.base == nullptr) return DARK_OK;
-  if (ar.overflow) return DARK_EWORKSPACE;
+  if (ar.overflow || sv.overflow) return DARK_EWORKSPACE;
 
-  DARK_TRY(fused_launch_prep(pb, M, W, Ah, Mh));
-  DARK_TRY(fused_causal_states64(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, Spre, zpre, cpre, P, sl));
+  if (!handover) {
+    DARK_TRY(fused_launch_prep(pb, M, W, Ah, Mh));
+    DARK_TRY(fused_causal_states64(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, Spre, zpre, cpre, P, sl));
+  }
   const float inv_log2e = 0.6931471805599453f;
   const unsigned grid = (unsigned)(BH * P);
   typedef const unsigned short* cus;

@@ -863,32 +863,36 @@ dark_status fused_attn_causal_fwd(const Problem& pb, Arena& ar, const void* Q, c
                                   const float* M, const float* W, void* out) {
   const dark_params& p = pb.p;
   const long long BH = pb.BH();
-  // Slices: one workgroup per CU (one fits), whole 64-token tiles of the key pass.
-  long long want = (p.sched_cs_wgs > 0 ? p.sched_cs_wgs : 256) / BH;
-  want = want < 1 ? 1 : (want > kMaxP ? kMaxP : want);
-  int sl = (int)((p.L + want - 1) / want);
-  sl = ((sl + kTile - 1) / kTile) * kTile;
-  if (sl < kTile) sl = kTile;
-  const int P = p.L > 0 ? (p.L + sl - 1) / sl : 1;
+  int P, sl;
+  causal_slices(pb, &P, &sl);
 
   const size_t nstate = (size_t)BH * P * p.m;
-  _Float16* Ah = ar.take<_Float16>((size_t)p.H * p.m * p.d);
-  _Float16* Mh = ar.take<_Float16>((size_t)p.H * p.r * p.d);
+  // what the backward can take over goes to the caller's hand-over buffer when there is one
+  Arena sv(pb.saved, pb.saved_bytes);
+  const bool handover = pb.saved_mode == 1 && ar.base != nullptr;
+  const CausalKeep kp = take_causal_keep(handover ? sv : ar, pb, P);
+  _Float16 *Ah = kp.Ah, *Mh = kp.Mh;
+  float *Spre = kp.Spre, *zpre = kp.zpre, *cpre = kp.cpre, *nrm = kp.nrm;
   unsigned short* Spart = ar.take<unsigned short>(nstate * p.dv);
   float* zpart = ar.take<float>(nstate);
   float* cpart = ar.take<float>(nstate);
-  float* Spre = ar.take<float>(nstate * p.dv);
-  float* zpre = ar.take<float>(nstate);
-  float* cpre = ar.take<float>((size_t)BH * P);
-  float* nrm = ar.take<float>((size_t)BH * (p.L > 0 ? p.L : 1));
   if (ar.base == nullptr) return DARK_OK;
-  if (ar.overflow) return DARK_EWORKSPACE;
+  if (ar.overflow || sv.overflow) return DARK_EWORKSPACE;
   if (p.L == 0 || BH == 0) return DARK_OK;
 
   DARK_TRY(fused_launch_prep(pb, M, W, Ah, Mh));
   if (p.d == 64)
     return launch_causal<64>(pb, Q, K, V, Ah, Mh, Spart, zpart, cpart, Spre, zpre, cpre, nrm, out, P, sl);
   return launch_causal<128>(pb, Q, K, V, Ah, Mh, Spart, zpart, cpart, Spre, zpre, cpre, nrm, out, P, sl);
+}
+
+size_t fused_saved_causal_bytes(const Problem& pb) {
+  if (!fused_causal_supported(pb) || !fused_bwd_supported(pb, true) || pb.p.path == DARK_PATH_F32) return 0;
+  int P, sl;
+  causal_slices(pb, &P, &sl);
+  Arena a(nullptr, 0);
+  (void)take_causal_keep(a, pb, P);
+  return a.off;
 }
 
 }  // namespace dark

@@ -116,6 +116,37 @@ static dark_status allow_lds(KernelT kernel, size_t bytes) {
 
 }  // namespace fz
 
+// Slicing of a sequence for the causal kernels: about one workgroup per CU over all (b,h), slices of whole
+// 64-token tiles, at most 64 per (b,h).  Forward and backward must agree on it.
+inline void causal_slices(const Problem& pb, int* P, int* slice_len) {
+  const dark_params& p = pb.p;
+  long long want = (p.sched_cs_wgs > 0 ? p.sched_cs_wgs : 256) / (pb.BH() > 0 ? pb.BH() : 1);
+  want = want < 1 ? 1 : (want > 64 ? 64 : want);
+  int sl = (int)((p.L + want - 1) / want);
+  sl = ((sl + 63) / 64) * 64;
+  if (sl < 64) sl = 64;
+  *slice_len = sl;
+  *P = p.L > 0 ? (p.L + sl - 1) / sl : 1;
+}
+// What the causal forward can hand to the backward (and what both otherwise keep in the workspace): the fp16
+// operand copies, the key norms and the exclusive prefix states with their running shifts.
+struct CausalKeep {
+  _Float16 *Ah, *Mh;
+  float *Spre, *zpre, *cpre, *nrm;
+};
+inline CausalKeep take_causal_keep(Arena& a, const Problem& pb, int P) {
+  const dark_params& p = pb.p;
+  const size_t nstate = (size_t)pb.BH() * P * p.m;
+  CausalKeep k;
+  k.Ah = a.take<_Float16>((size_t)p.H * p.m * p.d);
+  k.Mh = a.take<_Float16>((size_t)p.H * p.r * p.d);
+  k.Spre = a.take<float>(nstate * p.dv);
+  k.zpre = a.take<float>(nstate);
+  k.cpre = a.take<float>((size_t)pb.BH() * P);
+  k.nrm = a.take<float>((size_t)pb.BH() * (p.L > 0 ? p.L : 1));
+  return k;
+}
+
 // Implemented in fused.hip, used by the other fused translation units as well.
 // A' = sqrt(scale) log2(e) W M as fp16 [H][m][d];  M' = sqrt(scale) sqrt(log2(e)/2) M as fp16 [H][r][d].
 // Requires r, d multiples of 4, d <= 256, r * d <= 16384.

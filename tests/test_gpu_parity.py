@@ -159,6 +159,50 @@ def test_gradient_of_the_draws(case, causal):
 
 
 # ---------------------------------------------------------------------------
+# causal forward + backward with the hand-over buffer
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(2, 3, 1000, 64, 64, 256, 64), (1, 2, 130, 64, 64, 256, 64), (1, 1, 64, 64, 64, 256, 64)])
+def test_saved_state_gives_the_same_bits(shape):
+    """dark_attn_causal_fwd_save + dark_attn_bwd_saved against the plain pair: the same kernels on the same
+    values, so every output agrees bit for bit; a second, smaller problem through the same buffer as well."""
+    B, H, L, d, r, m, dv = shape
+    inp = U.random_problem(61, B, H, L, d, r, m, dv, bf16=True, amp=1.5, backward=True)
+    dev = U.to_device(inp, True)
+    p = dk.make_params(B, H, L, d, r, m, dv, io_dtype=dk.DARK_BF16, out_dtype=dk.DARK_BF16)
+    assert dk.saved_bytes(p) > 0
+    out0 = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    g0 = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True,
+                          need=("dQ", "dK", "dV", "dM", "dW"))
+    out1, saved = dk.dark_attn_causal_fwd_save(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    assert saved is not None and saved.numel() >= dk.saved_bytes(p)
+    # unrelated work through the shared workspace between the two calls must not matter
+    dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    g1 = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, saved=saved,
+                          need=("dQ", "dK", "dV", "dM", "dW"))
+    torch.cuda.synchronize()
+    assert torch.equal(out0.view(torch.int16), out1.view(torch.int16))
+    for k in g0:
+        assert torch.equal(g0[k], g1[k]), k
+    # errors: a buffer that is too small or missing
+    with pytest.raises(dk.DarkError):
+        dk.dark_attn_causal_fwd_save(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"],
+                                     saved=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def test_saved_state_is_a_no_op_where_there_is_no_hand_over():
+    """fp32 inputs (fp32 path): dark_saved_bytes is 0, the pair behaves like the plain calls."""
+    inp = U.random_problem(62, 1, 2, 200, 24, 16, 80, 40, bf16=False, amp=2.0, backward=True)
+    dev = U.to_device(inp, False)
+    p = dk.make_params(1, 2, 200, 24, 16, 80, 40)
+    assert dk.saved_bytes(p) == 0
+    out1, saved = dk.dark_attn_causal_fwd_save(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    assert saved is None
+    out0 = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
+    torch.cuda.synchronize()
+    assert torch.equal(out0, out1)
+
+
+# ---------------------------------------------------------------------------
 # forward, small shapes spanning several tiles with ragged tails
 # ---------------------------------------------------------------------------
 SMALL = [
