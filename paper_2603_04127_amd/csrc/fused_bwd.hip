@@ -472,20 +472,27 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_bwd_suffix(const float* __restrict__ dRn, const float* __restrict__ dRd,
                                                     float* __restrict__ Rn, float* __restrict__ Rd, int P, long long BH) {
-  const long long per = (long long)kF * kD + kF;
+  // four consecutive entries per thread; per (b,h) the kF x kD entries of Rn, then the kF of Rd
+  const long long per4 = ((long long)kF * kD + kF) / 4;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= BH * per) return;
-  const long long bh = idx / per, e = idx % per;
-  float run = 0.f;
-  for (int p = P - 1; p >= 0; --p) {
-    const size_t sb = (size_t)bh * P + p;
-    if (e < (long long)kF * kD) {
-      Rn[sb * kF * kD + e] = run;
-      run += dRn[sb * kF * kD + e];
-    } else {
-      Rd[sb * kF + (e - (long long)kF * kD)] = run;
-      run += dRd[sb * kF + (e - (long long)kF * kD)];
-    }
+  if (idx >= BH * per4) return;
+  const long long bh = idx / per4, e = 4 * (idx % per4);
+  const bool isn = e < (long long)kF * kD;
+  const float* src = isn ? dRn + (size_t)bh * P * kF * kD + e : dRd + (size_t)bh * P * kF + (e - (long long)kF * kD);
+  float* dst = isn ? Rn + (size_t)bh * P * kF * kD + e : Rd + (size_t)bh * P * kF + (e - (long long)kF * kD);
+  const size_t pitch = isn ? (size_t)kF * kD : (size_t)kF;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  for (int p0 = P - 1; p0 >= 0; p0 -= 8) {   // eight slices' loads in flight, then the (ordered) running sums
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p0 - u >= 0) v[u] = *reinterpret_cast<const f32x4*>(src + (size_t)(p0 - u) * pitch);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p0 - u >= 0) {
+        *reinterpret_cast<f32x4*>(dst + (size_t)(p0 - u) * pitch) = run;
+        run += v[u];
+      }
   }
 }
 
@@ -773,46 +780,72 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_bwd_sum(const float* __restrict__ T, const float* __restrict__ RM,
                                                  float* __restrict__ Tsum, float* __restrict__ Rmsum, int B, int H, int P) {
-  const long long per = (long long)kF * kD + kD * kD;
+  // four consecutive entries per thread; per head the kF x kD entries of T, then the kD x kD of Rm
+  const long long per4 = ((long long)kF * kD + kD * kD) / 4;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (long long)H * per) return;
-  const int h = (int)(idx / per);
-  const long long e = idx % per;
-  float run = 0.f;
-  if (e < (long long)kF * kD) {
-    for (int b = 0; b < B; ++b)
-      for (int p = 0; p < P; ++p) run += T[(((size_t)b * H + h) * P + p) * kF * kD + e];
-    Tsum[(size_t)h * kF * kD + e] = run;
-  } else {
-    const long long e2 = e - (long long)kF * kD;
-    for (int b = 0; b < B; ++b)
-      for (int p = 0; p < P; ++p) run += RM[(((size_t)b * H + h) * P + p) * kD * kD + e2];
-    Rmsum[(size_t)h * kD * kD + e2] = run;
+  if (idx >= (long long)H * per4) return;
+  const int h = (int)(idx / per4);
+  const long long e = 4 * (idx % per4);
+  const bool ist = e < (long long)kF * kD;
+  const size_t pitch = ist ? (size_t)kF * kD : (size_t)kD * kD;
+  const float* src = ist ? T + e : RM + (e - (long long)kF * kD);
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  const int n = B * P;   // slice s = b P + p of head h lies at ((b H + h) P + p) pitch
+  for (int s0 = 0; s0 < n; s0 += 8) {
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int sidx = s0 + u;
+      if (sidx < n) v[u] = *reinterpret_cast<const f32x4*>(src + (((size_t)(sidx / P) * H + h) * P + sidx % P) * pitch);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < n) run += v[u];
   }
+  float* dst = ist ? Tsum + (size_t)h * kF * kD + e : Rmsum + (size_t)h * kD * kD + (e - (long long)kF * kD);
+  *reinterpret_cast<f32x4*>(dst) = run;
 }
 
 // ---------------------------------------------------------------------------
 // k_bwd_dm: dM[h][r][d] = alpha sum_j W[h][j][r] Tsum[h][j][d] - alpha^2 sum_e M[h][r][e] Rmsum[h][e][d].
-// One block per (h, four rows r): thread (r, d), the contraction split over nothing (320 terms).
+// One block per (h, four rows r): thread (r, d).  The four columns of W and rows of M go to LDS first (the
+// strided reads once, together); the 320 terms of a thread are then read sixteen at a time.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_bwd_dm(const float* __restrict__ Tsum, const float* __restrict__ Rmsum,
                                                 const float* __restrict__ M, const float* __restrict__ W,
                                                 float* __restrict__ dM, int H, int w_shared, float alpha) {
-  const int h = blockIdx.x / (kD / 4), r = 4 * (blockIdx.x % (kD / 4)) + threadIdx.x / kD, d = threadIdx.x % kD;
+  __shared__ float Ws[kF * 4];
+  __shared__ float Ms[4 * kD];
+  const int h = blockIdx.x / (kD / 4), r0 = 4 * (blockIdx.x % (kD / 4));
+  const int rr = threadIdx.x / kD, d = threadIdx.x % kD;
   const float* Wh = W + (w_shared ? 0 : (size_t)h * kF * kD);
-  const float* Mr = M + ((size_t)h * kD + r) * kD;
-  float a1 = 0.f, a2 = 0.f, b1 = 0.f, b2 = 0.f;
-#pragma unroll 4
-  for (int j = 0; j < kF; j += 2) {
-    a1 = fmaf(Wh[(size_t)j * kD + r], Tsum[((size_t)h * kF + j) * kD + d], a1);
-    b1 = fmaf(Wh[(size_t)(j + 1) * kD + r], Tsum[((size_t)h * kF + j + 1) * kD + d], b1);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int i = threadIdx.x + 256 * u;   // (j, c): W[j][r0 + c]
+    Ws[i] = Wh[(size_t)(i / 4) * kD + r0 + i % 4];
   }
-#pragma unroll 4
-  for (int e = 0; e < kD; e += 2) {
-    a2 = fmaf(Mr[e], Rmsum[((size_t)h * kD + e) * kD + d], a2);
-    b2 = fmaf(Mr[e + 1], Rmsum[((size_t)h * kD + e + 1) * kD + d], b2);
+  Ms[threadIdx.x] = M[((size_t)h * kD + r0 + rr) * kD + d];
+  __syncthreads();
+  const float* Tp = Tsum + (size_t)h * kF * kD + d;
+  const float* Rp = Rmsum + (size_t)h * kD * kD + d;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int j0 = 0; j0 < kF; j0 += 16) {
+    float t[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) t[u] = Tp[(size_t)(j0 + u) * kD];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc[u % 4] = fmaf(Ws[(j0 + u) * 4 + rr], t[u], acc[u % 4]);
   }
-  dM[((size_t)h * kD + r) * kD + d] = alpha * (a1 + b1) - alpha * alpha * (a2 + b2);
+  float acc2[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int e0 = 0; e0 < kD; e0 += 16) {
+    float t[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) t[u] = Rp[(size_t)(e0 + u) * kD];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc2[u % 4] = fmaf(Ms[rr * kD + e0 + u], t[u], acc2[u % 4]);
+  }
+  dM[((size_t)h * kD + r0 + rr) * kD + d] =
+      alpha * ((acc[0] + acc[1]) + (acc[2] + acc[3])) - alpha * alpha * ((acc2[0] + acc2[1]) + (acc2[2] + acc2[3]));
 }
 
 }  // namespace
@@ -864,7 +897,7 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   DARK_LAUNCH(KID_BWD_FWD, pb.st, k_bwd_fwd, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah,
               nrm, Spre, zpre, cpre, dQ, lam, gdv, dRn, dRd, TQ, p.H, p.L, P, sl, inv_log2e);
   {
-    const long long n = BH * ((long long)kF * kD + kF);
+    const long long n = BH * ((long long)kF * kD + kF) / 4;
     DARK_LAUNCH(KID_BWD_SUFFIX, pb.st, k_bwd_suffix, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, dRn, dRd, Rsn, Rsd, P,
                 BH);
   }
@@ -872,7 +905,7 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
   DARK_LAUNCH(KID_BWD_REV, pb.st, k_bwd_rev, dim3(grid), dim3(512), BwdSmem::total, (cus)Q, (cus)K, (cus)V, (cus)dOut, Ah, Mh,
               nrm, cpre, lam, gdv, Rsn, Rsd, dK, dV, TQ, TK, RM, p.H, p.L, P, sl, inv_log2e);
   if (dM != nullptr || dW != nullptr) {
-    const long long n = (long long)p.H * ((long long)kF * kD + kD * kD);
+    const long long n = (long long)p.H * ((long long)kF * kD + kD * kD) / 4;
     DARK_LAUNCH(KID_BWD_DM, pb.st, k_bwd_sum, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, TK, RM, Tsum, Rmsum, p.B, p.H,
                 P);
     if (dM != nullptr)
