@@ -141,8 +141,8 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
                                                     const unsigned short* __restrict__ Vg,
                                                     const _Float16* __restrict__ Ah, const _Float16* __restrict__ Mh,
                                                     unsigned short* __restrict__ Spart, float* __restrict__ zpart,
-                                                    float* __restrict__ cpart, int H, int L, int m, int P,
-                                                    int slice_len, int n_work) {
+                                                    float* __restrict__ cpart, float* __restrict__ nrm_out, int H,
+                                                    int L, int m, int P, int slice_len, int n_work) {
   using SM = KvSmem;
   constexpr int D = 64, DV = 64, R = 64;
   constexpr int XROW = SM::XS * 2;  // bytes per staged key row
@@ -259,7 +259,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       // all four lane groups hold the same n' and write the same 16 bytes
       // A norm beyond the fp16 range turns into +inf: the token's features are exp2(-inf) = 0, which is their
       // value to within fp32 next to any key of ordinary norm (and 0/0 = NaN in the output if every key is so).
-      const float n = (tok_begin + tl2 * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : tot[tl2][0];
+      const int tokn = tok_begin + tl2 * kTile + 16 * wv + l16;
+      const float n = (tokn >= tok_end) ? kF16Max : tot[tl2][0];
+      if (nrm_out != nullptr && fb == 0 && g16 == 0 && tokn < tok_end) nrm_out[(size_t)bh * L + tokn] = n;
       const _Float16 hi = (_Float16)n;
       const _Float16 lo = (float)hi > kF16Max ? (_Float16)0.f : (_Float16)(n - (float)hi);
       fp16x2 hl;
@@ -381,7 +383,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       sq0 = sq1 = 0.f;
     }
     if (slot == 22) {  // all four lane groups hold the same n' and write the same 16 bytes: no branch
-      const float n = (tok_begin + (t + 2) * kTile + 16 * wv + l16 >= tok_end) ? kF16Max : ntot[0];
+      const int tokn = tok_begin + (t + 2) * kTile + 16 * wv + l16;
+      const float n = (tokn >= tok_end) ? kF16Max : ntot[0];
+      if (nrm_out != nullptr && fb == 0 && g16 == 0 && tokn < tok_end) nrm_out[(size_t)bh * L + tokn] = n;
       const _Float16 hi = (_Float16)n;   // +inf beyond the fp16 range (see the first tiles above)
       const _Float16 lo = (float)hi > kF16Max ? (_Float16)0.f : (_Float16)(n - (float)hi);
       fp16x2 hl;
@@ -1317,6 +1321,7 @@ struct FusedBufs {
   float* zt;
   float* cf;
   float* nrm;  // key norms [BH][L], d = 128 only
+  float* nrm_out;  // where the key pass leaves the key norms it computes (causal callers), else null
 };
 
 void plan_bufs(const Problem& pb, const Plan& pl, Arena& ar, FusedBufs& b) {
@@ -1338,13 +1343,13 @@ dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, con
   if (pl.tp) {
     DARK_TRY(allow_lds(k_kv_reduce<true>, KvSmem::total));
     DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<true>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
-                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m,
-                pl.P, pl.slice_len, pl.n_work);
+                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, b.nrm_out, p.H,
+                p.L, p.m, pl.P, pl.slice_len, pl.n_work);
   } else {
     DARK_TRY(allow_lds(k_kv_reduce<false>, KvSmem::total));
     DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<false>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
-                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, p.H, p.L, p.m,
-                pl.P, pl.slice_len, pl.n_work);
+                (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, b.nrm_out, p.H,
+                p.L, p.m, pl.P, pl.slice_len, pl.n_work);
   }
   return DARK_OK;
 }
@@ -1431,7 +1436,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
 
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
                                    const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
-                                   int slice_len) {
+                                   int slice_len, float* nrm_out) {
   const dark_params& p = pb.p;
   Plan pl{};
   pl.nfb = p.m / 256;
@@ -1446,6 +1451,7 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
   b.Spart = Spart;
   b.zpart = zpart;
   b.cpart = cpart;
+  b.nrm_out = nrm_out;
   if (p.d != 64) return DARK_EUNSUPPORTED;
   return launch_kv(pb, pl, b, K, V);
 }

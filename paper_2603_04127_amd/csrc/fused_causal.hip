@@ -816,8 +816,8 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
   if (D == 128 || p.sched_cs_state == 1) {
     DARK_TRY((launch_slice_state<D>(pb, K, V, Ah, Mh, nrm, Spart, zpart, cpart, P, slice_len)));
   } else {
-    DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
-    DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
+    // the key pass computes the key norms on its way and leaves them in nrm
+    DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len, nrm));
   }
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
               Spre, zpre, cpre, p.m, P);
@@ -844,8 +844,7 @@ dark_status fused_causal_states64(const Problem& pb, const void* K, const void* 
                                   float* Spre, float* zpre, float* cpre, int P, int slice_len) {
   const dark_params& p = pb.p;
   if (p.d != 64 || p.dv != 64 || P > kMaxP) return DARK_EUNSUPPORTED;
-  DARK_TRY((launch_key_norms<64>(pb, K, Mh, nrm)));
-  DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len));
+  DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len, nrm));
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<64>), dim3((unsigned)(pb.BH() * (p.m / 8))), dim3(256), 0, Spart, zpart,
               cpart, Spre, zpre, cpre, p.m, P);
   return DARK_OK;

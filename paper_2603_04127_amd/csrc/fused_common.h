@@ -153,10 +153,11 @@ inline CausalKeep take_causal_keep(Arena& a, const Problem& pb, int P) {
 dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W, _Float16* Ah, _Float16* Mh);
 // Key/value pass over P slices of slice_len tokens (a multiple of 64) per (b,h):
 // Spart [BH][P][m][dv] (bf16), zpart and cpart [BH][P][m] (per-slice, per-feature shifts, log2 domain).
+// nrm_out (may be null): [BH][L], receives the key norms |M' k|^2 that the pass computes on its way.
 // Requires d = r = dv = 64.
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
                                    const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
-                                   int slice_len);
+                                   int slice_len, float* nrm_out = nullptr);
 // Implemented in fused_causal.hip.
 bool fused_causal_supported(const Problem& pb);
 // Key norms nrm [BH][L], slice states ([BH][P][m][dv] bf16 with per-feature shifts) and their exclusive prefix
