@@ -581,7 +581,7 @@ __global__ __launch_bounds__(256) void k_kv_merge(const unsigned short* __restri
                                                   const float* __restrict__ zpart, const float* __restrict__ cpart,
                                                   unsigned short* __restrict__ St, float* __restrict__ zt,
                                                   float* __restrict__ cf, int m, int P) {
-  constexpr int PP = 8;  // slices per pass
+  constexpr int PP = DV == 64 ? 16 : 8;  // slices per pass (one memory round trip each): as many as the registers hold
   __shared__ float tile[64][DV + 1];
   __shared__ float fac[PP][64];
   __shared__ float red[4];
@@ -611,7 +611,16 @@ __global__ __launch_bounds__(256) void k_kv_merge(const unsigned short* __restri
       zv[u] = tid < 64 ? zpart[((size_t)bh * P + p0 + pu) * m + 64 * blk + tid] : 0.f;
     }
     if (p0 == 0) {
-      for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[(size_t)bh * P * m + i]);
+      // largest shift of the (b,h): P m values (m a multiple of 64), sixteen 16-byte loads in flight per thread
+      const f32x4* cp4 = reinterpret_cast<const f32x4*>(cpart + (size_t)bh * P * m);
+      const int n4 = P * m / 4;
+      for (int i0 = tid; i0 < n4; i0 += 256 * 16) {
+        f32x4 cv[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) cv[u] = cp4[min(i0 + 256 * u, n4 - 1)];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) cs = fmaxf(fmaxf(cs, fmaxf(cv[u][0], cv[u][1])), fmaxf(cv[u][2], cv[u][3]));
+      }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
       if (tid % 64 == 0) red[tid / 64] = cs;
@@ -691,7 +700,17 @@ __global__ __launch_bounds__(256) void k_kv_merge_t(const unsigned short* __rest
   }
   // c* over every slice and feature of the (b,h)
   float cs = -INFINITY;
-  for (int i = tid; i < P * m; i += 256) cs = fmaxf(cs, cpart[sbase * m + i]);
+  {  // P m values, m a multiple of 64: 16-byte loads, all of a round in flight together
+    const f32x4* cp4 = reinterpret_cast<const f32x4*>(cpart + sbase * m);
+    const int n4 = P * m / 4;
+    for (int i0 = tid; i0 < n4; i0 += 256 * 4) {
+      f32x4 cv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) cv[u] = cp4[min(i0 + 256 * u, n4 - 1)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) cs = fmaxf(fmaxf(cs, fmaxf(cv[u][0], cv[u][1])), fmaxf(cv[u][2], cv[u][3]));
+    }
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cs = fmaxf(cs, __shfl_xor(cs, o, 64));
   if (tid % 64 == 0) red[tid / 64] = cs;

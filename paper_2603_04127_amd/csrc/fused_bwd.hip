@@ -80,14 +80,6 @@ __device__ __forceinline__ float bf_lo(unsigned w) { return __uint_as_float(w <<
 __device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 constexpr unsigned kOnes = 0x3f803f80u;
 
-// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global load and
-// store in flight, which would expose the latency of the next tile's prefetch and of the gradient stores at
-// each of the tile's barriers.  Registers filled by global loads are private to the lane; the compiler
-// still waits for them where they are used.
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 struct BwdSmem {
   // byte offsets; F = forward-order kernel, R = reverse-order kernel (same map, a few regions differ in use)
   static constexpr size_t al = 0;                                  // A' fp16 [256][LDX]

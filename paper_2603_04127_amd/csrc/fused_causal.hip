@@ -115,6 +115,7 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restr
   typedef float fvec __attribute__((ext_vector_type(EPT)));
   __shared__ float cmax[kMaxP];
   __shared__ float cst[kMaxP];
+  __shared__ float cl[16][256];
   const int nblk = m / 8;
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
@@ -146,14 +147,30 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restr
       zv[u] = zpart[row];
     }
     if (p0 == 0) {
-      for (int p = wv; p < P; p += 4) {
-        float c = -INFINITY;
-        for (int i = lane; i < m; i += 64) c = fmaxf(c, cpart[((size_t)bh * P + p) * m + i]);
+      // largest shift of every slice: sixteen slices' shifts are fetched together (one memory round trip),
+      // parked in LDS, and reduced a slice per wave
+      for (int q0 = 0; q0 < P; q0 += 16) {
+        for (int i0 = 0; i0 < m; i0 += 256) {
+          float cv[16];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) c = fmaxf(c, __shfl_xor(c, o, 64));
-        if (lane == 0) cmax[p] = c;
+          for (int u = 0; u < 16; ++u)
+            cv[u] = i0 + tid < m ? cpart[((size_t)bh * P + min(q0 + u, P - 1)) * m + i0 + tid] : -INFINITY;
+          if (i0 > 0) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) cv[u] = fmaxf(cv[u], cl[u][tid]);
+          }
+#pragma unroll
+          for (int u = 0; u < 16; ++u) cl[u][tid] = cv[u];
+        }
+        __syncthreads();
+        for (int u = wv; u < 16 && q0 + u < P; u += 4) {
+          float c = fmaxf(fmaxf(cl[u][lane], cl[u][lane + 64]), fmaxf(cl[u][lane + 128], cl[u][lane + 192]));
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) c = fmaxf(c, __shfl_xor(c, o, 64));
+          if (lane == 0) cmax[q0 + u] = c;
+        }
+        __syncthreads();
       }
-      __syncthreads();
       if (tid == 0) {
         float run = -INFINITY;
         for (int p = 0; p < P; ++p) {

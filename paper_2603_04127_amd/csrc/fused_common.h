@@ -98,6 +98,15 @@ __device__ static inline void dma16_to_lds(const void* gsrc, void* lds_wave_base
 }
 __device__ static inline void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
+// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global load and
+// store in flight, which would expose the latency of the next tile's prefetch and of the output stores at
+// each of a tile's barriers.  Registers filled by global loads are private to the lane; the compiler
+// still waits for them where they are used.  Not for data that reaches LDS by direct global -> LDS loads:
+// those need wait_vmcnt0() before the barrier.
+__device__ static inline void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Raises a kernel's dynamic-LDS limit when it needs more than the default; done once per kernel
 // and size (the attribute call is host work we do not want on every launch).
 template <typename KernelT>
