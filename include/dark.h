@@ -20,9 +20,9 @@
  *    M may be NULL in every entry point: it then stands for the identity (Sigma = I, the
  *    isotropic positive random features of Section 2, Eq. (1), which the paper compares
  *    against in Section 6) and r must equal d (else DARK_EINVAL).  The identity is written
- *    into the workspace and the same kernels run; only the key norms of the causal MFMA
- *    kernels take a shorter route (|k|^2 without a projection).  dM of dark_attn_bwd is then
- *    the gradient at M = I.
+ *    into the workspace and the same kernels run; only the key-norm kernel of the causal
+ *    MFMA path at d = 128 takes a shorter route (|k|^2 without a projection).  dM of
+ *    dark_attn_bwd is then the gradient at M = I.
  *    Q, K, V, dOut, phi and out have the element type `io_dtype`
  *    (out: `out_dtype`); gradients are always float32.
  *  - Each query and key is multiplied by sqrt(scale) before the feature map, so
