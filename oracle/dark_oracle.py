@@ -42,7 +42,7 @@ import numpy as np
 __all__ = [
     "alpha_of", "logits", "featurize", "kernel_estimate",
     "attn_bidir", "attn_causal", "attn_brute", "attn_loops",
-    "attn_bwd_brute", "attn_row",
+    "attn_bwd_brute", "attn_row", "whitening_geometry",
 ]
 
 
@@ -241,3 +241,28 @@ def attn_bwd_brute(Q, K, V, M, W, G, causal: bool, scale=None, with_dW=False):
         # logit_j = w_j^T x~ - ... depends on w_j through the first term only
         return dQ, dK, dV, dM, dlq.T @ Qt + dlk.T @ Kt
     return dQ, dK, dV, dM
+
+
+def whitening_geometry(Q, K, r=None, floor=1e-6):
+    """Geometry that whitens the inputs (Section 4.1 and Proposition C.1: with input covariance Lambda,
+    M = Lambda^{-1/2}, Sigma = Lambda^{-1}, makes M q and M k isotropic).
+
+    Q, K: [N, d] rows of one head (the paper assumes Cov(q) = Cov(k) = Lambda, Section 3, so the two are
+    pooled).  Readings where the paper is silent: Lambda is estimated as the centred sample covariance of
+    the 2N pooled rows (divisor 2N); with Lambda = U diag(lambda) U^T, lambda descending, the result is
+    M = diag(lambda_1..r ^ -1/2) U[:, :r]^T (rows = principal directions; for r = d this is Lambda^{-1/2}
+    up to a rotation of the rows, which leaves Sigma = M^T M unchanged; for r < d, allowed by Appendix B,
+    the r directions of largest variance); eigenvalues below floor * lambda_1 are raised to it.
+    Returns (M [r, d], Lambda [d, d]).
+    """
+    X = np.concatenate([_f64(Q), _f64(K)], axis=0)
+    d = X.shape[1]
+    r = d if r is None else int(r)
+    Xc = X - X.mean(axis=0, keepdims=True)
+    Lam = Xc.T @ Xc / X.shape[0]
+    w, U = np.linalg.eigh(Lam)
+    order = np.argsort(w)[::-1]
+    w, U = w[order], U[:, order]
+    w = np.maximum(w, floor * w[0])
+    M = (U[:, :r] / np.sqrt(w[:r])[None, :]).T
+    return M, Lam

@@ -218,3 +218,44 @@ def test_gradient_of_the_draws_finite_differences(causal):
     # the four other gradients do not change when dW is asked for
     for a, b in zip(O.attn_bwd_brute(Q, K, V, M, W, G, causal), O.attn_bwd_brute(Q, K, V, M, W, G, causal, with_dW=True)):
         np.testing.assert_array_equal(a, b)
+
+
+# --- whitening geometry (Section 4.1, Proposition C.1) ----------------------------------------------
+def test_whitening_geometry():
+    g = _rng(31)
+    d, N = 9, 4000
+    C = g.standard_normal((d, d))
+    C = C @ C.T + 0.05 * np.eye(d)
+    Lc = np.linalg.cholesky(C)
+    mu = g.standard_normal(d)
+    Q = g.standard_normal((N, d)) @ Lc.T + mu
+    K = g.standard_normal((N, d)) @ Lc.T + mu
+    M, Lam = O.whitening_geometry(Q, K)
+    # the estimate is the centred pooled sample covariance (numpy's own routine, bias = divisor N)
+    np.testing.assert_allclose(Lam, np.cov(np.concatenate([Q, K]).T, bias=True), rtol=1e-10, atol=1e-12)
+    # whitening: Cov(M x) = M Lambda M^T = I, and Sigma = M^T M = Lambda^{-1} (library inverse)
+    np.testing.assert_allclose(M @ Lam @ M.T, np.eye(d), atol=1e-9)
+    np.testing.assert_allclose(M.T @ M, np.linalg.inv(Lam), rtol=1e-8)
+    # close to the population statement M C M^T = I within sampling error
+    assert np.abs(M @ C @ M.T - np.eye(d)).max() < 0.12
+    # Proposition C.1: |q - k|^2 in the Lambda^{-1} geometry = sum_i delta_i^2 / lambda_i = |Mq - Mk|^2
+    lam, U = np.linalg.eigh(Lam)
+    q, k = Q[3], K[5]
+    delta = U.T @ (q - k)
+    want = float(np.sum(delta ** 2 / lam))
+    np.testing.assert_allclose((q - k) @ np.linalg.inv(Lam) @ (q - k), want, rtol=1e-9)
+    np.testing.assert_allclose(np.sum((M @ q - M @ k) ** 2), want, rtol=1e-9)
+    # a common offset of all rows changes nothing
+    M2, _ = O.whitening_geometry(Q + 7.0, K + 7.0)
+    np.testing.assert_allclose(M2.T @ M2, M.T @ M, rtol=1e-7)
+    # r < d: the r directions of largest variance, whitened
+    Mr, _ = O.whitening_geometry(Q, K, r=4)
+    assert Mr.shape == (4, d)
+    np.testing.assert_allclose(Mr @ Lam @ Mr.T, np.eye(4), atol=1e-9)
+    top = U[:, np.argsort(lam)[::-1][:4]]
+    np.testing.assert_allclose(Mr.T @ Mr @ top, top / np.sort(lam)[::-1][:4][None, :], rtol=1e-8, atol=1e-10)
+    # the floor: a direction without variance does not blow up
+    Qd = Q.copy(); Kd = K.copy()
+    Qd[:, 0] = 1.0; Kd[:, 0] = 1.0
+    Mf, Lf = O.whitening_geometry(Qd, Kd, floor=1e-6)
+    assert np.isfinite(Mf).all() and np.abs(Mf).max() <= 1.0001 / np.sqrt(1e-6 * np.linalg.eigvalsh(Lf).max())
