@@ -53,6 +53,9 @@ def algorithmic_work(cfg):
         "f32_gemm": ("alu", th * f_tok),   # all GEMM launches of one step together
         # dark_featurize, per launch (one tensor): rows read once, features written once
         "fused_featurize": ("hbm", th * (d + m) * s_in),
+        # dark_whiten: the second moments read every row of Q and K once (the per-head eigen-decomposition is
+        # a fixed cost that does not grow with the number of rows)
+        "whiten_moments": ("hbm", 2 * th * d * s_in),
         # backward, forward-order pass (tiles of T = 32 tokens): both projections, numerator and denominator
         # again, the logit gradients of the queries (state part and tile triangle), dQ, and the updates of
         # S, Rn and T_Q; reverse-order pass: projections, dV, the logit gradients of the keys, dK (with the
@@ -148,10 +151,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps (default: a quarter of --steps)")
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2, the headline)")
     ap.add_argument("--path", choices=["auto", "f32", "fused"], default="auto")
-    ap.add_argument("--op", choices=["attn", "featurize"], default="attn",
+    ap.add_argument("--op", choices=["attn", "featurize", "whiten"], default="attn",
                     help="attn (default): the attention step the metric is quoted on; featurize: dark_featurize of "
                          "the configuration's Q (query contract) and K (key contract), a side measurement of that "
-                         "entry point (value = rows/s)")
+                         "entry point (value = rows/s); whiten: dark_whiten of the configuration's Q and K (value = rows/s)")
     ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -195,6 +198,9 @@ def main():
         if args.op == "featurize":
             dk.dark_featurize(c["Q"], c["M"], c["W"], True, path=path)
             dk.dark_featurize(c["K"], c["M"], c["W"], False, path=path)
+            return
+        if args.op == "whiten":
+            dk.dark_whiten(c["Q"], c["K"])
             return
         if cfg.causal and cfg.backward:
             # training step: the forward leaves its operand copies, key norms and prefix states to the backward
@@ -242,6 +248,10 @@ def main():
         th = cfg.B * cfg.H * cfg.L
         flops = 2 * th * (2 * cfg.d * cfg.m + 2 * cfg.d * cfg.r)
         nbytes = 2 * per_kernel["fused_featurize"][1]
+    if args.op == "whiten":
+        th = cfg.B * cfg.H * cfg.L
+        flops = 2 * th * 2 * cfg.d * cfg.d
+        nbytes = per_kernel["whiten_moments"][1]
 
     # Per-kernel device time: a second loop in which the library attaches start/stop events to every
     # launch (stamped with the kernel's own begin and end on the launch stream; the stream is drained
@@ -256,6 +266,8 @@ def main():
     dk.timing_enable(False)
     kernels = {k: {"launches": n, "avg_us": 1e3 * t / n, "us_per_step": 1e3 * t / ksteps} for k, (n, t) in kt.items()}
     dom = max(kt.items(), key=lambda kv: kv[1][1])[0]
+    if args.op == "whiten":
+        dom = "whiten_moments"   # the part that scales with the data; the eigen-decomposition is a fixed cost per head
     bound, units = per_kernel.get(dom, ("hbm", nbytes))
     us_step = kernels[dom]["us_per_step"]
     peak, unit = PEAK[bound]
@@ -276,7 +288,8 @@ def main():
 
     line = {
         "metric": ("DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)" if args.op == "attn"
-                   else "dark_featurize rows/sec (query rows + key rows); % of MFMA/HBM roofline (1 GPU)"),
+                   else "dark_featurize rows/sec (query rows + key rows); % of MFMA/HBM roofline (1 GPU)" if args.op == "featurize"
+                   else "dark_whiten rows/sec (query rows + key rows); % of HBM roofline (1 GPU)"),
         "value": (tokens if args.op == "attn" else 2 * cfg.B * cfg.H * cfg.L) / (ms * 1e-3),
         "unit": "tokens/s" if args.op == "attn" else "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,

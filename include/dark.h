@@ -62,7 +62,8 @@ typedef enum {
   DARK_OP_FEATURIZE = 0,
   DARK_OP_ATTN_FWD = 1,
   DARK_OP_ATTN_CAUSAL_FWD = 2,
-  DARK_OP_ATTN_BWD = 3
+  DARK_OP_ATTN_BWD = 3,
+  DARK_OP_WHITEN = 4
 } dark_op;
 
 /*
@@ -239,6 +240,26 @@ dark_status dark_attn_bwd_saved(const dark_params* p, const void* Q, const void*
                                 const void* saved, size_t saved_bytes,
                                 float* dQ, float* dK, float* dV, float* dM, float* dW,
                                 void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Whitening geometry: an initial M from the statistics of the inputs (paper: Section 4.1,
+ * "if the input covariance is Lambda then choosing M = Lambda^{-1/2} whitens the inputs";
+ * Proposition C.1).  Per head h, over all B * L rows of Q and of K (pooled: the paper
+ * assumes Cov(q) = Cov(k), Section 3; K may be NULL, then Q alone):
+ *   Lambda_h = centred sample covariance (divisor = number of rows),
+ *   Lambda_h = U diag(lambda) U^T with lambda descending, each lambda raised to at least
+ *              1e-6 * lambda_1,
+ *   M_h      = diag(lambda_1..r ^ -1/2) U[:, :r]^T      (so M Lambda M^T = I_r and, for r = d,
+ *              M^T M = Lambda^-1; the rows of M are determined up to sign).
+ * Uses p->B, H, L, d, r, io_dtype (Q, K: [B, H, L, d] in io_dtype); m, dv are ignored.
+ *   M_out:   [H, r, d] float32.
+ *   cov_out: [H, d, d] float32, receives Lambda; may be NULL.
+ * Workspace: dark_workspace_bytes(p, DARK_OP_WHITEN, 0).  DARK_EUNSUPPORTED for d > 128 or
+ * r > d; DARK_EINVAL for B * L == 0.  The estimator, the pooling and the floor are this
+ * library's readings; the paper states only the population identity.
+ */
+dark_status dark_whiten(const dark_params* p, const void* Q, const void* K, float* M_out, float* cov_out,
+                        void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel

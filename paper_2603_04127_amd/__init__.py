@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdark.so")
 
 DARK_OK, DARK_EINVAL, DARK_EUNSUPPORTED, DARK_EWORKSPACE, DARK_EALIGN, DARK_EHIP, DARK_ESCRATCH = range(7)
 DARK_F32, DARK_BF16 = 0, 1
-OP_FEATURIZE, OP_ATTN_FWD, OP_ATTN_CAUSAL_FWD, OP_ATTN_BWD = range(4)
+OP_FEATURIZE, OP_ATTN_FWD, OP_ATTN_CAUSAL_FWD, OP_ATTN_BWD, OP_WHITEN = range(5)
 PATH_AUTO, PATH_F32, PATH_FUSED = range(3)
 
 
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_attn_bwd_dw.restype = i32
     L.dark_attn_bwd_dw.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_whiten.restype = i32
+    L.dark_whiten.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_saved_bytes.restype = sz
     L.dark_saved_bytes.argtypes = [pp]
     L.dark_attn_causal_fwd_save.restype = i32
@@ -233,6 +235,21 @@ def static_scratch_bytes() -> int:
 def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None, sched=None):
     """Causal random-feature attention (keys l <= i), out [B,H,L,dv]."""
     return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype, sched)
+
+
+def dark_whiten(Q, K=None, *, r=None, want_cov=False):
+    """Whitening geometry M [H, r, d] (float32) from the rows of Q and K [B, H, L, d]; with want_cov also the
+    covariance estimate [H, d, d]."""
+    torch = _torch()
+    B, H, L, d = Q.shape
+    r = d if r is None else int(r)
+    p = make_params(B, H, L, d, r, 64, 1, io_dtype=_dtype_code(Q))
+    M = torch.empty((H, r, d), dtype=torch.float32, device=Q.device)
+    cov = torch.empty((H, d, d), dtype=torch.float32, device=Q.device) if want_cov else None
+    ws = _workspace(workspace_bytes(p, OP_WHITEN), Q.device)
+    _check(lib().dark_whiten(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(M), _ptr(cov), ws.data_ptr(), ws.numel(),
+                             _stream()), "dark_whiten")
+    return (M, cov) if want_cov else M
 
 
 def saved_bytes(p: DarkParams) -> int:

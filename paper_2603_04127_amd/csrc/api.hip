@@ -38,7 +38,7 @@ const char* kernel_name(int k) {
       "f32_gemm",     "f32_load",   "f32_rowstat",  "f32_headmax",  "f32_exp",      "f32_sum_slices",
       "f32_finish",   "f32_scan",   "f32_bwd_elem", "fused_prep",   "fused_kv_reduce", "fused_kv_merge",
       "fused_readout", "fused_key_norms", "fused_causal_state", "fused_causal_prefix", "fused_causal_scan", "fused_featurize",
-      "fused_bwd_fwd", "fused_bwd_suffix", "fused_bwd_rev", "fused_bwd_dm"};
+      "fused_bwd_fwd", "fused_bwd_suffix", "fused_bwd_rev", "fused_bwd_dm", "whiten_moments", "whiten_eig"};
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }
@@ -190,8 +190,14 @@ const char* dark_status_string(dark_status s) {
 size_t dark_workspace_bytes(const dark_params* p, int op, int causal) {
   Problem pb;
   if (check_params(p, &pb) != DARK_OK) return 0;
-  if (op < DARK_OP_FEATURIZE || op > DARK_OP_ATTN_BWD) return 0;
+  if (op < DARK_OP_FEATURIZE || op > DARK_OP_WHITEN) return 0;
   if (pb.p.B == 0 || pb.p.L == 0) return 0;
+  if (op == DARK_OP_WHITEN) {
+    if (!whiten_supported(pb)) return 0;
+    Arena ar(nullptr, 0);
+    (void)whiten(pb, ar, nullptr, nullptr, nullptr, nullptr);
+    return ar.off;
+  }
   return measure(pb, op, causal != 0 || op == DARK_OP_ATTN_CAUSAL_FWD);
 }
 
@@ -287,6 +293,22 @@ dark_status dark_attn_causal_fwd(const dark_params* p, const void* Q, const void
                                  const float* M, const float* W, void* out, void* ws, size_t ws_bytes,
                                  void* hip_stream) {
   return attn_common(p, DARK_OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, ws, ws_bytes, hip_stream);
+}
+
+dark_status dark_whiten(const dark_params* p, const void* Q, const void* K, float* M_out, float* cov_out, void* ws,
+                        size_t ws_bytes, void* hip_stream) {
+  Problem pb;
+  DARK_TRY(check_params(p, &pb));
+  if (pb.p.B == 0 || pb.p.L == 0) return DARK_EINVAL;  // no rows, no covariance
+  if (Q == nullptr || M_out == nullptr) return DARK_EINVAL;
+  if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(M_out, 16) || !aligned(cov_out, 16)) return DARK_EALIGN;
+  if (!whiten_supported(pb)) return DARK_EUNSUPPORTED;
+  Arena measure_ar(nullptr, 0);
+  (void)whiten(pb, measure_ar, nullptr, nullptr, nullptr, nullptr);
+  DARK_TRY(check_ws(ws, ws_bytes, measure_ar.off));
+  pb.st = static_cast<hipStream_t>(hip_stream);
+  Arena ar(ws, ws_bytes);
+  return whiten(pb, ar, Q, K, M_out, cov_out);
 }
 
 size_t dark_saved_bytes(const dark_params* p) {

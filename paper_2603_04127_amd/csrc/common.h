@@ -37,6 +37,8 @@ enum KernelId : int {
   KID_BWD_SUFFIX,      // fused backward: exclusive suffix sums of the slices' reverse-state pieces
   KID_BWD_REV,         // fused backward: reverse-order pass (dV, dK, key half of dA, norm-term matrix)
   KID_BWD_DM,          // fused backward: sums over slices and dM per head
+  KID_WHITEN_MOMENTS,  // whitening geometry: second moments of the rows of Q and K
+  KID_WHITEN_EIG,      // whitening geometry: eigen-decomposition, M = Lambda^-1/2
   KID_COUNT
 };
 
@@ -127,6 +129,9 @@ dark_status launch_dw(const Problem& pb, const float* T, int nb, const float* M,
 // Bytes of the hand-over buffer of the causal forward/backward pair on the MFMA path (0: no hand-over for
 // these parameters).  fused_causal.hip.
 size_t fused_saved_causal_bytes(const Problem& pb);
+// Whitening geometry (whiten.hip).  With arena.base == nullptr it only measures.
+bool whiten_supported(const Problem& pb);
+dark_status whiten(const Problem& pb, Arena& ar, const void* Q, const void* K, float* M, float* cov_out);
 // fused MFMA feature map (fused_feat.hip).
 bool fused_featurize_supported(const Problem& pb);
 dark_status fused_featurize(const Problem& pb, Arena& ar, const void* X, const float* M, const float* W,
