@@ -56,6 +56,8 @@ def algorithmic_work(cfg):
         # dark_whiten: the second moments read every row of Q and K once (the per-head eigen-decomposition is
         # a fixed cost that does not grow with the number of rows)
         "whiten_moments": ("hbm", 2 * th * d * s_in),
+        # dark_decode_step: the fp32 state of every (b,h) is read and written once
+        "decode_step": ("hbm", 2 * cfg.B * cfg.H * m * (dv + 1) * 4),
         # backward, forward-order pass (tiles of T = 32 tokens): both projections, numerator and denominator
         # again, the logit gradients of the queries (state part and tile triangle), dQ, and the updates of
         # S, Rn and T_Q; reverse-order pass: projections, dV, the logit gradients of the keys, dK (with the
@@ -151,10 +153,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=None, help="untimed warm-up steps (default: a quarter of --steps)")
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2, the headline)")
     ap.add_argument("--path", choices=["auto", "f32", "fused"], default="auto")
-    ap.add_argument("--op", choices=["attn", "featurize", "whiten"], default="attn",
+    ap.add_argument("--op", choices=["attn", "featurize", "whiten", "decode"], default="attn",
                     help="attn (default): the attention step the metric is quoted on; featurize: dark_featurize of "
                          "the configuration's Q (query contract) and K (key contract), a side measurement of that "
-                         "entry point (value = rows/s); whiten: dark_whiten of the configuration's Q and K (value = rows/s)")
+                         "entry point (value = rows/s); whiten: dark_whiten of the configuration's Q and K (value = rows/s); decode: "
+                         "dark_decode_step, one token per (b,h) of the configuration per step (value = tokens/s)")
     ap.add_argument("--copies", type=int, default=3, help="distinct input copies rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -187,6 +190,14 @@ def main():
                     # same distribution, different memory: rotate batch and sequence
                     c[n] = torch.roll(dev0[n], shifts=(k % max(cfg.B, 1), 17 * k), dims=(0, 2)).contiguous()
         c["out"] = torch.empty_like(c["V"])
+        if args.op == "decode":
+            # the recurrent state of every (b,h), filled by a short run of tokens; one more token per step
+            c["state"] = dk.decode_state(cfg.B, cfg.H, cfg.m, cfg.dv)
+            for t in range(4):
+                dk.dark_decode_step(c["Q"][:, :, t].contiguous(), c["K"][:, :, t].contiguous(),
+                                    c["V"][:, :, t].contiguous(), c["M"], c["W"], c["state"])
+            c["q1"], c["k1"], c["v1"] = (c[n][:, :, 5].contiguous() for n in ("Q", "K", "V"))
+            c["o1"] = torch.empty_like(c["v1"])
         if cfg.backward:
             f32 = dict(dtype=torch.float32, device="cuda")
             c["grads"] = {"dQ": torch.empty(c["Q"].shape, **f32), "dK": torch.empty(c["K"].shape, **f32),
@@ -201,6 +212,9 @@ def main():
             return
         if args.op == "whiten":
             dk.dark_whiten(c["Q"], c["K"])
+            return
+        if args.op == "decode":
+            dk.dark_decode_step(c["q1"], c["k1"], c["v1"], c["M"], c["W"], c["state"], out=c["o1"])
             return
         if cfg.causal and cfg.backward:
             # training step: the forward leaves its operand copies, key norms and prefix states to the backward
@@ -252,6 +266,9 @@ def main():
         th = cfg.B * cfg.H * cfg.L
         flops = 2 * th * 2 * cfg.d * cfg.d
         nbytes = per_kernel["whiten_moments"][1]
+    if args.op == "decode":
+        flops = cfg.B * cfg.H * (4 * cfg.d * cfg.r + 4 * cfg.r * cfg.m + 4 * cfg.m * (cfg.dv + 1))
+        nbytes = per_kernel["decode_step"][1]
 
     # Per-kernel device time: a second loop in which the library attaches start/stop events to every
     # launch (stamped with the kernel's own begin and end on the launch stream; the stream is drained
@@ -289,9 +306,10 @@ def main():
     line = {
         "metric": ("DARK attention fwd tokens/sec and TFLOP/s; % of MFMA/HBM roofline (1 GPU)" if args.op == "attn"
                    else "dark_featurize rows/sec (query rows + key rows); % of MFMA/HBM roofline (1 GPU)" if args.op == "featurize"
-                   else "dark_whiten rows/sec (query rows + key rows); % of HBM roofline (1 GPU)"),
-        "value": (tokens if args.op == "attn" else 2 * cfg.B * cfg.H * cfg.L) / (ms * 1e-3),
-        "unit": "tokens/s" if args.op == "attn" else "rows/s",
+                   else "dark_whiten rows/sec (query rows + key rows); % of HBM roofline (1 GPU)" if args.op == "whiten"
+                   else "dark_decode_step tokens/sec (one token per batch entry, all heads); % of HBM roofline (1 GPU)"),
+        "value": (tokens if args.op == "attn" else cfg.B if args.op == "decode" else 2 * cfg.B * cfg.H * cfg.L) / (ms * 1e-3),
+        "unit": "tokens/s" if args.op in ("attn", "decode") else "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",

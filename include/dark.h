@@ -262,6 +262,22 @@ dark_status dark_whiten(const dark_params* p, const void* Q, const void* K, floa
                         void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * One token of causal attention as a recurrence (the causal form of the paper's linear
+ * attention, Section 2, advanced by one position; serving).  Per (b, h), with the new query,
+ * key and value of that position (q, k: [B, H, d], v: [B, H, dv], in io_dtype):
+ *   S <- S + phi(k) v^T,   z <- z + phi(k),   out = phi(q)^T S / phi(q)^T z      (out: [B, H, dv], io_dtype)
+ * which is row t of dark_attn_causal_fwd over the tokens seen so far.  The state belongs to the
+ * caller: S [B, H, m, dv], z [B, H, m], c [B, H], all float32.  It is kept under one shift per
+ * (b, h): S = sum_l exp(logit(k_l) - c) v_l^T with c (natural log) the largest key logit so far; start
+ * with S = 0, z = 0, c = -infinity.  Keys more than ~87 nats below c vanish (fp32).  p->L is ignored;
+ * p->out_dtype is ignored.  No workspace.  DARK_EUNSUPPORTED when 2 d + 2 r + 2 m + dv exceeds ~12000.
+ * M may be NULL (identity, r == d).  fp32 arithmetic for every io_dtype.
+ */
+dark_status dark_decode_step(const dark_params* p, const void* q, const void* k, const void* v,
+                             const float* M, const float* W, float* S, float* z, float* c,
+                             void* out, void* hip_stream);
+
+/*
  * Per-kernel device timing for benchmarks.  While enabled (on != 0) every kernel
  * launch of the library carries a start and a stop event that the launch itself
  * stamps with the kernel's begin and end on the device, and the launch stream is

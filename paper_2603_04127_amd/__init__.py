@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
     L.dark_attn_bwd.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_attn_bwd_dw.restype = i32
     L.dark_attn_bwd_dw.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.dark_decode_step.restype = i32
+    L.dark_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dark_whiten.restype = i32
     L.dark_whiten.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     L.dark_saved_bytes.restype = sz
@@ -235,6 +237,27 @@ def static_scratch_bytes() -> int:
 def dark_attn_causal_fwd(Q, K, V, M, W, *, out=None, chunk=0, scale=0.0, path=PATH_AUTO, out_dtype=None, sched=None):
     """Causal random-feature attention (keys l <= i), out [B,H,L,dv]."""
     return _attn("dark_attn_causal_fwd", OP_ATTN_CAUSAL_FWD, Q, K, V, M, W, out, chunk, scale, path, out_dtype, sched)
+
+
+def decode_state(B, H, m, dv, device="cuda"):
+    """Empty recurrent state (S, z, c) of dark_decode_step."""
+    torch = _torch()
+    return (torch.zeros((B, H, m, dv), dtype=torch.float32, device=device),
+            torch.zeros((B, H, m), dtype=torch.float32, device=device),
+            torch.full((B, H), float("-inf"), dtype=torch.float32, device=device))
+
+
+def dark_decode_step(q, k, v, M, W, state, *, out=None, scale=0.0):
+    """One token: q, k [B,H,d], v [B,H,dv]; state = (S, z, c) is updated in place; returns out [B,H,dv]."""
+    torch = _torch()
+    B, H, d = q.shape
+    S, z, c = state
+    p = _params_from(q[:, :, None, :], v[:, :, None, :], M, W, scale=scale)
+    if out is None:
+        out = torch.empty(v.shape, dtype=q.dtype, device=q.device)
+    _check(lib().dark_decode_step(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(M), _ptr(W), _ptr(S), _ptr(z), _ptr(c),
+                                  _ptr(out), _stream()), "dark_decode_step")
+    return out
 
 
 def dark_whiten(Q, K=None, *, r=None, want_cov=False):

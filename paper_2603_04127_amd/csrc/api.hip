@@ -38,7 +38,7 @@ const char* kernel_name(int k) {
       "f32_gemm",     "f32_load",   "f32_rowstat",  "f32_headmax",  "f32_exp",      "f32_sum_slices",
       "f32_finish",   "f32_scan",   "f32_bwd_elem", "fused_prep",   "fused_kv_reduce", "fused_kv_merge",
       "fused_readout", "fused_key_norms", "fused_causal_state", "fused_causal_prefix", "fused_causal_scan", "fused_featurize",
-      "fused_bwd_fwd", "fused_bwd_suffix", "fused_bwd_rev", "fused_bwd_dm", "whiten_moments", "whiten_eig"};
+      "fused_bwd_fwd", "fused_bwd_suffix", "fused_bwd_rev", "fused_bwd_dm", "whiten_moments", "whiten_eig", "decode_step"};
   return (k >= 0 && k < KID_COUNT) ? names[k] : "?";
 }
 bool timing_on() { return g_timing; }
@@ -309,6 +309,20 @@ dark_status dark_whiten(const dark_params* p, const void* Q, const void* K, floa
   pb.st = static_cast<hipStream_t>(hip_stream);
   Arena ar(ws, ws_bytes);
   return whiten(pb, ar, Q, K, M_out, cov_out);
+}
+
+dark_status dark_decode_step(const dark_params* p, const void* q, const void* k, const void* v, const float* M,
+                             const float* W, float* S, float* z, float* c, void* out, void* hip_stream) {
+  Problem pb;
+  DARK_TRY(check_params(p, &pb));
+  if (pb.p.B == 0) return DARK_OK;
+  if (!q || !k || !v || !W || !S || !z || !c || !out) return DARK_EINVAL;
+  if (M == nullptr && pb.p.r != pb.p.d) return DARK_EINVAL;  // M == NULL: identity, needs r == d
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(M, 16) || !aligned(W, 16) || !aligned(S, 16) ||
+      !aligned(z, 16) || !aligned(c, 4) || !aligned(out, 16))
+    return DARK_EALIGN;
+  pb.st = static_cast<hipStream_t>(hip_stream);
+  return decode_step(pb, q, k, v, M, W, S, z, c, out);
 }
 
 size_t dark_saved_bytes(const dark_params* p) {

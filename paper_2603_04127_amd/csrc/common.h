@@ -39,6 +39,7 @@ enum KernelId : int {
   KID_BWD_DM,          // fused backward: sums over slices and dM per head
   KID_WHITEN_MOMENTS,  // whitening geometry: second moments of the rows of Q and K
   KID_WHITEN_EIG,      // whitening geometry: eigen-decomposition, M = Lambda^-1/2
+  KID_DECODE,          // one-token recurrence of causal attention
   KID_COUNT
 };
 
@@ -129,6 +130,9 @@ dark_status launch_dw(const Problem& pb, const float* T, int nb, const float* M,
 // Bytes of the hand-over buffer of the causal forward/backward pair on the MFMA path (0: no hand-over for
 // these parameters).  fused_causal.hip.
 size_t fused_saved_causal_bytes(const Problem& pb);
+// One-token causal recurrence (decode.hip).
+dark_status decode_step(const Problem& pb, const void* q, const void* k, const void* v, const float* M,
+                        const float* W, float* S, float* z, float* c, void* out);
 // Whitening geometry (whiten.hip).  With arena.base == nullptr it only measures.
 bool whiten_supported(const Problem& pb);
 dark_status whiten(const Problem& pb, Arena& ar, const void* Q, const void* K, float* M, float* cov_out);
