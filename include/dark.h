@@ -242,9 +242,9 @@ dark_status dark_attn_bwd_saved(const dark_params* p, const void* Q, const void*
                                 void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
- * Whitening geometry: an initial M from the statistics of the inputs (paper: Section 4.1,
- * "if the input covariance is Lambda then choosing M = Lambda^{-1/2} whitens the inputs";
- * Proposition C.1).  Per head h, over all B * L rows of Q and of K (pooled: the paper
+ * Whitening geometry: an initial M from the statistics of the inputs (paper: Section 4.1
+ * and Proposition C.1: with M the inverse square root of the input covariance Lambda, M q and
+ * M k have identity covariance).  Per head h, over all B * L rows of Q and of K (pooled: the paper
  * assumes Cov(q) = Cov(k), Section 3; K may be NULL, then Q alone):
  *   Lambda_h = centred sample covariance (divisor = number of rows),
  *   Lambda_h = U diag(lambda) U^T with lambda descending, each lambda raised to at least

@@ -77,6 +77,48 @@ def test_argument_errors_before_any_device_work():
     assert f(ctypes.byref(q), A, A, A, A, A, A, ws, big, None) == dk.DARK_EUNSUPPORTED
 
 
+def test_argument_errors_of_the_later_entry_points():
+    L = dk.lib()
+    p = _p()
+    A = 1 << 20
+    ws = 1 << 24
+    big = 1 << 30
+    P = ctypes.byref(p)
+    # whitening: needs rows, Q and M_out; K and cov_out are optional
+    assert dk.workspace_bytes(p, dk.OP_WHITEN) > 0
+    assert L.dark_whiten(ctypes.byref(_p(L=0)), A, A, A, A, ws, big, None) == dk.DARK_EINVAL
+    assert L.dark_whiten(P, None, A, A, A, ws, big, None) == dk.DARK_EINVAL
+    assert L.dark_whiten(P, A, A, None, A, ws, big, None) == dk.DARK_EINVAL
+    assert L.dark_whiten(P, A, A + 8, A, A, ws, big, None) == dk.DARK_EALIGN
+    assert L.dark_whiten(ctypes.byref(_p(d=256, r=256)), A, A, A, A, ws, big, None) == dk.DARK_EUNSUPPORTED
+    assert L.dark_whiten(ctypes.byref(_p(r=32)), A, A, A, A, ws, big, None) == dk.DARK_EUNSUPPORTED
+    assert L.dark_whiten(P, A, None, A, None, None, 0, None) == dk.DARK_EWORKSPACE
+    # decode step: every state pointer is required; M may be NULL only when r == d
+    f = L.dark_decode_step
+    assert f(ctypes.byref(_p(B=0)), A, A, A, A, A, A, A, A, A, None) == dk.DARK_OK
+    assert f(P, A, A, A, A, A, None, A, A, A, None) == dk.DARK_EINVAL
+    assert f(P, A, A, A, A, A, A, A, None, A, None) == dk.DARK_EINVAL
+    assert f(ctypes.byref(_p(r=8)), A, A, A, None, A, A, A, A, A, None) == dk.DARK_EINVAL
+    assert f(P, A, A, A, A, A, A + 4, A, A, A, None) == dk.DARK_EALIGN
+    # hand-over pair: parameters without a hand-over report 0 bytes and ignore the buffer
+    assert dk.saved_bytes(p) == 0
+    q = dk.make_params(B=1, H=2, L=1024, d=64, r=64, m=256, dv=64, io_dtype=dk.DARK_BF16)
+    n = dk.saved_bytes(q)
+    assert n > 0
+    Q = ctypes.byref(q)
+    g = L.dark_attn_causal_fwd_save
+    assert g(Q, A, A, A, A, A, A, None, 0, ws, big, None) == dk.DARK_EWORKSPACE
+    assert g(Q, A, A, A, A, A, A, ws, n - 1, ws, big, None) == dk.DARK_EWORKSPACE
+    assert g(Q, A, A, A, A, A, A, ws + 64, n, ws, big, None) == dk.DARK_EALIGN
+    h = L.dark_attn_bwd_saved
+    assert h(Q, A, A, A, A, A, A, None, 0, A, A, A, A, A, ws, big, None) == dk.DARK_EWORKSPACE
+    assert h(Q, A, A, A, A, A, None, ws, n, A, A, A, A, A, ws, big, None) == dk.DARK_EINVAL
+    # identity geometry (M == NULL) needs r == d on every entry point
+    assert L.dark_attn_fwd(ctypes.byref(_p(r=8)), A, A, A, None, A, A, ws, big, None) == dk.DARK_EINVAL
+    assert L.dark_attn_bwd_dw(ctypes.byref(_p(r=8)), 0, A, A, A, None, A, A, A, A, A, A, A, ws, big, None) \
+        == dk.DARK_EINVAL
+
+
 def test_timing_slots_named():
     L = dk.lib()
     n = L.dark_timing_slots()
