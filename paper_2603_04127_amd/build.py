@@ -9,10 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdark.so")
-SOURCES = ["api.hip", "generic.hip", "fused.hip", "fused_feat.hip", "fused_causal.hip", "fused_bwd.hip", "ceilings.hip", "whiten.hip", "decode.hip"]
+SOURCES = ["api.hip", "generic.hip", "fused.hip", "fused_feat.hip", "fused_causal.hip", "fused_scan.hip", "fused_bwd.hip", "ceilings.hip", "whiten.hip", "decode.hip"]
 # per-file extra flags: the fused kernels never produce NaNs from finite inputs and want v_max3_f32
 EXTRA = {"fused.hip": ["-fno-honor-nans"], "fused_feat.hip": ["-fno-honor-nans"],
-         "fused_causal.hip": ["-fno-honor-nans"], "fused_bwd.hip": ["-fno-honor-nans"], "whiten.hip": ["-fno-honor-nans"]}
+         "fused_causal.hip": ["-fno-honor-nans"], "fused_scan.hip": ["-fno-honor-nans"], "fused_bwd.hip": ["-fno-honor-nans"], "whiten.hip": ["-fno-honor-nans"]}
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -11,8 +11,8 @@
 //   k_key_norms               n'(k_l) = |M' k_l|^2 for every key (log2 domain)
 //   k_kv_prefix               exclusive prefix of the slice states, brought to one running scalar
 //                             shift c*_p = max of the shifts of slices 0..p
-//   k_causal_scan             per (b,h, slice): starts from the prefix state and walks the slice in
-//                             tiles of 32 tokens
+//   k_causal_scan (fused_scan.hip)   per (b,h, slice): starts from the prefix state and walks the
+//                             slice in tiles of 32 tokens
 // (k_kv_reduce serves d = 64; the wide head uses k_slice_state, which keeps its accumulators within
 // the register file.)
 // Everything is in the log2 domain with the fp16 operands A', M' of the bidirectional path.
@@ -408,365 +408,6 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   if (hf == 0) cpart[srow0 + 64 * fg + 32 * hv + l32] = c;
 }
 
-// ---------------------------------------------------------------------------
-// k_causal_scan
-// Workgroup = 8 waves over one slice of one (b,h), all value columns.  Wave (fg, role) =
-// (w % 4, w / 4): the pair (fg, 0), (fg, 1) shares the features [64 fg, 64 fg + 64) and sits on
-// the same SIMD, where the matrix work of one overlaps the vector work of the other.
-//   role 0 projects and exponentiates the tile's queries, role 1 its keys (tokens are MFMA columns,
-//   lane = token); each leaves its packed features in an LDS patch for the partner;
-//   both then form the masked intra-tile scores P^T[k][q] over the pair's features and, for their
-//   own half of the value columns (one or two blocks of 32):  N = phi_Q S_old + P V,  S += phi_K^T V.
-//   role 0 owns the denominator (phi_Q . z + row sums of P), the row shift mu and z (read before the
-//   tile's first barrier, updated after it by the same wave).
-// The A' rows of the pair stay in registers for the whole slice; S is 64 x dv/2 per wave.
-// The eight waves' partial numerators meet in LDS; 512 threads combine them with the factors
-// 2^(mu_fg - max mu), normalise and store 8-byte pieces of whole rows.  Three barriers per tile.
-// ---------------------------------------------------------------------------
-template <int D>
-struct CsSmem {
-  static constexpr int AS = D + 8;
-  static constexpr int CTW = D / 64;                         // 32-column blocks of V per wave (dv = d)
-  static constexpr size_t x_bytes = (size_t)kCT * AS * 2;
-  static constexpr size_t v_bytes = (size_t)kCT * D * 2;     // one tile of V, all columns
-  static constexpr int TBS = 64 * 2 + 8;
-  static constexpr size_t tb_bytes = (size_t)kCT * TBS;      // per wave: its packed features [tok][64]
-  static constexpr int NBS = 32 * CTW + 4;
-  static constexpr size_t nb_bytes = (size_t)kCT * NBS * 4;  // per wave: partial numerator [q][32 CTW]
-  static constexpr size_t dm_bytes = (size_t)4 * 2 * kCT * 4;  // per feature group: D, mu
-  static constexpr size_t zl_bytes = (size_t)4 * 64 * 4;       // per feature group: z
-  static constexpr size_t ns_bytes = (size_t)kCT * 4;
-  static constexpr size_t total = 2 * x_bytes + 2 * v_bytes + 8 * (tb_bytes + nb_bytes) + dm_bytes + zl_bytes + ns_bytes;
-};
-
-template <int D, bool OUT_BF16>
-__global__ __launch_bounds__(512, 1) void k_causal_scan(const unsigned short* __restrict__ Qg,
-                                                         const unsigned short* __restrict__ Kg,
-                                                         const unsigned short* __restrict__ Vg,
-                                                         const _Float16* __restrict__ Ah,
-                                                         const float* __restrict__ nrm,
-                                                         const float* __restrict__ Spre,
-                                                         const float* __restrict__ zpre,
-                                                         const float* __restrict__ cpre, void* __restrict__ outp, int H,
-                                                         int L, int P, int slice_len) {
-  using SM = CsSmem<D>;
-  constexpr int DVT = D, m = 256, NS = D / 16, CTW = SM::CTW;
-  constexpr int WCOLS = 32 * CTW;  // value columns per wave: role r owns columns [WCOLS r, WCOLS r + WCOLS)
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16* Xq = reinterpret_cast<_Float16*>(smem);
-  _Float16* Xk = reinterpret_cast<_Float16*>(smem + SM::x_bytes);
-  unsigned short* Vt2 = reinterpret_cast<unsigned short*>(smem + 2 * SM::x_bytes);
-  unsigned char* patch0 = smem + 2 * SM::x_bytes + 2 * SM::v_bytes;
-  float* nb0 = reinterpret_cast<float*>(patch0 + 8 * SM::tb_bytes);
-  float* dm0 = reinterpret_cast<float*>(patch0 + 8 * (SM::tb_bytes + SM::nb_bytes));
-  float* zl0 = dm0 + 4 * 2 * kCT;
-  float* ns = zl0 + 4 * 64;
-
-  const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
-  const int l32 = lane % 32, hf = lane / 32;
-  const int j16 = l32 % 16, g2 = l32 / 16;
-  const int fg = wv % 4, role = wv / 4;
-  const int p = blockIdx.x % P;
-  const int bh = blockIdx.x / P;
-  const int h = bh % H;
-  const int tok_begin = p * slice_len;
-  const int tok_end = min(L, tok_begin + slice_len);
-  const int ntile = (tok_end - tok_begin + kCT - 1) / kCT;
-  if (ntile <= 0) return;
-
-  unsigned char* my_patch = patch0 + wv * SM::tb_bytes;
-  const unsigned char* k_patch = patch0 + (4 + fg) * SM::tb_bytes;
-  float* nbw = nb0 + wv * (SM::nb_bytes / 4);
-  float* dmg = dm0 + fg * 2 * kCT;
-  float* zl = zl0 + fg * 64;
-
-  // --- resident operands: the pair's rows of A' (A operand of the projection: lane = feature) ---
-  half8 afr[2][NS];
-#pragma unroll
-  for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-      afr[fb][s] = *reinterpret_cast<const half8*>(Ah + ((size_t)h * m + 64 * fg + 32 * fb + l32) * D + 16 * s + 8 * hf);
-  const size_t srow0 = ((size_t)bh * P + p) * m;
-  const float cs = cpre[(size_t)bh * P + p];
-  f32x16 S[2][CTW];
-#pragma unroll
-  for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int feat = 64 * fg + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
-#pragma unroll
-      for (int ct = 0; ct < CTW; ++ct) S[fb][ct][v] = Spre[(srow0 + feat) * DVT + WCOLS * role + 32 * ct + l32];
-    }
-  if (role == 0) zl[lane] = zpre[srow0 + 64 * fg + lane];
-
-  // --- staging: V straight to LDS, Q and K through registers (bf16 -> fp16) --------------------
-  constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a Q (or K) tile: 512 or 256
-  u32x4 qreg = {0u, 0u, 0u, 0u}, kreg = {0u, 0u, 0u, 0u};
-  float nreg = 0.f;
-  const unsigned short* Qb = Qg + (size_t)bh * L * D;
-  const unsigned short* Kb = Kg + (size_t)bh * L * D;
-  const unsigned short* Vb = Vg + (size_t)bh * L * DVT;
-  auto load_tile = [&](int t, int tid) {
-    const int t0 = tok_begin + t * kCT;
-    {
-      // V straight to LDS: a wave moves a 1 KB run of whole rows (64 / CPR rows of CPR 16-byte chunks);
-      // the XOR swizzle of the chunks is applied on the source side
-      constexpr int CPR = DVT / 8, RPW = 64 / CPR;
-      if (tid / 64 < kCT / RPW) {
-        const int ln = tid % 64, r = RPW * (tid / 64) + ln / CPR, pos = ln % CPR;
-        const int tok = min(t0 + r, tok_end - 1), cc = pos ^ (r & 7);
-        dma16_to_lds(Vb + (size_t)tok * DVT + 8 * cc, Vt2 + (t % 2) * kCT * DVT + (tid / 64) * 512);
-      }
-    }
-    const int ci = tid % NCH, tok = min(t0 + ci / (D / 8), tok_end - 1), kc = ci % (D / 8);
-    if (NCH == 512) {
-      qreg = *reinterpret_cast<const u32x4*>(Qb + (size_t)tok * D + 8 * kc);
-      kreg = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
-    } else {  // threads 0..255 fetch Q, the others K
-      qreg = *reinterpret_cast<const u32x4*>((tid < NCH ? Qb : Kb) + (size_t)tok * D + 8 * kc);
-    }
-    nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
-  };
-  auto store_tile = [&](int t, int tid) {
-    const int ci = tid % NCH, tok = ci / (D / 8), kc = ci % (D / 8);
-    if (NCH == 512) {
-      *reinterpret_cast<u32x4*>(Xq + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(qreg);
-      *reinterpret_cast<u32x4*>(Xk + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg);
-    } else {
-      *reinterpret_cast<u32x4*>((tid < NCH ? Xq : Xk) + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(qreg);
-    }
-    const float nsv = tok_begin + t * kCT + tid % kCT < tok_end ? -(nreg + cs) : -1e30f;
-    if (tid < kCT) ns[tid] = nsv;
-    wait_vmcnt0();  // the V tile written by dma16_to_lds has landed
-  };
-
-  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-  load_tile(0, tid);
-  store_tile(0, tid);
-  __syncthreads();
-
-  for (int t = 0; t < ntile; ++t) {
-    int tid_o = threadIdx.x;
-    asm volatile("" : "+v"(tid_o));  // thread-derived addresses are recomputed per tile, not kept
-    const unsigned short* Vt = Vt2 + (t % 2) * kCT * DVT;
-    load_tile(min(t + 1, ntile - 1), tid_o);  // a whole tile ahead; unconditional (the last one twice)
-
-    // --- phase A: this wave's side of the feature map ---------------------------------------
-    const _Float16* X = role == 0 ? Xq : Xk;
-    const float init = role == 0 ? 0.f : ns[l32];
-    f32x16 U[2];
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) U[fb][v] = init;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const half8 b = *reinterpret_cast<const half8*>(X + l32 * SM::AS + 16 * s + 8 * hf);
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb) U[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[fb][s], b, U[fb], 0, 0, 0);
-    }
-    u32x4 pw[2][2];  // own packed features, [fb][hh]: k-slot s <-> accumulator register 8 hh + s
-    float mu = 0.f, den = 0.f;
-    if (role == 0) {
-      mu = -INFINITY;
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) mu = max3(mu, U[fb][v], U[fb][v + 1]);
-      mu = fmaxf(mu, __shfl_xor(mu, 32, 64));
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          // z of the features this lane's registers hold: rows 8 g + 4 hf + [0,4) of block fb (as it was
-          // before this tile: it is updated in phase B).  phi_Q . z uses the bf16-rounded features
-          // that enter N.
-          const f32x4 zq = *reinterpret_cast<const f32x4*>(zl + 32 * fb + 8 * g + 4 * hf);
-          const unsigned w0 = pack_bf16(fast_exp2(U[fb][4 * g] - mu), fast_exp2(U[fb][4 * g + 1] - mu));
-          const unsigned w1 = pack_bf16(fast_exp2(U[fb][4 * g + 2] - mu), fast_exp2(U[fb][4 * g + 3] - mu));
-          den = fmaf(__uint_as_float(w0 << 16), zq[0], den);
-          den = fmaf(__uint_as_float(w0 & 0xffff0000u), zq[1], den);
-          den = fmaf(__uint_as_float(w1 << 16), zq[2], den);
-          den = fmaf(__uint_as_float(w1 & 0xffff0000u), zq[3], den);
-          pw[fb][g / 2][2 * (g % 2)] = w0;
-          pw[fb][g / 2][2 * (g % 2) + 1] = w1;
-        }
-    } else {
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            pw[fb][hh][q] = pack_bf16(fast_exp2(U[fb][8 * hh + 2 * q]), fast_exp2(U[fb][8 * hh + 2 * q + 1]));
-    }
-    // own features, row-major [tok][feat], for the partner
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w = {pw[fb][g / 2][2 * (g % 2)], pw[fb][g / 2][2 * (g % 2) + 1]};
-        *reinterpret_cast<u32x2*>(my_patch + l32 * SM::TBS + (32 * fb + 8 * g + 4 * hf) * 2) = w;
-      }
-    __syncthreads();
-
-    // --- phase B ------------------------------------------------------------------------------
-    // A side's features as an operand fragment with the accumulator's permutation of the
-    // contraction index: k-slots 0..3 <-> features 16 hh + 4 hf + [0,4), slots 4..7 <-> those + 8.
-    // (A wave reads its own side back from its patch as well: that keeps the registers free.)
-    const unsigned char* q_patch = patch0 + fg * SM::tb_bytes;
-    auto read_frag = [&](const unsigned char* pt, int fb, int hh) {
-      const unsigned char* pr = pt + l32 * SM::TBS + (32 * fb + 16 * hh + 4 * hf) * 2;
-      const u32x2 lo = *reinterpret_cast<const u32x2*>(pr), hi = *reinterpret_cast<const u32x2*>(pr + 16);
-      return u32x4{lo[0], lo[1], hi[0], hi[1]};
-    };
-    // phi_K^T fragments (rows = the pair's features, contraction over tokens)
-    auto k_frag = [&](int fb, int hh) {
-      const unsigned short* tr = reinterpret_cast<const unsigned short*>(k_patch + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
-                                 32 * fb + 16 * g2 + 4 * (j16 % 4);
-      const u32x2 l2 = lds_read_tr16(tr), h2 = lds_read_tr16(tr + 8 * (SM::TBS / 2));
-      return u32x4{l2[0], l2[1], h2[0], h2[1]};
-    };
-    // intra-tile scores P^T[k][q] over the pair's features
-    f32x16 Pt;
-#pragma unroll
-    for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        u32x4 fq = read_frag(q_patch, fb, hh), fk = read_frag(k_patch, fb, hh);
-        Pt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&fk), *reinterpret_cast<bf16x8*>(&fq),
-                                                     (fb == 0 && hh == 0) ? zero16 : Pt, 0, 0, 0);
-      }
-    // masked scores (k <= q), packed; the denominator sums the same bf16-rounded kernel values that
-    // multiply V, so the intra-tile part of N / D is an exact convex combination of value rows
-    u32x4 pp[2];
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int v = 8 * hh + 2 * q;
-        const int krow = 8 * (v / 4) + 4 * hf + (v % 4);
-        const float x0 = krow <= l32 ? Pt[v] : 0.f, x1 = krow + 1 <= l32 ? Pt[v + 1] : 0.f;
-        const unsigned w = pack_bf16(x0, x1);
-        pp[hh][q] = w;
-        if (role == 0) den += __uint_as_float(w << 16) + __uint_as_float(w & 0xffff0000u);
-      }
-    // this wave's value columns, one block of 32 at a time
-#pragma unroll
-    for (int ct = 0; ct < CTW; ++ct) {
-      // V fragments: k-slot s of half hf is token 16 hh + 8 (s/4) + 4 hf + s%4
-      u32x4 bv[2];
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        const int tok = 16 * hh + 4 * hf + j16 / 4;
-        const int chunk = 4 * (CTW * role + ct) + 2 * g2 + (j16 % 4) / 2;
-        const unsigned short* vr = Vt + tok * DVT + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
-        const u32x2 lo = lds_read_tr16(vr), hi = lds_read_tr16(vr + 8 * DVT);
-        bv[hh] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-      }
-      // numerator: the state as it was before this tile, then the intra-tile term
-      f32x16 N;
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb)
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          u32x4 fq = read_frag(q_patch, fb, hh), sb;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) sb[q] = pack_bf16(S[fb][ct][8 * hh + 2 * q], S[fb][ct][8 * hh + 2 * q + 1]);
-          N = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&fq), *reinterpret_cast<bf16x8*>(&sb),
-                                                      (fb == 0 && hh == 0) ? zero16 : N, 0, 0, 0);
-        }
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-        N = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pp[hh]), *reinterpret_cast<bf16x8*>(&bv[hh]),
-                                                    N, 0, 0, 0);
-      // state update (after the read-out above): S += phi_K^T V; role 0 also sums phi_K over the tile
-      // (every column of that MFMA result is equal: one lane per half holds every sum of its rows)
-#pragma unroll
-      for (int fb = 0; fb < 2; ++fb) {
-        u32x4 ak0 = k_frag(fb, 0), ak1 = k_frag(fb, 1);
-        S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak0),
-                                                            *reinterpret_cast<bf16x8*>(&bv[0]), S[fb][ct], 0, 0, 0);
-        S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1),
-                                                            *reinterpret_cast<bf16x8*>(&bv[1]), S[fb][ct], 0, 0, 0);
-        if (role == 0 && ct == 0) {
-          u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
-          f32x16 dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak0),
-                                                              *reinterpret_cast<bf16x8*>(&o4), zero16, 0, 0, 0);
-          dz = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak1), *reinterpret_cast<bf16x8*>(&o4),
-                                                       dz, 0, 0, 0);
-          if (l32 == 0) {  // rows 8 g + 4 hf + [0,4) are four adjacent floats of z
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              f32x4* zp = reinterpret_cast<f32x4*>(zl + 32 * fb + 8 * g + 4 * hf);
-              f32x4 zv = *zp;
-#pragma unroll
-              for (int i = 0; i < 4; ++i) zv[i] += dz[4 * g + i];
-              *zp = zv;
-            }
-          }
-        }
-      }
-      // partial numerator of this block
-#pragma unroll
-      for (int v = 0; v < 16; ++v) nbw[(8 * (v / 4) + 4 * hf + (v % 4)) * SM::NBS + 32 * ct + l32] = N[v];
-    }
-    if (role == 0) {
-      den += __shfl_xor(den, 32, 64);
-      if (hf == 0) {
-        dmg[l32] = den;
-        dmg[kCT + l32] = mu;
-      }
-    }
-    __syncthreads();
-    // --- combine the four feature groups, normalise, store ------------------------------------
-    {
-      constexpr int CPT = DVT / 16;  // output columns per thread: 4 or 8
-      const int q = tid_o / 16, cg = tid_o % 16;  // row, group of CPT columns; groups 0..7 belong to role 0's waves
-      float muw[4], mx = -INFINITY;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        muw[g] = dm0[g * 2 * kCT + kCT + q];
-        mx = fmaxf(mx, muw[g]);
-      }
-      float dsum = 0.f, num[CPT];
-#pragma unroll
-      for (int e = 0; e < CPT; ++e) num[e] = 0.f;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float f = fast_exp2(muw[g] - mx);
-        dsum = fmaf(f, dm0[g * 2 * kCT + q], dsum);
-        const float* np = nb0 + (g + 4 * (cg / 8)) * (SM::nb_bytes / 4) + q * SM::NBS + CPT * (cg % 8);
-#pragma unroll
-        for (int e4 = 0; e4 < CPT / 4; ++e4) {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(np + 4 * e4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) num[4 * e4 + e] = fmaf(f, a[e], num[4 * e4 + e]);
-        }
-      }
-      const float inv = __builtin_amdgcn_rcpf(dsum);
-      const int tok = tok_begin + t * kCT + q;
-      if (tok < tok_end) {
-        const size_t o = ((size_t)bh * L + tok) * DVT + CPT * cg;
-#pragma unroll
-        for (int e4 = 0; e4 < CPT / 4; ++e4) {
-          if (OUT_BF16) {
-            u32x2 w = {pack_bf16(num[4 * e4] * inv, num[4 * e4 + 1] * inv), pack_bf16(num[4 * e4 + 2] * inv, num[4 * e4 + 3] * inv)};
-            *reinterpret_cast<u32x2*>(reinterpret_cast<unsigned short*>(outp) + o + 4 * e4) = w;
-          } else {
-            *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(outp) + o + 4 * e4) =
-                f32x4{num[4 * e4] * inv, num[4 * e4 + 1] * inv, num[4 * e4 + 2] * inv, num[4 * e4 + 3] * inv};
-          }
-        }
-      }
-    }
-    store_tile(min(t + 1, ntile - 1), tid_o);
-    __syncthreads();
-  }
-}
-
 // The same norms for M = I: nrm[row] = (scale log2(e) / 2) |k_row|^2, with no projection: D / 8 lanes per
 // key row, 16 bytes each, squares summed in fp32, the partial sums added across the row's lanes.
 template <int D>
@@ -838,14 +479,7 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
   }
   DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
               Spre, zpre, cpre, p.m, P);
-  const unsigned grid = BH * P;
-  const unsigned short *Qp = (const unsigned short*)Q, *Kp = (const unsigned short*)K, *Vp = (const unsigned short*)V;
-  const size_t lds = CsSmem<D>::total;
-  auto kern = p.out_dtype == DARK_BF16 ? k_causal_scan<D, true> : k_causal_scan<D, false>;
-  DARK_TRY(allow_lds(kern, lds));
-  DARK_LAUNCH(KID_CAUSAL_SCAN, pb.st, kern, dim3(grid), dim3(512), lds, Qp, Kp, Vp, Ah, nrm, Spre, zpre, cpre, out, p.H,
-              p.L, P, slice_len);
-  return DARK_OK;
+  return fused_launch_scan_ws(pb, Q, K, V, Ah, nrm, Spre, zpre, cpre, out, P, slice_len);
 }
 
 }  // namespace

@@ -167,6 +167,10 @@ dark_status fused_launch_prep(const Problem& pb, const float* M, const float* W,
 dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void* V, const _Float16* Ah,
                                    const _Float16* Mh, unsigned short* Spart, float* zpart, float* cpart, int P,
                                    int slice_len, float* nrm_out = nullptr);
+// Implemented in fused_scan.hip: the scan over the tiles of every slice, from the prefix states.
+dark_status fused_launch_scan_ws(const Problem& pb, const void* Q, const void* K, const void* V, const _Float16* Ah,
+                                 const float* nrm, const float* Spre, const float* zpre, const float* cpre, void* out,
+                                 int P, int slice_len);
 // Implemented in fused_causal.hip.
 bool fused_causal_supported(const Problem& pb);
 // Key norms nrm [BH][L], slice states ([BH][P][m][dv] bf16 with per-feature shifts) and their exclusive prefix
