@@ -198,12 +198,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
       if (t < ntile) {
         const int par = t % 2;
         const _Float16* X = sub == 0 ? Xq : Xk;
-        const float init = sub == 0 ? 0.f : ns[l32];
-        f32x16 U[4];
-#pragma unroll
-        for (int fq = 0; fq < 4; ++fq)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) U[fq][v] = init;
+        f32x16 U[4] = {zero16, zero16, zero16, zero16};
         {
           // the fragments are requested four k-steps ahead of the products that use them
           constexpr int PF = 4;
@@ -253,13 +248,14 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
             dmq[(par * 2 + half) * 2 * kCT + kCT + l32] = mu;
           }
         } else {
+          const float nsl = ns[l32];  // -(norm + shift) of this lane's key
 #pragma unroll
           for (int fq = 0; fq < 4; ++fq) {
             unsigned char* pt = patch(par, 1, 2 * half + fq / 2) + l32 * SM::TBS + (32 * (fq % 2) + 4 * hf) * 2;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-              const unsigned w0 = pack_bf16(fast_exp2(U[fq][4 * g]), fast_exp2(U[fq][4 * g + 1]));
-              const unsigned w1 = pack_bf16(fast_exp2(U[fq][4 * g + 2]), fast_exp2(U[fq][4 * g + 3]));
+              const unsigned w0 = pack_bf16(fast_exp2(U[fq][4 * g] + nsl), fast_exp2(U[fq][4 * g + 1] + nsl));
+              const unsigned w1 = pack_bf16(fast_exp2(U[fq][4 * g + 2] + nsl), fast_exp2(U[fq][4 * g + 3] + nsl));
               *reinterpret_cast<u32x2*>(pt + 16 * g) = u32x2{w0, w1};
             }
           }
@@ -347,7 +343,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
           const float x0 = krow <= l32 ? Pt[v] : 0.f, x1 = krow + 1 <= l32 ? Pt[v + 1] : 0.f;
           pp[hh][q] = pack_bf16(x0, x1);
         }
-      if (sub == 0) {
+      if (sub == 1) {  // (the wave that shares its SIMD with the key wave, the lighter of the two)
         // denominator of the half: phi_Q . z_old from the query wave plus the row sums of the masked scores
         // (lane = query; the two half-waves hold complementary keys)
         float rs = 0.f;
