@@ -85,9 +85,11 @@ typedef enum {
  *     running prefix (causal forward, backward).  Keys more than about 80 nats (2^115) below the shift they
  *     are stored under vanish; a row all of whose keys have vanished comes out non-finite (0/0).
  * fp32 kernels (DARK_PATH_F32; any shape and dtype): inputs of any finite magnitude; bidirectional attention
- * keeps a shift per feature and per row and has no range limit; the causal and backward passes keep one
- * shift per (b, h) and feature for the whole sequence and are specified for key logits that spread over
- * less than about 80 nats along a sequence.
+ * keeps a shift per feature and per row and has no range limit; the causal passes (forward and backward)
+ * keep the per-feature shifts per chunk, as running maxima along the sequence, and rescale the chunk states
+ * where they are added up: key logits may rise or fall along a sequence without limit, and what has to stay
+ * within about 80 nats is the spread of a feature's key logits inside one chunk (p->chunk positions, the
+ * keys after the query included).
  * None of these conditions is checked on the host: the entry points only enqueue work.
  */
 typedef enum {

@@ -563,8 +563,16 @@ __global__ void k_load_rows(const T* __restrict__ src, float* __restrict__ dst, 
     dst[row * ld + c] = c < cols ? load_as_f32(src, row * cols + c) : (ones ? 1.f : 0.f);
 }
 
+// Shift groups: the key-side stabilisers are per feature and per group of G consecutive positions of a
+// (b,h) (G = L: one group per (b,h), the bidirectional case; G = the chunk length in the causal passes).
+// Index of the group that holds `row` of a [B*H, L] row space.
+__device__ __forceinline__ long long shift_group(long long row, int L, int G) {
+  const long long bh = row / L;
+  return bh * ((L + G - 1) / G) + (row - bh * L) / G;
+}
+
 // One wave per row: n = 1/2 |x~|^2, logits = U - n (+ bias_j) in place, rowmax.
-// bias (optional) is a per-(b,h) vector of m per-feature shifts (the key-side stabilisers,
+// bias (optional): m per-feature shifts for every shift group (the key-side stabilisers,
 // which the query side adds back so that every product phi_Q,j * phi_K,j is unchanged).
 // exp_rows != 0: the row is left as exp(logit - rowmax) instead (the query features), the logits of up
 // to 512 features staying in registers in between, so the row is read and written once.
@@ -593,12 +601,12 @@ __device__ __forceinline__ void store_v(float* p, const float (&o)[V]) {
 template <int V>
 __global__ __launch_bounds__(256) void k_rowstat(float* __restrict__ U, const float* __restrict__ Xt,
                                                  float* __restrict__ rowmax, const float* __restrict__ bias,
-                                                 long long rows, int m, int r, int L, int exp_rows) {
+                                                 long long rows, int m, int r, int L, int exp_rows, int G) {
   constexpr int kKeep = 8 / (V == 4 ? 4 : 1);  // groups kept in registers: up to 512 features
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   int lane = threadIdx.x % kWave;
-  const float* bs = bias ? bias + (row / L) * m : nullptr;
+  const float* bs = bias ? bias + shift_group(row, L, G) * m : nullptr;
   const float* xt = Xt + row * r;
   float s = 0.f;
   for (int t = lane; t < r; t += kWave) s = fmaf(xt[t], xt[t], s);
@@ -673,24 +681,28 @@ __global__ __launch_bounds__(256) void k_headmax(const float* __restrict__ rowma
   if (threadIdx.x == 0) headmax[blockIdx.x] = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
 }
 
-// Per-feature maximum over the L rows of each (b,h): colmax[bh][j] = max_l logit[bh][l][j].
-// One block per (bh, 64-column group); threads = 64 columns x 16 row phases, eight loads in flight.
+// Per-feature maximum over the rows of each shift group: colmax[group][j] = max over the group's rows l of
+// logit[bh][l][j].  One block per (group, 64-column group); threads = 64 columns x 16 row phases, eight
+// loads in flight.
 constexpr int kColmaxPhases = 16;
 // rown (optional): a per-row term subtracted from every entry first (the norm term n_l).
 __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __restrict__ logit,
                                                                float* __restrict__ colmax, int L, int m,
-                                                               const float* __restrict__ rown) {
+                                                               const float* __restrict__ rown, int G) {
   __shared__ float sm[kColmaxPhases][64];
   const int groups = (m + 63) / 64;
-  const long long bh = blockIdx.x / groups;
+  const int ng = (L + G - 1) / G;
+  const long long sg = blockIdx.x / groups;  // shift group
+  const long long bh = sg / ng;
+  const int l0 = (int)(sg % ng) * G, l1 = min(L, l0 + G);
   const int j = (blockIdx.x % groups) * 64 + threadIdx.x % 64;
   const int ph = threadIdx.x / 64;
   float mx = -INFINITY;
   if (j < m) {
     const float* p = logit + bh * L * (long long)m + j;
     const float* rn = rown ? rown + bh * L : nullptr;
-    int l = ph;
-    for (; l + 7 * kColmaxPhases < L; l += 8 * kColmaxPhases) {
+    int l = l0 + ph;
+    for (; l + 7 * kColmaxPhases < l1; l += 8 * kColmaxPhases) {
       float v[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) v[u] = p[(long long)(l + u * kColmaxPhases) * m];
@@ -701,31 +713,51 @@ __global__ __launch_bounds__(64 * kColmaxPhases) void k_colmax(const float* __re
 #pragma unroll
       for (int u = 0; u < 8; ++u) mx = fmaxf(mx, v[u]);
     }
-    for (; l < L; l += kColmaxPhases) mx = fmaxf(mx, p[(long long)l * m] - (rn ? rn[l] : 0.f));
+    for (; l < l1; l += kColmaxPhases) mx = fmaxf(mx, p[(long long)l * m] - (rn ? rn[l] : 0.f));
   }
   sm[ph][threadIdx.x % 64] = mx;
   __syncthreads();
   if (ph == 0 && j < m) {
 #pragma unroll
     for (int u = 1; u < kColmaxPhases; ++u) mx = fmaxf(mx, sm[u][threadIdx.x]);
-    colmax[bh * m + j] = mx;
+    colmax[sg * m + j] = mx;
+  }
+}
+
+// Causal passes: the shift of a group becomes the maximum over the groups up to it (in place), so that a
+// key is never stored under a shift set by keys that come after its chunk, and the shifts only grow along
+// the sequence.  One thread per (b,h, feature); eight groups' values are loaded before the first is rewritten.
+__global__ __launch_bounds__(256) void k_runmax(float* __restrict__ colmax, long long BH, int ng, int m) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i >= BH * m) return;
+  float* p = colmax + (i / m) * ng * m + i % m;
+  float run = -INFINITY;
+  for (int g0 = 0; g0 < ng; g0 += 8) {
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = g0 + u < ng ? p[(long long)(g0 + u) * m] : -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      run = fmaxf(run, t[u]);
+      if (g0 + u < ng) p[(long long)(g0 + u) * m] = run;
+    }
   }
 }
 
 // Phi = exp(logit - c) * mult.  mode 0: c = cvec[row];  1: c = cvec[row / L] (per head);
-// 2: c = cvec[(row / L) * m + j] (per head and feature).
+// 2: c = cvec[group(row) * m + j] (per shift group of G positions and feature).
 // rown (optional): a per-row term added to c (the norm term n_l, when the logits do not hold it yet).
 // One wave per row, V features per lane and step (V = 4 needs m % 4 == 0 and 16-byte aligned rows).
 template <typename T, int V>
 __global__ __launch_bounds__(256) void k_exp(const float* __restrict__ logit, T* __restrict__ out,
                                              const float* __restrict__ cvec, long long rows, int m, int L, int mode,
-                                             float mult, const float* __restrict__ rown) {
+                                             float mult, const float* __restrict__ rown, int G) {
   long long row = blockIdx.x * 4LL + threadIdx.x / kWave;
   if (row >= rows) return;
   const int lane = threadIdx.x % kWave;
   const float rn = rown ? rown[row] : 0.f;
   const float crow = (mode == 0 ? cvec[row] : (mode == 1 ? cvec[row / L] : 0.f)) + rn;
-  const float* cj = mode == 2 ? cvec + (row / L) * m : nullptr;
+  const float* cj = mode == 2 ? cvec + shift_group(row, L, G) * m : nullptr;
   const float* src = logit + row * m;
   for (int j = lane; j < m / V; j += kWave) {
     float v[V], c[V];
@@ -784,28 +816,39 @@ __global__ void k_finish(const float* __restrict__ ND, T* __restrict__ out, long
 }
 
 // Exclusive scan over the chunk axis of st[bh][chunk][E] (forward, or reverse for the
-// backward pass), in place.
-__global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long long E, int reverse) {
+// backward pass), in place.  E = m * ld: row j of a chunk's state belongs to feature j and is expressed
+// under that chunk's shift cm[bh][chunk][j] (running maxima: non-decreasing along the sequence).  What has
+// been summed so far is brought to the shift of the chunk it is handed to before it is stored: forward, the
+// sum over earlier chunks times exp(cm[c - 1] - cm[c]); reverse, the sum over later chunks times
+// exp(cm[c] - cm[c + 1]) (there the states hold query features, which carry the shifts with the opposite
+// sign).  Both factors are at most one.  cm == nullptr: plain sums.
+__global__ void k_scan(float* __restrict__ st, long long BH, int nchunk, long long E, int reverse,
+                       const float* __restrict__ cm, int m, int ld) {
   long long total = BH * E;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
     long long bh = i / E, e = i % E;
     float* p = st + bh * nchunk * E + e;
+    const float* cj = cm ? cm + bh * nchunk * m + e / ld : nullptr;
     float run = 0.f;
+    float cprev = 0.f;  // shift of the chunk handled last
     // eight chunks' entries are loaded before the first is overwritten: the loads do not depend on the
     // running sum, but the compiler may not move them across the stores by itself
     constexpr int kBatch = 8;
     for (int c0 = 0; c0 < nchunk; c0 += kBatch) {
-      float t[kBatch];
+      float t[kBatch], cs[kBatch];
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int c = reverse ? nchunk - 1 - (c0 + u) : c0 + u;
         t[u] = c0 + u < nchunk ? p[c * E] : 0.f;
+        cs[u] = cj && c0 + u < nchunk ? cj[(long long)c * m] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int c = reverse ? nchunk - 1 - (c0 + u) : c0 + u;
         if (c0 + u < nchunk) {
+          if (cj && c0 + u > 0) run *= expf(reverse ? cs[u] - cprev : cprev - cs[u]);
+          cprev = cs[u];
           p[c * E] = run;
           run += t[u];
         }
@@ -1004,11 +1047,15 @@ dark_status make_As(const Problem& pb, const float* M, const float* W, float* As
 // Queries: c = row maximum (after adding `qbias`, if given).  Keys: c = maximum over the
 // (b,h) slice (STAB_KEY_HEAD, the dark_featurize contract) or per feature over the slice
 // (STAB_KEY_FEATURE, used inside attention where the query side adds the shifts back).
+// G: positions per shift group of the per-feature key shifts (0 = L: one group per (b,h)); `running`: the
+// shift of a group is the maximum over the groups up to it (the causal passes).
 dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, const float* As, StabMode mode,
-                     const float* qbias = nullptr, bool exp_rows = false) {
+                     const float* qbias = nullptr, bool exp_rows = false, int G = 0, bool running = false) {
   const dark_params& p = pb.p;
   const long long rows = pb.rows();
   const float alpha = std::sqrt(pb.scale);
+  if (G <= 0) G = p.L;
+  const int ng = (p.L + G - 1) / G;
   {
     Gemm g = gemm_base(fb.Xf, M, fb.Xt, p.L, p.r, p.d);
     g.sAm = p.d; g.sAk = 1; g.sBk = 1; g.sBn = p.d; g.sCm = p.r; g.sCn = 1;
@@ -1032,33 +1079,37 @@ dark_status features(const Problem& pb, const FeatBufs& fb, const float* M, cons
     // The logits stay U: the norm term (kept in fb.rowmax, which this mode does not otherwise use) is
     // applied where they are read, by the per-feature maximum here and by exp_inplace.
     DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rownorm, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Xt, fb.rowmax, rows, p.r);
-    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ((p.m + 63) / 64))), dim3(64 * kColmaxPhases), 0, fb.Phi,
-                fb.colmax, p.L, p.m, fb.rowmax);
+    DARK_LAUNCH(KID_HEADMAX, pb.st, k_colmax, dim3((unsigned)(pb.BH() * ng * ((p.m + 63) / 64))), dim3(64 * kColmaxPhases),
+                0, fb.Phi, fb.colmax, p.L, p.m, fb.rowmax, G);
+    if (running && ng > 1)
+      DARK_LAUNCH(KID_HEADMAX, pb.st, k_runmax, dim3((unsigned)((pb.BH() * p.m + 255) / 256)), dim3(256), 0, fb.colmax,
+                  pb.BH(), ng, p.m);
     return DARK_OK;
   }
   const float* bias = mode == STAB_QUERY_ROW ? qbias : nullptr;
   if (p.m % 4 == 0 && ((reinterpret_cast<uintptr_t>(fb.Phi) | reinterpret_cast<uintptr_t>(bias)) & 15) == 0)
     DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat<4>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
-                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
+                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0, G);
   else
     DARK_LAUNCH(KID_ROWSTAT, pb.st, k_rowstat<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, fb.Phi, fb.Xt,
-                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0);
+                fb.rowmax, bias, rows, p.m, p.r, p.L, exp_rows ? 1 : 0, G);
   if (mode == STAB_KEY_HEAD)
     DARK_LAUNCH(KID_HEADMAX, pb.st, k_headmax, dim3((unsigned)pb.BH()), dim3(256), 0, fb.rowmax, fb.headmax, p.L);
   return DARK_OK;
 }
 
-dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode) {
+dark_status exp_inplace(const Problem& pb, const FeatBufs& fb, StabMode mode, int G = 0) {
   const long long rows = pb.rows();
+  if (G <= 0) G = pb.p.L;
   const float* c = mode == STAB_QUERY_ROW ? fb.rowmax : (mode == STAB_KEY_HEAD ? fb.headmax : fb.colmax);
   const float* rown = mode == STAB_KEY_FEATURE ? fb.rowmax : nullptr;
   const unsigned grid = (unsigned)((rows + 3) / 4);
   if (pb.p.m % 4 == 0 && ((reinterpret_cast<uintptr_t>(fb.Phi) | reinterpret_cast<uintptr_t>(c)) & 15) == 0)
     DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 4>), dim3(grid), dim3(256), 0, fb.Phi, fb.Phi, c, rows, pb.p.m, pb.p.L,
-                (int)mode, 1.0f, rown);
+                (int)mode, 1.0f, rown, G);
   else
     DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 1>), dim3(grid), dim3(256), 0, fb.Phi, fb.Phi, c, rows, pb.p.m, pb.p.L,
-                (int)mode, 1.0f, rown);
+                (int)mode, 1.0f, rown, G);
   return DARK_OK;
 }
 
@@ -1153,17 +1204,17 @@ dark_status f32_featurize(const Problem& pb, Arena& ar, const void* X, const flo
     if (p.io_dtype == DARK_BF16) {
       if (vec)
         DARK_LAUNCH(KID_EXP, pb.st, (k_exp<__hip_bfloat16, 4>), dim3(grid), dim3(256), 0, fb.Phi, (__hip_bfloat16*)phi, cvec,
-                    rows, p.m, p.L, kmode, mult, (const float*)nullptr);
+                    rows, p.m, p.L, kmode, mult, (const float*)nullptr, p.L);
       else
         DARK_LAUNCH(KID_EXP, pb.st, (k_exp<__hip_bfloat16, 1>), dim3(grid), dim3(256), 0, fb.Phi, (__hip_bfloat16*)phi, cvec,
-                    rows, p.m, p.L, kmode, mult, (const float*)nullptr);
+                    rows, p.m, p.L, kmode, mult, (const float*)nullptr, p.L);
     } else {
       if (vec && (reinterpret_cast<uintptr_t>(phi) & 15) == 0)
         DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 4>), dim3(grid), dim3(256), 0, fb.Phi, (float*)phi, cvec, rows, p.m, p.L,
-                    kmode, mult, (const float*)nullptr);
+                    kmode, mult, (const float*)nullptr, p.L);
       else
         DARK_LAUNCH(KID_EXP, pb.st, (k_exp<float, 1>), dim3(grid), dim3(256), 0, fb.Phi, (float*)phi, cvec, rows, p.m, p.L,
-                    kmode, mult, (const float*)nullptr);
+                    kmode, mult, (const float*)nullptr, p.L);
     }
   }
   if (stab != nullptr) {
@@ -1209,11 +1260,11 @@ void plan_attn(const Problem& pb, Arena& ar, bool causal, bool keep_xt, AttnBufs
   b.q.rowmax = ar.take<float>((size_t)rows);
   b.k.rowmax = ar.take<float>((size_t)rows);
   b.q.headmax = b.k.headmax = nullptr;
-  b.q.colmax = b.k.colmax = ar.take<float>((size_t)pb.BH() * p.m);
+  b.nchunk = (p.L + pb.chunk - 1) / pb.chunk;
+  b.q.colmax = b.k.colmax = ar.take<float>((size_t)pb.BH() * (causal ? b.nchunk : 1) * p.m);
   b.Vx = ar.take<float>((size_t)rows * ldv);
   b.ND = ar.take<float>((size_t)rows * ldv);
   b.P = (p.L + slice_len(pb) - 1) / slice_len(pb);
-  b.nchunk = (p.L + pb.chunk - 1) / pb.chunk;
   if (causal) {
     b.part = nullptr;
     b.SZ = ar.take<float>((size_t)pb.BH() * b.nchunk * p.m * ldv);
@@ -1343,9 +1394,13 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
   // Keys first: phi_K,lj = exp(logit_lj - c_j), c_j the per-feature maximum over the head.  The
   // queries add c_j back (phi_Q,ij = exp(logit_ij + c_j - rowmax_i)), so every product
   // phi_Q,ij phi_K,lj is the unshifted one times a per-row factor that cancels in N / D.
-  DARK_TRY(features(pb, b.k, M, b.As, STAB_KEY_FEATURE));
-  DARK_TRY(exp_inplace(pb, b.k, STAB_KEY_FEATURE));
-  DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax, true));  // leaves the query features
+  // Causal: c_j is kept per chunk, the maximum over the chunks up to it, so that no key is stored under a
+  // shift set by later keys (a query sees nothing of them); the states of earlier chunks are brought to
+  // the chunk's shifts where they are added up (k_scan), by factors exp(c_earlier - c_later) <= 1.
+  const int G = causal ? pb.chunk : 0;
+  DARK_TRY(features(pb, b.k, M, b.As, STAB_KEY_FEATURE, nullptr, false, G, causal));
+  DARK_TRY(exp_inplace(pb, b.k, STAB_KEY_FEATURE, G));
+  DARK_TRY(features(pb, b.q, M, b.As, STAB_QUERY_ROW, b.k.colmax, true, G));  // leaves the query features
   const long long st_elems = (long long)p.m * ldv;
   if (!causal) {
     // [S|z] = Phi_K^T [V|1]: per-slice partial states, then a fixed-order sum (Section 2: K'^T V first).
@@ -1359,7 +1414,7 @@ dark_status forward_core(const Problem& pb, AttnBufs& b, bool causal, const void
     const int C = pb.chunk;
     DARK_TRY(piece_states(pb, b.k.Phi, p.m, b.Vx, dv1, ldv, b.SZ, ldv, C, b.nchunk, 0.f));
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, b.SZ, pb.BH(), b.nchunk,
-                st_elems, 0);
+                st_elems, 0, (const float*)b.k.colmax, p.m, ldv);
     // inter-chunk: Phi_Q,c [S|z]_{<c};  intra-chunk: tril(Phi_Q,c Phi_K,c^T) [V_c|1]
     DARK_TRY(chunk_tiles(pb, b.q.Phi, p.m, b.k.Phi, p.m, p.m, b.Pm));
     DARK_TRY(run_chunk_pair(pb,
@@ -1451,7 +1506,7 @@ dark_status f32_attn_bwd(const Problem& pb, Arena& ar, bool causal, const void* 
   } else {
     DARK_TRY(piece_states(pb, b.q.Phi, p.m, dND, dv1, ldv, R, ldv, C, b.nchunk, 0.f));
     DARK_LAUNCH(KID_SCAN, pb.st, k_scan, dim3(grid_for(pb.BH() * st_elems)), dim3(256), 0, R, pb.BH(), b.nchunk,
-                st_elems, 1);
+                st_elems, 1, (const float*)b.k.colmax, p.m, ldv);
     DARK_TRY(chunk_tiles(pb, dND, ldv, b.Vx, ldv, dv1, Em));  // E_il = dN_i . v_l + dD_i, l <= i
     // b.Pm = tril(Phi_Q Phi_K^T) is left over from forward_core.
     Gemm gq = make_rows_times_state(pb, dND, dv1, ldv, b.SZ, ldv, true, true, st_elems, dPq, p.m, p.m, C, b.nchunk, 1.f,

@@ -317,8 +317,8 @@ def test_large_logits_are_stabilised():
     out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"])
     torch.cuda.synchronize()
     U.assert_close(_np(out), U.oracle_attn(inp, False), 2e-3, "large logits")
-    # Causal prefixes share one shift per feature, so the spread of one feature's key logits
-    # along the sequence has to fit the fp32 exponent range; a milder case covers that path.
+    # Causal: the keys of a chunk share one shift per feature, so the spread of one feature's key
+    # logits inside a chunk has to fit the fp32 exponent range; a milder case covers that path.
     inp = U.random_problem(7, 1, 1, 200, 16, 16, 32, 8, amp=12.0)
     inp["W"] = inp["W"] * 3.0
     lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
@@ -565,8 +565,8 @@ def test_logit_spread_beyond_the_supported_range(causal):
     block) are specified for.  The MFMA paths then return non-finite rows (0/0) where every key a row depends
     on has vanished below the shift, and since all features share that shift, whatever survives dominates
     what vanished: the finite rows are still the oracle's.  The bidirectional fp32 kernels have no such
-    limit.  (The fp32 causal kernels keep one shift per feature for the whole sequence and are specified for
-    the same ~80 nats; beyond it they are not checked.)"""
+    limit.  (The fp32 causal kernels keep their shifts per chunk and are specified for a spread of ~80 nats
+    inside a chunk, which this input exceeds many times over; they are not checked here.)"""
     inp = U.random_problem(33, 1, 2, 400, 64, 64, 256, 64, bf16=True, amp=1.0)
     for n in ("Q", "K"):
         inp[n] *= np.float32(15.0)
@@ -605,6 +605,65 @@ def test_causal_key_logits_growing_along_the_sequence(path):
     torch.cuda.synchronize()
     e = U.assert_close(got, U.oracle_attn(inp, True), U.TOL["bf16"], f"rising key logits, {path}")
     print(f"causal, key logits rising ~60 nats along the sequence ({path}): {U.fmt(e)}")
+
+
+def _drifting_keys(K, r0, seed, elen):
+    """Keys = a fixed direction of length elen times a factor that falls from r0 to 1 along the sequence, plus
+    0.3 of the given keys: every feature's key logits rise smoothly along the sequence (through the norm term)
+    while neighbouring keys stay within a few nats of each other."""
+    B, H, L, d = K.shape
+    e = np.random.default_rng(seed).standard_normal((1, H, 1, d))
+    e = elen * e / np.linalg.norm(e, axis=-1, keepdims=True)
+    ramp = np.linspace(r0, 1.0, L)[None, None, :, None]
+    return (ramp * e + 0.3 * K).astype(np.float32)
+
+
+def _first_keys_below_global_shift(inp):
+    """Smallest distance, over the features, between a feature's largest key logit of the whole sequence and
+    its largest over the first ten keys (head 0)."""
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
+    return float((lg.max(axis=0) - lg[:10].max(axis=0)).min())
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_causal_key_logits_rising_far_along_the_sequence(path):
+    """Every feature's key logits rise by 100 to 200 nats from the first token to the last: under one shift
+    per feature for the whole sequence all features of the first keys would underflow fp32 (e^-88) and the
+    first rows would be 0/0.  The causal kernels keep their shifts per chunk (fp32 kernels: running maxima
+    per feature, the chunk states rescaled where they are added up) or per slice (MFMA kernels: a running
+    scalar), so only the spread inside a chunk or slice counts (here about 30 nats)."""
+    L = 2000
+    inp = U.random_problem(36, 1, 2, L, 64, 64, 256, 64, bf16=True, amp=1.0)
+    inp["K"] = _drifting_keys(inp["K"], 8.0, 36, 6.0)
+    _reround(inp, "K")
+    gap = _first_keys_below_global_shift(inp)
+    assert gap > 90.0
+    dev = U.to_device(inp, True)
+    got = _np(dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=path))
+    torch.cuda.synchronize()
+    assert np.isfinite(got).all()
+    e = U.assert_close(got, U.oracle_attn(inp, True), U.TOL["bf16"], f"key logits rising far, {path}")
+    print(f"causal, first keys {gap:.0f} nats below every feature's largest key logit ({path}): {U.fmt(e)}")
+
+
+def test_causal_backward_with_key_logits_rising_far_along_the_sequence():
+    """Gradients of the fp32 causal kernels on the same kind of input: the suffix sums of the backward are
+    rescaled between chunks like the prefix sums of the forward."""
+    L = 600
+    inp = U.random_problem(37, 1, 1, L, 16, 16, 64, 16, amp=1.0)
+    inp["K"] = _drifting_keys(inp["K"], 8.0, 37, 4.0)
+    assert _first_keys_below_global_shift(inp) > 88.0
+    rng = np.random.default_rng(5)
+    G = rng.standard_normal(inp["V"].shape).astype(np.float32)
+    dev = U.to_device(inp, False)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], torch.from_numpy(G).cuda(), True, chunk=64)
+    torch.cuda.synchronize()
+    want = O.attn_bwd_brute(inp["Q"][0, 0], inp["K"][0, 0], inp["V"][0, 0], inp["M"][0], inp["W"][0], G[0, 0], True)
+    for name, w in zip(("dQ", "dK", "dV", "dM"), want):
+        got = _np(g[name])
+        got = got[0, 0] if name != "dM" else got[0]
+        assert np.isfinite(got).all(), name
+        U.assert_close_grad(got, w, 2e-4, f"rising key logits, {name}")
 
 
 def test_fused_matches_f32_path_and_is_deterministic():
