@@ -81,9 +81,10 @@ typedef enum {
  *   - The projection operands are rounded to fp16, so a logit w.x~ carries an error of about 2^-11 |w.x~|:
  *     the tolerance quoted for the bf16 path holds for |w.x~| up to a few hundred.
  *   - Stabilisers: one shift per (b, h) and block of 64 features (bidirectional; the readout adds a running
- *     shift per row when a row's logits leave the fp32 exponent range), one scalar shift per (b, h) along the
- *     running prefix (causal forward, backward).  Keys more than about 80 nats (2^115) below the shift they
- *     are stored under vanish; a row all of whose keys have vanished comes out non-finite (0/0).
+ *     shift per row when a row's logits leave the fp32 exponent range), one scalar shift per slice of a
+ *     sequence, the running maximum along it (causal forward and backward: key logits may rise or fall along
+ *     a sequence without limit).  Keys more than about 80 nats (2^115) below the shift they are stored under
+ *     vanish; a row all of whose keys have vanished comes out non-finite (0/0).
  * fp32 kernels (DARK_PATH_F32; any shape and dtype): inputs of any finite magnitude; bidirectional attention
  * keeps a shift per feature and per row and has no range limit; the causal passes (forward and backward)
  * keep the per-feature shifts per chunk, as running maxima along the sequence, and rescale the chunk states

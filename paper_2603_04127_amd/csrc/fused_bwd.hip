@@ -26,9 +26,11 @@
 //   k_bwd_rev     per (b,h, slice), tiles in reverse order: dV, dK, the key half of T, Rm
 //   k_bwd_sum, k_bwd_dm   sums over slices, then dM per head (sum over the batch in fixed order)
 // Everything is in the log2 domain with the fp16 operands A' = alpha log2e W M and M' of the forward path.
-// One scalar key shift per (b,h) (the largest of the slice shifts) is used throughout, so that states of
-// different slices add without rescaling: the spread of the key logits along one sequence has to fit the
-// fp32 exponent range (about 2^100 between the smallest useful and the largest feature).
+// Key shifts: one scalar per slice, the forward path's running shift c*_p (the largest shift of slices 0..p),
+// under which the slice's prefix state is stored and its keys are featurised in both tile kernels; the
+// suffix sums bring the later slices' contributions down to it.  So the key logits may rise or fall along a
+// sequence without limit; what has to fit the fp32 exponent range (about 2^100 between the smallest useful
+// and the largest feature) is their spread inside one slice.
 #include <cmath>
 
 #include "fused_common.h"
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   const us* Kb = Kg + (size_t)bh * L * kD;
   const us* Vb = Vg + (size_t)bh * L * kD;
   const us* Gb = Gg + (size_t)bh * L * kD;
-  const float c_ref = cpre[(size_t)bh * P + P - 1];
+  const float c_ref = cpre[(size_t)bh * P + p];  // the running shift of this slice: its prefix state is expressed in it
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   load_a(smem, Ah, h, tid);
@@ -229,17 +231,16 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
   f32x16 S[2], Rn[2], Tq[2];
   float rd_acc = 0.f;
   {
-    const float f = fast_exp2(cpre[(size_t)bh * P + p] - c_ref);  // the prefix is expressed in the running shift of slice p
     const size_t sb = ((size_t)bh * P + p) * kF;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int ft = 32 * wv + 8 * (v / 4) + 4 * hf + (v % 4);
-        S[db][v] = f * Spre[(sb + ft) * kD + 32 * db + l32];
+        S[db][v] = Spre[(sb + ft) * kD + 32 * db + l32];
       }
     if (tid < kF) {
-      const float z0 = f * zpre[sb + tid];
+      const float z0 = zpre[sb + tid];
       zs[tid] = z0;
       zb[tid] = (us)(pack_bf16(z0, 0.f) & 0xffffu);
     }
@@ -459,11 +460,14 @@ __global__ __launch_bounds__(512, 1) void k_bwd_fwd(const us* __restrict__ Qg, c
 }
 
 // ---------------------------------------------------------------------------
-// k_bwd_suffix: Rsuf_p = sum_{p' > p} dR_p' (p' descending: fixed order), in place of nothing: separate
-// output.  One thread per state entry; the Rd vector rides at the end.
+// k_bwd_suffix: Rsuf_p = sum_{p' > p} 2^(c*_p - c*_p') dR_p' (p' descending: fixed order), separate output.
+// The contribution of slice p' was formed with denominators in the scale of its own running shift c*_p', and
+// meets key features of slice p, which are in the scale of c*_p <= c*_p': the factor (at most one) brings it
+// there.  One thread per four state entries; the Rd vector rides at the end.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_bwd_suffix(const float* __restrict__ dRn, const float* __restrict__ dRd,
-                                                    float* __restrict__ Rn, float* __restrict__ Rd, int P, long long BH) {
+                                                    const float* __restrict__ cpre, float* __restrict__ Rn,
+                                                    float* __restrict__ Rd, int P, long long BH) {
   // four consecutive entries per thread; per (b,h) the kF x kD entries of Rn, then the kF of Rd
   const long long per4 = ((long long)kF * kD + kF) / 4;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -473,15 +477,23 @@ __global__ __launch_bounds__(256) void k_bwd_suffix(const float* __restrict__ dR
   const float* src = isn ? dRn + (size_t)bh * P * kF * kD + e : dRd + (size_t)bh * P * kF + (e - (long long)kF * kD);
   float* dst = isn ? Rn + (size_t)bh * P * kF * kD + e : Rd + (size_t)bh * P * kF + (e - (long long)kF * kD);
   const size_t pitch = isn ? (size_t)kF * kD : (size_t)kF;
+  const float* cb = cpre + (size_t)bh * P;
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  float c_later = 0.f;  // shift of the slice handled last
   for (int p0 = P - 1; p0 >= 0; p0 -= 8) {   // eight slices' loads in flight, then the (ordered) running sums
     f32x4 v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (p0 - u >= 0) v[u] = *reinterpret_cast<const f32x4*>(src + (size_t)(p0 - u) * pitch);
+    float c[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
       if (p0 - u >= 0) {
+        v[u] = *reinterpret_cast<const f32x4*>(src + (size_t)(p0 - u) * pitch);
+        c[u] = cb[p0 - u];
+      }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (p0 - u >= 0) {
+        if (p0 - u < P - 1) run *= fast_exp2(c[u] - c_later);
+        c_later = c[u];
         *reinterpret_cast<f32x4*>(dst + (size_t)(p0 - u) * pitch) = run;
         run += v[u];
       }
@@ -532,7 +544,7 @@ __global__ __launch_bounds__(512, 1) void k_bwd_rev(const us* __restrict__ Qg, c
   const us* Kb = Kg + (size_t)bh * L * kD;
   const us* Vb = Vg + (size_t)bh * L * kD;
   const us* Gb = Gg + (size_t)bh * L * kD;
-  const float c_ref = cpre[(size_t)bh * P + P - 1];
+  const float c_ref = cpre[(size_t)bh * P + p];  // keys of this slice are featurised under its own running shift
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   load_a(smem, Ah, h, tid);
@@ -890,7 +902,7 @@ dark_status fused_attn_bwd(const Problem& pb, Arena& ar, const void* Q, const vo
               nrm, Spre, zpre, cpre, dQ, lam, gdv, dRn, dRd, TQ, p.H, p.L, P, sl, inv_log2e);
   {
     const long long n = BH * ((long long)kF * kD + kF) / 4;
-    DARK_LAUNCH(KID_BWD_SUFFIX, pb.st, k_bwd_suffix, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, dRn, dRd, Rsn, Rsd, P,
+    DARK_LAUNCH(KID_BWD_SUFFIX, pb.st, k_bwd_suffix, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, dRn, dRd, cpre, Rsn, Rsd, P,
                 BH);
   }
   DARK_TRY(allow_lds(k_bwd_rev, BwdSmem::total));

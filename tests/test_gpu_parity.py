@@ -386,6 +386,26 @@ def test_fused_backward(shape):
         print(f"fused backward {shape} {k}: {U.fmt_grad(e)}")
 
 
+def test_fused_backward_with_key_logits_rising_far_along_the_sequence():
+    """MFMA backward on keys whose logits rise 100 to 200 nats along the sequence (see
+    test_causal_key_logits_rising_far_along_the_sequence): the tile kernels work under the running shift of
+    their own slice and the suffix sums are rescaled between slices, so the gradients of the first rows, whose
+    keys lie ~100 nats below the last slice's shift, are finite and the oracle's."""
+    L = 1500
+    inp = U.random_problem(38, 1, 1, L, 64, 64, 256, 64, bf16=True, backward=True, amp=1.0)
+    inp["K"] = _drifting_keys(inp["K"], 8.0, 38, 6.0)
+    _reround(inp, "K")
+    assert _first_keys_below_global_shift(inp) > 90.0
+    dev = U.to_device(inp, True)
+    g = dk.dark_attn_bwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], dev["dOut"], True, path=dk.PATH_FUSED)
+    torch.cuda.synchronize()
+    want = dict(zip(("dQ", "dK", "dV", "dM"), U.oracle_bwd(inp, True)))
+    for k in ("dQ", "dK", "dV", "dM"):
+        assert np.isfinite(_np(g[k])).all(), k
+        e = U.assert_close_grad(_np(g[k]), want[k], U.TOL["bf16"], f"fused backward, rising key logits, {k}")
+        print(f"fused backward, rising key logits, {k}: {U.fmt_grad(e)}")
+
+
 def test_fused_backward_is_deterministic_and_matches_f32_path():
     inp = U.random_problem(32, 2, 2, 700, 64, 64, 256, 64, bf16=True, backward=True)
     dev = U.to_device(inp, True)
