@@ -741,7 +741,7 @@ FUSED_CAUSAL_SHAPES = [
     (1, 1, 7, 64, 64, 256, 64),        # shorter than a tile
     (1, 1, 1, 64, 64, 256, 64),        # a single position: out == v
     (1, 1, 2100, 64, 64, 256, 64),     # many slices for one head: long prefix chain
-    (1, 2, 333, 128, 128, 256, 128),   # wide head: two workgroups per slice, one per half of the value columns
+    (1, 2, 333, 128, 128, 256, 128),   # wide head: the state waves own two blocks of value columns each
     (2, 2, 900, 128, 128, 256, 128),
 ]
 
@@ -758,6 +758,20 @@ def test_fused_causal_forward(shape, out_f32):
     assert out.dtype == (torch.float32 if out_f32 else torch.bfloat16)
     e = U.assert_close(_np(out), U.oracle_attn(inp, True), U.TOL["bf16"], f"fused causal {shape}")
     print(f"fused causal {shape} out_f32={out_f32}: {U.fmt(e)}")
+
+
+@pytest.mark.parametrize("L,d,wgs", [(1000, 64, 2), (4096 + 37, 64, 2), (777, 128, 2), (33, 128, 1), (65, 64, 1)])
+def test_fused_causal_long_slices(L, d, wgs):
+    """Few workgroups in the causal pass, so that one slice runs over many tiles: the scan's feature waves run a
+    tile ahead of its state waves through double-buffered patches many times over, with a ragged last tile
+    (and, for the shortest cases, a last tile of one token right after the first)."""
+    inp = U.random_problem(25, 1, 2, L, d, d, 256, d, bf16=True, amp=2.0)
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_causal_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED,
+                                  sched={"cs_wgs": wgs})
+    torch.cuda.synchronize()
+    e = U.assert_close(_np(out), U.oracle_attn(inp, True), U.TOL["bf16"], f"fused causal long slices L={L} d={d}")
+    print(f"fused causal long slices L={L} d={d} wgs={wgs}: {U.fmt(e)}")
 
 
 def test_fused_causal_first_row_and_last_row():
