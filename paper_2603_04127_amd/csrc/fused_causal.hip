@@ -211,8 +211,13 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restr
 // half of the value columns.  z comes from an MFMA against ones in the hv = 0 waves.
 // Shifts: one per wave (32 features), set from the first tile, raised only when a logit exceeds
 // it by more than kRaise; a raise is published with the features so that both waves rescale the
-// rows concerned.  K tiles are double-buffered, V tiles triple-buffered (they are still being
-// read after the barrier), one barrier per tile.
+// rows concerned.
+// NORMS: the key norms n'(k_l) = |M' k_l|^2 are formed here as well (and written out for the scan), one
+// tile ahead of their use: every wave projects the next tile onto its 16 rows of M' (16x16x32 MFMAs, the
+// rows resident in registers) and leaves 32 partial sums of squares; after the tile's barrier every lane
+// adds the eight partial sums of its token in a fixed order.  Otherwise the norms are read from nrm.
+// K tiles are stored two tiles ahead (three buffers: the tile being featurised, the one whose norms are
+// being formed, the one being written), V tiles behind the barrier (three buffers), one barrier per tile.
 // ---------------------------------------------------------------------------
 template <int D>
 struct SsSmem {
@@ -224,30 +229,35 @@ struct SsSmem {
   static constexpr size_t tb_bytes = (size_t)kCT * TBS;  // per feature group
   static constexpr size_t ns_bytes = (size_t)kCT * 4;
   static constexpr size_t dl_bytes = (size_t)8 * 4;
-  static constexpr size_t total = a_bytes + 2 * x_bytes + 3 * v_bytes + 2 * 4 * tb_bytes + 2 * ns_bytes + 2 * dl_bytes;
+  static constexpr size_t np_bytes = (size_t)kCT * 8 * 4;  // partial norms of a tile: [tok][wave]
+  static constexpr size_t total =
+      a_bytes + 3 * x_bytes + 3 * v_bytes + 2 * 4 * tb_bytes + 3 * ns_bytes + 2 * dl_bytes + 2 * np_bytes;
 };
 
-template <int D>
+template <int D, bool NORMS>
 __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __restrict__ Kg,
                                                         const unsigned short* __restrict__ Vg,
                                                         const _Float16* __restrict__ Ah,
-                                                        const float* __restrict__ nrm,
+                                                        const _Float16* __restrict__ Mh, float* __restrict__ nrm,
                                                         unsigned short* __restrict__ Spart,
                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
                                                         int L, int P, int slice_len) {
   using SM = SsSmem<D>;
   constexpr int DVT = D, DVW = D / 2, NCT = DVW / 32, m = 256;
+  static_assert(!NORMS || D == 128, "the norm stage gives every wave 16 rows of M': r = d = 128");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16* Asl = reinterpret_cast<_Float16*>(smem);
   unsigned char* xb = smem + SM::a_bytes;
-  unsigned char* vb = xb + 2 * SM::x_bytes;
+  unsigned char* vb = xb + 3 * SM::x_bytes;
   unsigned char* tbb = vb + 3 * SM::v_bytes;
   float* nsb = reinterpret_cast<float*>(tbb + 2 * 4 * SM::tb_bytes);
-  float* dlb = nsb + 2 * kCT;
+  float* dlb = nsb + 3 * kCT;
+  float* npb = dlb + 2 * 8;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   const int l32 = lane % 32, hf = lane / 32;
   const int j16 = l32 % 16, g2 = l32 / 16;
+  const int l16 = lane % 16, g16 = lane / 16;
   const int fg = wv % 4, hv = wv / 4;
   const int bh = blockIdx.x / P, p = blockIdx.x % P;
   const int h = bh % H;
@@ -261,6 +271,13 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
     *reinterpret_cast<u32x4*>(Asl + row * SM::AS + 8 * kc) =
         *reinterpret_cast<const u32x4*>(Ah + ((size_t)h * m + row) * D + 8 * kc);
   }
+  // norm stage: rows 16 wv + [0,16) of M' as the A operand of 16x16x32 MFMAs (lane = row l16, k = 32 s + 8 g16 + [0,8))
+  half8 mf[NORMS ? D / 32 : 1];
+  if (NORMS) {
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s)
+      mf[s] = *reinterpret_cast<const half8*>(Mh + ((size_t)h * D + 16 * wv + l16) * D + 32 * s + 8 * g16);
+  }
 
   constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a K (or V) tile
   const bool stager = tid < NCH;
@@ -268,27 +285,65 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   float nreg = 0.f;
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DVT;
-  auto load_tile = [&](int t) {
+  auto load_k = [&](int t) {
     const int t0 = tok_begin + t * kCT;
     if (stager) {
       const int tok = min(t0 + tid / (D / 8), tok_end - 1), kc = tid % (D / 8);
       kreg = *reinterpret_cast<const u32x4*>(Kb + (size_t)tok * D + 8 * kc);
-      vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * kc);
     }
     // no arithmetic on the loaded value here: it would make the wave wait for everything above
-    nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
+    if (!NORMS) nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
   };
-  auto store_tile = [&](int t) {
-    _Float16* xs = reinterpret_cast<_Float16*>(xb + (t % 2) * SM::x_bytes);
-    unsigned short* vt = reinterpret_cast<unsigned short*>(vb + (t % 3) * SM::v_bytes);
+  auto load_v = [&](int t) {
+    const int t0 = tok_begin + t * kCT;
+    if (stager) {
+      const int tok = min(t0 + tid / (D / 8), tok_end - 1), kc = tid % (D / 8);
+      vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * kc);
+    }
+  };
+  auto store_k = [&](int t) {
+    _Float16* xs = reinterpret_cast<_Float16*>(xb + (t % 3) * SM::x_bytes);
     if (stager) {
       const int tok = tid / (D / 8), kc = tid % (D / 8);
       *reinterpret_cast<u32x4*>(xs + tok * SM::AS + 8 * kc) = bf16x8_to_f16x8(kreg);
+    }
+    if (!NORMS) {
+      // keys past the end of the slice: features exactly zero
+      const float nsv = tok_begin + t * kCT + tid % kCT < tok_end ? -nreg : -1e30f;
+      if (tid < kCT) nsb[(t % 3) * kCT + tid] = nsv;
+    }
+  };
+  auto store_v = [&](int t) {
+    unsigned short* vt = reinterpret_cast<unsigned short*>(vb + (t % 3) * SM::v_bytes);
+    if (stager) {
+      const int tok = tid / (D / 8), kc = tid % (D / 8);
       *reinterpret_cast<u32x4*>(vt + tok * DVT + 8 * (kc ^ (tok & 7))) = vreg;
     }
-    // keys past the end of the slice: features exactly zero
-    const float nsv = tok_begin + t * kCT + tid % kCT < tok_end ? -nreg : -1e30f;
-    if (tid < kCT) nsb[(t % 2) * kCT + tid] = nsv;
+  };
+  // this wave's partial norms of tile t (its 16 rows of M'), from the tile in LDS
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  auto partial_norms = [&](int t) {
+    const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 3) * SM::x_bytes);
+    float* np = npb + (t % 2) * kCT * 8;
+    half8 xf[2][NORMS ? D / 32 : 1];
+#pragma unroll
+    for (int tb2 = 0; tb2 < 2; ++tb2)
+#pragma unroll
+      for (int s = 0; s < (NORMS ? D / 32 : 1); ++s)
+        xf[tb2][s] = *reinterpret_cast<const half8*>(xs + (16 * tb2 + l16) * SM::AS + 32 * s + 8 * g16);
+#pragma unroll
+    for (int tb2 = 0; tb2 < 2; ++tb2) {
+      f32x4 acc = zero4;  // x~[row 16 wv + 4 g16 + i][token 16 tb2 + l16]
+#pragma unroll
+      for (int s = 0; s < (NORMS ? D / 32 : 1); ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(mf[s], xf[tb2][s], acc, 0, 0, 0);
+      float sq = acc[0] * acc[0];
+      sq = fmaf(acc[1], acc[1], sq);
+      sq = fmaf(acc[2], acc[2], sq);
+      sq = fmaf(acc[3], acc[3], sq);
+      sq += __shfl_xor(sq, 16, 64);
+      sq += __shfl_xor(sq, 32, 64);
+      if (g16 == 0) np[(16 * tb2 + l16) * 8 + wv] = sq;
+    }
   };
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -301,19 +356,41 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   }
   float c = 0.f;  // this wave's shift (log2 domain), wave-uniform
 
-  load_tile(0);
-  store_tile(0);
-  if (ntile > 1) load_tile(1);
+  // prologue: K tiles 0 and 1 in LDS, K tile 2 and V tile 1 on their way, V tile 0 in LDS, norms of tile 0
+  load_k(0);
+  load_v(0);
+  store_k(0);
+  store_v(0);
+  if (ntile > 1) {
+    load_k(1);
+    store_k(1);
+    load_v(1);
+  }
+  if (ntile > 2) load_k(2);
   __syncthreads();
+  if (NORMS) {
+    partial_norms(0);
+    __syncthreads();
+  }
 
   for (int t = 0; t < ntile; ++t) {
-    if (t + 1 < ntile) store_tile(t + 1);
-    if (t + 2 < ntile) load_tile(t + 2);
-    const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 2) * SM::x_bytes);
+    if (t + 2 < ntile) store_k(t + 2);
+    if (t + 3 < ntile) load_k(t + 3);
+    const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 3) * SM::x_bytes);
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vb + (t % 3) * SM::v_bytes);
     unsigned char* tb = tbb + ((t % 2) * 4 + fg) * SM::tb_bytes;
     // --- this wave's 32 features of the tile ----------------------------------------------
-    const float nk = nsb[(t % 2) * kCT + l32] - c;
+    float nk;
+    if (NORMS) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(npb + (t % 2) * kCT * 8 + l32 * 8);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(npb + (t % 2) * kCT * 8 + l32 * 8 + 4);
+      const float n = ((a[0] + a[1]) + (a[2] + a[3])) + ((b[0] + b[1]) + (b[2] + b[3]));
+      // keys past the end of the slice: features exactly zero
+      nk = (tok_begin + t * kCT + l32 < tok_end ? -n : -1e30f) - c;
+      if (wv == 0 && hf == 0 && tok_begin + t * kCT + l32 < tok_end) nrm[(size_t)bh * L + tok_begin + t * kCT + l32] = n;
+    } else {
+      nk = nsb[(t % 3) * kCT + l32] - c;
+    }
     f32x16 U;
 #pragma unroll
     for (int v = 0; v < 16; ++v) U[v] = nk;
@@ -342,7 +419,11 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
                  pack_bf16(fast_exp2(U[4 * g + 2]), fast_exp2(U[4 * g + 3]))};
       *reinterpret_cast<u32x2*>(tb + l32 * SM::TBS + (32 * hv + 8 * g + 4 * hf) * 2) = w;
     }
+    if (NORMS && t + 1 < ntile) partial_norms(t + 1);
     __syncthreads();
+    // the V tile two ahead goes where the tile before this one was (read before the barrier above)
+    if (t + 1 < ntile) store_v(t + 1);
+    if (t + 2 < ntile) load_v(t + 2);
     // --- a raise by either wave of the pair rescales the rows of its 32 features (rare) ------
     if (t > 0) {
       const float d0 = dlb[(t % 2) * 8 + fg], d1 = dlb[(t % 2) * 8 + 4 + fg];
@@ -457,11 +538,15 @@ template <int D>
 dark_status launch_slice_state(const Problem& pb, const void* K, const void* V, const _Float16* Ah, const _Float16* Mh,
                                float* nrm, unsigned short* Spart, float* zpart, float* cpart, int P, int slice_len) {
   const dark_params& p = pb.p;
-  DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
-  auto kern = k_slice_state<D>;
+  // d = 128 with a geometry: the state kernel forms the norms on its way (one pass over K less); identity
+  // geometry: the norms need no projection and come from their own small kernel
+  constexpr bool can_fold = D == 128;
+  const bool fold = can_fold && !pb.m_identity;
+  if (!fold) DARK_TRY((launch_key_norms<D>(pb, K, Mh, nrm)));
+  auto kern = fold ? k_slice_state<D, can_fold> : k_slice_state<D, false>;
   DARK_TRY(allow_lds(kern, SsSmem<D>::total));
   DARK_LAUNCH(KID_CAUSAL_STATE, pb.st, kern, dim3((unsigned)(pb.BH() * P)), dim3(512), SsSmem<D>::total,
-              (const unsigned short*)K, (const unsigned short*)V, Ah, nrm, Spart, zpart, cpart, p.H, p.L, P, slice_len);
+              (const unsigned short*)K, (const unsigned short*)V, Ah, Mh, nrm, Spart, zpart, cpart, p.H, p.L, P, slice_len);
   return DARK_OK;
 }
 
