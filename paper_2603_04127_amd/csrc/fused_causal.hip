@@ -204,20 +204,19 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restr
 
 // ---------------------------------------------------------------------------
 // k_slice_state: [S|z] = phi_K^T [V|1] over one slice of one (b,h), all dv columns.
-// Workgroup = 8 waves: wave (fg, hv) = (w % 4, w / 4) projects the 32 features 64 fg + 32 hv + [0,32)
-// of each 32-token tile (tokens as MFMA columns), exponentiates, and leaves the packed features in
-// an LDS patch shared with its partner (fg, 1 - hv); after the tile's barrier both waves read the
-// patch with transposing loads and add phi_K^T V for all 64 features of the group to their own
-// half of the value columns.  z comes from an MFMA against ones in the hv = 0 waves.
+// Workgroup = 8 waves: wave w owns the 32 features 32 w + [0,32) (w = 2 fg + hv below): it projects them for
+// each 32-token tile (tokens as MFMA columns), exponentiates, leaves the packed features in LDS, reads them
+// back with transposing loads (its own writes: no barrier) and adds phi_K^T V for all value columns and
+// phi_K^T 1 to its accumulators.  Nothing passes between waves but the tiles themselves, so the one barrier
+// of a step is the one that publishes the next tiles, and the waves are free to drift apart inside a step.
 // Shifts: one per wave (32 features), set from the first tile, raised only when a logit exceeds
-// it by more than kRaise; a raise is published with the features so that both waves rescale the
-// rows concerned.
+// it by more than kRaise; a raise rescales the wave's accumulators.
 // NORMS: the key norms n'(k_l) = |M' k_l|^2 are formed here as well (and written out for the scan), one
 // tile ahead of their use: every wave projects the next tile onto its 16 rows of M' (16x16x32 MFMAs, the
 // rows resident in registers) and leaves 32 partial sums of squares; after the tile's barrier every lane
 // adds the eight partial sums of its token in a fixed order.  Otherwise the norms are read from nrm.
 // K tiles are stored two tiles ahead (three buffers: the tile being featurised, the one whose norms are
-// being formed, the one being written), V tiles behind the barrier (three buffers), one barrier per tile.
+// being formed, the one being written), V tiles one ahead, at the end of a step.
 // ---------------------------------------------------------------------------
 template <int D>
 struct SsSmem {
@@ -243,7 +242,7 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
                                                         float* __restrict__ zpart, float* __restrict__ cpart, int H,
                                                         int L, int P, int slice_len) {
   using SM = SsSmem<D>;
-  constexpr int DVT = D, DVW = D / 2, NCT = DVW / 32, m = 256;
+  constexpr int DVT = D, NCT = D / 32, m = 256;
   static_assert(!NORMS || D == 128, "the norm stage gives every wave 16 rows of M': r = d = 128");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   _Float16* Asl = reinterpret_cast<_Float16*>(smem);
@@ -347,16 +346,12 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   };
 
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 S[2][NCT], zacc[2];
+  f32x16 S[NCT], zacc = zero16;  // rows: this wave's 32 features; zacc: every column alike
 #pragma unroll
-  for (int fb = 0; fb < 2; ++fb) {
-    zacc[fb] = zero16;
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) S[fb][ct] = zero16;
-  }
+  for (int ct = 0; ct < NCT; ++ct) S[ct] = zero16;
   float c = 0.f;  // this wave's shift (log2 domain), wave-uniform
 
-  // prologue: K tiles 0 and 1 in LDS, K tile 2 and V tile 1 on their way, V tile 0 in LDS, norms of tile 0
+  // prologue: K tiles 0 and 1 and V tile 0 in LDS, K tile 2 and V tile 1 on their way, norms of tile 0
   load_k(0);
   load_v(0);
   store_k(0);
@@ -374,8 +369,6 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   }
 
   for (int t = 0; t < ntile; ++t) {
-    if (t + 2 < ntile) store_k(t + 2);
-    if (t + 3 < ntile) load_k(t + 3);
     const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 3) * SM::x_bytes);
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vb + (t % 3) * SM::v_bytes);
     unsigned char* tb = tbb + ((t % 2) * 4 + fg) * SM::tb_bytes;
@@ -403,16 +396,22 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
     float mx = -INFINITY;
 #pragma unroll
     for (int v = 0; v < 16; v += 2) mx = max3(mx, U[v], U[v + 1]);
-    float delta = 0.f;
     if (t == 0 || __any(mx > kRaise)) {  // wave-uniform; after the first tile this is rare
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      delta = mx;
-      c += delta;
+      c += mx;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) U[v] -= delta;
+      for (int v = 0; v < 16; ++v) U[v] -= mx;
+      if (t > 0) {  // what has been summed under the old shift comes down to the new one
+        const float f = fast_exp2(-mx);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          zacc[v] *= f;
+#pragma unroll
+          for (int ct = 0; ct < NCT; ++ct) S[ct][v] *= f;
+        }
+      }
     }
-    if (lane == 0) dlb[(t % 2) * 8 + wv] = delta;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       u32x2 w = {pack_bf16(fast_exp2(U[4 * g]), fast_exp2(U[4 * g + 1])),
@@ -420,72 +419,52 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       *reinterpret_cast<u32x2*>(tb + l32 * SM::TBS + (32 * hv + 8 * g + 4 * hf) * 2) = w;
     }
     if (NORMS && t + 1 < ntile) partial_norms(t + 1);
-    __syncthreads();
-    // the V tile two ahead goes where the tile before this one was (read before the barrier above)
-    if (t + 1 < ntile) store_v(t + 1);
-    if (t + 2 < ntile) load_v(t + 2);
-    // --- a raise by either wave of the pair rescales the rows of its 32 features (rare) ------
-    if (t > 0) {
-      const float d0 = dlb[(t % 2) * 8 + fg], d1 = dlb[(t % 2) * 8 + 4 + fg];
-      if (d0 != 0.f || d1 != 0.f) {
-        const float f0 = fast_exp2(-d0), f1 = fast_exp2(-d1);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          zacc[0][v] *= f0;
-          zacc[1][v] *= f1;
-#pragma unroll
-          for (int ct = 0; ct < NCT; ++ct) {
-            S[0][ct][v] *= f0;
-            S[1][ct][v] *= f1;
-          }
-        }
-      }
-    }
-    // --- S += phi_K^T V, z += phi_K^T 1: k-slot s of half hf is token 16 hh + 8 (s/4) + 4 hf + s%4 ---
+    // --- S += phi_K^T V, z += phi_K^T 1 for this wave's features (its own half of the patch, read back
+    // transposed: LDS operations of one wave complete in order); k-slot s of half hf is token
+    // 16 hh + 8 (s/4) + 4 hf + s%4 ---
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       u32x4 bv[NCT];
 #pragma unroll
       for (int ct = 0; ct < NCT; ++ct) {
         const int tok = 16 * hh + 4 * hf + j16 / 4;
-        const int chunk = (DVW * hv) / 8 + 4 * ct + 2 * g2 + (j16 % 4) / 2;
+        const int chunk = 4 * ct + 2 * g2 + (j16 % 4) / 2;
         const unsigned short* vr = vt + tok * DVT + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
         u32x2 lo = lds_read_tr16(vr);
         u32x2 hi = lds_read_tr16(vr + 8 * DVT);
         bv[ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};
       }
+      const unsigned short* tr = reinterpret_cast<const unsigned short*>(tb + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
+                                 32 * hv + 16 * g2 + 4 * (j16 % 4);
+      u32x2 lo = lds_read_tr16(tr);
+      u32x2 hi = lds_read_tr16(tr + 8 * (SM::TBS / 2));
+      u32x4 ak = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
-      for (int fb = 0; fb < 2; ++fb) {
-        const unsigned short* tr = reinterpret_cast<const unsigned short*>(tb + (16 * hh + 4 * hf + j16 / 4) * SM::TBS) +
-                                   32 * fb + 16 * g2 + 4 * (j16 % 4);
-        u32x2 lo = lds_read_tr16(tr);
-        u32x2 hi = lds_read_tr16(tr + 8 * (SM::TBS / 2));
-        u32x4 ak = {lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-        for (int ct = 0; ct < NCT; ++ct)
-          S[fb][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
-                                                              *reinterpret_cast<bf16x8*>(&bv[ct]), S[fb][ct], 0, 0, 0);
-        if (hv == 0) {
-          u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
-          zacc[fb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak),
-                                                             *reinterpret_cast<bf16x8*>(&o4), zacc[fb], 0, 0, 0);
-        }
-      }
+      for (int ct = 0; ct < NCT; ++ct)
+        S[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak), *reinterpret_cast<bf16x8*>(&bv[ct]),
+                                                        S[ct], 0, 0, 0);
+      u32x4 o4 = {kOnesBf16x2, kOnesBf16x2, kOnesBf16x2, kOnesBf16x2};
+      zacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&ak), *reinterpret_cast<bf16x8*>(&o4), zacc,
+                                                     0, 0, 0);
     }
+    // --- the tiles to come: K two tiles ahead, V one; then the step's only barrier ------------------
+    if (t + 2 < ntile) store_k(t + 2);
+    if (t + 1 < ntile) store_v(t + 1);
+    if (t + 3 < ntile) load_k(t + 3);
+    if (t + 2 < ntile) load_v(t + 2);
+    __syncthreads();
   }
 
   // --- the slice's state ---------------------------------------------------------------------
   const size_t srow0 = ((size_t)bh * P + p) * m;
 #pragma unroll
-  for (int fb = 0; fb < 2; ++fb)
+  for (int v = 0; v < 16; ++v) {
+    const int feat = 64 * fg + 32 * hv + 8 * (v / 4) + 4 * hf + (v % 4);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int feat = 64 * fg + 32 * fb + 8 * (v / 4) + 4 * hf + (v % 4);
-#pragma unroll
-      for (int ct = 0; ct < NCT; ++ct)
-        Spart[(srow0 + feat) * DVT + DVW * hv + 32 * ct + l32] = (unsigned short)(pack_bf16(S[fb][ct][v], 0.f) & 0xffffu);
-      if (hv == 0 && l32 == 0) zpart[srow0 + feat] = zacc[fb][v];
-    }
+    for (int ct = 0; ct < NCT; ++ct)
+      Spart[(srow0 + feat) * DVT + 32 * ct + l32] = (unsigned short)(pack_bf16(S[ct][v], 0.f) & 0xffffu);
+    if (l32 == 0) zpart[srow0 + feat] = zacc[v];
+  }
   if (hf == 0) cpart[srow0 + 64 * fg + 32 * hv + l32] = c;
 }
 
