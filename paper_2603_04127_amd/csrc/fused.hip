@@ -133,6 +133,12 @@ struct KvSmem {
   static constexpr size_t total = x_bytes + v_bytes + m_bytes;
 };
 constexpr float kF16Max = 65504.f;
+// The key pass looks at a feature's running sum z after every block instead of at the block's logits before the
+// exponentials: below 2^64 (a single feature value above it, or 2^20 positions at 2^44, would cross it) the state
+// is far from the end of the fp32 range even after the products with V; beyond it the feature's shift is raised
+// by the block's largest logit, at least by 2^32.
+constexpr float kZBig = 1.8446744073709552e19f;  // 2^64
+constexpr float kZDown = 32.0f;
 
 // TP: the partial state is written feature-contiguous ([bh][p][dv][m], the layout of the merged S^T) for
 // k_kv_merge_t; otherwise [bh][p][m][dv], which the causal prefix kernel reads.
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
                                                     const _Float16* __restrict__ Ah, const _Float16* __restrict__ Mh,
                                                     unsigned short* __restrict__ Spart, float* __restrict__ zpart,
                                                     float* __restrict__ cpart, float* __restrict__ nrm_out, int H,
-                                                    int L, int m, int P, int slice_len, int n_work) {
+                                                    int L, int m, int P, int slice_len, int n_work, int n_first) {
   using SM = KvSmem;
   constexpr int D = 64, DV = 64, R = 64;
   constexpr int XROW = SM::XS * 2;  // bytes per staged key row
@@ -402,7 +408,15 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       if (slot == 31) load_k(kreg, t + 4);
     }
   };
+  // Two workgroups share a CU, and the instruction arbiter serves the older wave first: the workgroup that
+  // arrived second (the grid is dealt out in order, n_first workgroups fill the first slot of every CU) would
+  // run at 60 % of the first one's pace and then finish alone, on a half-empty CU.  It takes the higher
+  // priority for the first 70 % of its tiles, after which the two end together.
+  const bool second = (int)blockIdx.x >= n_first;
+  const int prio_tiles = (7 * ntile + 5) / 10;
+  if (second) __builtin_amdgcn_s_setprio(1);
   for (int t = 0; t < ntile; ++t) {
+    if (second && t == prio_tiles) __builtin_amdgcn_s_setprio(0);
     // the buffer indices are rotated at the end of the body and kept in scalar registers;
     // bp: buffer of V(t-1); the very first block adds zero features times V(0)
     const int bp = (t == 0) ? 0 : v2;
@@ -415,33 +429,34 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       u32x4 bvb[2];
       fetch_bv(bvb, vprev, 1);
       __builtin_amdgcn_sched_barrier(0);
-      // B(k), first part: largest shifted logit of the block; the first half of C(k-1) runs meanwhile
-      float mall = U[cur][0];
-#pragma unroll
-      for (int v = 1; v < 9; v += 2) mall = max3(mall, U[cur][v], U[cur][v + 1]);
-      __builtin_amdgcn_sched_barrier(0);
+      // First half of C(k-1).  The shifted logits of the block are not examined before the exponentials:
+      // a feature's shift is set from its first block (below) and found too low afterwards, from the sum z.
       S[pft][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[nxt][0]),
                                                           *reinterpret_cast<bf16x8*>(&bva[0]), S[pft][0], 0, 0, 0);
-#pragma unroll
-      for (int v = 9; v < 15; v += 2) mall = max3(mall, U[cur][v], U[cur][v + 1]);
-      mall = fmaxf(mall, U[cur][15]);
-      __builtin_amdgcn_sched_barrier(0);
       S[pft][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&pk[nxt][0]),
                                                           *reinterpret_cast<bf16x8*>(&bva[1]), S[pft][1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      const bool first = (t == 0 && k < 2);
-      if (first || __any(mall > kTau)) {
-        float m0 = fmaxf(mall, __shfl_xor(mall, 32, 64));
-        const float delta = (first || m0 > kRaise) ? m0 : 0.f;
+      // Raise the shift of every feature whose largest logit in U[cur] asks for it (all of them when the shift is
+      // being set for the first time), rescale what the feature has accumulated, and move U[cur] to the new shift.
+      auto reshift = [&](bool set, float zold) {
+        float mall = U[cur][0];
+#pragma unroll
+        for (int v = 1; v < 15; v += 2) mall = max3(mall, U[cur][v], U[cur][v + 1]);
+        mall = fmaxf(mall, U[cur][15]);
+        const float m0 = fmaxf(mall, __shfl_xor(mall, 32, 64));
+        // a feature whose sum has left the range is brought down by at least 2^kZDown even if this block's own
+        // logits are small (its earlier blocks were the large ones)
+        const bool over = !(fabsf(zl[ft] + __shfl_xor(zl[ft], 32, 64)) < kZBig);
+        const float delta = set ? m0 : (over ? fmaxf(m0, kZDown) : (m0 > kRaise ? m0 : 0.f));
         float ceff;
         afr[ft][4] = fold_frag(c[ft] + delta, ceff);
         const float deff = ceff - c[ft];
         c[ft] = ceff;
 #pragma unroll
         for (int v = 0; v < 16; ++v) U[cur][v] -= deff;
-        if (!first) {
+        if (!set) {
           const float f = fast_exp2(-deff);
-          zl[ft] *= f;
+          zl[ft] = zold * f;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const float fr = __shfl(f, 8 * (v / 4) + 4 * hf + (v % 4), 64);
@@ -449,7 +464,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
             for (int ct = 0; ct < 2; ++ct) S[ft][ct][v] *= fr;
           }
         }
-      }
+      };
+      if (t == 0 && k < 2) reshift(true, 0.f);  // workgroup-uniform
+      const float zprev = zl[ft];
       __builtin_amdgcn_sched_barrier(0);
       // B(k), second part, in eight pieces; piece i follows MFMA i of A(k+1) (i < 5) or of C(k-1)
 #pragma unroll
@@ -477,6 +494,18 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
 #pragma unroll
         for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(pk[cur][hh][q]));
       asm volatile("" : "+v"(zl[ft]));
+      // Rare: a sum that is no longer below 2^kZBig (or not finite: an exponential overflowed) means the shift of
+      // some feature is too low.  Nothing of this block has reached S yet (C(k) is issued with the next block) and
+      // U[cur] is intact, so the block is simply redone under the raised shift.
+      if (__any(!(fabsf(zl[ft]) < kZBig))) {
+        reshift(false, zprev);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float ea = fast_exp2(U[cur][2 * i]), eb = fast_exp2(U[cur][2 * i + 1]);
+          pk[cur][i / 4][i % 4] = pack_bf16(ea, eb);
+          zl[ft] = (zl[ft] + ea) + eb;
+        }
+      }
     }
     __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2): V(t+1) has landed; the two key loads may still fly
     __syncthreads();
@@ -803,7 +832,11 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   // items share first the (b,h) and then at least the head.  A workgroup takes a contiguous run of
   // them: A' is refilled only when the run crosses into the next head, and S^T, z of the next (b,h) are
   // already resident when a second buffer exists (the run of a workgroup rarely spans more than two).
-  const int item_begin = blockIdx.x * items_per_wg;
+  // Workgroups are dealt to the eight XCDs round-robin; neighbouring runs of items (which share S^T, z and
+  // A') go to workgroups of one XCD, so that its L2 fetches each of them once.
+  const int nwg = gridDim.x;
+  const int wg = nwg % 8 == 0 ? (blockIdx.x % 8) * (nwg / 8) + blockIdx.x / 8 : blockIdx.x;
+  const int item_begin = wg * items_per_wg;
   const int item_end = min(n_items, item_begin + items_per_wg);
   auto bh_of = [&](int vb) { return (vb % Bsz) * H + vb / Bsz; };
   const int vb0 = item_begin / chunks_per_bh;
@@ -933,10 +966,14 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       }
     }
   };
+  if (item_begin >= item_end) return;  // workgroup-uniform
   // The first tile's rows are requested before the first LDS fill, so that the two cold fetches overlap.
-  if (item_begin < item_end) {
+  {
     const int t00 = (item_begin % chunks_per_bh) * NT + 64 * wv;
-    if (t00 < L) {
+    if constexpr (NBUF == 2) {
+      fetch_x(bh_of(vb0), t00);  // rows past the end repeat the last row (a tile past the end is never used)
+      have_x = t00 < L;
+    } else if (t00 < L) {
       fetch_x(bh_of(vb0), t00);
       have_x = true;
     }
@@ -946,16 +983,66 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   const float* zl = reinterpret_cast<const float*>(smem + kSBase + SM::s_bytes(m));
   const float* cl = zl + m;
   const int h0 = vb0 / Bsz;
+  if constexpr (NBUF == 2) {
+    // First fill, outside the item loop and free of branches: every load of both buffers is in flight before the
+    // first wait, one memory round trip.  (Inside the loop the compiler has to assume that loads of an earlier
+    // refill may still be pending on the same registers and waits before each group.)  Buffer 1 takes what the
+    // next (b,h) of the run needs; when the run has no second (b,h) it takes the first one's once more.
+    const bool two = (item_end - 1) / chunks_per_bh > vb0;
+    const int hn = two ? (vb0 + 1) / Bsz : h0;
+    const int bh2[2] = {bh_of(vb0), bh_of(two ? vb0 + 1 : vb0)};
+    const int hh2[2] = {h0, hn};
+    constexpr int NA = m * D / 8 / NT, NS = DV * m / 4 / NT;
+    static_assert(NT >= m, "one z per thread");
+    u32x4 av[2][NA];
+    u32x2 sv[2][NS];
+    float zv[2], cv[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+#pragma unroll
+      for (int u = 0; u < NA; ++u) {
+        const int ci = tid + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
+        av[q][u] = *reinterpret_cast<const u32x4*>(Ah + ((size_t)hh2[q] * m + row) * D + 8 * kc);
+      }
+#pragma unroll
+      for (int u = 0; u < NS; ++u) {
+        const int ci = tid + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+        sv[q][u] = *reinterpret_cast<const u32x2*>(St + ((size_t)bh2[q] * DV + row) * m + 4 * fc);
+      }
+      zv[q] = zt[(size_t)bh2[q] * m + min(tid, m - 1)];
+      cv[q] = cf[(size_t)bh2[q] * (m / 64) + min(tid, m / 64 - 1)];
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      _Float16* al = reinterpret_cast<_Float16*>(smem + q * kABytes);
+      unsigned char* base = smem + kSBase + q * kBufBytes;
+      unsigned short* sl = reinterpret_cast<unsigned short*>(base);
+      float* zq = reinterpret_cast<float*>(base + SM::s_bytes(m));
+#pragma unroll
+      for (int u = 0; u < NA; ++u) {
+        const int ci = tid + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
+        *reinterpret_cast<u32x4*>(al + row * SM::AS + 8 * kc) = av[q][u];
+      }
+#pragma unroll
+      for (int u = 0; u < NS; ++u) {
+        const int ci = tid + NT * u, row = ci / (m / 4), fc = ci % (m / 4);
+        *reinterpret_cast<u32x2*>(sl + row * SS + 4 * fc) = sv[q][u];
+      }
+      if (tid < m) zq[tid] = zv[q];
+      if (tid < m / 64) zq[m + tid] = cv[q];
+    }
+    __syncthreads();
+    cur_vb = vb0;
+    cur_h = h0;
+    // (the A' of a second head sits in buffer (hn - h0) % 2 = 1, where the loop looks for it)
+  }
   for (int item = item_begin; item < item_end; ++item) {
     const int vb = item / chunks_per_bh, chunk = item % chunks_per_bh;
     const int bh = bh_of(vb);
     if (vb != cur_vb) {
       const int h = vb / Bsz, k = vb - vb0, ha = h - h0;
-      if (cur_vb < 0) {
-        // first fill: with two buffers, also what the next (b,h) of the run needs
-        const bool two = NBUF == 2 && (item_end - 1) / chunks_per_bh > vb;
-        const int hn = (vb + 1) / Bsz;
-        fill(h, 0, (two && hn != h) ? hn : -1, bh, 0, two ? bh_of(vb + 1) : -1, 1);
+      if (cur_vb < 0) {  // first fill (single-buffered kernels; with two buffers it happened before the loop)
+        fill(h, 0, -1, bh, 0, -1, 1);
         __syncthreads();
       } else {
         const bool came_with_first = NBUF == 2 && k == 1;
@@ -1234,33 +1321,29 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
         const bool mine = NHP == 1 || l32 / SR == hp;
         const int srow = l32 % SR;
         if (OUT_BF16) {
+          // bf16 output: no LDS turn.  A lane holds, per block of 32 columns, four 8-byte pieces of its token's
+          // row (columns 8 g + 4 hf + [0,4)); swapping halves between lanes l and l + 32 (v_permlane32_swap)
+          // joins the two pieces of an even g in the lower lane and those of the odd g in the upper one, so
+          // every lane stores 16 contiguous bytes and a store instruction covers 32-byte runs of 32 rows.
+          if (hp == 0) {
+            const int tok = t0 + 32 * tt + l32;
+            unsigned short* orow = reinterpret_cast<unsigned short*>(outp) + ((size_t)bh * L + min(tok, L - 1)) * DV + 8 * hf;
 #pragma unroll
-          for (int c64 = 0; c64 < DV / 64; ++c64) {  // 64 output columns (one 128-byte row piece) at a time
-            if (mine) {
+            for (int ct = 0; ct < DV / 32; ++ct)
 #pragma unroll
-              for (int cl2 = 0; cl2 < 2; ++cl2)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                  const int ct = 2 * c64 + cl2;
-                  u32x2 w = {pack_bf16(O[ct][tt][4 * g] * inv, O[ct][tt][4 * g + 1] * inv),
-                             pack_bf16(O[ct][tt][4 * g + 2] * inv, O[ct][tt][4 * g + 3] * inv)};
-                  *reinterpret_cast<u32x2*>(stage + srow * SM::stage_row + (32 * cl2 + 8 * g + 4 * hf) * 2) = w;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int ps = 0; ps < SR / 8; ++ps) {
-              const int tok = t0 + 32 * tt + SR * hp + 8 * ps + row;
-              u32x4 w = *reinterpret_cast<const u32x4*>(stage + (8 * ps + row) * SM::stage_row + 16 * ch);
-              // streaming store: the output is not read again by this launch, and lines left dirty in the
-              // L2 would all be written back at the end of the kernel, on the critical path of the step
-              if (tok < wg_end)
-                __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(reinterpret_cast<unsigned short*>(outp) +
-                                                                        ((size_t)bh * L + tok) * DV + 64 * c64 + 8 * ch));
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+              for (int gp = 0; gp < 2; ++gp) {
+                const int g0 = 2 * gp, g1 = g0 + 1;
+                const unsigned a0 = pack_bf16(O[ct][tt][4 * g0] * inv, O[ct][tt][4 * g0 + 1] * inv);
+                const unsigned a1 = pack_bf16(O[ct][tt][4 * g0 + 2] * inv, O[ct][tt][4 * g0 + 3] * inv);
+                const unsigned b0 = pack_bf16(O[ct][tt][4 * g1] * inv, O[ct][tt][4 * g1 + 1] * inv);
+                const unsigned b1 = pack_bf16(O[ct][tt][4 * g1 + 2] * inv, O[ct][tt][4 * g1 + 3] * inv);
+                const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+                const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
+                // streaming store: the output is not read again by this launch, and lines left dirty in the
+                // L2 would all be written back at the end of the kernel, on the critical path of the step
+                if (tok < wg_end) *reinterpret_cast<u32x4*>(orow + 32 * ct + 16 * gp) = w;
+              }
           }
         } else {
 #pragma unroll
@@ -1293,6 +1376,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
 }
 
 constexpr size_t kLdsMax = 160 * 1024;
+constexpr int kNumCU = 256;  // compute units of the MI355X
 
 struct Plan {
   int P, slice_len, nfb, n_work, kv_grid;
@@ -1363,12 +1447,12 @@ dark_status launch_kv(const Problem& pb, const Plan& pl, const FusedBufs& b, con
     DARK_TRY(allow_lds(k_kv_reduce<true>, KvSmem::total));
     DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<true>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
                 (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, b.nrm_out, p.H,
-                p.L, p.m, pl.P, pl.slice_len, pl.n_work);
+                p.L, p.m, pl.P, pl.slice_len, pl.n_work, kNumCU);
   } else {
     DARK_TRY(allow_lds(k_kv_reduce<false>, KvSmem::total));
     DARK_LAUNCH(KID_KV_REDUCE, pb.st, k_kv_reduce<false>, dim3(pl.kv_grid), dim3(256), KvSmem::total,
                 (const unsigned short*)K, (const unsigned short*)V, b.Ah, b.Mh, b.Spart, b.zpart, b.cpart, b.nrm_out, p.H,
-                p.L, p.m, pl.P, pl.slice_len, pl.n_work);
+                p.L, p.m, pl.P, pl.slice_len, pl.n_work, kNumCU);
   }
   return DARK_OK;
 }
