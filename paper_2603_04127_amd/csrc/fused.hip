@@ -1036,7 +1036,15 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     cur_h = h0;
     // (the A' of a second head sits in buffer (hn - h0) % 2 = 1, where the loop looks for it)
   }
+  // Two waves share a SIMD and the arbiter serves the older one (waves 0 .. NW/2 - 1) first; the younger
+  // half of the workgroup takes the higher priority for the first two thirds of the run, so that both halves
+  // finish together instead of the younger one working its last item alone.
+  const int prio_items = (2 * (item_end - item_begin) + 1) / 3;
   for (int item = item_begin; item < item_end; ++item) {
+    if (NW == 8 && wv >= NW / 2) {
+      if (item - item_begin < prio_items) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+    }
     const int vb = item / chunks_per_bh, chunk = item % chunks_per_bh;
     const int bh = bh_of(vb);
     if (vb != cur_vb) {
