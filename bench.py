@@ -28,7 +28,8 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu": (157.3, "TF
 
 
 def algorithmic_work(cfg):
-    """Per-step algorithmic flops and HBM bytes of the forward pass, and per kernel.
+    """Per-step algorithmic flops and HBM bytes of the forward pass (plus the backward pass where the
+    configuration has one), and per kernel.
 
     Per token-head: projections of q and k through A = W M (2dm each), the norm terms
     (2dr each; the query-side one cancels in the ratio but is part of the definition),
@@ -42,6 +43,11 @@ def algorithmic_work(cfg):
     if cfg.causal:
         f_tok += m * (cfg.chunk + 1) + (dv + 1) * (cfg.chunk + 1)
     b_tok = (2 * d + dv) * s_in + dv * s_in
+    if cfg.backward:
+        # Backward pass (a call of its own): every forward contraction has two gradient contractions of the same
+        # size; it reads Q, K, V and dOut and writes dQ, dK, dV in fp32 (dM is a few KB per head).
+        f_tok *= 3
+        b_tok += (2 * d + dv) * s_in + dv * s_in + (2 * d + dv) * 4
     per_kernel = {
         # kernel name -> (bound, algorithmic units per launch) ; bytes for hbm, flops otherwise
         "fused_kv_reduce": ("hbm", th * (d + dv) * s_in),

@@ -791,15 +791,17 @@ template <int D, int DV>
 struct RoSmem {
   static constexpr int AS = D + 8;
   static constexpr int stage_row = 128 + 8;                   // bytes: 64 bf16 or 32 fp32, plus pad
-  __host__ __device__ static constexpr int stage_rows(int nbuf) { return nbuf == 2 ? 16 : 32; }  // tokens per pass
-  __host__ __device__ static constexpr size_t stage_bytes(int nbuf) { return (size_t)stage_rows(nbuf) * stage_row; }
+  // the per-wave output stage (fp32 output only: bf16 rows leave from registers): 16 tokens per pass in the
+  // eight-wave kernels, whose operands leave no room for more, else 32
+  __host__ __device__ static constexpr int stage_rows(int nw) { return nw == 8 ? 16 : 32; }
+  __host__ __device__ static constexpr size_t stage_bytes(int nw) { return (size_t)stage_rows(nw) * stage_row; }
   __host__ __device__ static constexpr size_t a_bytes(int m) { return (size_t)m * AS * 2; }
   __host__ __device__ static constexpr size_t s_bytes(int m) { return (size_t)DV * (m + 4) * 2; }
   __host__ __device__ static constexpr size_t misc_bytes(int m) { return (size_t)m * 4 + 16 * (size_t)((m / 64 + 3) / 4); }  // z, shifts
   // nbuf copies of A', S^T, z and the shifts (two where the LDS allows: the next head and (b,h) are then
   // resident before the workgroup's run of items reaches them; the output stage is halved to make room)
   __host__ __device__ static size_t total(int m, int nw, int nbuf) {
-    return nbuf * (a_bytes(m) + s_bytes(m) + misc_bytes(m)) + nw * stage_bytes(nbuf);
+    return nbuf * (a_bytes(m) + s_bytes(m) + misc_bytes(m)) + nw * stage_bytes(nw);
   }
 };
 template <int D, int NFB, int NW>
@@ -820,12 +822,12 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   constexpr size_t kABytes = SM::a_bytes(m);
   constexpr size_t kSBase = NBUF * kABytes;
   constexpr size_t kBufBytes = SM::s_bytes(m) + SM::misc_bytes(m);
-  constexpr int SR = SM::stage_rows(NBUF);
+  constexpr int SR = SM::stage_rows(NW);
   const int SS = m + 4;
   constexpr int NT = 64 * NW;
 
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
-  unsigned char* stage = smem + kSBase + NBUF * kBufBytes + wv * SM::stage_bytes(NBUF);
+  unsigned char* stage = smem + kSBase + NBUF * kBufBytes + wv * SM::stage_bytes(NW);
   const int l32 = lane % 32, hf = lane / 32;
 
   // Work items are (head, batch entry, 64 NW-token chunk) triples, head slowest, so that neighbouring
@@ -1412,7 +1414,7 @@ Plan make_plan(const Problem& pb) {
   // readout: (b,h, 256-token chunk) items dealt out in contiguous runs to about as many
   // workgroups as fit on the chip at once
   // one workgroup per CU: eight waves when the registers (d = 64) and the LDS allow, else four
-  pl.ro_nw = (p.d == 64 && p.m == 256) ? 8 : 4;
+  pl.ro_nw = p.d == 64 ? 8 : 4;
   const int ro_tok = 64 * pl.ro_nw;
   pl.chunks_per_bh = (p.L + ro_tok - 1) / ro_tok;
   pl.n_items = (int)(BH * pl.chunks_per_bh);
@@ -1538,7 +1540,7 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
   if (p.d == 64 && p.m == 256) {
     DARK_TRY((launch_ro<64, 64, 1, 8>(pb, pl, b, Q, out)));
   } else if (p.d == 64) {
-    DARK_TRY((launch_ro<64, 64, 2, 4>(pb, pl, b, Q, out)));
+    DARK_TRY((launch_ro<64, 64, 2, 8>(pb, pl, b, Q, out)));
   } else {
     DARK_TRY((launch_ro<128, 128, 1, 4>(pb, pl, b, Q, out)));
   }
