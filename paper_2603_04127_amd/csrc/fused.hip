@@ -703,11 +703,13 @@ __global__ __launch_bounds__(256) void k_kv_merge(const unsigned short* __restri
 // P <= kMergeTMaxP slices.
 // ---------------------------------------------------------------------------
 constexpr int kMergeTMaxP = 8;
+template <int P>  // the number of slices, so that no thread requests a slice twice
 __global__ __launch_bounds__(256) void k_kv_merge_t(const unsigned short* __restrict__ Spart,
                                                     const float* __restrict__ zpart, const float* __restrict__ cpart,
                                                     unsigned short* __restrict__ St, float* __restrict__ zt,
-                                                    float* __restrict__ cf, int m, int P) {
-  constexpr int DV = 64, PP = kMergeTMaxP;
+                                                    float* __restrict__ cf, int m) {
+  constexpr int DV = 64, PP = P;
+  static_assert(P >= 1 && P <= kMergeTMaxP, "slice count");
   __shared__ float fac[PP][64];
   __shared__ float red[4];
   const int nblk = m / 64;
@@ -1001,6 +1003,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     float zv[2], cv[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
+      if (q == 1 && !two) break;  // workgroup-uniform: a run inside one (b,h) needs no second buffer
 #pragma unroll
       for (int u = 0; u < NA; ++u) {
         const int ci = tid + NT * u, row = ci / (D / 8), kc = ci % (D / 8);
@@ -1016,6 +1019,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
+      if (q == 1 && !two) break;
       _Float16* al = reinterpret_cast<_Float16*>(smem + q * kABytes);
       unsigned char* base = smem + kSBase + q * kBufBytes;
       unsigned short* sl = reinterpret_cast<unsigned short*>(base);
@@ -1528,10 +1532,19 @@ dark_status fused_attn_fwd(const Problem& pb, Arena& ar, const void* Q, const vo
     DARK_TRY(fused_launch_slice_state128(pb, K, V, b.Ah, b.Mh, b.nrm, b.Spart, b.zpart, b.cpart, pl.P, pl.slice_len));
   }
   const unsigned mgrid = (unsigned)(pb.BH() * (p.m / 64));
-  if (pl.tp)
-    DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge_t, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St, b.zt,
-                b.cf, p.m, pl.P);
-  else if (p.dv == 64)
+  if (pl.tp) {
+#define DARK_MERGE_T(PV)                                                                                              \
+  case PV:                                                                                                           \
+    DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge_t<PV>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St, \
+                b.zt, b.cf, p.m);                                                                                    \
+    break;
+    switch (pl.P) {
+      DARK_MERGE_T(1) DARK_MERGE_T(2) DARK_MERGE_T(3) DARK_MERGE_T(4) DARK_MERGE_T(5) DARK_MERGE_T(6) DARK_MERGE_T(7)
+      DARK_MERGE_T(8)
+      default: return DARK_EUNSUPPORTED;
+    }
+#undef DARK_MERGE_T
+  } else if (p.dv == 64)
     DARK_LAUNCH(KID_KV_MERGE, pb.st, k_kv_merge<64>, dim3(mgrid), dim3(256), 0, b.Spart, b.zpart, b.cpart, b.St,
                 b.zt, b.cf, p.m, pl.P);
   else
