@@ -730,6 +730,30 @@ def test_fused_shift_raised_mid_slice():
     U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], "fused, shift raised mid-slice")
 
 
+def test_fused_exponential_overflows_mid_slice():
+    """A steeper ramp: from one 32-token block to the next some key logits rise by more than 2^128 = 88.7 nats,
+    so that under the shift in force the exponential itself overflows.  The key pass sees that only after the
+    block, in the running sum z, and has to redo the block under a raised shift before anything of it reaches
+    the state."""
+    from paper_2603_04127_amd import synth
+    inp = U.random_problem(22, 1, 1, 900, 64, 64, 256, 64, bf16=True, amp=1.0)
+    ramp = np.linspace(0.02, 10.0, 900, dtype=np.float32)[None, None, :, None]
+    bits = synth.to_bf16_bits(inp["K"] * ramp)
+    inp["K_bits"], inp["K"] = bits, synth.bf16_bits_to_f32(bits)
+    inp["W"] = inp["W"] * 5.0
+    lg = O.logits(inp["K"][0, 0], inp["M"][0], inp["W"][0])
+    run, jump = lg[:32].max(axis=0), np.zeros(lg.shape[1])
+    for b in range(1, (900 + 31) // 32):
+        bm = lg[32 * b:32 * b + 32].max(axis=0)
+        jump, run = np.maximum(jump, bm - run), np.maximum(run, bm)
+    # (the shift in force is at most the running maximum, so the rise the kernel sees is at least this one)
+    assert np.sum(jump > 95.0) >= 2, np.sort(jump)[-8:]
+    dev = U.to_device(inp, True)
+    out = dk.dark_attn_fwd(dev["Q"], dev["K"], dev["V"], dev["M"], dev["W"], path=dk.PATH_FUSED, sched={"kv_wgs": 1})
+    torch.cuda.synchronize()
+    U.assert_close(_np(out), U.oracle_attn(inp, False), U.TOL["bf16"], "fused, exponential overflows mid-slice")
+
+
 # ---------------------------------------------------------------------------
 # fused MFMA causal path (bf16 inputs), forced
 # ---------------------------------------------------------------------------
