@@ -213,13 +213,13 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
     kr[1] = *reinterpret_cast<const u32x4*>(src + 32);
   };
   // V tile -> LDS: lane i of a wave fills position i % 8 of row r0 + i / 8 with the row's 16-byte piece
-  // (i % 8) ^ (row & 7).  Rows past the end of the slice repeat its last row (their features are zero).
+  // (i % 8) ^ v_swz(row).  Rows past the end of the slice repeat its last row (their features are zero).
   auto dma_v = [&](int tile, int vb) {
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const int row = 16 * wv + 8 * u + lane / 8;
       const int tok = min(tok_begin + tile * kTile + row, tok_end - 1);
-      dma16_to_lds(Vb + (size_t)tok * DV + 8 * ((lane % 8) ^ (row & 7)), Vt + vb * SM::v_buf + (16 * wv + 8 * u) * 128);
+      dma16_to_lds(Vb + (size_t)tok * DV + 8 * ((lane % 8) ^ v_swz<128>(row)), Vt + vb * SM::v_buf + (16 * wv + 8 * u) * 128);
     }
   };
   // Convert the fetched key rows, store them, and write n' of this wave's 16 rows into their extra slots.
@@ -283,8 +283,8 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
   const unsigned xoff4 = l32 * XROW + 128 + 16 * hf;  // the extra slots (lower half-wave) / the zeros behind them (upper)
   const int jj = l32 % 16, tl = 4 * hf + jj / 4, kq = 2 * (l32 / 16) + (jj % 4) / 2;
   unsigned voff[2];
-  voff[0] = tl * 128 + 16 * (kq ^ (tl & 7)) + 8 * (jj % 2);
-  voff[1] = tl * 128 + 16 * ((kq + 4) ^ (tl & 7)) + 8 * (jj % 2);
+  voff[0] = tl * 128 + 16 * (kq ^ v_swz<128>(tl)) + 8 * (jj % 2);
+  voff[1] = tl * 128 + 16 * ((kq + 4) ^ v_swz<128>(tl)) + 8 * (jj % 2);
 
   f32x16 S[2][2], U[2];
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};

@@ -316,7 +316,7 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
     unsigned short* vt = reinterpret_cast<unsigned short*>(vb + (t % 3) * SM::v_bytes);
     if (stager) {
       const int tok = tid / (D / 8), kc = tid % (D / 8);
-      *reinterpret_cast<u32x4*>(vt + tok * DVT + 8 * (kc ^ (tok & 7))) = vreg;
+      *reinterpret_cast<u32x4*>(vt + tok * DVT + 8 * (kc ^ v_swz<2 * DVT>(tok))) = vreg;
     }
   };
   // this wave's partial norms of tile t (its 16 rows of M'), from the tile in LDS
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       for (int ct = 0; ct < NCT; ++ct) {
         const int tok = 16 * hh + 4 * hf + j16 / 4;
         const int chunk = 4 * ct + 2 * g2 + (j16 % 4) / 2;
-        const unsigned short* vr = vt + tok * DVT + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
+        const unsigned short* vr = vt + tok * DVT + 8 * (chunk ^ v_swz<2 * DVT>(tok)) + 4 * (j16 % 2);
         u32x2 lo = lds_read_tr16(vr);
         u32x2 hi = lds_read_tr16(vr + 8 * DVT);
         bv[ct] = u32x4{lo[0], lo[1], hi[0], hi[1]};

@@ -87,6 +87,18 @@ __device__ static inline u32x2 lds_read_tr16(const unsigned short* p) {
   return *reinterpret_cast<u32x2*>(&v);
 }
 
+// XOR swizzle of the 16-byte chunks of a row of a bf16 V tile in LDS (ROWB bytes per row: 64 or 128 value columns):
+// chunk q of row `row` sits at position q ^ v_swz<ROWB>(row).  The transposing reads of the products phi^T V fetch,
+// per group of 16 lanes, two neighbouring chunks of four consecutive rows; rows of 128 (256) bytes fall onto the
+// same banks every second row (every row), and with this choice the 32 lanes that the LDS serves together find their
+// 32 eight-byte words on 32 different bank pairs (2.4 cycles per instruction, the rate of a contiguous read;
+// XOR with the row number itself: 4 cycles at 128-byte rows, 8 at 256-byte rows).
+template <int ROWB>
+__device__ static inline int v_swz(int row) {
+  static_assert(ROWB == 128 || ROWB == 256, "V tile rows of 64 or 128 bf16");
+  return ROWB == 128 ? 2 * (row & 3) + ((row >> 2) & 1) : 4 * (row & 3);
+}
+
 // Direct global -> LDS load of 16 bytes per lane (global_load_lds_dwordx4): lane i of the wave
 // writes the 16 bytes at gsrc (its own address) to LDS at lds_wave_base + 16 i.  The load is
 // counted by vmcnt like any global load, but it is issued from inline assembly so that the

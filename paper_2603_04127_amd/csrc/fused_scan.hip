@@ -135,7 +135,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
     if (tid / 64 < kCT / RPW) {
       const int t0 = tok_begin + t * kCT;
       const int ln = tid % 64, r = RPW * (tid / 64) + ln / CPR, pos = ln % CPR;
-      const int tok = min(t0 + r, tok_end - 1), cc = pos ^ (r & 7);
+      const int tok = min(t0 + r, tok_end - 1), cc = pos ^ v_swz<2 * DVT>(r);
       dma16_to_lds(Vb + (size_t)tok * DVT + 8 * cc, Vt2 + (t % 2) * kCT * DVT + (tid / 64) * 512);
     }
   };
@@ -305,7 +305,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
         for (int hh = 0; hh < 2; ++hh) {
           const int tok = 16 * hh + 4 * hf + j16 / 4;
           const int chunk = 4 * (CTW * sub + ct) + 2 * g2 + (j16 % 4) / 2;
-          const unsigned short* vr = Vt + tok * DVT + 8 * (chunk ^ (tok & 7)) + 4 * (j16 % 2);
+          const unsigned short* vr = Vt + tok * DVT + 8 * (chunk ^ v_swz<2 * DVT>(tok)) + 4 * (j16 % 2);
           const u32x2 lo = lds_read_tr16(vr), hi = lds_read_tr16(vr + 8 * DVT);
           bv[ct][hh] = u32x4{lo[0], lo[1], hi[0], hi[1]};
         }
