@@ -280,11 +280,13 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
 
   constexpr int NCH = kCT * D / 8;  // 16-byte pieces of a K (or V) tile
   const bool stager = tid < NCH;
-  u32x4 kreg = {0u, 0u, 0u, 0u}, vreg = {0u, 0u, 0u, 0u};
-  float nreg = 0.f;
+  // rows in flight from global memory, by tile parity: K four tiles ahead of its use (two ahead of its store),
+  // V three (two); a request is two steps old when its store needs it, which covers the latency under load
+  u32x4 kregs[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}}, vregs[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+  float nregs[2] = {0.f, 0.f};
   const unsigned short* Kb = Kg + (size_t)bh * L * D;
   const unsigned short* Vb = Vg + (size_t)bh * L * DVT;
-  auto load_k = [&](int t) {
+  auto load_k = [&](int t, u32x4& kreg, float& nreg) {
     const int t0 = tok_begin + t * kCT;
     if (stager) {
       const int tok = min(t0 + tid / (D / 8), tok_end - 1), kc = tid % (D / 8);
@@ -293,14 +295,14 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
     // no arithmetic on the loaded value here: it would make the wave wait for everything above
     if (!NORMS) nreg = nrm[(size_t)bh * L + min(t0 + tid % kCT, tok_end - 1)];
   };
-  auto load_v = [&](int t) {
+  auto load_v = [&](int t, u32x4& vreg) {
     const int t0 = tok_begin + t * kCT;
     if (stager) {
       const int tok = min(t0 + tid / (D / 8), tok_end - 1), kc = tid % (D / 8);
       vreg = *reinterpret_cast<const u32x4*>(Vb + (size_t)tok * DVT + 8 * kc);
     }
   };
-  auto store_k = [&](int t) {
+  auto store_k = [&](int t, const u32x4& kreg, const float& nreg) {
     _Float16* xs = reinterpret_cast<_Float16*>(xb + (t % 3) * SM::x_bytes);
     if (stager) {
       const int tok = tid / (D / 8), kc = tid % (D / 8);
@@ -312,7 +314,7 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       if (tid < kCT) nsb[(t % 3) * kCT + tid] = nsv;
     }
   };
-  auto store_v = [&](int t) {
+  auto store_v = [&](int t, const u32x4& vreg) {
     unsigned short* vt = reinterpret_cast<unsigned short*>(vb + (t % 3) * SM::v_bytes);
     if (stager) {
       const int tok = tid / (D / 8), kc = tid % (D / 8);
@@ -339,8 +341,8 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
       sq = fmaf(acc[1], acc[1], sq);
       sq = fmaf(acc[2], acc[2], sq);
       sq = fmaf(acc[3], acc[3], sq);
-      sq += __shfl_xor(sq, 16, 64);
-      sq += __shfl_xor(sq, 32, 64);
+      sq += xor16(sq);
+      sq += xor32(sq);
       if (g16 == 0) np[(16 * tb2 + l16) * 8 + wv] = sq;
     }
   };
@@ -351,24 +353,25 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
   for (int ct = 0; ct < NCT; ++ct) S[ct] = zero16;
   float c = 0.f;  // this wave's shift (log2 domain), wave-uniform
 
-  // prologue: K tiles 0 and 1 and V tile 0 in LDS, K tile 2 and V tile 1 on their way, norms of tile 0
-  load_k(0);
-  load_v(0);
-  store_k(0);
-  store_v(0);
-  if (ntile > 1) {
-    load_k(1);
-    store_k(1);
-    load_v(1);
-  }
-  if (ntile > 2) load_k(2);
+  // prologue: K tiles 0 and 1 and V tile 0 in LDS, K tiles 2, 3 and V tiles 1, 2 on their way, norms of tile 0
+  load_k(0, kregs[0], nregs[0]);
+  if (ntile > 1) load_k(1, kregs[1], nregs[1]);
+  load_v(0, vregs[0]);
+  store_k(0, kregs[0], nregs[0]);
+  if (ntile > 1) store_k(1, kregs[1], nregs[1]);
+  store_v(0, vregs[0]);
+  if (ntile > 2) load_k(2, kregs[0], nregs[0]);
+  if (ntile > 3) load_k(3, kregs[1], nregs[1]);
+  if (ntile > 1) load_v(1, vregs[1]);
+  if (ntile > 2) load_v(2, vregs[0]);
   __syncthreads();
   if (NORMS) {
     partial_norms(0);
     __syncthreads();
   }
 
-  for (int t = 0; t < ntile; ++t) {
+  // one step; kr, nr: the register set of this tile's parity (holds tile t + 2), vr: the other parity's (tile t + 1)
+  auto step = [&](int t, u32x4& kr, float& nr, u32x4& vr) {
     const _Float16* xs = reinterpret_cast<const _Float16*>(xb + (t % 3) * SM::x_bytes);
     const unsigned short* vt = reinterpret_cast<const unsigned short*>(vb + (t % 3) * SM::v_bytes);
     unsigned char* tb = tbb + ((t % 2) * 4 + fg) * SM::tb_bytes;
@@ -448,11 +451,15 @@ __global__ __launch_bounds__(512, 1) void k_slice_state(const unsigned short* __
                                                      0, 0, 0);
     }
     // --- the tiles to come: K two tiles ahead, V one; then the step's only barrier ------------------
-    if (t + 2 < ntile) store_k(t + 2);
-    if (t + 1 < ntile) store_v(t + 1);
-    if (t + 3 < ntile) load_k(t + 3);
-    if (t + 2 < ntile) load_v(t + 2);
+    if (t + 2 < ntile) store_k(t + 2, kr, nr);
+    if (t + 1 < ntile) store_v(t + 1, vr);
+    if (t + 4 < ntile) load_k(t + 4, kr, nr);
+    if (t + 3 < ntile) load_v(t + 3, vr);
     __syncthreads();
+  };
+  for (int t = 0; t < ntile; t += 2) {
+    step(t, kregs[0], nregs[0], vregs[1]);
+    if (t + 1 < ntile) step(t + 1, kregs[1], nregs[1], vregs[0]);
   }
 
   // --- the slice's state ---------------------------------------------------------------------

@@ -87,6 +87,23 @@ __device__ static inline u32x2 lds_read_tr16(const unsigned short* p) {
   return *reinterpret_cast<u32x2*>(&v);
 }
 
+// The value of lane l ^ 32 / l ^ 16, by the lane-swap instructions of gfx950 (vector ALU, no trip through the LDS
+// crossbar as __shfl_xor takes).  v_permlane32_swap exchanges the upper half of its first operand with the lower
+// half of the second; v_permlane16_swap does the same with the odd rows of 16 lanes of the first and the even rows
+// of the second.  With both operands the same value, the second result of the former and the first... see below.
+__device__ static inline float xor32(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // r[0] = {lower: own lower, upper: own lower}; r[1] = {lower: own upper, upper: own upper}
+  return __uint_as_float(threadIdx.x & 32 ? r[0] : r[1]);
+}
+__device__ static inline float xor16(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  // rows of 16 lanes: r[0] = {even rows: own, odd rows: the even row below}; r[1] = {even rows: the odd row above, odd rows: own}
+  return __uint_as_float(threadIdx.x & 16 ? r[0] : r[1]);
+}
+
 // XOR swizzle of the 16-byte chunks of a row of a bf16 V tile in LDS (ROWB bytes per row: 64 or 128 value columns):
 // chunk q of row `row` sits at position q ^ v_swz<ROWB>(row).  The transposing reads of the products phi^T V fetch,
 // per group of 16 lanes, two neighbouring chunks of four consecutive rows; rows of 128 (256) bytes fall onto the
