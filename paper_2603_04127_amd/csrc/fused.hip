@@ -1205,7 +1205,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       }
     }
     have_x = more;
-    const float dt0 = den[0] + __shfl_xor(den[0], 32, 64), dt1 = den[1] + __shfl_xor(den[1], 32, 64);
+    const float dt0 = den[0] + xor32(den[0]), dt1 = den[1] + xor32(den[1]);
     const bool redo = __any(!(dt0 > kDenLo && dt0 < kDenHi) || !(dt1 > kDenLo && dt1 < kDenHi));
 
     // ---- careful path: running per-token shift, raised whenever a block exceeds it by 2^kTau ---
@@ -1327,7 +1327,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
     // out[token 32 tt + l32][c = 32 ct + 8 (v/4) + 4 hf + v%4].
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const float inv = 1.f / (den[tt] + __shfl_xor(den[tt], 32, 64));
+      const float inv = 1.f / (den[tt] + xor32(den[tt]));
       const int row = lane / 8, ch = lane % 8;  // read side: 8 lanes per token row, 16 bytes each
       constexpr int NHP = 32 / SR;              // passes of SR tokens through the stage
 #pragma unroll

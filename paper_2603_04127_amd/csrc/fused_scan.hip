@@ -220,7 +220,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
           for (int fq = 0; fq < 4; ++fq)
 #pragma unroll
             for (int v = 0; v < 16; v += 2) mu = max3(mu, U[fq][v], U[fq][v + 1]);
-          mu = fmaxf(mu, __shfl_xor(mu, 32, 64));
+          mu = fmaxf(mu, xor32(mu));
           const float* zt = zb + par * 256 + 128 * half;
           // z of the features this lane's registers hold: rows 8 g + 4 hf + [0,4) of block fq, as it was
           // before this tile (fetched two groups ahead of their use).  phi_Q . z uses the bf16-rounded
@@ -242,7 +242,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
               *reinterpret_cast<u32x2*>(pt + 16 * g) = u32x2{w0, w1};
             }
           }
-          den += __shfl_xor(den, 32, 64);
+          den += xor32(den);
           if (hf == 0) {
             dmq[(par * 2 + half) * 2 * kCT + l32] = den;
             dmq[(par * 2 + half) * 2 * kCT + kCT + l32] = mu;
@@ -351,7 +351,7 @@ __device__ __forceinline__ void ws_body(unsigned char* smem, const unsigned shor
         for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
           for (int q = 0; q < 4; ++q) rs += __uint_as_float(pp[hh][q] << 16) + __uint_as_float(pp[hh][q] & 0xffff0000u);
-        rs += __shfl_xor(rs, 32, 64);
+        rs += xor32(rs);
         if (hf == 0) dden[half * kCT + l32] = dmq[(par * 2 + half) * 2 * kCT + l32] + rs;
       }
       // numerators: the state as it was before this tile, then the intra-tile term
