@@ -105,8 +105,10 @@ __global__ __launch_bounds__(256, 4) void k_key_norms(const unsigned short* __re
 // same for z.  Slice p's own keys are featurised with c*_p by the scan, so nothing it adds to the
 // state can exceed what k_kv_reduce already bounded.
 // Workgroup = (b,h, 8 features); a thread owns 8 DV / 256 adjacent state entries.
+// PB: slices whose entries a thread requests together (the smallest of 4, 8, 16 that covers P, so that a short
+// chain of slices does not request its last slice over and over to fill the batch).
 // ---------------------------------------------------------------------------
-template <int DV>
+template <int DV, int PB>
 __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restrict__ Spart,
                                                    const float* __restrict__ zpart,
                                                    const float* __restrict__ cpart, float* __restrict__ Spre,
@@ -120,7 +122,6 @@ __global__ __launch_bounds__(256) void k_kv_prefix(const unsigned short* __restr
   const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int tid = threadIdx.x, lane = tid % 64, wv = tid / 64;
   // the state entries of all slices are requested before anything waits
-  constexpr int PB = 16;
   const int feat = 8 * blk + (tid * EPT) / DV;
   const int col = (tid * EPT) % DV;
   fvec acc;
@@ -548,7 +549,8 @@ dark_status launch_causal(const Problem& pb, const void* Q, const void* K, const
     // the key pass computes the key norms on its way and leaves them in nrm
     DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len, nrm));
   }
-  DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<D>), dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
+  auto prefix = P <= 4 ? k_kv_prefix<D, 4> : P <= 8 ? k_kv_prefix<D, 8> : k_kv_prefix<D, 16>;
+  DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, prefix, dim3(BH * (p.m / 8)), dim3(256), 0, Spart, zpart, cpart,
               Spre, zpre, cpre, p.m, P);
   return fused_launch_scan_ws(pb, Q, K, V, Ah, nrm, Spre, zpre, cpre, out, P, slice_len);
 }
@@ -567,7 +569,8 @@ dark_status fused_causal_states64(const Problem& pb, const void* K, const void* 
   const dark_params& p = pb.p;
   if (p.d != 64 || p.dv != 64 || P > kMaxP) return DARK_EUNSUPPORTED;
   DARK_TRY(fused_launch_kv_reduce(pb, K, V, Ah, Mh, Spart, zpart, cpart, P, slice_len, nrm));
-  DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, (k_kv_prefix<64>), dim3((unsigned)(pb.BH() * (p.m / 8))), dim3(256), 0, Spart, zpart,
+  auto prefix = P <= 4 ? k_kv_prefix<64, 4> : P <= 8 ? k_kv_prefix<64, 8> : k_kv_prefix<64, 16>;
+  DARK_LAUNCH(KID_CAUSAL_PREFIX, pb.st, prefix, dim3((unsigned)(pb.BH() * (p.m / 8))), dim3(256), 0, Spart, zpart,
               cpart, Spre, zpre, cpre, p.m, P);
   return DARK_OK;
 }
