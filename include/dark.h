@@ -316,6 +316,25 @@ dark_status dark_ceiling_copy(void* dst, const void* src, size_t nbytes, void* h
 dark_status dark_ceiling_read(const void* src, size_t nbytes, void* sink, void* hip_stream);
 dark_status dark_ceiling_mfma(int iters, void* sink, double* flops, void* hip_stream);
 
+/*
+ * Wall-clock timeline of the two large kernels of the bidirectional MFMA forward,
+ * for libraries built with -DDARK_TIMELINE (python -m paper_2603_04127_amd.timeline
+ * builds one beside the ordinary library).  In such a build every wave of the
+ * key/value pass (which = 0) and of the readout (which = 1) stores the device's
+ * 100 MHz wall clock at fixed points of its run into a device array, 16 slots per
+ * wave:
+ *   which = 0: [workgroup (first 512)][wave (4)][slot]: 0 kernel start, 1 M' in LDS,
+ *              2 first barrier passed, 3 tile loop begins, 4 tile loop done, 5 kernel end
+ *   which = 1: [workgroup (first 256)][wave (8)][slot]: 0 kernel start, 1 first fill
+ *              done, 2 + 3 i, 3 + 3 i, 4 + 3 i: unit loop begins, unit loop done, rows
+ *              stored, for the wave's items i = 0, 1, 2; 15 kernel end
+ * dark_timeline_read copies n slots (int64 ticks) of the last launch to `host`
+ * (host pointer; synchronises the device).  The ordinary build records nothing
+ * and returns DARK_EUNSUPPORTED.  DARK_EINVAL for a null pointer, an unknown
+ * `which` or n beyond the array.
+ */
+dark_status dark_timeline_read(int which, int64_t* host, size_t n);
+
 #ifdef __cplusplus
 }
 #endif

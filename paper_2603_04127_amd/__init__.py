@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
     L.dark_timing_read.restype = i32
     L.dark_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int64),
                                    ctypes.POINTER(ctypes.c_double)]
+    L.dark_timeline_read.restype = i32
+    L.dark_timeline_read.argtypes = [i32, ctypes.POINTER(ctypes.c_int64), sz]
     L.dark_ceiling_copy.restype = i32
     L.dark_ceiling_copy.argtypes = [vp, vp, sz, vp]
     L.dark_ceiling_read.restype = i32
@@ -362,6 +364,14 @@ def timing_read() -> dict:
         if n.value:
             out[name.value.decode()] = (n.value, ms.value)
     return out
+
+
+def timeline_read(which: int, n: int):
+    """The wall-clock stamps of the last launch of the key/value pass (which = 0) or the readout (which = 1)
+    as a list of n int64 ticks; raises unless the loaded library was built with -DDARK_TIMELINE."""
+    buf = (ctypes.c_int64 * n)()
+    _check(lib().dark_timeline_read(int(which), buf, n), "dark_timeline_read")
+    return list(buf)
 
 
 # ----------------------------------------------------------------------------

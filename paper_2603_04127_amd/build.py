@@ -20,13 +20,20 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True) -> str:
+LIB_TIMELINE = os.path.join(HERE, "libdark_timeline.so")
+
+
+def build(verbose: bool = True, timeline: bool = False) -> str:
+    """Compile every source and link the library.  timeline=True builds a second library beside it,
+    libdark_timeline.so, whose two large forward kernels record wall-clock stamps (-DDARK_TIMELINE)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
+    suffix = ".tl.o" if timeline else ".o"
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(CSRC, src.replace(".hip", suffix))
+        extra = EXTRA.get(src, []) + (["-DDARK_TIMELINE"] if timeline else [])
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd)))
@@ -34,11 +41,12 @@ def build(verbose: bool = True) -> str:
     for src, pr in procs:
         if pr.wait() != 0:
             raise RuntimeError(f"hipcc failed on {src}")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    lib = LIB_TIMELINE if timeline else LIB
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -25,6 +25,24 @@ namespace dark {
 using namespace fz;
 namespace {
 
+// Wall-clock stamps for dark_timeline_read (builds with -DDARK_TIMELINE only).  Every lane stores the same value
+// to the same slot, with no branch around the store: behind a lane test, or with the slot kept in a register
+// across the loop, the compiler's register allocation of these kernels falls apart.
+constexpr int kTlKvWgs = 512, kTlRoWgs = 256, kTlSlots = 16;
+#ifdef DARK_TIMELINE
+__device__ long long g_tl_kv[kTlKvWgs * 4 * kTlSlots];
+__device__ long long g_tl_ro[kTlRoWgs * 8 * kTlSlots];
+#define DARK_STAMP(arr, nwg, nwv, slot)                                                                          \
+  __builtin_nontemporal_store((long long)wall_clock64(),                                                        \
+                              arr + ((size_t)(blockIdx.x % (nwg)) * (nwv) + threadIdx.x / 64) * kTlSlots + (slot))
+#else
+#define DARK_STAMP(arr, nwg, nwv, slot) \
+  do {                                   \
+  } while (0)
+#endif
+#define KV_STAMP(slot) DARK_STAMP(g_tl_kv, kTlKvWgs, 4, slot)
+#define RO_STAMP(slot) DARK_STAMP(g_tl_ro, kTlRoWgs, 8, slot)
+
 // ---------------------------------------------------------------------------
 // k_prep: A'[h][j][:] = alpha log2e sum_t W[h][j][t] M[h][t][:]  (fp16),  M' = alpha sqrt(log2e/2) M.
 // One block per (h, 256 / (d/4) feature rows).  Every global load of the block (its W rows and all
@@ -157,6 +175,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
   unsigned char* Vt = smem + SM::x_bytes;
   _Float16* Ms = reinterpret_cast<_Float16*>(smem + SM::x_bytes + SM::v_bytes);
 
+  KV_STAMP(0);
   const int nfb = m / 256;
   const int q8 = blockIdx.x / (8 * nfb), rem = blockIdx.x % (8 * nfb);
   const int fb = rem / 8, work = q8 * 8 + rem % 8;
@@ -332,7 +351,9 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
     // 16 zero bytes behind each row's extra slots (never written again): the upper half-wave, whose feature-side
     // extra slots are zero, reads these instead of the row's norm, which may be infinite (inf x 0 = NaN)
     *reinterpret_cast<u32x4*>(Xs + (tid / kTile) * SM::x_buf + (tid % kTile) * XROW + 144) = u32x4{0u, 0u, 0u, 0u};
+    KV_STAMP(1);
     __syncthreads();  // M' is read by every wave's norm MFMAs
+    KV_STAMP(2);
     stage01(kreg, k1);
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
@@ -349,6 +370,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
     for (int s = 0; s < 4; ++s) asm volatile("" ::"v"(afr[ft][s]));
   __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2): everything but the two loads of tile 2
   __syncthreads();
+  KV_STAMP(3);
   fetch_xa(Xs);
 #pragma unroll
   for (int s = 0; s < 5; ++s)
@@ -520,6 +542,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
       v1 = __builtin_amdgcn_readfirstlane(r2);
     }
   }
+  KV_STAMP(4);
   // drain: C of the last block (second half of the last tile, feature tile 1)
   {
     const unsigned char* vlast = Vt + v2 * SM::v_buf + 32 * 128;  // after the last rotation v2 is the last tile's buffer
@@ -597,6 +620,7 @@ __global__ __launch_bounds__(256, 2) void k_kv_reduce(const unsigned short* __re
 #pragma unroll
   for (int ft = 0; ft < 2; ++ft)
     if (hf == 0) cpart[pbase * m + f0 + 32 * ft + l32] = c[ft];
+  KV_STAMP(5);
 }
 
 // ---------------------------------------------------------------------------
@@ -838,6 +862,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
   // already resident when a second buffer exists (the run of a workgroup rarely spans more than two).
   // Workgroups are dealt to the eight XCDs round-robin; neighbouring runs of items (which share S^T, z and
   // A') go to workgroups of one XCD, so that its L2 fetches each of them once.
+  if (NW == 8) RO_STAMP(0);
   const int nwg = gridDim.x;
   const int wg = nwg % 8 == 0 ? (blockIdx.x % 8) * (nwg / 8) + blockIdx.x / 8 : blockIdx.x;
   const int item_begin = wg * items_per_wg;
@@ -1038,6 +1063,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
       if (tid < m / 64) zq[m + tid] = cv[q];
     }
     __syncthreads();
+    RO_STAMP(1);
     cur_vb = vb0;
     cur_h = h0;
     // (the A' of a second head sits in buffer (hn - h0) % 2 = 1, where the loop looks for it)
@@ -1141,6 +1167,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
           for (int tt = 0; tt < 2; ++tt)
             U[0][tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[s2], xf[tt][s2], s2 == 0 ? zero16 : U[0][tt], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        if (NW == 8 && fb == 0) RO_STAMP(item == item_begin ? 2 : item == item_begin + 1 ? 5 : 8);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
           const int cur = g & 1, nxt = cur ^ 1;
@@ -1204,6 +1231,7 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
         }
       }
     }
+    if (NW == 8) RO_STAMP(item == item_begin ? 3 : item == item_begin + 1 ? 6 : 9);
     have_x = more;
     const float dt0 = den[0] + xor32(den[0]), dt1 = den[1] + xor32(den[1]);
     const bool redo = __any(!(dt0 > kDenLo && dt0 < kDenHi) || !(dt1 > kDenLo && dt1 < kDenHi));
@@ -1386,7 +1414,9 @@ __global__ __launch_bounds__(64 * NW, 1) void k_readout(const unsigned short* __
         }
       }
     }
+    if (NW == 8) RO_STAMP(item == item_begin ? 4 : item == item_begin + 1 ? 7 : 10);
   }
+  if (NW == 8) RO_STAMP(15);
 }
 
 constexpr size_t kLdsMax = 160 * 1024;
@@ -1583,3 +1613,18 @@ dark_status fused_launch_kv_reduce(const Problem& pb, const void* K, const void*
 }
 
 }  // namespace dark
+
+extern "C" dark_status dark_timeline_read(int which, int64_t* host, size_t n) {
+  using namespace dark;
+  if (host == nullptr || (which != 0 && which != 1)) return DARK_EINVAL;
+  const size_t cap = which == 0 ? (size_t)kTlKvWgs * 4 * kTlSlots : (size_t)kTlRoWgs * 8 * kTlSlots;
+  if (n > cap) return DARK_EINVAL;
+#ifdef DARK_TIMELINE
+  static_assert(sizeof(long long) == sizeof(int64_t), "tick type");
+  const hipError_t e = which == 0 ? hipMemcpyFromSymbol(host, HIP_SYMBOL(g_tl_kv), n * sizeof(int64_t), 0, hipMemcpyDeviceToHost)
+                                  : hipMemcpyFromSymbol(host, HIP_SYMBOL(g_tl_ro), n * sizeof(int64_t), 0, hipMemcpyDeviceToHost);
+  return e == hipSuccess ? DARK_OK : DARK_EHIP;
+#else
+  return DARK_EUNSUPPORTED;
+#endif
+}

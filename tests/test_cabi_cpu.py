@@ -126,3 +126,13 @@ def test_timing_slots_named():
     name = ctypes.c_char_p()
     assert L.dark_timing_read(0, ctypes.byref(name), None, None) == dk.DARK_OK and name.value
     assert L.dark_timing_read(n, None, None, None) == dk.DARK_EINVAL
+
+
+def test_timeline_is_a_build_option():
+    """The ordinary library records no timeline: the call validates its arguments and says so (no HIP call)."""
+    L = dk.lib()
+    buf = (ctypes.c_int64 * 16)()
+    assert L.dark_timeline_read(0, buf, 16) == dk.DARK_EUNSUPPORTED
+    assert L.dark_timeline_read(2, buf, 16) == dk.DARK_EINVAL
+    assert L.dark_timeline_read(1, None, 16) == dk.DARK_EINVAL
+    assert L.dark_timeline_read(1, buf, 10 ** 9) == dk.DARK_EINVAL
